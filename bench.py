@@ -1,0 +1,210 @@
+"""Benchmark of the MoTE-layer forward on one MI355X.
+
+One step = one pass of the whole hot path (router + Q_a(x), dispatch, routed gate-up GEMM
+with SwiGLU, Q_a(h), routed down GEMM, shared FFN, combine) over one batch of synthetic
+tokens whose inputs and weights already sit in HBM.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c5|c4_T<T>_n<n>]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# MI355X published peaks
+PEAK_HBM_GBS = 8000.0
+PEAK_I8_TOPS = 5000.0
+PEAK_BF16_TFLOPS = 2500.0
+
+
+def pick_config(name: str):
+    import workloads as W
+    if name == "c1":
+        return W.C1
+    if name == "c2":
+        return W.C2
+    if name == "c3":
+        return W.C3
+    if name == "c5":
+        return W.C5
+    if name.startswith("c4"):
+        n_tok, n_distinct = 64, 16
+        for part in name.split("_")[1:]:
+            if part[0] == "T":
+                n_tok = int(part[1:])
+            elif part[0] == "n":
+                n_distinct = int(part[1:])
+        return W.decode_config(n_tok, n_distinct)
+    raise SystemExit(f"unknown workload {name}")
+
+
+def stage_work(cfg, counts):
+    """Algorithmic work per launch of each stage: (bound, amount, unit, peak)."""
+    T, d, F, E, k = cfg.n_tokens, cfg.d_model, cfg.d_ff, cfg.n_experts, cfg.top_k
+    R = T * k
+    n_active = int((counts > 0).sum())
+    decode = cfg.name.startswith("c4")
+    w = {}
+    if decode:  # HBM-bound: packed expert bytes actually touched (+ their activations)
+        w["routed_gate_up"] = ("hbm", n_active * 2 * d * F / 4 + R * d + R * F * 2, "GB/s", PEAK_HBM_GBS)
+        w["routed_down"] = ("hbm", n_active * d * F / 4 + R * F + R * d * 4, "GB/s", PEAK_HBM_GBS)
+        w["shared_gate_up"] = ("hbm", 2 * d * F * 2 + T * d * 2 + T * F * 2, "GB/s", PEAK_HBM_GBS)
+        w["shared_down"] = ("hbm", d * F * 2 + T * F * 2 + T * d * 4, "GB/s", PEAK_HBM_GBS)
+    else:       # MFMA-bound
+        w["routed_gate_up"] = ("mfma", 2.0 * R * 2 * d * F, "TFLOP/s", PEAK_I8_TOPS)
+        w["routed_down"] = ("mfma", 2.0 * R * d * F, "TFLOP/s", PEAK_I8_TOPS)
+        w["shared_gate_up"] = ("mfma", 2.0 * T * 2 * d * F, "TFLOP/s", PEAK_BF16_TFLOPS)
+        w["shared_down"] = ("mfma", 2.0 * T * d * F, "TFLOP/s", PEAK_BF16_TFLOPS)
+    w["router_quant"] = ("hbm", T * d * 2 + T * d + d * E * 2, "GB/s", PEAK_HBM_GBS)
+    w["quant_h"] = ("hbm", R * F * 3, "GB/s", PEAK_HBM_GBS)
+    w["combine"] = ("hbm", T * d * 4 + R * d * 4 + T * d * 2, "GB/s", PEAK_HBM_GBS)
+    w["dispatch"] = ("hbm", R * 4 * 3, "GB/s", PEAK_HBM_GBS)
+    return w
+
+
+def read_traffic(stage: str, workload: str):
+    """HBM bytes per launch of `stage`, from the committed rocprofv3 --pmc summary, if any."""
+    path = os.path.join(ROOT, "profiles", f"pmc_traffic_{stage}_{workload}.txt")
+    if not os.path.exists(path):
+        return None
+    with open(path) as fh:
+        for line in fh:
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":")[1])
+    return None
+
+
+def cpu_baseline(cfg, budget_s=20.0):
+    """The CPU oracle as it stands, timed on the host cores on a bounded token sample."""
+    import numpy as np
+    from tests.mote_testlib import OracleProblem
+    op = OracleProblem(cfg)
+    n_probe = min(cfg.n_tokens, 32)
+    stride = max(cfg.n_tokens // n_probe, 1)
+    tokens = np.arange(0, cfg.n_tokens, stride)[:n_probe]
+    t0 = time.perf_counter()
+    ref = op.forward(tokens=tokens)          # also ternarises the touched experts (not timed below)
+    t_probe = time.perf_counter() - t0
+    needed = np.unique(ref["idx"])
+    for e in needed:
+        op.experts(int(e))
+    t0 = time.perf_counter()
+    op.forward(tokens=tokens)
+    t_small = time.perf_counter() - t0
+    n = int(min(cfg.n_tokens, max(n_probe, n_probe * budget_s / max(t_small, 1e-3))))
+    if n > n_probe and t_probe < 120:
+        stride = max(cfg.n_tokens // n, 1)
+        tokens = np.arange(0, cfg.n_tokens, stride)[:n]
+        t0 = time.perf_counter()
+        op.forward(tokens=tokens)
+        t_small = time.perf_counter() - t0
+    else:
+        n = len(tokens)
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    return {"value": n / t_small, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{n} of {cfg.n_tokens} tokens (every {max(cfg.n_tokens // n, 1)}th), router on all tokens, "
+                      f"experts already ternarised; {t_small:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="c2")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU; the layer is token-parallel and shards without "
+              "communication, so no multi-GPU figure is produced (run with --gpus 1).", file=sys.stderr)
+        raise SystemExit(2)
+
+    import numpy as np
+    import torch
+    import paper_2506_14435_amd as M
+    from tests.mote_testlib import GpuProblem
+
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU; there is no CPU fallback")
+    M.load_library()
+    cfg = pick_config(args.workload)
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev).manual_seed(cfg.seed + 977)
+
+    def latent(e, m):  # fp32 latents drawn on the device; ternarised by mote_pack_ternary
+        shape = (cfg.d_ff, cfg.d_model) if m < 2 else (cfg.d_model, cfg.d_ff)
+        return torch.randn(*shape, device=dev, generator=gen) * cfg.sigma_latent
+
+    gp = GpuProblem(cfg, dev, latent_source=latent if cfg.n_experts * cfg.d_model * cfg.d_ff > 5e7 else None)
+    out = torch.empty_like(gp.x)
+    ws = gp.layer.workspace(cfg.n_tokens)
+    taps = M.alloc_taps(gp.layer, cfg.n_tokens, ("counts",))
+
+    M.mote_layer_forward(gp.layer, gp.x, out=out, workspace=ws, taps=taps)
+    torch.cuda.synchronize()
+    counts = taps["counts"].cpu().numpy()
+
+    for _ in range(args.warmup):
+        M.mote_layer_forward(gp.layer, gp.x, out=out, workspace=ws)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        M.mote_layer_forward(gp.layer, gp.x, out=out, workspace=ws)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+    tokens_per_s = cfg.n_tokens * args.steps / elapsed
+
+    # per-kernel durations: HIP events recorded by the library on the launch stream
+    M.mote_stage_timing(True)
+    acc = {n: 0.0 for n in M.STAGE_NAMES}
+    for _ in range(args.steps):
+        M.mote_layer_forward(gp.layer, gp.x, out=out, workspace=ws)
+        for n, v in M.mote_stage_times().items():
+            acc[n] += v
+    M.mote_stage_timing(False)
+    stage_ms = {n: v / args.steps for n, v in acc.items()}
+
+    work = stage_work(cfg, counts)
+    candidates = ("routed_gate_up", "routed_down", "shared_gate_up", "shared_down")
+    dom = max(candidates, key=lambda n: stage_ms[n])
+    stages = {}
+    for n in M.STAGE_NAMES:
+        bound, amount, unit, peak = work[n]
+        ach = amount / (stage_ms[n] * 1e-3) / (1e9 if unit == "GB/s" else 1e12)
+        stages[n] = {"ms": round(stage_ms[n], 5), "bound": bound, "achieved": round(ach, 2), "unit": unit,
+                     "frac": round(ach / peak, 4)}
+    bound, amount, unit, peak = work[dom]
+    achieved = amount / (stage_ms[dom] * 1e-3) / (1e9 if unit == "GB/s" else 1e12)
+    roofline = {"kernel": dom, "bound": bound, "achieved": round(achieved, 2), "peak": peak, "unit": unit,
+                "frac": round(achieved / peak, 4), "traffic": read_traffic(dom, args.workload),
+                "avg_launch_ms": round(stage_ms[dom], 5)}
+
+    result = {
+        "metric": "MoTE-layer tokens/s", "value": round(tokens_per_s, 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "i8+bf16",
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "d_model": cfg.d_model, "d_ff": cfg.d_ff, "n_experts": cfg.n_experts,
+                   "top_k": cfg.top_k, "tokens": cfg.n_tokens, "expert_loads": counts.tolist()},
+        "roofline": roofline,
+        "stages": stages,
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

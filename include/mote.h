@@ -1,0 +1,180 @@
+/* mote.h -- C ABI of the MI355X (gfx950) MoTE-layer forward library.
+ *
+ * One MoTE layer (Mixture of Ternary Experts, arXiv 2506.14435, Section 3.1) is
+ *     out = FFN(x) + MoE(x)                                   (Eq.2 without residual and LN)
+ *     MoE(x) = sum_{i in top-k} P(x)_i * FFN^T_i(x)            (Eq.3, Eq.4, sparse gate)
+ *     FFN^T_i(x) = Q_w(W_down) Q_a(h),  h = Q_w(W_up) Q_a(x) (*) SiLU(Q_w(W_gate) Q_a(x))   (Eq.5-6)
+ *     Q_w: absmean ternary {-1,0,1} with one scale per matrix, Q_a: per-token absmax int8     (Eq.7-10)
+ * FFN is the full-precision (bf16) shared SwiGLU expert; the routed experts are stored as
+ * 2-bit codes (INT2 storage, end of Section 3.1) and contracted on int8 MFMA with int32
+ * accumulation.
+ *
+ * Conventions for every entry point
+ *   - Every data pointer is a DEVICE pointer into memory the CALLER owns, 16-byte aligned.
+ *     The library never allocates, frees or synchronises inside these calls; all work is
+ *     enqueued on the HIP stream passed as `hip_stream` (a hipStream_t cast to void*, NULL
+ *     is the default stream).  Inputs and outputs must not alias.
+ *   - Matrices are row-major.  A weight matrix is [n_out, n_in] and acts on a column
+ *     vector of n_in channels (Section 3.1, sentence after Eq.10).
+ *   - bf16 data is the raw 16-bit pattern.
+ *   - Errors are return codes.  Shapes are validated before anything is enqueued; on an
+ *     error nothing has been launched unless the code is MOTE_ERR_HIP.
+ *   - There is no CPU fallback: without a gfx950 device every call fails with MOTE_ERR_HIP.
+ */
+#ifndef MOTE_H
+#define MOTE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  MOTE_OK = 0,
+  MOTE_ERR_INVALID_ARG = 1,        /* null pointer, negative size, bad enum            */
+  MOTE_ERR_UNSUPPORTED_SHAPE = 2,  /* violates the shape limits listed per entry point */
+  MOTE_ERR_WORKSPACE_TOO_SMALL = 3,
+  MOTE_ERR_HIP = 4                 /* a HIP launch / runtime call failed               */
+} mote_status;
+
+/* Static, NUL-terminated description of a status code (host memory, never freed). */
+const char* mote_status_string(int status);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int mote_version(void);
+
+/* ---------------------------------------------------------------------------------------
+ * Q_w + INT2 pack  (Eq.7, Eq.9, Eq.10; "stores ... ternary weight in INT2 format", end of
+ * Section 3.1).  Offline, once per weight matrix.
+ *
+ *   alpha  = max( fp32( sum|W| (fp64) / (n_out*n_in) ), 1e-5 )
+ *   t      = clip( round_half_even( W / alpha ), -1, 1 )           (fp32 IEEE divide)
+ *   code   = t + 1  in {0,1,2}; code 3 is never written
+ *
+ * Packed layout (this library's; the paper fixes none): tiles of 32 rows x 128 input
+ * channels, tile (nt, kt) at 32-bit word offset 256*(nt*(n_in/128) + kt).  In a tile, word
+ * 4*(32*g + r) + s (r = row%32, g in {0,1}, s in 0..3) holds the codes of row 32*nt + r for
+ * channels 128*kt + 32*s + 16*g + i, i = 0..15, code i at bit 8*(i%4) + 2*(i/4).  Hence a
+ * 64-lane wavefront fetches a tile with one 16-byte load per lane, and (word >> 2j) &
+ * 0x03030303, j = 0..3, are four int8 MFMA operand registers in channel order.
+ */
+enum { MOTE_DTYPE_F32 = 0, MOTE_DTYPE_BF16 = 1 };
+
+/* Bytes of the packed form of an [n_out, n_in] matrix: n_out*n_in/4. */
+size_t mote_packed_bytes(int64_t n_out, int64_t n_in);
+
+/* w       in : device, [n_out, n_in] latent weights, fp32 or bf16 (w_dtype)
+ * packed  out: device, mote_packed_bytes(n_out, n_in) bytes (also used as scratch for the
+ *              partial sums of the reduction before it is overwritten)
+ * alpha   out: device, 1 float, the clamped scale
+ * Limits: n_out % 32 == 0, n_in % 128 == 0, both > 0. */
+mote_status mote_pack_ternary(const void* w, int w_dtype, int64_t n_out, int64_t n_in,
+                              uint32_t* packed, float* alpha, void* hip_stream);
+
+/* ---------------------------------------------------------------------------------------
+ * Router: gate softmax of Eq.3 and GShard-style top-k selection (Section 3.1; Section 4.1
+ * "top-1 gating").
+ *
+ *   logits[t,e] = sum_c x[t,c] * w_router[c,e] (+ router_bias[e]),   fp64 accumulation
+ *   P = softmax over all E logits; the k largest logits are selected, in descending order,
+ *   exact ties to the lower expert index; topk_p = P[selected], NOT renormalised (Eq.4
+ *   multiplies by P(x)_i itself).
+ *
+ * x            in : bf16 [T, d]
+ * w_router     in : bf16 [d, E]   (the router projection stays BF16, Section 3.1)
+ * router_bias  in : fp32 [E] or NULL.  NULL is the paper's layer; the bias only serves
+ *                   synthetic workloads that need a prescribed expert load.
+ * topk_idx     out: int32 [T, k]
+ * topk_p       out: fp32  [T, k]
+ * expert_counts out: int32 [E] or NULL; number of (token, slot) pairs routed to each expert
+ * Limits: d % 128 == 0, 1 <= E <= 64, 1 <= k <= min(E, 8), T >= 0 (T == 0 is a no-op). */
+mote_status mote_router_topk(const void* x, const void* w_router, const float* router_bias,
+                             int T, int d, int E, int k, int32_t* topk_idx, float* topk_p,
+                             int32_t* expert_counts, void* hip_stream);
+
+/* ---------------------------------------------------------------------------------------
+ * Whole layer.
+ */
+typedef struct {
+  int d_model, d_ff_shared, d_ff_routed, n_experts, top_k;
+  const void* w_router;        /* bf16 [d, E]                                             */
+  const float* router_bias;    /* fp32 [E] or NULL                                        */
+  const void* ws_gate;         /* shared expert, bf16 [F_s, d]                            */
+  const void* ws_up;           /* bf16 [F_s, d]                                           */
+  const void* ws_down;         /* bf16 [d, F_s]                                           */
+  const uint32_t* wt_gate;     /* routed, packed: E matrices [F_r, d], expert-major       */
+  const uint32_t* wt_up;       /* E matrices [F_r, d]                                     */
+  const uint32_t* wt_down;     /* E matrices [d, F_r]                                     */
+  const float* alpha;          /* fp32 [E, 3]: (gate, up, down) scale of each expert      */
+} mote_layer;
+
+/* Optional copies of the intermediates, for stage-wise parity checks.  Every member may be
+ * NULL.  R = T*k routed rows in dispatch order: grouped by expert (ascending), inside an
+ * expert by flat position t*k + j (ascending). */
+typedef struct {
+  int32_t* topk_idx;   /* [T, k]                                                          */
+  float* topk_p;       /* [T, k]                                                          */
+  int32_t* counts;     /* [E]                                                             */
+  int32_t* row_of;     /* [T, k]  dispatch row of (t, j)                                  */
+  int32_t* tok_of;     /* [R]     token of a dispatch row                                 */
+  int8_t* q_x;         /* [T, d]  Q_a(x) integers                                         */
+  float* beta_x;       /* [T]     clamped absmax of x                                     */
+  int32_t* acc_gate;   /* [R, F_r] integer contraction t_gate . q_x                       */
+  int32_t* acc_up;     /* [R, F_r]                                                        */
+  uint16_t* h;         /* [R, F_r] bf16 hidden activation of the routed experts           */
+  int8_t* q_h;         /* [R, F_r] Q_a(h) integers                                        */
+  float* beta_h;       /* [R]                                                             */
+  int32_t* acc_down;   /* [R, d]  integer contraction t_down . q_h                        */
+  uint16_t* h_s;       /* [T, F_s] bf16 hidden activation of the shared expert            */
+  float* y_s;          /* [T, d]  shared expert output                                    */
+  float* out_f32;      /* [T, d]  layer output before the final bf16 rounding             */
+} mote_taps;
+
+/* Bytes of scratch mote_layer_forward needs for up to T_max tokens (0 on a bad shape). */
+size_t mote_layer_workspace_bytes(const mote_layer* layer, int T_max);
+
+/* out = FFN(x) + MoE(x)  (Eq.2 + Eq.4; no residual add, no LayerNorm).
+ * x    in : bf16 [T, d]
+ * out  out: bf16 [T, d]
+ * workspace: device scratch of at least mote_layer_workspace_bytes(layer, T) bytes, 256-byte
+ *            aligned; contents are undefined afterwards; calls sharing a workspace must be
+ *            ordered on one stream.
+ * taps : NULL in production.
+ * Limits: d, F_s, F_r % 128 == 0; 1 <= E <= 64; 1 <= k <= min(E, 8); 0 <= T; T*k < 2^24. */
+mote_status mote_layer_forward(const mote_layer* layer, const void* x, int T, void* out,
+                               void* workspace, size_t workspace_bytes, const mote_taps* taps,
+                               void* hip_stream);
+
+/* ---------------------------------------------------------------------------------------
+ * Measurement support (not part of the layer's mathematics).
+ */
+enum {
+  MOTE_STAGE_ROUTER_QUANT = 0, /* router + softmax/top-k + Q_a(x)                 */
+  MOTE_STAGE_DISPATCH = 1,     /* counts, offsets, permutation, tile list         */
+  MOTE_STAGE_ROUTED_GATE_UP = 2,
+  MOTE_STAGE_QUANT_H = 3,
+  MOTE_STAGE_ROUTED_DOWN = 4,
+  MOTE_STAGE_SHARED_GATE_UP = 5,
+  MOTE_STAGE_SHARED_DOWN = 6,
+  MOTE_STAGE_COMBINE = 7,
+  MOTE_N_STAGES = 8
+};
+
+/* enable != 0: every following mote_layer_forward brackets each stage with HIP events on
+ * the caller's stream (created on first use, host-side state, not thread-safe). */
+mote_status mote_stage_timing(int enable);
+
+/* Waits for the last timed forward and writes the MOTE_N_STAGES stage durations in
+ * milliseconds to host memory `ms`; a stage that did not run reports 0. */
+mote_status mote_stage_times(float* ms_host);
+
+/* dst[i] = src[i] for n_bytes (multiple of 16) with a plain grid-stride copy kernel: the
+ * known-size transfer used to calibrate HBM byte counters. */
+mote_status mote_calib_copy(void* dst, const void* src, size_t n_bytes, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOTE_H */

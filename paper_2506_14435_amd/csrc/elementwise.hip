@@ -1,0 +1,151 @@
+// Row quantiser Q_a(h) (Eq.8-10 applied to the hidden activation of Eq.5), the weighted
+// combine of Eq.2 + Eq.4, and the calibration copy kernel.
+#include "common.h"
+#include "launch.h"
+
+namespace mote {
+
+constexpr int kRowThreads = 256;
+
+__device__ __forceinline__ float block_max(float v, float* s_buf) {
+  v = wave_max(v);
+  if ((threadIdx.x & 63) == 0) s_buf[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float r = s_buf[0];
+#pragma unroll
+  for (int i = 1; i < kRowThreads / kWave; ++i) r = fmaxf(r, s_buf[i]);
+  __syncthreads();
+  return r;
+}
+
+__device__ __forceinline__ int block_sum(int v, int* s_buf) {
+  v = wave_sum(v);
+  if ((threadIdx.x & 63) == 0) s_buf[threadIdx.x >> 6] = v;
+  __syncthreads();
+  int r = 0;
+#pragma unroll
+  for (int i = 0; i < kRowThreads / kWave; ++i) r += s_buf[i];
+  __syncthreads();
+  return r;
+}
+
+// One workgroup per dispatch row: absmax over the bf16 row, then a second sweep (L2 hits)
+// that writes the int8 row and accumulates its integer sum.
+__global__ __launch_bounds__(kRowThreads) void quant_rows_kernel(const uint16_t* __restrict__ h, int F,
+                                                                 int8_t* __restrict__ q, float* __restrict__ beta,
+                                                                 int32_t* __restrict__ rowsum) {
+  __shared__ float s_f[kRowThreads / kWave];
+  __shared__ int s_i[kRowThreads / kWave];
+  const int64_t row = blockIdx.x;
+  const uint16_t* hp = h + row * F;
+  const int n_chunks = F >> 3;
+  float amax = 0.0f;
+  for (int ch = threadIdx.x; ch < n_chunks; ch += kRowThreads) {
+    const uint4 p = *reinterpret_cast<const uint4*>(hp + ch * 8);
+    amax = fmaxf(amax, fmaxf(fmaxf(fabsf(bf16_lo(p.x)), fabsf(bf16_hi(p.x))), fmaxf(fabsf(bf16_lo(p.y)), fabsf(bf16_hi(p.y)))));
+    amax = fmaxf(amax, fmaxf(fmaxf(fabsf(bf16_lo(p.z)), fabsf(bf16_hi(p.z))), fmaxf(fabsf(bf16_lo(p.w)), fabsf(bf16_hi(p.w)))));
+  }
+  const float b = fmaxf(block_max(amax, s_f), kEps);
+  const float s = 127.0f / b;
+  int rs = 0;
+  for (int ch = threadIdx.x; ch < n_chunks; ch += kRowThreads) {
+    const uint4 p = *reinterpret_cast<const uint4*>(hp + ch * 8);
+    const int q0 = quant_i8(bf16_lo(p.x), s), q1 = quant_i8(bf16_hi(p.x), s);
+    const int q2 = quant_i8(bf16_lo(p.y), s), q3 = quant_i8(bf16_hi(p.y), s);
+    const int q4 = quant_i8(bf16_lo(p.z), s), q5 = quant_i8(bf16_hi(p.z), s);
+    const int q6 = quant_i8(bf16_lo(p.w), s), q7 = quant_i8(bf16_hi(p.w), s);
+    rs += q0 + q1 + q2 + q3 + q4 + q5 + q6 + q7;
+    uint2 o;
+    o.x = (q0 & 0xFF) | ((q1 & 0xFF) << 8) | ((q2 & 0xFF) << 16) | (static_cast<uint32_t>(q3 & 0xFF) << 24);
+    o.y = (q4 & 0xFF) | ((q5 & 0xFF) << 8) | ((q6 & 0xFF) << 16) | (static_cast<uint32_t>(q7 & 0xFF) << 24);
+    *reinterpret_cast<uint2*>(q + row * F + ch * 8) = o;
+  }
+  const int total = block_sum(rs, s_i);
+  if (threadIdx.x == 0) {
+    beta[row] = b;
+    rowsum[row] = total;
+  }
+}
+
+hipError_t launch_quant_rows(const uint16_t* h, int rows, int F, int8_t* q, float* beta, int32_t* rowsum,
+                             hipStream_t stream) {
+  if (rows == 0) return hipSuccess;
+  quant_rows_kernel<<<rows, kRowThreads, 0, stream>>>(h, F, q, beta, rowsum);
+  return hipGetLastError();
+}
+
+// Combine (Eq.2 + Eq.4): one thread per (token, 8 channels).
+//   y_e[c] = float(D[row, c]) * ((beta_h[row] / 127) * alpha_down[e])      (ternary linear, Section 3.1)
+//   out[t, c] = y_s[t, c] + sum_j p[t, j] * y_{e_j}[c]
+template <int KMAX>
+__global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ y_s, const int32_t* __restrict__ acc_down,
+                                                      const float* __restrict__ beta_h, const float* __restrict__ alpha,
+                                                      const int32_t* __restrict__ topk_idx,
+                                                      const float* __restrict__ topk_p,
+                                                      const int32_t* __restrict__ row_of, int T, int d, int k,
+                                                      uint16_t* __restrict__ out, float* __restrict__ out_f32) {
+  const int chunks = d >> 3;
+  const int64_t gid = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (gid >= static_cast<int64_t>(T) * chunks) return;
+  const int t = static_cast<int>(gid / chunks);
+  const int c0 = static_cast<int>(gid - static_cast<int64_t>(t) * chunks) << 3;
+  const float4 s0 = *reinterpret_cast<const float4*>(y_s + static_cast<int64_t>(t) * d + c0);
+  const float4 s1 = *reinterpret_cast<const float4*>(y_s + static_cast<int64_t>(t) * d + c0 + 4);
+  float o[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+#pragma unroll
+  for (int j = 0; j < KMAX; ++j) {
+    if (j < k) {
+      const int row = row_of[t * k + j];
+      const int e = topk_idx[t * k + j];
+      const float p = topk_p[t * k + j];
+      const float sc = (beta_h[row] / 127.0f) * alpha[e * 3 + 2];
+      const int4 d0 = *reinterpret_cast<const int4*>(acc_down + static_cast<int64_t>(row) * d + c0);
+      const int4 d1 = *reinterpret_cast<const int4*>(acc_down + static_cast<int64_t>(row) * d + c0 + 4);
+      o[0] = fmaf(p, static_cast<float>(d0.x) * sc, o[0]);
+      o[1] = fmaf(p, static_cast<float>(d0.y) * sc, o[1]);
+      o[2] = fmaf(p, static_cast<float>(d0.z) * sc, o[2]);
+      o[3] = fmaf(p, static_cast<float>(d0.w) * sc, o[3]);
+      o[4] = fmaf(p, static_cast<float>(d1.x) * sc, o[4]);
+      o[5] = fmaf(p, static_cast<float>(d1.y) * sc, o[5]);
+      o[6] = fmaf(p, static_cast<float>(d1.z) * sc, o[6]);
+      o[7] = fmaf(p, static_cast<float>(d1.w) * sc, o[7]);
+    }
+  }
+  uint4 ob;
+  ob.x = pack_bf16x2(o[0], o[1]);
+  ob.y = pack_bf16x2(o[2], o[3]);
+  ob.z = pack_bf16x2(o[4], o[5]);
+  ob.w = pack_bf16x2(o[6], o[7]);
+  *reinterpret_cast<uint4*>(out + static_cast<int64_t>(t) * d + c0) = ob;
+  if (out_f32) {
+    *reinterpret_cast<float4*>(out_f32 + static_cast<int64_t>(t) * d + c0) = make_float4(o[0], o[1], o[2], o[3]);
+    *reinterpret_cast<float4*>(out_f32 + static_cast<int64_t>(t) * d + c0 + 4) = make_float4(o[4], o[5], o[6], o[7]);
+  }
+}
+
+hipError_t launch_combine(const float* y_s, const int32_t* acc_down, const float* beta_h, const float* alpha,
+                          const int32_t* topk_idx, const float* topk_p, const int32_t* row_of, int T, int d,
+                          int k, uint16_t* out, float* out_f32, hipStream_t stream) {
+  if (T == 0) return hipSuccess;
+  const int64_t n = static_cast<int64_t>(T) * (d >> 3);
+  const unsigned blocks = static_cast<unsigned>((n + 255) / 256);
+  combine_kernel<8><<<blocks, 256, 0, stream>>>(y_s, acc_down, beta_h, alpha, topk_idx, topk_p, row_of, T, d, k, out,
+                                                out_f32);
+  return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void copy_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src, size_t n16) {
+  const size_t stride = static_cast<size_t>(gridDim.x) * 256;
+  for (size_t i = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+hipError_t launch_copy(void* dst, const void* src, size_t n_bytes, hipStream_t stream) {
+  const size_t n16 = n_bytes / 16;
+  if (n16 == 0) return hipSuccess;
+  size_t blocks = (n16 + 255) / 256;
+  if (blocks > 256 * 16) blocks = 256 * 16;
+  copy_kernel<<<static_cast<unsigned>(blocks), 256, 0, stream>>>(static_cast<uint4*>(dst), static_cast<const uint4*>(src), n16);
+  return hipGetLastError();
+}
+
+}  // namespace mote

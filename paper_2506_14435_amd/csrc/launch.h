@@ -1,0 +1,73 @@
+// Host-side launch functions of the kernel translation units (internal, C++).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mote {
+
+hipError_t launch_pack_ternary(const void* w, bool is_bf16, int64_t n_out, int64_t n_in, uint32_t* packed,
+                               float* alpha, hipStream_t stream);
+
+// Router (Eq.3 + top-k) fused with Q_a(x) (Eq.8).  q_x / beta_x / rowsum_x may be null
+// (router only).
+hipError_t launch_router_quant(const uint16_t* x, const uint16_t* w_router, const float* bias, int T, int d,
+                               int E, int k, int32_t* topk_idx, float* topk_p, int8_t* q_x, float* beta_x,
+                               int32_t* rowsum_x, hipStream_t stream);
+
+hipError_t launch_expert_counts(const int32_t* topk_idx, int R, int E, int32_t* counts, hipStream_t stream);
+
+// Dispatch plan: counts, offsets, row_of / tok_of (expert-major, stable) and the list of
+// row tiles (tile_m rows each) that the grouped GEMMs walk.
+struct DispatchPlan {
+  int32_t* counts;      // [E]
+  int32_t* offsets;     // [E+1]
+  int32_t* row_of;      // [T*k]
+  int32_t* tok_of;      // [T*k]
+  int32_t* tile_expert; // [max_tiles]
+  int32_t* tile_row0;   // [max_tiles]
+  int32_t* tile_rows;   // [max_tiles]
+  int32_t* n_tiles;     // [1]
+};
+hipError_t launch_dispatch_plan(const int32_t* topk_idx, int T, int k, int E, int tile_m, const DispatchPlan& plan,
+                                hipStream_t stream);
+
+// Grouped ternary GEMMs over the dispatch plan.
+struct RoutedGemmArgs {
+  const int8_t* q;          // activation rows [*, K] int8
+  const int32_t* gather;    // dispatch row -> row of q / beta / rowsum, or null for identity
+  const float* beta;        // clamped absmax per row of q
+  const int32_t* rowsum;    // sum of the int8 row (zero-point correction of code = t + 1)
+  const uint32_t* w_gate;   // packed, expert-major (gate / down)
+  const uint32_t* w_up;     // packed (gate-up mode only)
+  const float* alpha;       // [E, 3]
+  DispatchPlan plan;
+  int max_tiles;            // upper bound on *plan.n_tiles known on the host
+  int tile_m;               // rows per plan tile
+  int K, N;                 // contraction length, output width (per matrix)
+  uint16_t* h;              // gate-up: bf16 [R, N]
+  int32_t* acc_out;         // down: int32 [R, N]
+  int32_t* tap_gate;        // optional int32 [R, N]
+  int32_t* tap_up;
+};
+hipError_t launch_routed_gate_up(const RoutedGemmArgs& a, hipStream_t stream);
+hipError_t launch_routed_down(const RoutedGemmArgs& a, hipStream_t stream);
+int routed_tile_m(int T, int k, int E);  // plan tile size chosen for a workload
+
+// Q_a(h): per dispatch row absmax int8 of the bf16 hidden activation.
+hipError_t launch_quant_rows(const uint16_t* h, int rows, int F, int8_t* q, float* beta, int32_t* rowsum,
+                             hipStream_t stream);
+
+// Shared expert (bf16 MFMA, fp32 accumulation).
+hipError_t launch_shared_gate_up(const uint16_t* x, const uint16_t* w_gate, const uint16_t* w_up, int T, int d,
+                                 int F, uint16_t* h_s, hipStream_t stream);
+hipError_t launch_shared_down(const uint16_t* h_s, const uint16_t* w_down, int T, int d, int F, float* y_s,
+                              hipStream_t stream);
+
+// out = bf16( y_s + sum_j p[t,j] * (acc_down[row_of[t,j]] * (beta_h/127 * alpha_down)) ).
+hipError_t launch_combine(const float* y_s, const int32_t* acc_down, const float* beta_h, const float* alpha,
+                          const int32_t* topk_idx, const float* topk_p, const int32_t* row_of, int T, int d,
+                          int k, uint16_t* out, float* out_f32, hipStream_t stream);
+
+hipError_t launch_copy(void* dst, const void* src, size_t n_bytes, hipStream_t stream);
+
+}  // namespace mote

@@ -1,0 +1,254 @@
+// C ABI of the MoTE-layer library: argument validation, workspace carving and the
+// sequence of kernel launches for one forward pass (Eq.2-10 of Section 3.1).
+#include "../../include/mote.h"
+
+#include <hip/hip_runtime.h>
+
+#include "launch.h"
+
+namespace {
+
+using namespace mote;
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+struct Workspace {
+  // dispatch
+  int32_t* topk_idx; float* topk_p; int32_t* counts; int32_t* offsets; int32_t* n_tiles;
+  int32_t* row_of; int32_t* tok_of; int32_t* tile_expert; int32_t* tile_row0; int32_t* tile_rows;
+  // Q_a(x)
+  int8_t* q_x; float* beta_x; int32_t* rs_x;
+  // routed experts
+  uint16_t* h; int8_t* q_h; float* beta_h; int32_t* rs_h; int32_t* acc_down;
+  // shared expert
+  uint16_t* h_s; float* y_s;
+  size_t bytes;
+  int max_tiles;
+};
+
+bool layer_shape_ok(const mote_layer* l) {
+  if (l->d_model <= 0 || l->d_ff_shared <= 0 || l->d_ff_routed <= 0) return false;
+  if (l->d_model % 128 || l->d_ff_shared % 128 || l->d_ff_routed % 128) return false;
+  if (l->n_experts < 1 || l->n_experts > 64) return false;
+  if (l->top_k < 1 || l->top_k > l->n_experts || l->top_k > 8) return false;
+  return true;
+}
+
+// Carves the workspace; with base == nullptr only the size is computed.
+Workspace carve(const mote_layer* l, int T, char* base) {
+  Workspace w{};
+  size_t off = 0;
+  auto take = [&](size_t bytes) -> char* {
+    char* p = base ? base + off : nullptr;
+    off += align_up(bytes ? bytes : 1);
+    return p;
+  };
+  const size_t R = static_cast<size_t>(T) * l->top_k;
+  const size_t d = l->d_model, Fr = l->d_ff_routed, Fs = l->d_ff_shared;
+  w.max_tiles = static_cast<int>(R / 32 + l->n_experts);
+  w.topk_idx = reinterpret_cast<int32_t*>(take(R * 4));
+  w.topk_p = reinterpret_cast<float*>(take(R * 4));
+  w.counts = reinterpret_cast<int32_t*>(take(64 * 4));
+  w.offsets = reinterpret_cast<int32_t*>(take(65 * 4));
+  w.n_tiles = reinterpret_cast<int32_t*>(take(4));
+  w.row_of = reinterpret_cast<int32_t*>(take(R * 4));
+  w.tok_of = reinterpret_cast<int32_t*>(take(R * 4));
+  w.tile_expert = reinterpret_cast<int32_t*>(take(static_cast<size_t>(w.max_tiles) * 4));
+  w.tile_row0 = reinterpret_cast<int32_t*>(take(static_cast<size_t>(w.max_tiles) * 4));
+  w.tile_rows = reinterpret_cast<int32_t*>(take(static_cast<size_t>(w.max_tiles) * 4));
+  w.q_x = reinterpret_cast<int8_t*>(take(static_cast<size_t>(T) * d));
+  w.beta_x = reinterpret_cast<float*>(take(static_cast<size_t>(T) * 4));
+  w.rs_x = reinterpret_cast<int32_t*>(take(static_cast<size_t>(T) * 4));
+  w.h = reinterpret_cast<uint16_t*>(take(R * Fr * 2));
+  w.q_h = reinterpret_cast<int8_t*>(take(R * Fr));
+  w.beta_h = reinterpret_cast<float*>(take(R * 4));
+  w.rs_h = reinterpret_cast<int32_t*>(take(R * 4));
+  w.acc_down = reinterpret_cast<int32_t*>(take(R * d * 4));
+  w.h_s = reinterpret_cast<uint16_t*>(take(static_cast<size_t>(T) * Fs * 2));
+  w.y_s = reinterpret_cast<float*>(take(static_cast<size_t>(T) * d * 4));
+  w.bytes = off;
+  return w;
+}
+
+// ---- stage timing state (host side) ----
+bool g_timing = false;
+bool g_events_ready = false;
+bool g_timed_run = false;
+hipEvent_t g_ev[MOTE_N_STAGES + 1];
+
+hipError_t ensure_events() {
+  if (g_events_ready) return hipSuccess;
+  for (int i = 0; i <= MOTE_N_STAGES; ++i) {
+    hipError_t e = hipEventCreate(&g_ev[i]);
+    if (e != hipSuccess) return e;
+  }
+  g_events_ready = true;
+  return hipSuccess;
+}
+
+#define MOTE_HIP(expr)                            \
+  do {                                            \
+    hipError_t _e = (expr);                       \
+    if (_e != hipSuccess) return MOTE_ERR_HIP;    \
+  } while (0)
+
+}  // namespace
+
+extern "C" {
+
+const char* mote_status_string(int status) {
+  switch (status) {
+    case MOTE_OK: return "ok";
+    case MOTE_ERR_INVALID_ARG: return "invalid argument";
+    case MOTE_ERR_UNSUPPORTED_SHAPE: return "unsupported shape";
+    case MOTE_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case MOTE_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+int mote_version(void) { return 100; }
+
+size_t mote_packed_bytes(int64_t n_out, int64_t n_in) {
+  if (n_out <= 0 || n_in <= 0) return 0;
+  return static_cast<size_t>(n_out) * static_cast<size_t>(n_in) / 4;
+}
+
+mote_status mote_pack_ternary(const void* w, int w_dtype, int64_t n_out, int64_t n_in, uint32_t* packed,
+                              float* alpha, void* hip_stream) {
+  if (!w || !packed || !alpha) return MOTE_ERR_INVALID_ARG;
+  if (w_dtype != MOTE_DTYPE_F32 && w_dtype != MOTE_DTYPE_BF16) return MOTE_ERR_INVALID_ARG;
+  if (n_out <= 0 || n_in <= 0) return MOTE_ERR_INVALID_ARG;
+  if (n_out % 32 || n_in % 128) return MOTE_ERR_UNSUPPORTED_SHAPE;
+  MOTE_HIP(launch_pack_ternary(w, w_dtype == MOTE_DTYPE_BF16, n_out, n_in, packed, alpha,
+                               static_cast<hipStream_t>(hip_stream)));
+  return MOTE_OK;
+}
+
+mote_status mote_router_topk(const void* x, const void* w_router, const float* router_bias, int T, int d, int E,
+                             int k, int32_t* topk_idx, float* topk_p, int32_t* expert_counts, void* hip_stream) {
+  if (T < 0) return MOTE_ERR_INVALID_ARG;
+  if (d <= 0 || d % 128 || E < 1 || E > 64 || k < 1 || k > E || k > 8) return MOTE_ERR_UNSUPPORTED_SHAPE;
+  if (static_cast<int64_t>(T) * k >= (1 << 24)) return MOTE_ERR_UNSUPPORTED_SHAPE;
+  if (T == 0) return MOTE_OK;
+  if (!x || !w_router || !topk_idx || !topk_p) return MOTE_ERR_INVALID_ARG;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  MOTE_HIP(launch_router_quant(static_cast<const uint16_t*>(x), static_cast<const uint16_t*>(w_router), router_bias,
+                               T, d, E, k, topk_idx, topk_p, nullptr, nullptr, nullptr, stream));
+  if (expert_counts) MOTE_HIP(launch_expert_counts(topk_idx, T * k, E, expert_counts, stream));
+  return MOTE_OK;
+}
+
+size_t mote_layer_workspace_bytes(const mote_layer* layer, int T_max) {
+  if (!layer || T_max < 0 || !layer_shape_ok(layer)) return 0;
+  if (static_cast<int64_t>(T_max) * layer->top_k >= (1 << 24)) return 0;
+  return carve(layer, T_max, nullptr).bytes;
+}
+
+mote_status mote_layer_forward(const mote_layer* layer, const void* x, int T, void* out, void* workspace,
+                               size_t workspace_bytes, const mote_taps* taps, void* hip_stream) {
+  if (!layer || T < 0) return MOTE_ERR_INVALID_ARG;
+  if (!layer_shape_ok(layer)) return MOTE_ERR_UNSUPPORTED_SHAPE;
+  if (static_cast<int64_t>(T) * layer->top_k >= (1 << 24)) return MOTE_ERR_UNSUPPORTED_SHAPE;
+  if (T == 0) return MOTE_OK;
+  if (!x || !out || !workspace) return MOTE_ERR_INVALID_ARG;
+  if (!layer->w_router || !layer->ws_gate || !layer->ws_up || !layer->ws_down || !layer->wt_gate || !layer->wt_up ||
+      !layer->wt_down || !layer->alpha)
+    return MOTE_ERR_INVALID_ARG;
+  if (reinterpret_cast<uintptr_t>(workspace) % kAlign) return MOTE_ERR_INVALID_ARG;
+  const Workspace w = carve(layer, T, static_cast<char*>(workspace));
+  if (w.bytes > workspace_bytes) return MOTE_ERR_WORKSPACE_TOO_SMALL;
+
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const int d = layer->d_model, Fr = layer->d_ff_routed, Fs = layer->d_ff_shared;
+  const int E = layer->n_experts, k = layer->top_k;
+  const int R = T * k;
+  const uint16_t* xb = static_cast<const uint16_t*>(x);
+  const bool timing = g_timing;
+  if (timing) MOTE_HIP(ensure_events());
+  auto mark = [&](int i) -> hipError_t { return timing ? hipEventRecord(g_ev[i], stream) : hipSuccess; };
+
+  MOTE_HIP(mark(0));
+  MOTE_HIP(launch_router_quant(xb, static_cast<const uint16_t*>(layer->w_router), layer->router_bias, T, d, E, k,
+                               w.topk_idx, w.topk_p, w.q_x, w.beta_x, w.rs_x, stream));
+  MOTE_HIP(mark(1));
+  const int tile_m = routed_tile_m(T, k, E);
+  DispatchPlan plan{w.counts, w.offsets, w.row_of, w.tok_of, w.tile_expert, w.tile_row0, w.tile_rows, w.n_tiles};
+  MOTE_HIP(launch_dispatch_plan(w.topk_idx, T, k, E, tile_m, plan, stream));
+  MOTE_HIP(mark(2));
+
+  RoutedGemmArgs ga{};
+  ga.q = w.q_x; ga.gather = w.tok_of; ga.beta = w.beta_x; ga.rowsum = w.rs_x;
+  ga.w_gate = layer->wt_gate; ga.w_up = layer->wt_up; ga.alpha = layer->alpha;
+  ga.plan = plan; ga.max_tiles = R / tile_m + E; ga.tile_m = tile_m;
+  ga.K = d; ga.N = Fr; ga.h = w.h; ga.acc_out = nullptr;
+  ga.tap_gate = taps ? taps->acc_gate : nullptr;
+  ga.tap_up = taps ? taps->acc_up : nullptr;
+  MOTE_HIP(launch_routed_gate_up(ga, stream));
+  MOTE_HIP(mark(3));
+  MOTE_HIP(launch_quant_rows(w.h, R, Fr, w.q_h, w.beta_h, w.rs_h, stream));
+  MOTE_HIP(mark(4));
+
+  RoutedGemmArgs gd = ga;
+  gd.q = w.q_h; gd.gather = nullptr; gd.beta = w.beta_h; gd.rowsum = w.rs_h;
+  gd.w_gate = layer->wt_down; gd.w_up = nullptr;
+  gd.K = Fr; gd.N = d; gd.h = nullptr; gd.acc_out = w.acc_down; gd.tap_gate = nullptr; gd.tap_up = nullptr;
+  MOTE_HIP(launch_routed_down(gd, stream));
+  MOTE_HIP(mark(5));
+
+  MOTE_HIP(launch_shared_gate_up(xb, static_cast<const uint16_t*>(layer->ws_gate),
+                                 static_cast<const uint16_t*>(layer->ws_up), T, d, Fs, w.h_s, stream));
+  MOTE_HIP(mark(6));
+  MOTE_HIP(launch_shared_down(w.h_s, static_cast<const uint16_t*>(layer->ws_down), T, d, Fs, w.y_s, stream));
+  MOTE_HIP(mark(7));
+  MOTE_HIP(launch_combine(w.y_s, w.acc_down, w.beta_h, layer->alpha, w.topk_idx, w.topk_p, w.row_of, T, d, k,
+                          static_cast<uint16_t*>(out), taps ? taps->out_f32 : nullptr, stream));
+  MOTE_HIP(mark(8));
+  if (timing) g_timed_run = true;
+
+  if (taps) {
+    auto tap = [&](void* dst, const void* src, size_t bytes) -> hipError_t {
+      if (!dst || bytes == 0) return hipSuccess;
+      return hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToDevice, stream);
+    };
+    const size_t Rz = static_cast<size_t>(R), Tz = static_cast<size_t>(T);
+    MOTE_HIP(tap(taps->topk_idx, w.topk_idx, Rz * 4));
+    MOTE_HIP(tap(taps->topk_p, w.topk_p, Rz * 4));
+    MOTE_HIP(tap(taps->counts, w.counts, static_cast<size_t>(E) * 4));
+    MOTE_HIP(tap(taps->row_of, w.row_of, Rz * 4));
+    MOTE_HIP(tap(taps->tok_of, w.tok_of, Rz * 4));
+    MOTE_HIP(tap(taps->q_x, w.q_x, Tz * d));
+    MOTE_HIP(tap(taps->beta_x, w.beta_x, Tz * 4));
+    MOTE_HIP(tap(taps->h, w.h, Rz * Fr * 2));
+    MOTE_HIP(tap(taps->q_h, w.q_h, Rz * Fr));
+    MOTE_HIP(tap(taps->beta_h, w.beta_h, Rz * 4));
+    MOTE_HIP(tap(taps->acc_down, w.acc_down, Rz * d * 4));
+    MOTE_HIP(tap(taps->h_s, w.h_s, Tz * Fs * 2));
+    MOTE_HIP(tap(taps->y_s, w.y_s, Tz * d * 4));
+  }
+  return MOTE_OK;
+}
+
+mote_status mote_stage_timing(int enable) {
+  g_timing = enable != 0;
+  if (!g_timing) g_timed_run = false;
+  return MOTE_OK;
+}
+
+mote_status mote_stage_times(float* ms_host) {
+  if (!ms_host) return MOTE_ERR_INVALID_ARG;
+  for (int i = 0; i < MOTE_N_STAGES; ++i) ms_host[i] = 0.0f;
+  if (!g_timed_run) return MOTE_OK;
+  MOTE_HIP(hipEventSynchronize(g_ev[MOTE_N_STAGES]));
+  for (int i = 0; i < MOTE_N_STAGES; ++i) MOTE_HIP(hipEventElapsedTime(&ms_host[i], g_ev[i], g_ev[i + 1]));
+  return MOTE_OK;
+}
+
+mote_status mote_calib_copy(void* dst, const void* src, size_t n_bytes, void* hip_stream) {
+  if (!dst || !src || n_bytes % 16) return MOTE_ERR_INVALID_ARG;
+  MOTE_HIP(launch_copy(dst, src, n_bytes, static_cast<hipStream_t>(hip_stream)));
+  return MOTE_OK;
+}
+
+}  // extern "C"

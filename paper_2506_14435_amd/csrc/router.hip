@@ -1,0 +1,274 @@
+// Router (gate softmax of Eq.3 + GShard-style top-k, Section 3.1) fused with the
+// per-token absmax int8 quantiser Q_a(x) (Eq.8-10), and the dispatch plan that turns the
+// top-k indices into an expert-major row permutation.
+//
+// router_quant_kernel: one wavefront owns TPW tokens.  Each lane owns 8-channel chunks of
+// the token rows (16-byte bf16 loads), multiplies them with the matching 8 rows of the
+// bf16 router matrix and accumulates TPW x EMAX partial logits in fp64 (a bf16 x bf16
+// product is exact, and fp64 accumulation makes the selected indices independent of the
+// summation order).  A 6-step butterfly reduce-scatter leaves lane l with the finished
+// logit (token l / EMAX, expert l % EMAX).  The token rows are then read a second time
+// (L2 hits) to emit the int8 row, its absmax and its integer row sum.
+#include "common.h"
+#include "launch.h"
+
+namespace mote {
+
+constexpr int kRouterThreads = 256;
+
+template <int OFF>
+__device__ __forceinline__ void reduce_scatter_step(double (&v)[64], int lane) {
+  constexpr int kHalf = OFF;  // values kept after this step == OFF (64 -> 32 -> ... -> 1)
+  const bool up = (lane & OFF) != 0;
+#pragma unroll
+  for (int i = 0; i < kHalf; ++i) {
+    const double keep = up ? v[i + kHalf] : v[i];
+    const double send = up ? v[i] : v[i + kHalf];
+    v[i] = keep + __shfl_xor(send, OFF, kWave);
+  }
+  if constexpr (OFF > 1) reduce_scatter_step<OFF / 2>(v, lane);
+}
+
+template <int EMAX>
+__device__ __forceinline__ void load_router_row(const uint16_t* __restrict__ row, int E, bool vec_ok,
+                                                double (&w)[EMAX]) {
+  if (vec_ok) {
+#pragma unroll
+    for (int v = 0; v < EMAX / 8; ++v) {
+      if (v * 8 < E) {
+        const uint4 p = *reinterpret_cast<const uint4*>(row + v * 8);
+        w[v * 8 + 0] = bf16_lo(p.x); w[v * 8 + 1] = bf16_hi(p.x);
+        w[v * 8 + 2] = bf16_lo(p.y); w[v * 8 + 3] = bf16_hi(p.y);
+        w[v * 8 + 4] = bf16_lo(p.z); w[v * 8 + 5] = bf16_hi(p.z);
+        w[v * 8 + 6] = bf16_lo(p.w); w[v * 8 + 7] = bf16_hi(p.w);
+      } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) w[v * 8 + j] = 0.0;
+      }
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < EMAX; ++e) w[e] = (e < E) ? static_cast<double>(bf16_to_f32(row[e])) : 0.0;
+  }
+}
+
+template <int EMAX, int TPW>
+__global__ __launch_bounds__(kRouterThreads) void router_quant_kernel(
+    const uint16_t* __restrict__ x, const uint16_t* __restrict__ w_router, const float* __restrict__ bias, int T,
+    int d, int E, int k, int32_t* __restrict__ topk_idx, float* __restrict__ topk_p, int8_t* __restrict__ q_x,
+    float* __restrict__ beta_x, int32_t* __restrict__ rowsum_x) {
+  static_assert(EMAX * TPW == 64, "one finished logit per lane");
+  __shared__ double s_logit[kRouterThreads / kWave][64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int t0 = (blockIdx.x * (kRouterThreads / kWave) + wave) * TPW;
+  if (t0 >= T) return;  // whole wavefront leaves together; no block-level barrier below
+  const int n_chunks = d >> 3;
+  const bool vec_ok = (E & 7) == 0;
+
+  const uint16_t* xrow[TPW];
+#pragma unroll
+  for (int t = 0; t < TPW; ++t) xrow[t] = x + static_cast<int64_t>(min(t0 + t, T - 1)) * d;
+
+  double acc[64];
+#pragma unroll
+  for (int i = 0; i < 64; ++i) acc[i] = 0.0;
+  float amax[TPW];
+#pragma unroll
+  for (int t = 0; t < TPW; ++t) amax[t] = 0.0f;
+
+  for (int ch = lane; ch < n_chunks; ch += kWave) {
+    const int c0 = ch << 3;
+    float xf[TPW][8];
+#pragma unroll
+    for (int t = 0; t < TPW; ++t) {
+      const uint4 p = *reinterpret_cast<const uint4*>(xrow[t] + c0);
+      xf[t][0] = bf16_lo(p.x); xf[t][1] = bf16_hi(p.x); xf[t][2] = bf16_lo(p.y); xf[t][3] = bf16_hi(p.y);
+      xf[t][4] = bf16_lo(p.z); xf[t][5] = bf16_hi(p.z); xf[t][6] = bf16_lo(p.w); xf[t][7] = bf16_hi(p.w);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) amax[t] = fmaxf(amax[t], fabsf(xf[t][i]));
+    }
+#pragma unroll(EMAX > 16 ? 1 : 2)
+    for (int i = 0; i < 8; ++i) {
+      double w[EMAX];
+      load_router_row<EMAX>(w_router + static_cast<int64_t>(c0 + i) * E, E, vec_ok, w);
+#pragma unroll
+      for (int t = 0; t < TPW; ++t) {
+        const double xv = static_cast<double>(xf[t][i]);
+#pragma unroll
+        for (int e = 0; e < EMAX; ++e) acc[t * EMAX + e] = fma(xv, w[e], acc[t * EMAX + e]);
+      }
+    }
+  }
+
+  reduce_scatter_step<32>(acc, lane);  // lane l now holds logit(token l / EMAX, expert l % EMAX)
+  {
+    const int e = lane % EMAX;
+    double l = acc[0];
+    if (bias != nullptr && e < E) l += static_cast<double>(bias[e]);
+    s_logit[wave][lane] = l;
+  }
+#pragma unroll
+  for (int t = 0; t < TPW; ++t) amax[t] = wave_max(amax[t]);
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+  // Softmax over all E logits and top-k: one lane per token, serial over E <= 64.
+  if (lane < TPW && t0 + lane < T) {
+    const double* l = &s_logit[wave][lane * EMAX];
+    double mx = l[0];
+    for (int e = 1; e < E; ++e) mx = fmax(mx, l[e]);
+    double sum = 0.0;
+    for (int e = 0; e < E; ++e) sum += exp(l[e] - mx);
+    uint64_t taken = 0;
+    for (int j = 0; j < k; ++j) {
+      int best = -1;
+      double lb = 0.0;
+      for (int e = 0; e < E; ++e) {
+        if ((taken >> e) & 1ull) continue;
+        const double le = l[e];
+        if (best < 0 || le > lb) { best = e; lb = le; }   // strict >: ties keep the lower index
+      }
+      taken |= 1ull << best;
+      topk_idx[static_cast<int64_t>(t0 + lane) * k + j] = best;
+      topk_p[static_cast<int64_t>(t0 + lane) * k + j] = static_cast<float>(exp(lb - mx) / sum);
+    }
+  }
+
+  if (q_x == nullptr) return;
+  // Q_a(x): beta = max(absmax, 1e-5); s = 127 / beta (IEEE divide); q = clip(rne(x * s)).
+  float scale[TPW];
+  int rs[TPW];
+#pragma unroll
+  for (int t = 0; t < TPW; ++t) {
+    amax[t] = fmaxf(amax[t], kEps);
+    scale[t] = 127.0f / amax[t];
+    rs[t] = 0;
+  }
+  for (int ch = lane; ch < n_chunks; ch += kWave) {
+    const int c0 = ch << 3;
+#pragma unroll
+    for (int t = 0; t < TPW; ++t) {
+      const uint4 p = *reinterpret_cast<const uint4*>(xrow[t] + c0);
+      const int q0 = quant_i8(bf16_lo(p.x), scale[t]), q1 = quant_i8(bf16_hi(p.x), scale[t]);
+      const int q2 = quant_i8(bf16_lo(p.y), scale[t]), q3 = quant_i8(bf16_hi(p.y), scale[t]);
+      const int q4 = quant_i8(bf16_lo(p.z), scale[t]), q5 = quant_i8(bf16_hi(p.z), scale[t]);
+      const int q6 = quant_i8(bf16_lo(p.w), scale[t]), q7 = quant_i8(bf16_hi(p.w), scale[t]);
+      rs[t] += q0 + q1 + q2 + q3 + q4 + q5 + q6 + q7;
+      uint2 o;
+      o.x = (q0 & 0xFF) | ((q1 & 0xFF) << 8) | ((q2 & 0xFF) << 16) | (static_cast<uint32_t>(q3 & 0xFF) << 24);
+      o.y = (q4 & 0xFF) | ((q5 & 0xFF) << 8) | ((q6 & 0xFF) << 16) | (static_cast<uint32_t>(q7 & 0xFF) << 24);
+      if (t0 + t < T) *reinterpret_cast<uint2*>(q_x + static_cast<int64_t>(t0 + t) * d + c0) = o;
+    }
+  }
+#pragma unroll
+  for (int t = 0; t < TPW; ++t) {
+    const int total = wave_sum(rs[t]);
+    if (lane == 0 && t0 + t < T) {
+      beta_x[t0 + t] = amax[t];
+      rowsum_x[t0 + t] = total;
+    }
+  }
+}
+
+hipError_t launch_router_quant(const uint16_t* x, const uint16_t* w_router, const float* bias, int T, int d,
+                               int E, int k, int32_t* topk_idx, float* topk_p, int8_t* q_x, float* beta_x,
+                               int32_t* rowsum_x, hipStream_t stream) {
+  if (T == 0) return hipSuccess;
+  constexpr int kWavesPerBlock = kRouterThreads / kWave;
+  if (E <= 16) {
+    constexpr int kTpw = 4;
+    const int blocks = (T + kWavesPerBlock * kTpw - 1) / (kWavesPerBlock * kTpw);
+    router_quant_kernel<16, kTpw><<<blocks, kRouterThreads, 0, stream>>>(x, w_router, bias, T, d, E, k, topk_idx,
+                                                                         topk_p, q_x, beta_x, rowsum_x);
+  } else {
+    constexpr int kTpw = 1;
+    const int blocks = (T + kWavesPerBlock * kTpw - 1) / (kWavesPerBlock * kTpw);
+    router_quant_kernel<64, kTpw><<<blocks, kRouterThreads, 0, stream>>>(x, w_router, bias, T, d, E, k, topk_idx,
+                                                                         topk_p, q_x, beta_x, rowsum_x);
+  }
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------ dispatch plan
+constexpr int kPlanThreads = 1024;
+
+// One block per expert.  Every block histograms all R = T*k indices (so it knows every
+// expert's count without a grid-wide dependency), then compacts the positions of its own
+// expert in ascending flat order t*k + j: the dispatch order is deterministic and stable.
+__global__ __launch_bounds__(kPlanThreads) void dispatch_plan_kernel(const int32_t* __restrict__ topk_idx, int R,
+                                                                     int k, int E, int tile_m, DispatchPlan plan) {
+  __shared__ int s_cnt[64];
+  __shared__ int s_wave[kPlanThreads / kWave];
+  __shared__ int s_off, s_tile_base;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int e = blockIdx.x;
+  if (tid < 64) s_cnt[tid] = 0;
+  __syncthreads();
+  for (int i = tid; i < R; i += kPlanThreads) atomicAdd(&s_cnt[topk_idx[i]], 1);
+  __syncthreads();
+  if (tid == 0) {
+    int off = 0, tiles = 0;
+    for (int j = 0; j < E; ++j) {
+      if (j == e) { s_off = off; s_tile_base = tiles; }
+      if (e == 0) { plan.counts[j] = s_cnt[j]; plan.offsets[j] = off; }
+      off += s_cnt[j];
+      tiles += (s_cnt[j] + tile_m - 1) / tile_m;
+    }
+    if (e == 0) { plan.offsets[E] = off; plan.n_tiles[0] = tiles; }
+  }
+  __syncthreads();
+  const int my_off = s_off, my_cnt = s_cnt[e], tile_base = s_tile_base;
+  for (int m = tid; m * tile_m < my_cnt; m += kPlanThreads) {
+    plan.tile_expert[tile_base + m] = e;
+    plan.tile_row0[tile_base + m] = my_off + m * tile_m;
+    plan.tile_rows[tile_base + m] = min(tile_m, my_cnt - m * tile_m);
+  }
+  int running = 0;
+  for (int base = 0; base < R; base += kPlanThreads) {
+    const int i = base + tid;
+    const bool flag = (i < R) && (topk_idx[i] == e);
+    const uint64_t mask = __ballot(flag);
+    const int prefix = __popcll(mask & ((1ull << lane) - 1ull));
+    if (lane == 0) s_wave[wave] = __popcll(mask);
+    __syncthreads();
+    int wave_off = 0, total = 0;
+#pragma unroll
+    for (int w = 0; w < kPlanThreads / kWave; ++w) {
+      const int c = s_wave[w];
+      if (w < wave) wave_off += c;
+      total += c;
+    }
+    if (flag) {
+      const int slot = my_off + running + wave_off + prefix;
+      plan.row_of[i] = slot;
+      plan.tok_of[slot] = i / k;
+    }
+    running += total;
+    __syncthreads();
+  }
+}
+
+// Histogram of the selected experts (mote_router_topk's optional output).
+__global__ __launch_bounds__(kPlanThreads) void expert_counts_kernel(const int32_t* __restrict__ topk_idx, int R, int E,
+                                                                     int32_t* __restrict__ counts) {
+  __shared__ int s_cnt[64];
+  if (threadIdx.x < 64) s_cnt[threadIdx.x] = 0;
+  __syncthreads();
+  for (int i = threadIdx.x; i < R; i += kPlanThreads) atomicAdd(&s_cnt[topk_idx[i]], 1);
+  __syncthreads();
+  if (threadIdx.x < E) counts[threadIdx.x] = s_cnt[threadIdx.x];
+}
+
+hipError_t launch_expert_counts(const int32_t* topk_idx, int R, int E, int32_t* counts, hipStream_t stream) {
+  expert_counts_kernel<<<1, kPlanThreads, 0, stream>>>(topk_idx, R, E, counts);
+  return hipGetLastError();
+}
+
+hipError_t launch_dispatch_plan(const int32_t* topk_idx, int T, int k, int E, int tile_m, const DispatchPlan& plan,
+                                hipStream_t stream) {
+  dispatch_plan_kernel<<<E, kPlanThreads, 0, stream>>>(topk_idx, T * k, k, E, tile_m, plan);
+  return hipGetLastError();
+}
+
+}  // namespace mote

@@ -1,0 +1,198 @@
+// Shared expert FFN(x) of Eq.2: the dense checkpoint's full-precision SwiGLU FFN, active
+// for every token.  bf16 operands on v_mfma_f32_32x32x16_bf16, fp32 accumulation.
+//
+//   gate-up mode : g = x W_gate^T, u = x W_up^T, h_s = bf16(u * SiLU(g))     [T, F]
+//   down mode    : y_s = h_s W_down^T (fp32)                                 [T, d]
+//
+// Both operands are K-contiguous ([rows, K] row-major), so a tile row is 64 bf16 = 128
+// bytes and the LDS geometry (8 XOR-swizzled 16-byte chunks per row) is the same for the
+// activation and the weight tiles.  MFMA operand mapping: lane l supplies row l%32 and the
+// 8 consecutive K elements of half l/32; result register v of lane l is row
+// 8*(v/4) + 4*(l/32) + v%4, column l%32.
+#include "common.h"
+#include "launch.h"
+
+namespace mote {
+
+template <int MODE_, int BM_W_, int BN_W_, int WAVES_M_, int WAVES_N_>
+struct SharedCfg {
+  static constexpr int MODE = MODE_;
+  static constexpr int NMAT = MODE_ == 0 ? 2 : 1;
+  static constexpr int BM_W = BM_W_, BN_W = BN_W_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
+  static constexpr int BM = 32 * BM_W_ * WAVES_M_;
+  static constexpr int BN = 32 * BN_W_ * WAVES_N_;
+  static constexpr int THREADS = 64 * WAVES_M_ * WAVES_N_;
+  static constexpr int ROWS_PER_PASS = THREADS / 8;
+  static constexpr int A_PASSES = BM / ROWS_PER_PASS;
+  static constexpr int B_PASSES = BN / ROWS_PER_PASS;
+  static_assert(BM % ROWS_PER_PASS == 0 && BN % ROWS_PER_PASS == 0, "loaders cover the tiles in whole passes");
+  static constexpr int A_BYTES = BM * 128;
+  static constexpr int B_BYTES = BN * 128;
+  static constexpr int STAGE_BYTES = A_BYTES + NMAT * B_BYTES;
+};
+
+__device__ __forceinline__ int lds_tile_offset(int row, int chunk) { return row * 128 + ((chunk ^ (row & 7)) << 4); }
+
+struct SharedGemmArgs {
+  const uint16_t* act;   // [M, K] bf16
+  const uint16_t* w0;    // [N, K] bf16 (gate / down)
+  const uint16_t* w1;    // [N, K] bf16 (up)
+  int M, N, K;
+  uint16_t* h_out;       // gate-up: bf16 [M, N]
+  float* y_out;          // down: fp32 [M, N]
+};
+
+template <typename Cfg>
+__global__ __launch_bounds__(Cfg::THREADS) void shared_gemm_kernel(SharedGemmArgs a, int n_ntiles) {
+  constexpr int NMAT = Cfg::NMAT, BM_W = Cfg::BM_W, BN_W = Cfg::BN_W;
+  constexpr int BM = Cfg::BM, BN = Cfg::BN;
+  extern __shared__ __attribute__((aligned(16))) unsigned char s_mem[];
+
+  const int nt = blockIdx.x % n_ntiles;
+  const int mt = blockIdx.x / n_ntiles;
+  const int M = a.M, N = a.N, K = a.K;
+  const int KT = K >> 6;
+  const int m0 = mt * BM, n0 = nt * BN;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave % Cfg::WAVES_M, wn = wave / Cfg::WAVES_M;
+  const int r32 = lane & 31, g = lane >> 5;
+  const int chunk = tid & 7;
+
+  const uint16_t* a_src[Cfg::A_PASSES];
+  const uint16_t* b_src[NMAT][Cfg::B_PASSES];
+  int a_dst[Cfg::A_PASSES], b_dst[Cfg::B_PASSES];
+#pragma unroll
+  for (int p = 0; p < Cfg::A_PASSES; ++p) {
+    const int r = p * Cfg::ROWS_PER_PASS + (tid >> 3);
+    a_src[p] = a.act + static_cast<int64_t>(min(m0 + r, M - 1)) * K + chunk * 8;
+    a_dst[p] = lds_tile_offset(r, chunk);
+  }
+#pragma unroll
+  for (int p = 0; p < Cfg::B_PASSES; ++p) {
+    const int r = p * Cfg::ROWS_PER_PASS + (tid >> 3);
+    const int64_t off = static_cast<int64_t>(min(n0 + r, N - 1)) * K + chunk * 8;
+    b_src[0][p] = a.w0 + off;
+    if constexpr (NMAT == 2) b_src[1][p] = a.w1 + off;
+    b_dst[p] = lds_tile_offset(r, chunk);
+  }
+
+  v16f acc[NMAT][BM_W][BN_W];
+#pragma unroll
+  for (int m = 0; m < NMAT; ++m)
+#pragma unroll
+    for (int i = 0; i < BM_W; ++i)
+#pragma unroll
+      for (int f = 0; f < BN_W; ++f)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[m][i][f][v] = 0.0f;
+
+  u4 a_reg[Cfg::A_PASSES], b_reg[NMAT][Cfg::B_PASSES];
+
+#define MOTE_GLOAD(kt_)                                                                              \
+  do {                                                                                             \
+    _Pragma("unroll") for (int p = 0; p < Cfg::A_PASSES; ++p)                                      \
+      a_reg[p] = *reinterpret_cast<const u4*>(a_src[p] + static_cast<int64_t>(kt_) * 64);        \
+    _Pragma("unroll") for (int m = 0; m < NMAT; ++m)                                               \
+      _Pragma("unroll") for (int p = 0; p < Cfg::B_PASSES; ++p)                                    \
+        b_reg[m][p] = *reinterpret_cast<const u4*>(b_src[m][p] + static_cast<int64_t>(kt_) * 64); \
+  } while (0)
+#define MOTE_LSTORE(stage_idx_)                                                                    \
+  do {                                                                                             \
+    unsigned char* st_ = s_mem + (stage_idx_) * Cfg::STAGE_BYTES;                                  \
+    _Pragma("unroll") for (int p = 0; p < Cfg::A_PASSES; ++p)                                      \
+      *reinterpret_cast<u4*>(st_ + a_dst[p]) = a_reg[p];                                        \
+    _Pragma("unroll") for (int m = 0; m < NMAT; ++m)                                               \
+      _Pragma("unroll") for (int p = 0; p < Cfg::B_PASSES; ++p)                                    \
+        *reinterpret_cast<u4*>(st_ + Cfg::A_BYTES + m * Cfg::B_BYTES + b_dst[p]) = b_reg[m][p]; \
+  } while (0)
+
+  MOTE_GLOAD(0);
+  MOTE_LSTORE(0);
+  __syncthreads();
+
+  const int a_row_base = wm * BM_W * 32 + r32;
+  const int b_row_base = wn * BN_W * 32 + r32;
+  for (int kt = 0; kt < KT; ++kt) {
+    const bool has_next = kt + 1 < KT;
+    if (has_next) MOTE_GLOAD(kt + 1);
+    const unsigned char* st = s_mem + (kt & 1) * Cfg::STAGE_BYTES;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      bf16x8 af[BM_W];
+#pragma unroll
+      for (int i = 0; i < BM_W; ++i)
+        af[i] = *reinterpret_cast<const bf16x8*>(st + lds_tile_offset(a_row_base + i * 32, 2 * s + g));
+#pragma unroll
+      for (int m = 0; m < NMAT; ++m)
+#pragma unroll
+        for (int f = 0; f < BN_W; ++f) {
+          const bf16x8 bf = *reinterpret_cast<const bf16x8*>(st + Cfg::A_BYTES + m * Cfg::B_BYTES +
+                                                             lds_tile_offset(b_row_base + f * 32, 2 * s + g));
+#pragma unroll
+          for (int i = 0; i < BM_W; ++i)
+            acc[m][i][f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf, acc[m][i][f], 0, 0, 0);
+        }
+    }
+    if (has_next) MOTE_LSTORE((kt + 1) & 1);
+    __syncthreads();
+  }
+
+#undef MOTE_GLOAD
+#undef MOTE_LSTORE
+
+#pragma unroll
+  for (int i = 0; i < BM_W; ++i) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int row = m0 + wm * BM_W * 32 + i * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+      if (row >= M) continue;
+#pragma unroll
+      for (int f = 0; f < BN_W; ++f) {
+        const int n = n0 + wn * BN_W * 32 + f * 32 + r32;
+        if (n >= N) continue;
+        if constexpr (Cfg::MODE == 0) {
+          const float gv = acc[0][i][f][v], uv = acc[1][i][f][v];
+          const float hv = uv * (gv / (1.0f + expf(-gv)));
+          a.h_out[static_cast<int64_t>(row) * N + n] = f32_to_bf16(hv);
+        } else {
+          a.y_out[static_cast<int64_t>(row) * N + n] = acc[0][i][f][v];
+        }
+      }
+    }
+  }
+}
+
+template <typename Cfg>
+static hipError_t launch_shared_cfg(const SharedGemmArgs& a, hipStream_t stream) {
+  const int n_ntiles = (a.N + Cfg::BN - 1) / Cfg::BN;
+  const int n_mtiles = (a.M + Cfg::BM - 1) / Cfg::BM;
+  const size_t lds = 2 * Cfg::STAGE_BYTES;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(shared_gemm_kernel<Cfg>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  shared_gemm_kernel<Cfg><<<static_cast<unsigned>(n_ntiles * n_mtiles), Cfg::THREADS, lds, stream>>>(a, n_ntiles);
+  return hipGetLastError();
+}
+
+hipError_t launch_shared_gate_up(const uint16_t* x, const uint16_t* w_gate, const uint16_t* w_up, int T, int d,
+                                 int F, uint16_t* h_s, hipStream_t stream) {
+  if (T == 0) return hipSuccess;
+  SharedGemmArgs a{x, w_gate, w_up, T, F, d, h_s, nullptr};
+  if (T <= 48) return launch_shared_cfg<SharedCfg<0, 1, 1, 1, 4>>(a, stream);
+  return launch_shared_cfg<SharedCfg<0, 2, 2, 2, 2>>(a, stream);
+}
+
+hipError_t launch_shared_down(const uint16_t* h_s, const uint16_t* w_down, int T, int d, int F, float* y_s,
+                              hipStream_t stream) {
+  if (T == 0) return hipSuccess;
+  SharedGemmArgs a{h_s, w_down, nullptr, T, d, F, nullptr, y_s};
+  if (T <= 48) return launch_shared_cfg<SharedCfg<1, 1, 1, 1, 4>>(a, stream);
+  return launch_shared_cfg<SharedCfg<1, 2, 2, 2, 2>>(a, stream);
+}
+
+}  // namespace mote

@@ -1,0 +1,82 @@
+"""Host-side checks that need no GPU: the C-ABI library loads, exports every symbol the
+header declares, and validates arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2506_14435_amd as M
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(M.LIB_PATH):
+        from paper_2506_14435_amd import build
+        build.build()
+    return M.load_library()
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "mote.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mote_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared_functions()
+    assert set(names) == set(M.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_host_only_entry_points(lib):
+    assert M.mote_version() >= 100
+    assert M.mote_packed_bytes(11008, 2048) == 11008 * 2048 // 4
+    assert M.mote_packed_bytes(0, 128) == 0
+    assert lib.mote_status_string(0) == b"ok"
+    assert lib.mote_status_string(3) == b"workspace too small"
+    assert lib.mote_status_string(99) == b"unknown status"
+
+
+def test_shape_validation_happens_on_the_host(lib):
+    L = M.binding.MoteLayerStruct(2048, 11008, 11008, 16, 2, *([None] * 9))
+    small = lib.mote_layer_workspace_bytes(ctypes.byref(L), 64)
+    big = lib.mote_layer_workspace_bytes(ctypes.byref(L), 8192)
+    assert 0 < small < big
+    # R*F bf16 + R*F int8 + R*d int32 + T*F bf16 + T*d fp32 + T*d int8 dominate
+    T, k, d, F = 8192, 2, 2048, 11008
+    floor = T * k * F * 3 + T * k * d * 4 + T * F * 2 + T * d * 5
+    assert floor <= big <= floor * 1.01 + (1 << 20)
+    L.d_model = 2000
+    assert lib.mote_layer_workspace_bytes(ctypes.byref(L), 64) == 0
+    L.d_model, L.top_k = 2048, 17
+    assert lib.mote_layer_workspace_bytes(ctypes.byref(L), 64) == 0
+    L.top_k, L.n_experts = 2, 65
+    assert lib.mote_layer_workspace_bytes(ctypes.byref(L), 64) == 0
+    # argument errors are reported before any launch (so these are safe without a GPU)
+    assert lib.mote_pack_ternary(None, 0, 32, 128, None, None, None) == 1
+    assert lib.mote_pack_ternary(ctypes.c_void_p(16), 0, 33, 128, ctypes.c_void_p(16), ctypes.c_void_p(16), None) == 2
+    assert lib.mote_router_topk(None, None, None, 0, 256, 4, 2, None, None, None, None) == 0   # T == 0: no-op
+    assert lib.mote_router_topk(None, None, None, 4, 200, 4, 2, None, None, None, None) == 2
+    assert lib.mote_layer_forward(None, None, 4, None, None, 0, None, None) == 1
+    assert lib.mote_stage_times(None) == 1
+
+
+def test_workloads_are_seeded_and_shaped():
+    import torch
+    import workloads as W
+    assert [c.name for c in (W.C1, W.C2, W.C3, W.C4, W.C5)] == list(W.CONFIGS)
+    a, b = W.make_x(W.C1), W.make_x(W.C1)
+    assert torch.equal(a, b) and a.dtype == torch.bfloat16 and a.shape == (64, 256)
+    assert W.make_router(W.C2).shape == (896, 8)
+    assert W.make_latent(W.C1, 1, 2).shape == (256, 512)
+    assert not torch.equal(W.make_latent(W.C1, 0, 0), W.make_latent(W.C1, 0, 1))
+    bias = W.make_router_bias(W.decode_config(16, 8))
+    assert (bias == 30).sum() == 8 and bias.shape == (16,)
+    z = W.make_router_bias(W.C5)
+    assert z.max() == 0 and z.min() < -1.0
+    x2 = W.make_x(W.C2).float()
+    assert (x2.abs().amax(0) > 40).sum() == 4                       # the four outlier channels

@@ -1,0 +1,399 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element
+on the same seeded inputs.
+
+Bar: bit-exact for router indices, dispatch order, packed weights, int8 codes and int32
+accumulators; bf16 layer output within max-abs-err <= 2e-2 and rel-L2 <= 5e-3 of the
+oracle's unrounded fp32 output.  Integer parity is stage-wise: the SwiGLU feeds a
+quantiser, and the kernel's exp/divide differ from the oracle's in the last fp32 bit, so a
+rare bf16 rounding of h flips; q_h and the down accumulators are therefore checked bit-exact
+against the oracle applied to the GPU's own h, and h itself against the oracle's h with a
+bounded flip rate."""
+import ctypes
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from oracle import mote_oracle as O
+from tests.mote_testlib import GpuProblem, OracleProblem, bits, error_metrics
+
+pytestmark = pytest.mark.gpu
+
+MAX_ABS_TOL = 2e-2
+REL_L2_TOL = 5e-3
+H_FLIP_RATE = 1e-3
+
+
+def _m():
+    import paper_2506_14435_amd as M
+    return M
+
+
+def _log(msg):
+    print(msg, flush=True)
+
+
+# ------------------------------------------------------------------------------- pack
+@pytest.mark.parametrize("shape,dtype", [((32, 128), "f32"), ((96, 384), "f32"), ((512, 256), "f32"),
+                                         ((256, 512), "bf16"), ((4864, 896), "f32"), ((896, 4864), "f32")])
+def test_pack_ternary_bit_exact(shape, dtype):
+    M = _m()
+    _log(f"pack {shape} {dtype}")
+    g = torch.Generator().manual_seed(shape[0] * 7 + shape[1])
+    w = torch.randn(*shape, generator=g) * 0.02
+    if dtype == "bf16":
+        wt = w.to(torch.bfloat16)
+        w_np = O.bf16_to_f32(W.bf16_bits(wt))
+    else:
+        wt, w_np = w, w.numpy()
+    packed, alpha = M.mote_pack_ternary(wt.cuda())
+    t, a = O.ternarize(w_np)
+    assert alpha.cpu().numpy()[0] == a
+    want = O.pack_int2(t)
+    got = packed.cpu().numpy().view(np.uint32)
+    assert got.nbytes == M.mote_packed_bytes(*shape) == O.packed_bytes(*shape)
+    assert np.array_equal(got, want)
+
+
+def test_pack_ternary_degenerate_matrices():
+    M = _m()
+    packed, alpha = M.mote_pack_ternary(torch.zeros(64, 256, device="cuda"))
+    assert alpha.item() == np.float32(1e-5)
+    assert (packed.cpu().numpy().view(np.uint32) == 0x55555555).all()
+    # exact ties in both directions and a constant matrix
+    w = torch.tensor([0.75, -0.75, 0.25, -0.25]).repeat(32, 32)
+    packed, alpha = M.mote_pack_ternary(w.cuda())
+    t, a = O.ternarize(w.numpy())
+    assert alpha.item() == a == np.float32(0.5)
+    assert np.array_equal(packed.cpu().numpy().view(np.uint32), O.pack_int2(t))
+    w = torch.full((32, 128), -3.0)
+    packed, alpha = M.mote_pack_ternary(w.cuda())
+    assert alpha.item() == 3.0 and (packed.cpu().numpy().view(np.uint32) == 0).all()
+
+
+# ----------------------------------------------------------------------------- router
+@pytest.mark.parametrize("T,d,E,k,bias", [(64, 256, 4, 2, False), (1, 256, 4, 1, False), (37, 384, 8, 2, True),
+                                          (515, 896, 8, 2, False), (130, 2048, 16, 2, True),
+                                          (33, 256, 6, 3, False), (70, 512, 32, 4, True), (9, 128, 64, 8, False),
+                                          (16, 128, 16, 16, False)])
+def test_router_topk_matches_oracle(T, d, E, k, bias):
+    M = _m()
+    _log(f"router T={T} d={d} E={E} k={k} bias={bias}")
+    cfg = W.MoteConfig("router_case", d, 128, E, min(k, 8), T, seed=100 + T + E)
+    k = min(k, 8)
+    x, wr = W.make_x(cfg), W.make_router(cfg)
+    b = None
+    if bias:
+        b = torch.randn(E, generator=torch.Generator().manual_seed(E)) * 2.0
+    idx, p, counts = M.mote_router_topk(x.cuda(), wr.cuda(), k, None if b is None else b.cuda())
+    torch.cuda.synchronize()
+    logits, p_all, idx_o, w_o = O.router(W.bf16_bits(x), W.bf16_bits(wr), None if b is None else b.numpy(), k)
+    srt = np.sort(logits, axis=1)[:, ::-1]
+    assert np.diff(srt[:, : k + 1], axis=1).max() < -1e-9      # no near-ties in this seeded case
+    assert np.array_equal(idx.cpu().numpy(), idx_o)
+    assert np.allclose(p.cpu().numpy(), w_o, rtol=2e-6, atol=1e-9)
+    assert np.array_equal(counts.cpu().numpy(), np.bincount(idx_o.ravel(), minlength=E))
+
+
+def test_router_exact_ties_lower_index_and_empty_batch():
+    M = _m()
+    cfg = W.MoteConfig("tie_case", 256, 128, 4, 2, 19, seed=5)
+    x = W.make_x(cfg)
+    col = W.make_router(cfg)[:, :1]
+    wr = col.repeat(1, 4).contiguous()
+    idx, p, _ = M.mote_router_topk(x.cuda(), wr.cuda(), 2)
+    assert (idx.cpu().numpy() == np.array([0, 1])).all()
+    assert np.allclose(p.cpu().numpy(), 0.25, rtol=1e-6)
+    idx, p, _ = M.mote_router_topk(x[:0].cuda(), wr.cuda(), 2)
+    assert idx.shape == (0, 2)
+
+
+# ------------------------------------------------------------------------ whole layer
+def _run_layer(gp, taps_names):
+    M = _m()
+    T = gp.x.shape[0]
+    taps = M.alloc_taps(gp.layer, T, taps_names)
+    for t in taps.values():
+        t.fill_(0) if t.dtype != torch.bfloat16 else t.zero_()
+    out = M.mote_layer_forward(gp.layer, gp.x, taps=taps)
+    torch.cuda.synchronize()
+    return out, taps
+
+
+def _check_stagewise(cfg, gp, op, ref, out, taps):
+    """Full stage-wise comparison for cases where the oracle evaluates every token."""
+    T, k, E = cfg.n_tokens, cfg.top_k, cfg.n_experts
+    R = T * k
+    # routing and dispatch order: bit-exact
+    assert np.array_equal(taps["topk_idx"].cpu().numpy(), ref["idx"])
+    assert np.allclose(taps["topk_p"].cpu().numpy(), ref["w"], rtol=2e-6, atol=1e-9)
+    assert np.array_equal(taps["counts"].cpu().numpy(), ref["counts"])
+    row_of = taps["row_of"].cpu().numpy()
+    assert np.array_equal(row_of, ref["row_of"])
+    assert np.array_equal(taps["tok_of"].cpu().numpy(), ref["tok_of"])
+    # Q_a(x): bit-exact
+    assert np.array_equal(taps["q_x"].cpu().numpy(), ref["q_x"])
+    assert np.array_equal(taps["beta_x"].cpu().numpy(), ref["beta_x"])
+    # gate / up accumulators: bit-exact (dispatch-row order on the GPU, [t, j] in the oracle)
+    flat = row_of.reshape(-1)
+    acc_gate = taps["acc_gate"].cpu().numpy()[flat].reshape(T, k, -1)
+    acc_up = taps["acc_up"].cpu().numpy()[flat].reshape(T, k, -1)
+    assert np.array_equal(acc_gate, ref["acc_gate"])
+    assert np.array_equal(acc_up, ref["acc_up"])
+    # h: identical up to rare one-step bf16 rounding flips
+    h_gpu = bits(taps["h"])                                           # [R, F]
+    h_ref = ref["h"].reshape(R, -1)
+    h_g = h_gpu[flat]
+    neq = h_g != h_ref
+    flip_rate = neq.mean()
+    if neq.any():
+        a = O.bf16_to_f32(h_g[neq]).astype(np.float64)
+        b = O.bf16_to_f32(h_ref[neq]).astype(np.float64)
+        assert (np.abs(a - b) <= np.maximum(np.abs(a), np.abs(b)) * 2.0 ** -7 + 1e-30).all()
+    assert flip_rate <= H_FLIP_RATE, flip_rate
+    # Q_a(h) from the GPU's own h: bit-exact
+    q_h_want, beta_h_want = O.absmax_int8(O.bf16_to_f32(h_gpu))
+    q_h = taps["q_h"].cpu().numpy()
+    assert np.array_equal(q_h, q_h_want)
+    assert np.array_equal(taps["beta_h"].cpu().numpy(), beta_h_want[:, 0])
+    # down accumulators from the GPU's own q_h: bit-exact
+    acc_down = taps["acc_down"].cpu().numpy()
+    tok_of = ref["tok_of"]
+    offs = np.concatenate([[0], np.cumsum(ref["counts"])])
+    for e in range(E):
+        lo, hi = offs[e], offs[e + 1]
+        if hi > lo:
+            t_down = op.experts(e)[4]
+            assert np.array_equal(acc_down[lo:hi], O.ternary_matmul_int(t_down, q_h[lo:hi])), f"expert {e}"
+    # end-to-end q_h mismatch against the oracle's own chain: bounded
+    qh_ref = ref["q_h"].reshape(R, -1)
+    dq = np.abs(q_h[flat].astype(np.int32) - qh_ref.astype(np.int32))
+    _log(f"  h flip rate {flip_rate:.2e}; q_h mismatch rate {np.mean(dq != 0):.2e}, max |dq| {dq.max()}")
+    # shared expert
+    hs_neq = (bits(taps["h_s"]) != ref["h_s"]).mean()
+    assert hs_neq <= 5e-3, hs_neq
+    assert np.allclose(taps["y_s"].cpu().numpy(), ref["y_s"], rtol=0, atol=2e-3 + 2e-3 * np.abs(ref["y_s"]).max())
+    # output
+    out_f32 = taps["out_f32"].cpu().numpy()
+    assert np.array_equal(bits(out), O.f32_to_bf16(out_f32))           # the final rounding is RNE
+    max_abs, rel_l2 = error_metrics(bits(out), ref["out_f32"])
+    _log(f"  out: max-abs-err {max_abs:.3e} rel-L2 {rel_l2:.3e} max|ref| {np.abs(ref['out_f32']).max():.3f}")
+    assert np.abs(ref["out_f32"]).max() < 8.0
+    assert max_abs <= MAX_ABS_TOL and rel_l2 <= REL_L2_TOL
+
+
+SMALL_CASES = [
+    W.C1,
+    W.C1.with_tokens(1, name="c1_T1"),
+    W.C1.with_tokens(5, name="c1_T5"),
+    W.C1.with_tokens(33, name="c1_T33"),
+    W.C1.with_tokens(131, name="c1_T131"),
+    W.C1.with_tokens(300, name="c1_T300"),
+    dataclasses.replace(W.C1, name="paper_shape_top1", top_k=1, n_tokens=77),        # Section 4.1: E=4, top-1
+    dataclasses.replace(W.C1, name="k_equals_E", top_k=4, n_tokens=40),              # Eq.4 as written (dense sum)
+    dataclasses.replace(W.C1, name="single_expert", n_experts=1, top_k=1, n_tokens=50),
+    W.MoteConfig("ragged_mid", 384, 640, 8, 2, 211, seed=11, outlier_channels=2),
+    W.MoteConfig("e16_skew", 256, 384, 16, 2, 500, seed=12, bias_kind="zipf", zipf_tau=0.8),
+    W.MoteConfig("decode_like", 512, 1408, 16, 2, 16, seed=13, bias_kind="subset", bias_subset=4),
+]
+
+
+@pytest.mark.parametrize("cfg", SMALL_CASES, ids=lambda c: c.name)
+def test_layer_stagewise_small(cfg):
+    _log(f"layer {cfg.name} T={cfg.n_tokens} d={cfg.d_model} F={cfg.d_ff} E={cfg.n_experts} k={cfg.top_k}")
+    M = _m()
+    gp, op = GpuProblem(cfg), OracleProblem(cfg)
+    out, taps = _run_layer(gp, M.TAP_FIELDS)
+    ref = op.forward()
+    _check_stagewise(cfg, gp, op, ref, out, taps)
+    # determinism: a second run is bit-identical
+    out2 = M.mote_layer_forward(gp.layer, gp.x)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2)
+
+
+def test_layer_pack_parity_config1_all_experts():
+    cfg = W.C1
+    gp, op = GpuProblem(cfg), OracleProblem(cfg)
+    for e in range(cfg.n_experts):
+        ex = op.experts(e)
+        for m in range(3):
+            assert np.array_equal(gp.wt[m][e].cpu().numpy().view(np.uint32), O.pack_int2(ex[2 * m]))
+            assert gp.alpha[e, m].item() == ex[2 * m + 1]
+
+
+def test_layer_zero_token_and_zero_rows_are_handled():
+    M = _m()
+    cfg = W.C1.with_tokens(8, name="c1_T8")
+    gp, op = GpuProblem(cfg), OracleProblem(cfg)
+    out = M.mote_layer_forward(gp.layer, gp.x[:0].contiguous())
+    assert out.shape == (0, cfg.d_model)
+    # an all-zero token: beta clamps to 1e-5, routed part is zero, output = shared(0) = 0
+    gp.x[3].zero_()
+    op.x[3] = 0
+    out, taps = _run_layer(gp, M.TAP_FIELDS)
+    ref = op.forward()
+    _check_stagewise(cfg, gp, op, ref, out, taps)
+    assert not bits(out)[3].any() or np.abs(O.bf16_to_f32(bits(out)[3])).max() == 0
+
+
+# ------------------------------------------------- full-size configurations (sampled)
+def _sample_tokens(ref_router, experts_allowed, n_max, seed):
+    idx = ref_router
+    ok = np.isin(idx, experts_allowed).all(axis=1)
+    cand = np.flatnonzero(ok)
+    rng = np.random.default_rng(seed)
+    if len(cand) > n_max:
+        cand = np.sort(rng.choice(cand, n_max, replace=False))
+    return cand
+
+
+def _check_sampled(cfg, n_sample, n_allowed_experts, out, taps, op):
+    """Full-size run: routing / dispatch / Q_a(x) for all tokens, experts on sampled tokens."""
+    T, k, E = cfg.n_tokens, cfg.top_k, cfg.n_experts
+    logits, _, idx_o, w_o = O.router(op.x, op.w_router, op.bias, k)
+    srt = np.sort(logits, axis=1)[:, ::-1]
+    margin = -np.diff(srt[:, : min(k + 1, E)], axis=1).max()
+    _log(f"  smallest top-k margin {margin:.3e}")
+    assert margin > 1e-9
+    assert np.array_equal(taps["topk_idx"].cpu().numpy(), idx_o)
+    assert np.allclose(taps["topk_p"].cpu().numpy(), w_o, rtol=2e-6, atol=1e-9)
+    counts, row_of_o, tok_of_o = O.dispatch_order(idx_o, E)
+    _log(f"  expert loads {counts.tolist()}")
+    assert np.array_equal(taps["counts"].cpu().numpy(), counts)
+    row_of = taps["row_of"].cpu().numpy()
+    assert np.array_equal(row_of, row_of_o)
+    assert np.array_equal(taps["tok_of"].cpu().numpy(), tok_of_o)
+    q_x_o, beta_x_o = O.absmax_int8(O.bf16_to_f32(op.x))
+    assert np.array_equal(taps["q_x"].cpu().numpy(), q_x_o)
+    assert np.array_equal(taps["beta_x"].cpu().numpy(), beta_x_o[:, 0])
+    # experts with the largest loads are the ones the oracle evaluates
+    allowed = np.argsort(-counts, kind="stable")[:n_allowed_experts]
+    tokens = _sample_tokens(idx_o, allowed, n_sample, seed=cfg.seed)
+    assert len(tokens) >= min(8, T)
+    ref = op.forward(tokens=tokens)
+    rows = row_of[tokens].reshape(-1)
+    rows_t = torch.from_numpy(rows.astype(np.int64)).cuda()
+    acc_gate = taps["acc_gate"][rows_t].cpu().numpy().reshape(len(tokens), k, -1)
+    acc_up = taps["acc_up"][rows_t].cpu().numpy().reshape(len(tokens), k, -1)
+    assert np.array_equal(acc_gate, ref["acc_gate"])
+    assert np.array_equal(acc_up, ref["acc_up"])
+    h_g = bits(taps["h"][rows_t])
+    flip = (h_g != ref["h"].reshape(len(rows), -1)).mean()
+    assert flip <= H_FLIP_RATE, flip
+    q_h_want, beta_h_want = O.absmax_int8(O.bf16_to_f32(h_g))
+    q_h = taps["q_h"][rows_t].cpu().numpy()
+    assert np.array_equal(q_h, q_h_want)
+    assert np.array_equal(taps["beta_h"][rows_t].cpu().numpy(), beta_h_want[:, 0])
+    acc_down = taps["acc_down"][rows_t].cpu().numpy()
+    e_of_row = idx_o[tokens].reshape(-1)
+    for e in np.unique(e_of_row):
+        sel = np.flatnonzero(e_of_row == e)
+        assert np.array_equal(acc_down[sel], O.ternary_matmul_int(op.experts(int(e))[4], q_h[sel])), f"expert {e}"
+    tok_t = torch.from_numpy(tokens.astype(np.int64)).cuda()
+    max_abs, rel_l2 = error_metrics(bits(out[tok_t]), ref["out_f32"])
+    _log(f"  {len(tokens)} sampled tokens over experts {sorted(allowed.tolist())}: h flip rate {flip:.2e}, "
+         f"max-abs-err {max_abs:.3e}, rel-L2 {rel_l2:.3e}, max|ref| {np.abs(ref['out_f32']).max():.3f}")
+    assert np.abs(ref["out_f32"]).max() < 8.0
+    assert max_abs <= MAX_ABS_TOL and rel_l2 <= REL_L2_TOL
+    return ref
+
+
+FULL_TAPS = ("topk_idx", "topk_p", "counts", "row_of", "tok_of", "q_x", "beta_x", "acc_gate", "acc_up", "h", "q_h",
+             "beta_h", "acc_down")
+
+
+def test_layer_config2_full():
+    """Qwen2.5-0.5B-shaped layer, T = 2048, outlier channels: every token against the oracle."""
+    cfg = W.C2
+    _log(f"layer {cfg.name}")
+    M = _m()
+    gp, op = GpuProblem(cfg), OracleProblem(cfg)
+    out, taps = _run_layer(gp, M.TAP_FIELDS)
+    ref = op.forward()
+    _check_stagewise(cfg, gp, op, ref, out, taps)
+    assert ref["counts"].max() / ref["counts"].min() < 2.5          # near-uniform load
+
+
+def test_layer_config3_prefill_sampled():
+    cfg = W.C3
+    _log(f"layer {cfg.name}")
+    gp, op = GpuProblem(cfg), OracleProblem(cfg)
+    out, taps = _run_layer(gp, FULL_TAPS)
+    _check_sampled(cfg, 48, 3, out, taps, op)
+
+
+@pytest.mark.parametrize("T,n", [(1, 2), (4, 4), (16, 8), (64, 16)])
+def test_layer_config4_decode(T, n):
+    cfg = W.decode_config(T, n)
+    _log(f"layer {cfg.name}")
+    gp, op = GpuProblem(cfg), OracleProblem(cfg)
+    out, taps = _run_layer(gp, FULL_TAPS)
+    _, _, idx_o, _ = O.router(op.x, op.w_router, op.bias, cfg.top_k)
+    assert len(np.unique(idx_o)) == n                                # the step touches exactly n experts
+    _check_sampled(cfg, 12, 3, out, taps, op)
+
+
+def test_layer_config5_skewed_sampled():
+    cfg = W.C5
+    _log(f"layer {cfg.name}")
+    gp, op = GpuProblem(cfg), OracleProblem(cfg)
+    out, taps = _run_layer(gp, FULL_TAPS)
+    _check_sampled(cfg, 24, 2, out, taps, op)
+    counts = taps["counts"].cpu().numpy()
+    assert 6.0 <= counts.max() / counts.min() <= 14.0                # loads imbalanced about 10x
+
+
+# ------------------------------------------------------------------------ error paths
+def test_bad_arguments_are_rejected_before_any_launch():
+    M = _m()
+    lib = M.load_library()
+    gp = GpuProblem(W.C1.with_tokens(4, name="c1_T4"))
+    L = gp.layer.struct
+    ws = gp.layer.workspace(4)
+    out = torch.empty_like(gp.x)
+    fwd = lambda layer, T, wsb: lib.mote_layer_forward(ctypes.byref(layer), gp.x.data_ptr(), T, out.data_ptr(),
+                                                       ws.data_ptr(), wsb, None, None)
+    assert fwd(L, 4, ws.numel()) == 0
+    assert fwd(L, 4, 16) == 3                                         # workspace too small
+    assert fwd(L, -1, ws.numel()) == 1
+    bad = type(L)()
+    ctypes.memmove(ctypes.byref(bad), ctypes.byref(L), ctypes.sizeof(L))
+    bad.d_model = 200
+    assert fwd(bad, 4, ws.numel()) == 2                               # unsupported shape
+    ctypes.memmove(ctypes.byref(bad), ctypes.byref(L), ctypes.sizeof(L))
+    bad.top_k = 9
+    assert fwd(bad, 4, ws.numel()) == 2
+    ctypes.memmove(ctypes.byref(bad), ctypes.byref(L), ctypes.sizeof(L))
+    bad.wt_up = None
+    assert fwd(bad, 4, ws.numel()) == 1
+    assert lib.mote_layer_workspace_bytes(ctypes.byref(bad), -3) == 0
+    w = torch.zeros(33, 128, device="cuda")
+    p = torch.zeros(1024, dtype=torch.int32, device="cuda")
+    a = torch.zeros(1, device="cuda")
+    assert lib.mote_pack_ternary(w.data_ptr(), 0, 33, 128, p.data_ptr(), a.data_ptr(), None) == 2
+    assert lib.mote_pack_ternary(w.data_ptr(), 7, 32, 128, p.data_ptr(), a.data_ptr(), None) == 1
+    assert lib.mote_pack_ternary(None, 0, 32, 128, p.data_ptr(), a.data_ptr(), None) == 1
+    assert lib.mote_router_topk(gp.x.data_ptr(), gp.w_router.data_ptr(), None, 4, 256, 4, 5, p.data_ptr(),
+                                a.data_ptr(), None, None) == 2
+    assert M.load_library().mote_status_string(2) == b"unsupported shape"
+    torch.cuda.synchronize()
+
+
+def test_stage_timing_reports_every_stage():
+    M = _m()
+    gp = GpuProblem(W.C1)
+    M.mote_stage_timing(True)
+    try:
+        M.mote_layer_forward(gp.layer, gp.x)
+        times = M.mote_stage_times()
+    finally:
+        M.mote_stage_timing(False)
+    assert set(times) == set(M.STAGE_NAMES) and all(v > 0 for v in times.values())
+    src = torch.arange(1 << 16, dtype=torch.int32, device="cuda")
+    dst = torch.zeros_like(src)
+    M.mote_calib_copy(dst, src)
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)
