@@ -107,6 +107,13 @@ def cpu_baseline(cfg, budget_s=20.0):
         t_small = time.perf_counter() - t0
     else:
         n = len(tokens)
+    reps = 1
+    if t_small < 0.5 * budget_s and n == cfg.n_tokens:     # whole workload fits: repeat it to fill the budget
+        reps = int(min(50, max(1, 0.5 * budget_s / t_small)))
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            op.forward(tokens=tokens)
+        t_small = (time.perf_counter() - t0) / reps
     try:
         from threadpoolctl import threadpool_info
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
@@ -114,7 +121,7 @@ def cpu_baseline(cfg, budget_s=20.0):
         cores = os.cpu_count() or 1
     return {"value": n / t_small, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
             "sample": f"{n} of {cfg.n_tokens} tokens (every {max(cfg.n_tokens // n, 1)}th), router on all tokens, "
-                      f"experts already ternarised; {t_small:.1f} s"}
+                      f"experts already ternarised; {reps} pass(es) of {t_small:.2f} s"}
 
 
 def main():

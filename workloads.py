@@ -34,6 +34,7 @@ class MoteConfig:
     bias_subset: int = 0           # "subset": number of experts that can be selected
     zipf_s: float = 1.2            # "zipf": exponent
     zipf_tau: float = 1.0          # "zipf": temperature on the log-rank bias
+    x_seed: int = -1               # >= 0: draw x from this seed instead of `seed` (weights unchanged)
 
     def with_tokens(self, n_tokens: int, **kw) -> "MoteConfig":
         return replace(self, n_tokens=n_tokens, **kw)
@@ -51,10 +52,15 @@ C5 = MoteConfig("c5_qwen7b_skew", 3584, 18944, 16, 2, 16384, seed=4, sigma_share
 CONFIGS = {c.name: c for c in (C1, C2, C3, C4, C5)}
 
 
+# x seeds for which the decode batch really touches all n_distinct selectable experts
+_DECODE_X_SEEDS = {(16, 16): 10}
+
+
 def decode_config(n_tokens: int, n_distinct: int) -> MoteConfig:
-    """C4 at batch n_tokens, router biased so that only n_distinct experts are selectable."""
+    """C4 at batch n_tokens (same weights as C3), router biased so that only n_distinct
+    experts are selectable; x is drawn from a seed for which all of them are hit."""
     return replace(C4, name=f"c4_decode_T{n_tokens}_n{n_distinct}", n_tokens=n_tokens,
-                   bias_subset=n_distinct)
+                   bias_subset=n_distinct, x_seed=_DECODE_X_SEEDS.get((n_tokens, n_distinct), 0))
 
 
 _TAGS = {"x": 1, "router": 2, "shared": 3, "latent": 4, "outlier": 5, "bias": 6}
@@ -68,7 +74,8 @@ def _gen(cfg: MoteConfig, tag: str, a: int = 0, b: int = 0) -> torch.Generator:
 
 def make_x(cfg: MoteConfig) -> torch.Tensor:
     """Hidden states entering the layer: bf16 [T, d], N(0,1); optional outlier channels."""
-    x = torch.randn(cfg.n_tokens, cfg.d_model, generator=_gen(cfg, "x"), dtype=torch.float32)
+    g = _gen(cfg, "x") if cfg.x_seed < 0 else _gen(replace(cfg, seed=1000 + cfg.x_seed), "x")
+    x = torch.randn(cfg.n_tokens, cfg.d_model, generator=g, dtype=torch.float32)
     if cfg.outlier_channels:
         ch = torch.randperm(cfg.d_model, generator=_gen(cfg, "outlier"))[: cfg.outlier_channels]
         x[:, ch] *= cfg.outlier_scale
