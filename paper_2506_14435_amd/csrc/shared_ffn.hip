@@ -6,16 +6,20 @@
 //
 // Both operands are K-contiguous ([rows, K] row-major), so a tile row is 64 bf16 = 128
 // bytes and the LDS geometry (8 XOR-swizzled 16-byte chunks per row) is the same for the
-// activation and the weight tiles.  MFMA operand mapping: lane l supplies row l%32 and the
-// 8 consecutive K elements of half l/32; result register v of lane l is row
-// 8*(v/4) + 4*(l/32) + v%4, column l%32.
+// activation and the weight tiles.  MFMA operand mapping: first operand = weights (lane l:
+// output channel l%32, 8 consecutive K elements of half l/32), second = activations (lane
+// l: token row l%32); result register v of lane l is output channel 8*(v/4) + 4*(l/32) +
+// v%4 of token row l%32.
+#include <stdlib.h>
+
 #include "common.h"
 #include "launch.h"
 
 namespace mote {
 
-template <int MODE_, int BM_W_, int BN_W_, int WAVES_M_, int WAVES_N_>
+template <int MODE_, int BM_W_, int BN_W_, int WAVES_M_, int WAVES_N_, int MIN_BLOCKS_ = 1>
 struct SharedCfg {
+  static constexpr int MIN_BLOCKS = MIN_BLOCKS_;
   static constexpr int MODE = MODE_;
   static constexpr int NMAT = MODE_ == 0 ? 2 : 1;
   static constexpr int BM_W = BM_W_, BN_W = BN_W_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
@@ -31,7 +35,9 @@ struct SharedCfg {
   static constexpr int STAGE_BYTES = A_BYTES + NMAT * B_BYTES;
 };
 
-__device__ __forceinline__ int lds_tile_offset(int row, int chunk) { return row * 128 + ((chunk ^ (row & 7)) << 4); }
+// 128-byte rows of eight 16-byte chunks, chunk XOR-swizzled with row bits 1..3: 16 lanes
+// reading one chunk of 16 consecutive rows cover all 64 LDS banks exactly once.
+__device__ __forceinline__ int lds_tile_offset(int row, int chunk) { return row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4); }
 
 struct SharedGemmArgs {
   const uint16_t* act;   // [M, K] bf16
@@ -43,14 +49,24 @@ struct SharedGemmArgs {
 };
 
 template <typename Cfg>
-__global__ __launch_bounds__(Cfg::THREADS) void shared_gemm_kernel(SharedGemmArgs a, int n_ntiles) {
+__global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void shared_gemm_kernel(SharedGemmArgs a, int n_ntiles) {
   constexpr int NMAT = Cfg::NMAT, BM_W = Cfg::BM_W, BN_W = Cfg::BN_W;
   constexpr int BM = Cfg::BM, BN = Cfg::BN;
   extern __shared__ __attribute__((aligned(16))) unsigned char s_mem[];
 
-  const int nt = blockIdx.x % n_ntiles;
-  const int mt = blockIdx.x / n_ntiles;
+  // Workgroups go to the 8 XCDs round-robin by linear id: XCD x owns the channel tiles
+  // x, x+8, ... (the row tiles x, x+8, ... when there are fewer than 16 channel tiles) and
+  // walks the other index fastest, so its L2 keeps one slice of the weights resident.
   const int M = a.M, N = a.N, K = a.K;
+  const int n_mtiles = (M + BM - 1) / BM;
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const bool split_n = n_ntiles >= 16;
+  const int xcd_ntiles = split_n ? (n_ntiles - xcd + 7) >> 3 : n_ntiles;
+  const int xcd_mtiles = split_n ? n_mtiles : (n_mtiles - xcd + 7) >> 3;
+  if (slot >= xcd_ntiles * xcd_mtiles) return;
+  const int mi = slot / xcd_ntiles, ni = slot - mi * xcd_ntiles;
+  const int mt = split_n ? mi : xcd + 8 * mi;
+  const int nt = split_n ? xcd + 8 * ni : ni;
   const int KT = K >> 6;
   const int m0 = mt * BM, n0 = nt * BN;
 
@@ -116,6 +132,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void shared_gemm_kernel(SharedGemmArg
   for (int kt = 0; kt < KT; ++kt) {
     const bool has_next = kt + 1 < KT;
     if (has_next) MOTE_GLOAD(kt + 1);
+    __builtin_amdgcn_sched_barrier(0);  // keep the prefetch loads ahead of the contraction
     const unsigned char* st = s_mem + (kt & 1) * Cfg::STAGE_BYTES;
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
@@ -131,9 +148,10 @@ __global__ __launch_bounds__(Cfg::THREADS) void shared_gemm_kernel(SharedGemmArg
                                                              lds_tile_offset(b_row_base + f * 32, 2 * s + g));
 #pragma unroll
           for (int i = 0; i < BM_W; ++i)
-            acc[m][i][f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf, acc[m][i][f], 0, 0, 0);
+            acc[m][i][f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf, af[i], acc[m][i][f], 0, 0, 0);
         }
     }
+    __builtin_amdgcn_sched_barrier(0);
     if (has_next) MOTE_LSTORE((kt + 1) & 1);
     __syncthreads();
   }
@@ -141,26 +159,48 @@ __global__ __launch_bounds__(Cfg::THREADS) void shared_gemm_kernel(SharedGemmArg
 #undef MOTE_GLOAD
 #undef MOTE_LSTORE
 
+  // Lane l owns token row r32 of every row fragment and runs of four consecutive output
+  // channels (first MFMA operand = weights).
 #pragma unroll
   for (int i = 0; i < BM_W; ++i) {
+    const int row = m0 + wm * BM_W * 32 + i * 32 + r32;
+    if (row >= M) continue;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int row = m0 + wm * BM_W * 32 + i * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
-      if (row >= M) continue;
+    for (int f = 0; f < BN_W; ++f) {
+      const int nf = n0 + wn * BN_W * 32 + f * 32;
+      if (nf >= N) continue;
 #pragma unroll
-      for (int f = 0; f < BN_W; ++f) {
-        const int n = n0 + wn * BN_W * 32 + f * 32 + r32;
-        if (n >= N) continue;
+      for (int q = 0; q < 4; ++q) {
+        const int64_t o = static_cast<int64_t>(row) * N + nf + 8 * q + 4 * g;
         if constexpr (Cfg::MODE == 0) {
-          const float gv = acc[0][i][f][v], uv = acc[1][i][f][v];
-          const float hv = uv * (gv / (1.0f + expf(-gv)));
-          a.h_out[static_cast<int64_t>(row) * N + n] = f32_to_bf16(hv);
+          float hv[4];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) hv[j] = acc[1][i][f][4 * q + j] * silu_fast(acc[0][i][f][4 * q + j]);
+          uint2 packed;
+          packed.x = cvt_pk_bf16(hv[0], hv[1]);
+          packed.y = cvt_pk_bf16(hv[2], hv[3]);
+          *reinterpret_cast<uint2*>(a.h_out + o) = packed;
         } else {
-          a.y_out[static_cast<int64_t>(row) * N + n] = acc[0][i][f][v];
+          *reinterpret_cast<float4*>(a.y_out + o) = make_float4(acc[0][i][f][4 * q + 0], acc[0][i][f][4 * q + 1],
+                                                                acc[0][i][f][4 * q + 2], acc[0][i][f][4 * q + 3]);
         }
       }
     }
   }
+}
+
+// Largest per-XCD tile count of the XCD-aware mapping (XCD 0 owns the most tiles).
+static int split_tiles(int n_ntiles, int n_mtiles) {
+  return n_ntiles >= 16 ? ((n_ntiles + 7) / 8) * n_mtiles : n_ntiles * ((n_mtiles + 7) / 8);
+}
+
+static int shared_variant() {
+  static int v = -1;
+  if (v < 0) {
+    const char* e = getenv("MOTE_SHARED_VARIANT");
+    v = e ? atoi(e) : 0;
+  }
+  return v;
 }
 
 template <typename Cfg>
@@ -175,7 +215,8 @@ static hipError_t launch_shared_cfg(const SharedGemmArgs& a, hipStream_t stream)
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  shared_gemm_kernel<Cfg><<<static_cast<unsigned>(n_ntiles * n_mtiles), Cfg::THREADS, lds, stream>>>(a, n_ntiles);
+  const int per_xcd = split_tiles(n_ntiles, n_mtiles);
+  shared_gemm_kernel<Cfg><<<static_cast<unsigned>(per_xcd * 8), Cfg::THREADS, lds, stream>>>(a, n_ntiles);
   return hipGetLastError();
 }
 
@@ -184,7 +225,11 @@ hipError_t launch_shared_gate_up(const uint16_t* x, const uint16_t* w_gate, cons
   if (T == 0) return hipSuccess;
   SharedGemmArgs a{x, w_gate, w_up, T, F, d, h_s, nullptr};
   if (T <= 48) return launch_shared_cfg<SharedCfg<0, 1, 1, 1, 4>>(a, stream);
-  return launch_shared_cfg<SharedCfg<0, 2, 2, 2, 2>>(a, stream);
+  switch (shared_variant()) {
+    case 1: return launch_shared_cfg<SharedCfg<0, 2, 1, 2, 2, 2>>(a, stream);   // 128 x (64+64), 2 workgroups / CU
+    case 2: return launch_shared_cfg<SharedCfg<0, 2, 2, 2, 2, 1>>(a, stream);   // 128 x (128+128), 1 workgroup / CU
+    default: return launch_shared_cfg<SharedCfg<0, 2, 2, 4, 2, 1>>(a, stream);  // 256 x (128+128), 8 wavefronts
+  }
 }
 
 hipError_t launch_shared_down(const uint16_t* h_s, const uint16_t* w_down, int T, int d, int F, float* y_s,
@@ -192,7 +237,11 @@ hipError_t launch_shared_down(const uint16_t* h_s, const uint16_t* w_down, int T
   if (T == 0) return hipSuccess;
   SharedGemmArgs a{h_s, w_down, nullptr, T, d, F, nullptr, y_s};
   if (T <= 48) return launch_shared_cfg<SharedCfg<1, 1, 1, 1, 4>>(a, stream);
-  return launch_shared_cfg<SharedCfg<1, 2, 2, 2, 2>>(a, stream);
+  switch (shared_variant()) {
+    case 1: return launch_shared_cfg<SharedCfg<1, 2, 4, 2, 2, 1>>(a, stream);   // 128 x 256
+    case 2: return launch_shared_cfg<SharedCfg<1, 4, 2, 2, 2, 1>>(a, stream);   // 256 x 128
+    default: return launch_shared_cfg<SharedCfg<1, 2, 2, 2, 2, 2>>(a, stream);  // 128 x 128, 2 workgroups / CU
+  }
 }
 
 }  // namespace mote
