@@ -1,0 +1,354 @@
+// Small-batch (decode) GEMMs of the MoTE layer: the weights are streamed from HBM exactly
+// once and every design choice serves bytes in flight, not MFMA rate.
+//
+//   routed_decode_kernel<0>: ternary gate-up (Eq.6) for the <= 32 rows of one expert tile
+//   routed_decode_kernel<1>: ternary down (Eq.5), K split across workgroups, int32 partials
+//   shared_decode_kernel<0/1>: bf16 shared expert (Eq.2) for T <= 64 tokens
+//
+// A workgroup of four wavefronts owns one 32-channel fragment of the output (both matrices
+// in gate-up mode) and splits the contraction length four ways.  A wavefront keeps a ring of
+// PD K steps in registers: the weight loads (one 16-byte load per lane = 1 KiB per packed
+// ternary tile, 64 contiguous bytes per lane for a bf16 row) and the matching activation
+// fragments are issued PD steps ahead of the MFMAs that consume them, nothing is staged in
+// LDS and there is no barrier in the K loop.  The four partial accumulators meet in LDS,
+// where the epilogue of the large-batch kernels is applied.  Cross-workgroup K splits (down
+// projections) are written as separate partial planes that the combine kernel adds in a
+// fixed order, so the result does not depend on scheduling.
+//
+// MFMA operand mapping as in the large-batch kernels: first operand = weights (lane l:
+// output channel l%32, K half l/32), second = activations (lane l: row l%32); result
+// register v of lane l is output channel 8*(v/4) + 4*(l/32) + v%4 of row l%32.
+#include "common.h"
+#include "launch.h"
+
+namespace mote {
+
+constexpr int kDecThreads = 256;
+
+__device__ __forceinline__ v4i unpack_codes_dec(uint32_t w) {
+  v4i b;
+  b.x = static_cast<int>(w & 0x03030303u);
+  b.y = static_cast<int>((w >> 2) & 0x03030303u);
+  b.z = static_cast<int>((w >> 4) & 0x03030303u);
+  b.w = static_cast<int>((w >> 6) & 0x03030303u);
+  return b;
+}
+
+// ------------------------------------------------------------------------- routed experts
+template <int MODE>
+__global__ __launch_bounds__(kDecThreads) void routed_decode_kernel(RoutedGemmArgs a, int n_frags, int kc_count,
+                                                                    int steps_per_wave) {
+  constexpr int NMAT = MODE == 0 ? 2 : 1;
+  constexpr int PD = 4;
+  __shared__ int s_part[4 * NMAT * 16 * 64];
+
+  const int K = a.K, N = a.N, KT = K >> 7;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int r32 = lane & 31, g = lane >> 5;
+  const int64_t expert_bytes = static_cast<int64_t>(N) * K / 4;
+  const int n_tiles = a.plan.n_tiles[0];
+  const int units = n_tiles * n_frags * kc_count;
+
+  for (int u = blockIdx.x; u < units; u += gridDim.x) {
+    const int kc = u % kc_count;
+    const int nf = (u / kc_count) % n_frags;
+    const int mt = u / (kc_count * n_frags);
+    const int expert = a.plan.tile_expert[mt];
+    const int row0 = a.plan.tile_row0[mt];
+    const int rows = a.plan.tile_rows[mt];
+    const int step0 = (kc * 4 + wave) * steps_per_wave;
+    const int nsteps = max(0, min(steps_per_wave, KT - step0));
+
+    // weight ring first: it does not depend on the row gather
+    const unsigned char* wg = reinterpret_cast<const unsigned char*>(a.w_gate) + expert * expert_bytes +
+                              (static_cast<int64_t>(nf) * KT + step0) * 1024 + lane * 16;
+    const unsigned char* wu = nullptr;
+    if constexpr (NMAT == 2)
+      wu = reinterpret_cast<const unsigned char*>(a.w_up) + expert * expert_bytes +
+           (static_cast<int64_t>(nf) * KT + step0) * 1024 + lane * 16;
+    u4 wr[PD][NMAT];
+    v4i ar[PD][4];
+#pragma unroll
+    for (int j = 0; j < PD; ++j) {
+      if (j < nsteps) {
+        wr[j][0] = *reinterpret_cast<const u4*>(wg + j * 1024);
+        if constexpr (NMAT == 2) wr[j][1] = *reinterpret_cast<const u4*>(wu + j * 1024);
+      }
+    }
+    // activation rows: lane (r32, g) reads 16 bytes per 32-channel sub-step
+    const int slot = row0 + min(r32, rows - 1);
+    const int src = a.gather ? a.gather[slot] : slot;
+    const unsigned char* ap = reinterpret_cast<const unsigned char*>(a.q) + static_cast<int64_t>(src) * K +
+                              static_cast<int64_t>(step0) * 128 + g * 16;
+    // epilogue metadata of the row this thread finishes (row tid % 32)
+    const float m_beta = a.beta[src];
+    const int m_rs = a.rowsum[src];
+#pragma unroll
+    for (int j = 0; j < PD; ++j) {
+      if (j < nsteps) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) ar[j][s] = *reinterpret_cast<const v4i*>(ap + j * 128 + s * 32);
+      }
+    }
+
+    v16i acc[NMAT];
+#pragma unroll
+    for (int m = 0; m < NMAT; ++m)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[m][v] = 0;
+
+    for (int base = 0; base < nsteps; base += PD) {
+#pragma unroll
+      for (int j = 0; j < PD; ++j) {
+        if (base + j < nsteps) {
+#pragma unroll
+          for (int s = 0; s < 4; ++s) {
+#pragma unroll
+            for (int m = 0; m < NMAT; ++m)
+              acc[m] = __builtin_amdgcn_mfma_i32_32x32x32_i8(unpack_codes_dec(wr[j][m][s]), ar[j][s], acc[m], 0, 0, 0);
+          }
+          const int nx = base + j + PD;
+          if (nx < nsteps) {
+            wr[j][0] = *reinterpret_cast<const u4*>(wg + static_cast<int64_t>(nx) * 1024);
+            if constexpr (NMAT == 2) wr[j][1] = *reinterpret_cast<const u4*>(wu + static_cast<int64_t>(nx) * 1024);
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+              ar[j][s] = *reinterpret_cast<const v4i*>(ap + static_cast<int64_t>(nx) * 128 + s * 32);
+          }
+        }
+      }
+    }
+
+    // partial accumulators of the four K slices meet in LDS
+#pragma unroll
+    for (int m = 0; m < NMAT; ++m)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) s_part[((wave * NMAT + m) * 16 + v) * 64 + lane] = acc[m][v];
+    __syncthreads();
+    // thread t finishes register quad q = t / 64 of lane t % 64: row (t % 32), four channels
+    {
+      const int q = tid >> 6;
+      int sum[NMAT][4];
+#pragma unroll
+      for (int m = 0; m < NMAT; ++m)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          int t = 0;
+#pragma unroll
+          for (int w = 0; w < 4; ++w) t += s_part[((w * NMAT + m) * 16 + 4 * q + j) * 64 + lane];
+          sum[m][j] = t;
+        }
+      if (r32 < rows) {
+        const int n = nf * 32 + 8 * q + 4 * g;
+        const int64_t o = static_cast<int64_t>(row0 + r32) * N + n;
+        if constexpr (MODE == 0) {
+          const float sx = m_beta / 127.0f;
+          const float sg = sx * a.alpha[expert * 3 + 0], su = sx * a.alpha[expert * 3 + 1];
+          float hv[4];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            sum[0][j] -= m_rs;
+            sum[1][j] -= m_rs;
+            hv[j] = (static_cast<float>(sum[1][j]) * su) * silu_fast(static_cast<float>(sum[0][j]) * sg);
+          }
+          uint2 packed;
+          packed.x = cvt_pk_bf16(hv[0], hv[1]);
+          packed.y = cvt_pk_bf16(hv[2], hv[3]);
+          *reinterpret_cast<uint2*>(a.h + o) = packed;
+          if (a.tap_gate != nullptr) {
+            *reinterpret_cast<int4*>(a.tap_gate + o) = make_int4(sum[0][0], sum[0][1], sum[0][2], sum[0][3]);
+            *reinterpret_cast<int4*>(a.tap_up + o) = make_int4(sum[1][0], sum[1][1], sum[1][2], sum[1][3]);
+          }
+        } else {
+          const int corr = kc == 0 ? m_rs : 0;   // the zero-point correction enters exactly one partial plane
+          *reinterpret_cast<int4*>(a.acc_out + static_cast<int64_t>(kc) * a.partial_stride + o) =
+              make_int4(sum[0][0] - corr, sum[0][1] - corr, sum[0][2] - corr, sum[0][3] - corr);
+        }
+      }
+    }
+    __syncthreads();
+  }
+}
+
+static int device_cus() {
+  static int n = 0;
+  if (n == 0) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+      n = 256;
+  }
+  return n;
+}
+
+int routed_decode_down_planes(int K) { return ((K >> 7) + 15) / 16; }
+
+hipError_t launch_routed_decode_gate_up(const RoutedGemmArgs& a, hipStream_t stream) {
+  if (a.max_tiles == 0) return hipSuccess;
+  const int n_frags = a.N / 32, KT = a.K >> 7;
+  const int64_t max_units = static_cast<int64_t>(a.max_tiles) * n_frags;
+  int64_t blocks = static_cast<int64_t>(device_cus()) * 4;
+  if (blocks > max_units) blocks = max_units;
+  routed_decode_kernel<0><<<static_cast<unsigned>(blocks), kDecThreads, 0, stream>>>(a, n_frags, 1, (KT + 3) / 4);
+  return hipGetLastError();
+}
+
+hipError_t launch_routed_decode_down(const RoutedGemmArgs& a, hipStream_t stream) {
+  if (a.max_tiles == 0) return hipSuccess;
+  const int n_frags = a.N / 32;
+  const int kc = routed_decode_down_planes(a.K);
+  const int64_t max_units = static_cast<int64_t>(a.max_tiles) * n_frags * kc;
+  int64_t blocks = static_cast<int64_t>(device_cus()) * 4;
+  if (blocks > max_units) blocks = max_units;
+  routed_decode_kernel<1><<<static_cast<unsigned>(blocks), kDecThreads, 0, stream>>>(a, n_frags, kc, 4);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------- shared expert
+struct SharedDecodeArgs {
+  const uint16_t* act;   // [M, K] bf16
+  const uint16_t* w0;    // [N, K] bf16 (gate / down)
+  const uint16_t* w1;    // [N, K] bf16 (up)
+  int M, N, K;
+  uint16_t* h_out;       // gate-up: bf16 [M, N]
+  float* y_out;          // down: fp32 partial planes [kc][M, N]
+  int64_t plane_stride;
+};
+
+// K steps are 64 bf16 elements; lane (n, g) reads the 64 contiguous bytes [64 g, 64 g + 64) of
+// its weight row in a step and uses them as four MFMA operands; the activation lane reads the
+// same byte range of its token row, so both operands agree on the channel order.
+template <int MODE, int MFR, int PD>
+__global__ __launch_bounds__(kDecThreads) void shared_decode_kernel(SharedDecodeArgs a, int kc_count,
+                                                                    int steps_per_wave) {
+  constexpr int NMAT = MODE == 0 ? 2 : 1;
+  __shared__ float s_part[4 * NMAT * MFR * 16 * 64];
+  const int M = a.M, N = a.N, K = a.K, KT = K >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int r32 = lane & 31, g = lane >> 5;
+  const int kc = blockIdx.x % kc_count;
+  const int nf = blockIdx.x / kc_count;
+  const int step0 = (kc * 4 + wave) * steps_per_wave;
+  const int nsteps = max(0, min(steps_per_wave, KT - step0));
+
+  const unsigned char* wp[NMAT];
+  wp[0] = reinterpret_cast<const unsigned char*>(a.w0) + (static_cast<int64_t>(nf * 32 + r32) * K + step0 * 64) * 2 + g * 64;
+  if constexpr (NMAT == 2)
+    wp[1] = reinterpret_cast<const unsigned char*>(a.w1) + (static_cast<int64_t>(nf * 32 + r32) * K + step0 * 64) * 2 + g * 64;
+  const unsigned char* ap[MFR];
+#pragma unroll
+  for (int i = 0; i < MFR; ++i)
+    ap[i] = reinterpret_cast<const unsigned char*>(a.act) +
+            (static_cast<int64_t>(min(i * 32 + r32, M - 1)) * K + step0 * 64) * 2 + g * 64;
+
+  bf16x8 wr[PD][NMAT][4], ar[PD][MFR][4];
+#pragma unroll
+  for (int j = 0; j < PD; ++j) {
+    if (j < nsteps) {
+#pragma unroll
+      for (int m = 0; m < NMAT; ++m)
+#pragma unroll
+        for (int s = 0; s < 4; ++s) wr[j][m][s] = *reinterpret_cast<const bf16x8*>(wp[m] + j * 128 + s * 16);
+#pragma unroll
+      for (int i = 0; i < MFR; ++i)
+#pragma unroll
+        for (int s = 0; s < 4; ++s) ar[j][i][s] = *reinterpret_cast<const bf16x8*>(ap[i] + j * 128 + s * 16);
+    }
+  }
+  v16f acc[NMAT][MFR];
+#pragma unroll
+  for (int m = 0; m < NMAT; ++m)
+#pragma unroll
+    for (int i = 0; i < MFR; ++i)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[m][i][v] = 0.0f;
+
+  for (int base = 0; base < nsteps; base += PD) {
+#pragma unroll
+    for (int j = 0; j < PD; ++j) {
+      if (base + j < nsteps) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+          for (int m = 0; m < NMAT; ++m)
+#pragma unroll
+            for (int i = 0; i < MFR; ++i)
+              acc[m][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[j][m][s], ar[j][i][s], acc[m][i], 0, 0, 0);
+        const int nx = base + j + PD;
+        if (nx < nsteps) {
+#pragma unroll
+          for (int m = 0; m < NMAT; ++m)
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+              wr[j][m][s] = *reinterpret_cast<const bf16x8*>(wp[m] + static_cast<int64_t>(nx) * 128 + s * 16);
+#pragma unroll
+          for (int i = 0; i < MFR; ++i)
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+              ar[j][i][s] = *reinterpret_cast<const bf16x8*>(ap[i] + static_cast<int64_t>(nx) * 128 + s * 16);
+        }
+      }
+    }
+  }
+
+#pragma unroll
+  for (int m = 0; m < NMAT; ++m)
+#pragma unroll
+    for (int i = 0; i < MFR; ++i)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) s_part[(((wave * NMAT + m) * MFR + i) * 16 + v) * 64 + lane] = acc[m][i][v];
+  __syncthreads();
+  const int q = tid >> 6;
+#pragma unroll
+  for (int i = 0; i < MFR; ++i) {
+    float sum[NMAT][4];
+#pragma unroll
+    for (int m = 0; m < NMAT; ++m)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        float t = 0.0f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) t += s_part[(((w * NMAT + m) * MFR + i) * 16 + 4 * q + j) * 64 + lane];
+        sum[m][j] = t;
+      }
+    const int row = i * 32 + r32;
+    if (row < M) {
+      const int64_t o = static_cast<int64_t>(row) * N + nf * 32 + 8 * q + 4 * g;
+      if constexpr (MODE == 0) {
+        uint2 packed;
+        packed.x = cvt_pk_bf16(sum[1][0] * silu_fast(sum[0][0]), sum[1][1] * silu_fast(sum[0][1]));
+        packed.y = cvt_pk_bf16(sum[1][2] * silu_fast(sum[0][2]), sum[1][3] * silu_fast(sum[0][3]));
+        *reinterpret_cast<uint2*>(a.h_out + o) = packed;
+      } else {
+        *reinterpret_cast<float4*>(a.y_out + static_cast<int64_t>(kc) * a.plane_stride + o) =
+            make_float4(sum[0][0], sum[0][1], sum[0][2], sum[0][3]);
+      }
+    }
+  }
+}
+
+int shared_decode_down_planes(int K) { return ((K >> 6) + 31) / 32; }
+
+hipError_t launch_shared_decode_gate_up(const uint16_t* x, const uint16_t* w_gate, const uint16_t* w_up, int T, int d,
+                                        int F, uint16_t* h_s, hipStream_t stream) {
+  SharedDecodeArgs a{x, w_gate, w_up, T, F, d, h_s, nullptr, 0};
+  const int n_frags = F / 32, KT = d >> 6;
+  const int spw = (KT + 3) / 4;
+  if (T <= 32) shared_decode_kernel<0, 1, 2><<<n_frags, kDecThreads, 0, stream>>>(a, 1, spw);
+  else shared_decode_kernel<0, 2, 2><<<n_frags, kDecThreads, 0, stream>>>(a, 1, spw);
+  return hipGetLastError();
+}
+
+hipError_t launch_shared_decode_down(const uint16_t* h_s, const uint16_t* w_down, int T, int d, int F, float* y_s,
+                                     hipStream_t stream) {
+  SharedDecodeArgs a{h_s, w_down, nullptr, T, d, F, nullptr, y_s, static_cast<int64_t>(T) * d};
+  const int n_frags = d / 32;
+  const int kc = shared_decode_down_planes(F);
+  if (T <= 32) shared_decode_kernel<1, 1, 4><<<n_frags * kc, kDecThreads, 0, stream>>>(a, kc, 8);
+  else shared_decode_kernel<1, 2, 2><<<n_frags * kc, kDecThreads, 0, stream>>>(a, kc, 8);
+  return hipGetLastError();
+}
+
+}  // namespace mote

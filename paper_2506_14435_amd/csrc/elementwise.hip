@@ -77,60 +77,67 @@ hipError_t launch_quant_rows(const uint16_t* h, int rows, int F, int8_t* q, floa
 // Combine (Eq.2 + Eq.4): one thread per (token, 8 channels).
 //   y_e[c] = float(D[row, c]) * ((beta_h[row] / 127) * alpha_down[e])      (ternary linear, Section 3.1)
 //   out[t, c] = y_s[t, c] + sum_j p[t, j] * y_{e_j}[c]
+// D and y_s may arrive as partial planes of a K split; they are added in plane order.
 template <int KMAX>
-__global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ y_s, const int32_t* __restrict__ acc_down,
-                                                      const float* __restrict__ beta_h, const float* __restrict__ alpha,
-                                                      const int32_t* __restrict__ topk_idx,
-                                                      const float* __restrict__ topk_p,
-                                                      const int32_t* __restrict__ row_of, int T, int d, int k,
-                                                      uint16_t* __restrict__ out, float* __restrict__ out_f32) {
+__global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
+  const int d = a.d, k = a.k;
   const int chunks = d >> 3;
   const int64_t gid = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
-  if (gid >= static_cast<int64_t>(T) * chunks) return;
+  if (gid >= static_cast<int64_t>(a.T) * chunks) return;
   const int t = static_cast<int>(gid / chunks);
   const int c0 = static_cast<int>(gid - static_cast<int64_t>(t) * chunks) << 3;
-  const float4 s0 = *reinterpret_cast<const float4*>(y_s + static_cast<int64_t>(t) * d + c0);
-  const float4 s1 = *reinterpret_cast<const float4*>(y_s + static_cast<int64_t>(t) * d + c0 + 4);
-  float o[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+  const int64_t yo = static_cast<int64_t>(t) * d + c0;
+  float o[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  for (int pl = 0; pl < a.y_planes; ++pl) {
+    const float4 s0 = *reinterpret_cast<const float4*>(a.y_s + pl * a.y_stride + yo);
+    const float4 s1 = *reinterpret_cast<const float4*>(a.y_s + pl * a.y_stride + yo + 4);
+    o[0] += s0.x; o[1] += s0.y; o[2] += s0.z; o[3] += s0.w;
+    o[4] += s1.x; o[5] += s1.y; o[6] += s1.z; o[7] += s1.w;
+  }
+  if (a.tap_y_s) {
+    *reinterpret_cast<float4*>(a.tap_y_s + yo) = make_float4(o[0], o[1], o[2], o[3]);
+    *reinterpret_cast<float4*>(a.tap_y_s + yo + 4) = make_float4(o[4], o[5], o[6], o[7]);
+  }
 #pragma unroll
   for (int j = 0; j < KMAX; ++j) {
     if (j < k) {
-      const int row = row_of[t * k + j];
-      const int e = topk_idx[t * k + j];
-      const float p = topk_p[t * k + j];
-      const float sc = (beta_h[row] / 127.0f) * alpha[e * 3 + 2];
-      const int4 d0 = *reinterpret_cast<const int4*>(acc_down + static_cast<int64_t>(row) * d + c0);
-      const int4 d1 = *reinterpret_cast<const int4*>(acc_down + static_cast<int64_t>(row) * d + c0 + 4);
-      o[0] = fmaf(p, static_cast<float>(d0.x) * sc, o[0]);
-      o[1] = fmaf(p, static_cast<float>(d0.y) * sc, o[1]);
-      o[2] = fmaf(p, static_cast<float>(d0.z) * sc, o[2]);
-      o[3] = fmaf(p, static_cast<float>(d0.w) * sc, o[3]);
-      o[4] = fmaf(p, static_cast<float>(d1.x) * sc, o[4]);
-      o[5] = fmaf(p, static_cast<float>(d1.y) * sc, o[5]);
-      o[6] = fmaf(p, static_cast<float>(d1.z) * sc, o[6]);
-      o[7] = fmaf(p, static_cast<float>(d1.w) * sc, o[7]);
+      const int row = a.row_of[t * k + j];
+      const int e = a.topk_idx[t * k + j];
+      const float p = a.topk_p[t * k + j];
+      const float sc = (a.beta_h[row] / 127.0f) * a.alpha[e * 3 + 2];
+      const int64_t ro = static_cast<int64_t>(row) * d + c0;
+      int dsum[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+      for (int pl = 0; pl < a.d_planes; ++pl) {
+        const int4 d0 = *reinterpret_cast<const int4*>(a.acc_down + pl * a.d_stride + ro);
+        const int4 d1 = *reinterpret_cast<const int4*>(a.acc_down + pl * a.d_stride + ro + 4);
+        dsum[0] += d0.x; dsum[1] += d0.y; dsum[2] += d0.z; dsum[3] += d0.w;
+        dsum[4] += d1.x; dsum[5] += d1.y; dsum[6] += d1.z; dsum[7] += d1.w;
+      }
+      if (a.tap_acc_down) {
+        *reinterpret_cast<int4*>(a.tap_acc_down + ro) = make_int4(dsum[0], dsum[1], dsum[2], dsum[3]);
+        *reinterpret_cast<int4*>(a.tap_acc_down + ro + 4) = make_int4(dsum[4], dsum[5], dsum[6], dsum[7]);
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) o[i] = fmaf(p, static_cast<float>(dsum[i]) * sc, o[i]);
     }
   }
   uint4 ob;
-  ob.x = pack_bf16x2(o[0], o[1]);
-  ob.y = pack_bf16x2(o[2], o[3]);
-  ob.z = pack_bf16x2(o[4], o[5]);
-  ob.w = pack_bf16x2(o[6], o[7]);
-  *reinterpret_cast<uint4*>(out + static_cast<int64_t>(t) * d + c0) = ob;
-  if (out_f32) {
-    *reinterpret_cast<float4*>(out_f32 + static_cast<int64_t>(t) * d + c0) = make_float4(o[0], o[1], o[2], o[3]);
-    *reinterpret_cast<float4*>(out_f32 + static_cast<int64_t>(t) * d + c0 + 4) = make_float4(o[4], o[5], o[6], o[7]);
+  ob.x = cvt_pk_bf16(o[0], o[1]);
+  ob.y = cvt_pk_bf16(o[2], o[3]);
+  ob.z = cvt_pk_bf16(o[4], o[5]);
+  ob.w = cvt_pk_bf16(o[6], o[7]);
+  *reinterpret_cast<uint4*>(a.out + yo) = ob;
+  if (a.out_f32) {
+    *reinterpret_cast<float4*>(a.out_f32 + yo) = make_float4(o[0], o[1], o[2], o[3]);
+    *reinterpret_cast<float4*>(a.out_f32 + yo + 4) = make_float4(o[4], o[5], o[6], o[7]);
   }
 }
 
-hipError_t launch_combine(const float* y_s, const int32_t* acc_down, const float* beta_h, const float* alpha,
-                          const int32_t* topk_idx, const float* topk_p, const int32_t* row_of, int T, int d,
-                          int k, uint16_t* out, float* out_f32, hipStream_t stream) {
-  if (T == 0) return hipSuccess;
-  const int64_t n = static_cast<int64_t>(T) * (d >> 3);
+hipError_t launch_combine(const CombineArgs& a, hipStream_t stream) {
+  if (a.T == 0) return hipSuccess;
+  const int64_t n = static_cast<int64_t>(a.T) * (a.d >> 3);
   const unsigned blocks = static_cast<unsigned>((n + 255) / 256);
-  combine_kernel<8><<<blocks, 256, 0, stream>>>(y_s, acc_down, beta_h, alpha, topk_idx, topk_p, row_of, T, d, k, out,
-                                                out_f32);
+  combine_kernel<8><<<blocks, 256, 0, stream>>>(a);
   return hipGetLastError();
 }
 

@@ -45,13 +45,26 @@ struct RoutedGemmArgs {
   int tile_m;               // rows per plan tile
   int K, N;                 // contraction length, output width (per matrix)
   uint16_t* h;              // gate-up: bf16 [R, N]
-  int32_t* acc_out;         // down: int32 [R, N]
+  int32_t* acc_out;         // down: int32 [R, N] (decode: partial planes [planes][R, N])
+  int64_t partial_stride;   // elements between partial planes (decode down)
   int32_t* tap_gate;        // optional int32 [R, N]
   int32_t* tap_up;
 };
 hipError_t launch_routed_gate_up(const RoutedGemmArgs& a, hipStream_t stream);
 hipError_t launch_routed_down(const RoutedGemmArgs& a, hipStream_t stream);
-int routed_tile_m(int T, int k, int E);  // plan tile size chosen for a workload
+int routed_tile_m(int T, int k, int E);  // plan tile size chosen for a workload (32 = decode kernels)
+
+// Decode (small batch) variants: weights streamed once, K split across wavefronts and, for the
+// down projections, across workgroups into partial planes that the combine kernel adds.
+hipError_t launch_routed_decode_gate_up(const RoutedGemmArgs& a, hipStream_t stream);
+hipError_t launch_routed_decode_down(const RoutedGemmArgs& a, hipStream_t stream);
+int routed_decode_down_planes(int K);
+constexpr int kSharedDecodeMaxTokens = 64;
+hipError_t launch_shared_decode_gate_up(const uint16_t* x, const uint16_t* w_gate, const uint16_t* w_up, int T, int d,
+                                        int F, uint16_t* h_s, hipStream_t stream);
+hipError_t launch_shared_decode_down(const uint16_t* h_s, const uint16_t* w_down, int T, int d, int F, float* y_s,
+                                     hipStream_t stream);
+int shared_decode_down_planes(int K);
 
 // Q_a(h): per dispatch row absmax int8 of the bf16 hidden activation.
 hipError_t launch_quant_rows(const uint16_t* h, int rows, int F, int8_t* q, float* beta, int32_t* rowsum,
@@ -64,9 +77,19 @@ hipError_t launch_shared_down(const uint16_t* h_s, const uint16_t* w_down, int T
                               hipStream_t stream);
 
 // out = bf16( y_s + sum_j p[t,j] * (acc_down[row_of[t,j]] * (beta_h/127 * alpha_down)) ).
-hipError_t launch_combine(const float* y_s, const int32_t* acc_down, const float* beta_h, const float* alpha,
-                          const int32_t* topk_idx, const float* topk_p, const int32_t* row_of, int T, int d,
-                          int k, uint16_t* out, float* out_f32, hipStream_t stream);
+// y_s and acc_down may come as several partial planes (decode K splits), added in plane order.
+struct CombineArgs {
+  const float* y_s; int y_planes; int64_t y_stride;
+  const int32_t* acc_down; int d_planes; int64_t d_stride;
+  const float* beta_h; const float* alpha;
+  const int32_t* topk_idx; const float* topk_p; const int32_t* row_of;
+  int T, d, k;
+  uint16_t* out;
+  float* out_f32;         // optional taps
+  float* tap_y_s;         // [T, d] summed shared output
+  int32_t* tap_acc_down;  // [R, d] summed down accumulators
+};
+hipError_t launch_combine(const CombineArgs& a, hipStream_t stream);
 
 hipError_t launch_copy(void* dst, const void* src, size_t n_bytes, hipStream_t stream);
 

@@ -25,6 +25,9 @@ struct Workspace {
   uint16_t* h_s; float* y_s;
   size_t bytes;
   int max_tiles;
+  int tile_m;        // 32: decode kernels, else large-batch kernels
+  int d_planes;      // partial planes of the routed down accumulators
+  int y_planes;      // partial planes of the shared expert output
 };
 
 bool layer_shape_ok(const mote_layer* l) {
@@ -47,6 +50,9 @@ Workspace carve(const mote_layer* l, int T, char* base) {
   const size_t R = static_cast<size_t>(T) * l->top_k;
   const size_t d = l->d_model, Fr = l->d_ff_routed, Fs = l->d_ff_shared;
   w.max_tiles = static_cast<int>(R / 32 + l->n_experts);
+  w.tile_m = routed_tile_m(T, l->top_k, l->n_experts);
+  w.d_planes = w.tile_m == 32 ? routed_decode_down_planes(l->d_ff_routed) : 1;
+  w.y_planes = T <= kSharedDecodeMaxTokens ? shared_decode_down_planes(l->d_ff_shared) : 1;
   w.topk_idx = reinterpret_cast<int32_t*>(take(R * 4));
   w.topk_p = reinterpret_cast<float*>(take(R * 4));
   w.counts = reinterpret_cast<int32_t*>(take(64 * 4));
@@ -64,9 +70,9 @@ Workspace carve(const mote_layer* l, int T, char* base) {
   w.q_h = reinterpret_cast<int8_t*>(take(R * Fr));
   w.beta_h = reinterpret_cast<float*>(take(R * 4));
   w.rs_h = reinterpret_cast<int32_t*>(take(R * 4));
-  w.acc_down = reinterpret_cast<int32_t*>(take(R * d * 4));
+  w.acc_down = reinterpret_cast<int32_t*>(take(R * d * 4 * static_cast<size_t>(w.d_planes)));
   w.h_s = reinterpret_cast<uint16_t*>(take(static_cast<size_t>(T) * Fs * 2));
-  w.y_s = reinterpret_cast<float*>(take(static_cast<size_t>(T) * d * 4));
+  w.y_s = reinterpret_cast<float*>(take(static_cast<size_t>(T) * d * 4 * static_cast<size_t>(w.y_planes)));
   w.bytes = off;
   return w;
 }
@@ -143,7 +149,16 @@ mote_status mote_router_topk(const void* x, const void* w_router, const float* r
 size_t mote_layer_workspace_bytes(const mote_layer* layer, int T_max) {
   if (!layer || T_max < 0 || !layer_shape_ok(layer)) return 0;
   if (static_cast<int64_t>(T_max) * layer->top_k >= (1 << 24)) return 0;
-  return carve(layer, T_max, nullptr).bytes;
+  // The kernel family (decode / large batch) and with it the number of partial planes depends
+  // on T; a workspace sized for T_max must serve every T <= T_max, so take the largest layout.
+  size_t need = carve(layer, T_max, nullptr).bytes;
+  const int t_shared = T_max < kSharedDecodeMaxTokens ? T_max : kSharedDecodeMaxTokens;
+  const int t_routed_cap = 48 * layer->n_experts / layer->top_k;
+  const int t_routed = T_max < t_routed_cap ? T_max : t_routed_cap;
+  const size_t a = carve(layer, t_shared, nullptr).bytes, b = carve(layer, t_routed, nullptr).bytes;
+  if (a > need) need = a;
+  if (b > need) need = b;
+  return need;
 }
 
 mote_status mote_layer_forward(const mote_layer* layer, const void* x, int T, void* out, void* workspace,
@@ -173,7 +188,9 @@ mote_status mote_layer_forward(const mote_layer* layer, const void* x, int T, vo
   MOTE_HIP(launch_router_quant(xb, static_cast<const uint16_t*>(layer->w_router), layer->router_bias, T, d, E, k,
                                w.topk_idx, w.topk_p, w.q_x, w.beta_x, w.rs_x, stream));
   MOTE_HIP(mark(1));
-  const int tile_m = routed_tile_m(T, k, E);
+  const int tile_m = w.tile_m;
+  const bool decode_routed = tile_m == 32;
+  const bool decode_shared = T <= kSharedDecodeMaxTokens;
   DispatchPlan plan{w.counts, w.offsets, w.row_of, w.tok_of, w.tile_expert, w.tile_row0, w.tile_rows, w.n_tiles};
   MOTE_HIP(launch_dispatch_plan(w.topk_idx, T, k, E, tile_m, plan, stream));
   MOTE_HIP(mark(2));
@@ -185,7 +202,8 @@ mote_status mote_layer_forward(const mote_layer* layer, const void* x, int T, vo
   ga.K = d; ga.N = Fr; ga.h = w.h; ga.acc_out = nullptr;
   ga.tap_gate = taps ? taps->acc_gate : nullptr;
   ga.tap_up = taps ? taps->acc_up : nullptr;
-  MOTE_HIP(launch_routed_gate_up(ga, stream));
+  ga.partial_stride = 0;
+  MOTE_HIP(decode_routed ? launch_routed_decode_gate_up(ga, stream) : launch_routed_gate_up(ga, stream));
   MOTE_HIP(mark(3));
   MOTE_HIP(launch_quant_rows(w.h, R, Fr, w.q_h, w.beta_h, w.rs_h, stream));
   MOTE_HIP(mark(4));
@@ -194,16 +212,30 @@ mote_status mote_layer_forward(const mote_layer* layer, const void* x, int T, vo
   gd.q = w.q_h; gd.gather = nullptr; gd.beta = w.beta_h; gd.rowsum = w.rs_h;
   gd.w_gate = layer->wt_down; gd.w_up = nullptr;
   gd.K = Fr; gd.N = d; gd.h = nullptr; gd.acc_out = w.acc_down; gd.tap_gate = nullptr; gd.tap_up = nullptr;
-  MOTE_HIP(launch_routed_down(gd, stream));
+  gd.partial_stride = static_cast<int64_t>(R) * d;
+  MOTE_HIP(decode_routed ? launch_routed_decode_down(gd, stream) : launch_routed_down(gd, stream));
   MOTE_HIP(mark(5));
 
-  MOTE_HIP(launch_shared_gate_up(xb, static_cast<const uint16_t*>(layer->ws_gate),
-                                 static_cast<const uint16_t*>(layer->ws_up), T, d, Fs, w.h_s, stream));
+  const uint16_t* sg = static_cast<const uint16_t*>(layer->ws_gate);
+  const uint16_t* su = static_cast<const uint16_t*>(layer->ws_up);
+  const uint16_t* sd = static_cast<const uint16_t*>(layer->ws_down);
+  MOTE_HIP(decode_shared ? launch_shared_decode_gate_up(xb, sg, su, T, d, Fs, w.h_s, stream)
+                         : launch_shared_gate_up(xb, sg, su, T, d, Fs, w.h_s, stream));
   MOTE_HIP(mark(6));
-  MOTE_HIP(launch_shared_down(w.h_s, static_cast<const uint16_t*>(layer->ws_down), T, d, Fs, w.y_s, stream));
+  MOTE_HIP(decode_shared ? launch_shared_decode_down(w.h_s, sd, T, d, Fs, w.y_s, stream)
+                         : launch_shared_down(w.h_s, sd, T, d, Fs, w.y_s, stream));
   MOTE_HIP(mark(7));
-  MOTE_HIP(launch_combine(w.y_s, w.acc_down, w.beta_h, layer->alpha, w.topk_idx, w.topk_p, w.row_of, T, d, k,
-                          static_cast<uint16_t*>(out), taps ? taps->out_f32 : nullptr, stream));
+  CombineArgs ca{};
+  ca.y_s = w.y_s; ca.y_planes = w.y_planes; ca.y_stride = static_cast<int64_t>(T) * d;
+  ca.acc_down = w.acc_down; ca.d_planes = w.d_planes; ca.d_stride = static_cast<int64_t>(R) * d;
+  ca.beta_h = w.beta_h; ca.alpha = layer->alpha;
+  ca.topk_idx = w.topk_idx; ca.topk_p = w.topk_p; ca.row_of = w.row_of;
+  ca.T = T; ca.d = d; ca.k = k;
+  ca.out = static_cast<uint16_t*>(out);
+  ca.out_f32 = taps ? taps->out_f32 : nullptr;
+  ca.tap_y_s = taps ? taps->y_s : nullptr;
+  ca.tap_acc_down = taps ? taps->acc_down : nullptr;
+  MOTE_HIP(launch_combine(ca, stream));
   MOTE_HIP(mark(8));
   if (timing) g_timed_run = true;
 
@@ -223,9 +255,7 @@ mote_status mote_layer_forward(const mote_layer* layer, const void* x, int T, vo
     MOTE_HIP(tap(taps->h, w.h, Rz * Fr * 2));
     MOTE_HIP(tap(taps->q_h, w.q_h, Rz * Fr));
     MOTE_HIP(tap(taps->beta_h, w.beta_h, Rz * 4));
-    MOTE_HIP(tap(taps->acc_down, w.acc_down, Rz * d * 4));
     MOTE_HIP(tap(taps->h_s, w.h_s, Tz * Fs * 2));
-    MOTE_HIP(tap(taps->y_s, w.y_s, Tz * d * 4));
   }
   return MOTE_OK;
 }

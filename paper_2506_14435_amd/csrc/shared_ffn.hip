@@ -224,7 +224,6 @@ hipError_t launch_shared_gate_up(const uint16_t* x, const uint16_t* w_gate, cons
                                  int F, uint16_t* h_s, hipStream_t stream) {
   if (T == 0) return hipSuccess;
   SharedGemmArgs a{x, w_gate, w_up, T, F, d, h_s, nullptr};
-  if (T <= 48) return launch_shared_cfg<SharedCfg<0, 1, 1, 1, 4>>(a, stream);
   switch (shared_variant()) {
     case 1: return launch_shared_cfg<SharedCfg<0, 2, 1, 2, 2, 2>>(a, stream);   // 128 x (64+64), 2 workgroups / CU
     case 2: return launch_shared_cfg<SharedCfg<0, 2, 2, 2, 2, 1>>(a, stream);   // 128 x (128+128), 1 workgroup / CU
@@ -236,7 +235,6 @@ hipError_t launch_shared_down(const uint16_t* h_s, const uint16_t* w_down, int T
                               hipStream_t stream) {
   if (T == 0) return hipSuccess;
   SharedGemmArgs a{h_s, w_down, nullptr, T, d, F, nullptr, y_s};
-  if (T <= 48) return launch_shared_cfg<SharedCfg<1, 1, 1, 1, 4>>(a, stream);
   switch (shared_variant()) {
     case 1: return launch_shared_cfg<SharedCfg<1, 2, 4, 2, 2, 1>>(a, stream);   // 128 x 256
     case 2: return launch_shared_cfg<SharedCfg<1, 4, 2, 2, 2, 1>>(a, stream);   // 256 x 128
