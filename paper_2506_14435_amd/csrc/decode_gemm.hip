@@ -171,6 +171,134 @@ __global__ __launch_bounds__(kDecThreads) void routed_decode_kernel(RoutedGemmAr
   }
 }
 
+// Streaming variant: a workgroup owns a contiguous run of output fragments of one
+// (row tile, K plane).  Each wavefront keeps its activation fragments for its four K steps
+// resident in registers for the whole run and streams only packed weights, two fragments
+// ahead (register double buffer refilled the moment a fragment has been consumed), so the
+// weight loads stay in flight across the per-fragment reduction and epilogue.  The LDS
+// reduction buffer is double buffered: one barrier per fragment.
+// Requires K <= 2048 per plane: gate-up with d_model <= 2048, and every down plane.
+template <int MODE>
+__global__ __launch_bounds__(kDecThreads, 2) void routed_stream_kernel(RoutedGemmArgs a, int n_frags, int kc_count) {
+  constexpr int NMAT = MODE == 0 ? 2 : 1;
+  __shared__ __attribute__((aligned(16))) int s_part[2][4 * NMAT * 16 * 64];
+
+  const int K = a.K, N = a.N, KT = K >> 7;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int r32 = lane & 31, g = lane >> 5, q = tid >> 6;
+  const int64_t expert_bytes = static_cast<int64_t>(N) * K / 4;
+  const int64_t frag_bytes = static_cast<int64_t>(KT) * 1024;
+  const int64_t total = static_cast<int64_t>(a.plan.n_tiles[0]) * kc_count * n_frags;
+  int64_t u = blockIdx.x * total / gridDim.x;
+  const int64_t hi = (blockIdx.x + 1) * total / gridDim.x;
+  int buf = 0;
+
+  while (u < hi) {
+    const int grp = static_cast<int>(u / n_frags);          // (row tile, K plane)
+    const int nf0 = static_cast<int>(u - static_cast<int64_t>(grp) * n_frags);
+    const int nf_end = static_cast<int>(min(static_cast<int64_t>(n_frags), nf0 + (hi - u)));
+    const int mt = grp / kc_count, kc = grp - mt * kc_count;
+    const int expert = a.plan.tile_expert[mt];
+    const int row0 = a.plan.tile_row0[mt];
+    const int rows = a.plan.tile_rows[mt];
+    const int step0 = (kc * 4 + wave) * 4;
+    const int nsteps = max(0, min(4, KT - step0));
+
+    const unsigned char* wb[NMAT];
+    wb[0] = reinterpret_cast<const unsigned char*>(a.w_gate) + expert * expert_bytes +
+            static_cast<int64_t>(step0) * 1024 + lane * 16;
+    if constexpr (NMAT == 2)
+      wb[1] = reinterpret_cast<const unsigned char*>(a.w_up) + expert * expert_bytes +
+              static_cast<int64_t>(step0) * 1024 + lane * 16;
+    u4 w_a[NMAT][4], w_b[NMAT][4];
+#define MOTE_LOADW(dst_, nf_)                                                               \
+  _Pragma("unroll") for (int m = 0; m < NMAT; ++m)                                          \
+    _Pragma("unroll") for (int s = 0; s < 4; ++s)                                           \
+      if (s < nsteps) dst_[m][s] = *reinterpret_cast<const u4*>(wb[m] + (nf_) * frag_bytes + s * 1024)
+    MOTE_LOADW(w_a, nf0);
+    if (nf0 + 1 < nf_end) { MOTE_LOADW(w_b, nf0 + 1); }
+
+    // resident activation fragments of this wavefront's K slice
+    const int slot = row0 + min(r32, rows - 1);
+    const int src = a.gather ? a.gather[slot] : slot;
+    const unsigned char* ap = reinterpret_cast<const unsigned char*>(a.q) + static_cast<int64_t>(src) * K +
+                              static_cast<int64_t>(step0) * 128 + g * 16;
+    const float m_beta = a.beta[src];
+    const int m_rs = a.rowsum[src];
+    v4i ar[4][4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+      if (s < nsteps) {
+#pragma unroll
+        for (int b = 0; b < 4; ++b) ar[s][b] = *reinterpret_cast<const v4i*>(ap + s * 128 + b * 32);
+      }
+    float sg = 0.0f, su = 0.0f;
+    if constexpr (MODE == 0) {
+      const float sx = m_beta / 127.0f;
+      sg = sx * a.alpha[expert * 3 + 0];
+      su = sx * a.alpha[expert * 3 + 1];
+    }
+    const int corr = (MODE == 0 || kc == 0) ? m_rs : 0;   // zero-point correction enters one plane only
+
+#define MOTE_FRAG(w_, nf_, nxt_)                                                                          \
+  {                                                                                                       \
+    v16i acc[NMAT];                                                                                       \
+    _Pragma("unroll") for (int m = 0; m < NMAT; ++m)                                                      \
+      _Pragma("unroll") for (int v = 0; v < 16; ++v) acc[m][v] = 0;                                       \
+    _Pragma("unroll") for (int s = 0; s < 4; ++s)                                                         \
+      if (s < nsteps) {                                                                                   \
+        _Pragma("unroll") for (int b = 0; b < 4; ++b)                                                     \
+          _Pragma("unroll") for (int m = 0; m < NMAT; ++m)                                                \
+            acc[m] = __builtin_amdgcn_mfma_i32_32x32x32_i8(unpack_codes_dec(w_[m][s][b]), ar[s][b],       \
+                                                           acc[m], 0, 0, 0);                              \
+      }                                                                                                   \
+    if ((nxt_) < nf_end) { MOTE_LOADW(w_, (nxt_)); }                                                      \
+    v4i* part = reinterpret_cast<v4i*>(s_part[buf]);   /* [wave][matrix][quad][lane] of 4 ints */         \
+    _Pragma("unroll") for (int m = 0; m < NMAT; ++m)                                                      \
+      _Pragma("unroll") for (int qq = 0; qq < 4; ++qq) {                                                  \
+        v4i t4 = {acc[m][4 * qq], acc[m][4 * qq + 1], acc[m][4 * qq + 2], acc[m][4 * qq + 3]};            \
+        part[((wave * NMAT + m) * 4 + qq) * 64 + lane] = t4;                                              \
+      }                                                                                                   \
+    __syncthreads();                                                                                      \
+    int sum[NMAT][4];                                                                                     \
+    _Pragma("unroll") for (int m = 0; m < NMAT; ++m) {                                                    \
+      v4i t4 = {-corr, -corr, -corr, -corr};                                                              \
+      _Pragma("unroll") for (int w = 0; w < 4; ++w) t4 += part[((w * NMAT + m) * 4 + q) * 64 + lane];     \
+      sum[m][0] = t4.x; sum[m][1] = t4.y; sum[m][2] = t4.z; sum[m][3] = t4.w;                             \
+    }                                                                                                     \
+    buf ^= 1;                                                                                             \
+    if (r32 < rows) {                                                                                     \
+      const int64_t o = static_cast<int64_t>(row0 + r32) * N + (nf_) * 32 + 8 * q + 4 * g;               \
+      if constexpr (MODE == 0) {                                                                          \
+        float hv[4];                                                                                      \
+        _Pragma("unroll") for (int j = 0; j < 4; ++j)                                                     \
+          hv[j] = (static_cast<float>(sum[NMAT - 1][j]) * su) * silu_fast(static_cast<float>(sum[0][j]) * sg); \
+        uint2 packed;                                                                                     \
+        packed.x = cvt_pk_bf16(hv[0], hv[1]);                                                             \
+        packed.y = cvt_pk_bf16(hv[2], hv[3]);                                                             \
+        *reinterpret_cast<uint2*>(a.h + o) = packed;                                                      \
+        if (a.tap_gate != nullptr) {                                                                      \
+          *reinterpret_cast<int4*>(a.tap_gate + o) = make_int4(sum[0][0], sum[0][1], sum[0][2], sum[0][3]); \
+          *reinterpret_cast<int4*>(a.tap_up + o) =                                                        \
+              make_int4(sum[NMAT - 1][0], sum[NMAT - 1][1], sum[NMAT - 1][2], sum[NMAT - 1][3]);          \
+        }                                                                                                 \
+      } else {                                                                                            \
+        *reinterpret_cast<int4*>(a.acc_out + static_cast<int64_t>(kc) * a.partial_stride + o) =           \
+            make_int4(sum[0][0], sum[0][1], sum[0][2], sum[0][3]);                                        \
+      }                                                                                                   \
+    }                                                                                                     \
+  }
+    for (int nf = nf0; nf < nf_end; nf += 2) {
+      MOTE_FRAG(w_a, nf, nf + 2);
+      if (nf + 1 < nf_end) MOTE_FRAG(w_b, nf + 1, nf + 3);
+    }
+#undef MOTE_FRAG
+#undef MOTE_LOADW
+    u += nf_end - nf0;
+  }
+}
+
 static int device_cus() {
   static int n = 0;
   if (n == 0) {
@@ -190,6 +318,10 @@ hipError_t launch_routed_decode_gate_up(const RoutedGemmArgs& a, hipStream_t str
   const int64_t max_units = static_cast<int64_t>(a.max_tiles) * n_frags;
   int64_t blocks = static_cast<int64_t>(device_cus()) * 4;
   if (blocks > max_units) blocks = max_units;
+  if (KT <= 16) {
+    routed_stream_kernel<0><<<device_cus() * 2, kDecThreads, 0, stream>>>(a, n_frags, 1);
+    return hipGetLastError();
+  }
   routed_decode_kernel<0><<<static_cast<unsigned>(blocks), kDecThreads, 0, stream>>>(a, n_frags, 1, (KT + 3) / 4);
   return hipGetLastError();
 }
@@ -201,7 +333,8 @@ hipError_t launch_routed_decode_down(const RoutedGemmArgs& a, hipStream_t stream
   const int64_t max_units = static_cast<int64_t>(a.max_tiles) * n_frags * kc;
   int64_t blocks = static_cast<int64_t>(device_cus()) * 4;
   if (blocks > max_units) blocks = max_units;
-  routed_decode_kernel<1><<<static_cast<unsigned>(blocks), kDecThreads, 0, stream>>>(a, n_frags, kc, 4);
+  (void)blocks;
+  routed_stream_kernel<1><<<device_cus() * 3, kDecThreads, 0, stream>>>(a, n_frags, kc);
   return hipGetLastError();
 }
 
