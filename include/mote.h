@@ -132,7 +132,9 @@ typedef struct {
   float* out_f32;      /* [T, d]  layer output before the final bf16 rounding             */
 } mote_taps;
 
-/* Bytes of scratch mote_layer_forward needs for up to T_max tokens (0 on a bad shape). */
+/* Bytes of scratch mote_layer_forward needs for a batch of T_max tokens (0 on a bad shape).
+ * The layout (kernel family, K-split partial planes) depends on the batch size: a caller that
+ * runs several batch sizes takes the largest value over the sizes it uses. */
 size_t mote_layer_workspace_bytes(const mote_layer* layer, int T_max);
 
 /* out = FFN(x) + MoE(x)  (Eq.2 + Eq.4; no residual add, no LayerNorm).

@@ -46,12 +46,15 @@ struct RoutedGemmArgs {
   int K, N;                 // contraction length, output width (per matrix)
   uint16_t* h;              // gate-up: bf16 [R, N]
   int32_t* acc_out;         // down: int32 [R, N] (decode: partial planes [planes][R, N])
-  int64_t partial_stride;   // elements between partial planes (decode down)
+  int64_t partial_stride;   // elements between partial planes (down projections)
+  int planes;               // K planes of the large-batch down projection (1: none)
   int32_t* tap_gate;        // optional int32 [R, N]
   int32_t* tap_up;
 };
 hipError_t launch_routed_gate_up(const RoutedGemmArgs& a, hipStream_t stream);
 hipError_t launch_routed_down(const RoutedGemmArgs& a, hipStream_t stream);
+int routed_down_planes(int T, int k, int E, int d, int F);   // large-batch down: K planes for a shape
+int shared_down_planes(int T, int d, int F);
 int routed_tile_m(int T, int k, int E);  // plan tile size chosen for a workload (32 = decode kernels)
 
 // Decode (small batch) variants: weights streamed once, K split across wavefronts and, for the

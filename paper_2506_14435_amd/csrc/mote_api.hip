@@ -51,8 +51,10 @@ Workspace carve(const mote_layer* l, int T, char* base) {
   const size_t d = l->d_model, Fr = l->d_ff_routed, Fs = l->d_ff_shared;
   w.max_tiles = static_cast<int>(R / 32 + l->n_experts);
   w.tile_m = routed_tile_m(T, l->top_k, l->n_experts);
-  w.d_planes = w.tile_m == 32 ? routed_decode_down_planes(l->d_ff_routed) : 1;
-  w.y_planes = T <= kSharedDecodeMaxTokens ? shared_decode_down_planes(l->d_ff_shared) : 1;
+  w.d_planes = w.tile_m == 32 ? routed_decode_down_planes(l->d_ff_routed)
+                              : routed_down_planes(T, l->top_k, l->n_experts, l->d_model, l->d_ff_routed);
+  w.y_planes = T <= kSharedDecodeMaxTokens ? shared_decode_down_planes(l->d_ff_shared)
+                                           : shared_down_planes(T, l->d_model, l->d_ff_shared);
   w.topk_idx = reinterpret_cast<int32_t*>(take(R * 4));
   w.topk_p = reinterpret_cast<float*>(take(R * 4));
   w.counts = reinterpret_cast<int32_t*>(take(64 * 4));
@@ -202,7 +204,7 @@ mote_status mote_layer_forward(const mote_layer* layer, const void* x, int T, vo
   ga.K = d; ga.N = Fr; ga.h = w.h; ga.acc_out = nullptr;
   ga.tap_gate = taps ? taps->acc_gate : nullptr;
   ga.tap_up = taps ? taps->acc_up : nullptr;
-  ga.partial_stride = 0;
+  ga.partial_stride = 0; ga.planes = 1;
   MOTE_HIP(decode_routed ? launch_routed_decode_gate_up(ga, stream) : launch_routed_gate_up(ga, stream));
   MOTE_HIP(mark(3));
   MOTE_HIP(launch_quant_rows(w.h, R, Fr, w.q_h, w.beta_h, w.rs_h, stream));
@@ -212,7 +214,7 @@ mote_status mote_layer_forward(const mote_layer* layer, const void* x, int T, vo
   gd.q = w.q_h; gd.gather = nullptr; gd.beta = w.beta_h; gd.rowsum = w.rs_h;
   gd.w_gate = layer->wt_down; gd.w_up = nullptr;
   gd.K = Fr; gd.N = d; gd.h = nullptr; gd.acc_out = w.acc_down; gd.tap_gate = nullptr; gd.tap_up = nullptr;
-  gd.partial_stride = static_cast<int64_t>(R) * d;
+  gd.partial_stride = static_cast<int64_t>(R) * d; gd.planes = w.d_planes;
   MOTE_HIP(decode_routed ? launch_routed_decode_down(gd, stream) : launch_routed_down(gd, stream));
   MOTE_HIP(mark(5));
 

@@ -2,8 +2,8 @@
 // per-token absmax int8 quantiser Q_a(x) (Eq.8-10), and the dispatch plan that turns the
 // top-k indices into an expert-major row permutation.
 //
-// router_quant_kernel: one wavefront owns TPW tokens.  Each lane owns 8-channel chunks of
-// the token rows (16-byte bf16 loads), multiplies them with the matching 8 rows of the
+// router_quant_kernel: one workgroup owns TPW tokens, its four wavefronts split the channels.
+// Each lane owns 8-channel chunks of the token rows (16-byte bf16 loads), multiplies them with the matching 8 rows of the
 // bf16 router matrix and accumulates TPW x EMAX partial logits in fp64 (a bf16 x bf16
 // product is exact, and fp64 accumulation makes the selected indices independent of the
 // summation order).  A 6-step butterfly reduce-scatter leaves lane l with the finished
@@ -14,7 +14,6 @@
 
 namespace mote {
 
-constexpr int kRouterThreads = 256;
 
 template <int OFF>
 __device__ __forceinline__ void reduce_scatter_step(double (&v)[64], int lane) {
@@ -52,16 +51,22 @@ __device__ __forceinline__ void load_router_row(const uint16_t* __restrict__ row
   }
 }
 
-template <int EMAX, int TPW>
-__global__ __launch_bounds__(kRouterThreads) void router_quant_kernel(
+template <int EMAX, int TPW, int NW>
+__global__ __launch_bounds__(64 * NW) void router_quant_kernel(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ w_router, const float* __restrict__ bias, int T,
     int d, int E, int k, int32_t* __restrict__ topk_idx, float* __restrict__ topk_p, int8_t* __restrict__ q_x,
     float* __restrict__ beta_x, int32_t* __restrict__ rowsum_x) {
   static_assert(EMAX * TPW == 64, "one finished logit per lane");
-  __shared__ double s_logit[kRouterThreads / kWave][64];
+  constexpr int kWaves = NW;               // wavefronts that split the channels of one token group
+  constexpr int kThreads = 64 * NW;
+  __shared__ double s_logit[kWaves][64];
+  __shared__ double s_total[64];
+  __shared__ float s_prob[64];
+  __shared__ float s_amax[kWaves][TPW];
+  __shared__ int s_rsum[kWaves][TPW];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int t0 = (blockIdx.x * (kRouterThreads / kWave) + wave) * TPW;
-  if (t0 >= T) return;  // whole wavefront leaves together; no block-level barrier below
+  const int t0 = blockIdx.x * TPW;   // the NW wavefronts of a workgroup split the channels of TPW tokens
+  if (t0 >= T) return;
   const int n_chunks = d >> 3;
   const bool vec_ok = (E & 7) == 0;
 
@@ -76,7 +81,7 @@ __global__ __launch_bounds__(kRouterThreads) void router_quant_kernel(
 #pragma unroll
   for (int t = 0; t < TPW; ++t) amax[t] = 0.0f;
 
-  for (int ch = lane; ch < n_chunks; ch += kWave) {
+  for (int ch = wave * kWave + lane; ch < n_chunks; ch += kThreads) {
     const int c0 = ch << 3;
     float xf[TPW][8];
 #pragma unroll
@@ -100,26 +105,48 @@ __global__ __launch_bounds__(kRouterThreads) void router_quant_kernel(
     }
   }
 
-  reduce_scatter_step<32>(acc, lane);  // lane l now holds logit(token l / EMAX, expert l % EMAX)
-  {
+  reduce_scatter_step<32>(acc, lane);  // lane l holds this wavefront's share of logit(token l / EMAX, expert l % EMAX)
+  s_logit[wave][lane] = acc[0];
+#pragma unroll
+  for (int t = 0; t < TPW; ++t) {
+    amax[t] = wave_max(amax[t]);
+    if (lane == 0) s_amax[wave][t] = amax[t];
+  }
+  __syncthreads();
+  if (wave == 0) {   // fixed summation order over the channel slices
+    double l = s_logit[0][lane];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) l += s_logit[w][lane];
     const int e = lane % EMAX;
-    double l = acc[0];
-    if (bias != nullptr && e < E) l += static_cast<double>(bias[e]);
-    s_logit[wave][lane] = l;
+    const bool valid = e < E;
+    if (bias != nullptr && valid) l += static_cast<double>(bias[e]);
+    if (!valid) l = -1.0e300;
+    // gate softmax (Eq.3) over the EMAX lanes of a token: max and sum by xor shuffles
+    double mx = l;
+#pragma unroll
+    for (int off = EMAX / 2; off > 0; off >>= 1) mx = fmax(mx, __shfl_xor(mx, off, kWave));
+    const float ex = valid ? expf(static_cast<float>(l - mx)) : 0.0f;
+    float sum = ex;
+#pragma unroll
+    for (int off = EMAX / 2; off > 0; off >>= 1) sum += __shfl_xor(sum, off, kWave);
+    s_total[lane] = l;
+    s_prob[lane] = ex / sum;
   }
 #pragma unroll
-  for (int t = 0; t < TPW; ++t) amax[t] = wave_max(amax[t]);
+  for (int t = 0; t < TPW; ++t) {
+    float m = s_amax[0][t];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) m = fmaxf(m, s_amax[w][t]);
+    amax[t] = m;
+  }
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
   // Softmax over all E logits and top-k: one lane per token, serial over E <= 64.
-  if (lane < TPW && t0 + lane < T) {
-    const double* l = &s_logit[wave][lane * EMAX];
-    double mx = l[0];
-    for (int e = 1; e < E; ++e) mx = fmax(mx, l[e]);
-    double sum = 0.0;
-    for (int e = 0; e < E; ++e) sum += exp(l[e] - mx);
+  if (wave == 0 && lane < TPW && t0 + lane < T) {
+    const double* l = &s_total[lane * EMAX];
+    const float* pr = &s_prob[lane * EMAX];
     uint64_t taken = 0;
     for (int j = 0; j < k; ++j) {
       int best = -1;
@@ -131,7 +158,7 @@ __global__ __launch_bounds__(kRouterThreads) void router_quant_kernel(
       }
       taken |= 1ull << best;
       topk_idx[static_cast<int64_t>(t0 + lane) * k + j] = best;
-      topk_p[static_cast<int64_t>(t0 + lane) * k + j] = static_cast<float>(exp(lb - mx) / sum);
+      topk_p[static_cast<int64_t>(t0 + lane) * k + j] = pr[best];
     }
   }
 
@@ -145,7 +172,7 @@ __global__ __launch_bounds__(kRouterThreads) void router_quant_kernel(
     scale[t] = 127.0f / amax[t];
     rs[t] = 0;
   }
-  for (int ch = lane; ch < n_chunks; ch += kWave) {
+  for (int ch = wave * kWave + lane; ch < n_chunks; ch += kThreads) {
     const int c0 = ch << 3;
 #pragma unroll
     for (int t = 0; t < TPW; ++t) {
@@ -163,11 +190,19 @@ __global__ __launch_bounds__(kRouterThreads) void router_quant_kernel(
   }
 #pragma unroll
   for (int t = 0; t < TPW; ++t) {
-    const int total = wave_sum(rs[t]);
-    if (lane == 0 && t0 + t < T) {
-      beta_x[t0 + t] = amax[t];
-      rowsum_x[t0 + t] = total;
-    }
+    const int part = wave_sum(rs[t]);
+    if (lane == 0) s_rsum[wave][t] = part;
+  }
+  __syncthreads();
+  if (threadIdx.x < TPW && t0 + threadIdx.x < T) {
+    int total = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) total += s_rsum[w][threadIdx.x];
+    float m = s_amax[0][threadIdx.x];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) m = fmaxf(m, s_amax[w][threadIdx.x]);
+    beta_x[t0 + threadIdx.x] = fmaxf(m, kEps);
+    rowsum_x[t0 + threadIdx.x] = total;
   }
 }
 
@@ -175,17 +210,25 @@ hipError_t launch_router_quant(const uint16_t* x, const uint16_t* w_router, cons
                                int E, int k, int32_t* topk_idx, float* topk_p, int8_t* q_x, float* beta_x,
                                int32_t* rowsum_x, hipStream_t stream) {
   if (T == 0) return hipSuccess;
-  constexpr int kWavesPerBlock = kRouterThreads / kWave;
+  // Few tokens: four wavefronts share a token group so that more of the chip takes part;
+  // many tokens: one wavefront per group keeps the cross-lane reduction cost per token low.
+  const bool coop = T <= 2048;
   if (E <= 16) {
     constexpr int kTpw = 4;
-    const int blocks = (T + kWavesPerBlock * kTpw - 1) / (kWavesPerBlock * kTpw);
-    router_quant_kernel<16, kTpw><<<blocks, kRouterThreads, 0, stream>>>(x, w_router, bias, T, d, E, k, topk_idx,
-                                                                         topk_p, q_x, beta_x, rowsum_x);
+    const int blocks = (T + kTpw - 1) / kTpw;
+    if (coop)
+      router_quant_kernel<16, kTpw, 4><<<blocks, 256, 0, stream>>>(x, w_router, bias, T, d, E, k, topk_idx, topk_p, q_x,
+                                                                   beta_x, rowsum_x);
+    else
+      router_quant_kernel<16, kTpw, 1><<<blocks, 64, 0, stream>>>(x, w_router, bias, T, d, E, k, topk_idx, topk_p, q_x,
+                                                                  beta_x, rowsum_x);
   } else {
-    constexpr int kTpw = 1;
-    const int blocks = (T + kWavesPerBlock * kTpw - 1) / (kWavesPerBlock * kTpw);
-    router_quant_kernel<64, kTpw><<<blocks, kRouterThreads, 0, stream>>>(x, w_router, bias, T, d, E, k, topk_idx,
-                                                                         topk_p, q_x, beta_x, rowsum_x);
+    if (coop)
+      router_quant_kernel<64, 1, 4><<<T, 256, 0, stream>>>(x, w_router, bias, T, d, E, k, topk_idx, topk_p, q_x, beta_x,
+                                                           rowsum_x);
+    else
+      router_quant_kernel<64, 1, 1><<<T, 64, 0, stream>>>(x, w_router, bias, T, d, E, k, topk_idx, topk_p, q_x, beta_x,
+                                                          rowsum_x);
   }
   return hipGetLastError();
 }

@@ -45,11 +45,12 @@ struct SharedGemmArgs {
   const uint16_t* w1;    // [N, K] bf16 (up)
   int M, N, K;
   uint16_t* h_out;       // gate-up: bf16 [M, N]
-  float* y_out;          // down: fp32 [M, N]
+  float* y_out;          // down: fp32 [planes][M, N]
+  int64_t plane_stride;  // elements between partial planes
 };
 
 template <typename Cfg>
-__global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void shared_gemm_kernel(SharedGemmArgs a, int n_ntiles) {
+__global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void shared_gemm_kernel(SharedGemmArgs a, int n_ntiles, int kplanes, int ktp) {
   constexpr int NMAT = Cfg::NMAT, BM_W = Cfg::BM_W, BN_W = Cfg::BN_W;
   constexpr int BM = Cfg::BM, BN = Cfg::BN;
   extern __shared__ __attribute__((aligned(16))) unsigned char s_mem[];
@@ -57,6 +58,9 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void shared_gemm_ker
   // Workgroups go to the 8 XCDs round-robin by linear id: XCD x owns the channel tiles
   // x, x+8, ... (the row tiles x, x+8, ... when there are fewer than 16 channel tiles) and
   // walks the other index fastest, so its L2 keeps one slice of the weights resident.
+  // With kplanes > 1 (down projection of small problems) the contraction is cut into planes of
+  // ktp K steps; each plane writes its own partial output, added later in plane order.
+  n_ntiles *= kplanes;
   const int M = a.M, N = a.N, K = a.K;
   const int n_mtiles = (M + BM - 1) / BM;
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
@@ -66,8 +70,10 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void shared_gemm_ker
   if (slot >= xcd_ntiles * xcd_mtiles) return;
   const int mi = slot / xcd_ntiles, ni = slot - mi * xcd_ntiles;
   const int mt = split_n ? mi : xcd + 8 * mi;
-  const int nt = split_n ? xcd + 8 * ni : ni;
-  const int KT = K >> 6;
+  const int ntk = split_n ? xcd + 8 * ni : ni;
+  const int nt = ntk / kplanes, kc = ntk - nt * kplanes;
+  const int kt0 = kc * ktp;
+  const int KT = min(ktp, (K >> 6) - kt0);   // K steps of this plane
   const int m0 = mt * BM, n0 = nt * BN;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -81,13 +87,13 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void shared_gemm_ker
 #pragma unroll
   for (int p = 0; p < Cfg::A_PASSES; ++p) {
     const int r = p * Cfg::ROWS_PER_PASS + (tid >> 3);
-    a_src[p] = a.act + static_cast<int64_t>(min(m0 + r, M - 1)) * K + chunk * 8;
+    a_src[p] = a.act + static_cast<int64_t>(min(m0 + r, M - 1)) * K + chunk * 8 + kt0 * 64;
     a_dst[p] = lds_tile_offset(r, chunk);
   }
 #pragma unroll
   for (int p = 0; p < Cfg::B_PASSES; ++p) {
     const int r = p * Cfg::ROWS_PER_PASS + (tid >> 3);
-    const int64_t off = static_cast<int64_t>(min(n0 + r, N - 1)) * K + chunk * 8;
+    const int64_t off = static_cast<int64_t>(min(n0 + r, N - 1)) * K + chunk * 8 + kt0 * 64;
     b_src[0][p] = a.w0 + off;
     if constexpr (NMAT == 2) b_src[1][p] = a.w1 + off;
     b_dst[p] = lds_tile_offset(r, chunk);
@@ -181,7 +187,7 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void shared_gemm_ker
           packed.y = cvt_pk_bf16(hv[2], hv[3]);
           *reinterpret_cast<uint2*>(a.h_out + o) = packed;
         } else {
-          *reinterpret_cast<float4*>(a.y_out + o) = make_float4(acc[0][i][f][4 * q + 0], acc[0][i][f][4 * q + 1],
+          *reinterpret_cast<float4*>(a.y_out + static_cast<int64_t>(kc) * a.plane_stride + o) = make_float4(acc[0][i][f][4 * q + 0], acc[0][i][f][4 * q + 1],
                                                                 acc[0][i][f][4 * q + 2], acc[0][i][f][4 * q + 3]);
         }
       }
@@ -204,8 +210,10 @@ static int shared_variant() {
 }
 
 template <typename Cfg>
-static hipError_t launch_shared_cfg(const SharedGemmArgs& a, hipStream_t stream) {
+static hipError_t launch_shared_cfg(const SharedGemmArgs& a, int kplanes, hipStream_t stream) {
   const int n_ntiles = (a.N + Cfg::BN - 1) / Cfg::BN;
+  const int KT = a.K >> 6;
+  const int ktp = (KT + kplanes - 1) / kplanes;
   const int n_mtiles = (a.M + Cfg::BM - 1) / Cfg::BM;
   const size_t lds = 2 * Cfg::STAGE_BYTES;
   static bool attr_set = false;
@@ -215,30 +223,50 @@ static hipError_t launch_shared_cfg(const SharedGemmArgs& a, hipStream_t stream)
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  const int per_xcd = split_tiles(n_ntiles, n_mtiles);
-  shared_gemm_kernel<Cfg><<<static_cast<unsigned>(per_xcd * 8), Cfg::THREADS, lds, stream>>>(a, n_ntiles);
+  const int per_xcd = split_tiles(n_ntiles * kplanes, n_mtiles);
+  shared_gemm_kernel<Cfg><<<static_cast<unsigned>(per_xcd * 8), Cfg::THREADS, lds, stream>>>(a, n_ntiles, kplanes, ktp);
   return hipGetLastError();
 }
 
 hipError_t launch_shared_gate_up(const uint16_t* x, const uint16_t* w_gate, const uint16_t* w_up, int T, int d,
                                  int F, uint16_t* h_s, hipStream_t stream) {
   if (T == 0) return hipSuccess;
-  SharedGemmArgs a{x, w_gate, w_up, T, F, d, h_s, nullptr};
-  switch (shared_variant()) {
-    case 1: return launch_shared_cfg<SharedCfg<0, 2, 1, 2, 2, 2>>(a, stream);   // 128 x (64+64), 2 workgroups / CU
-    case 2: return launch_shared_cfg<SharedCfg<0, 2, 2, 2, 2, 1>>(a, stream);   // 128 x (128+128), 1 workgroup / CU
-    default: return launch_shared_cfg<SharedCfg<0, 2, 2, 4, 2, 1>>(a, stream);  // 256 x (128+128), 8 wavefronts
+  SharedGemmArgs a{x, w_gate, w_up, T, F, d, h_s, nullptr, 0};
+  int v = shared_variant();
+  if (v == 0) {   // few 256-row tiles: the 128 x (64+64) tile at two workgroups per CU fills the chip better
+    const int64_t big_tiles = static_cast<int64_t>((T + 255) / 256) * (F / 128);
+    if (big_tiles < 2 * 256) v = 1;
   }
+  switch (v) {
+    case 1: return launch_shared_cfg<SharedCfg<0, 2, 1, 2, 2, 2>>(a, 1, stream);   // 128 x (64+64), 2 workgroups / CU
+    case 2: return launch_shared_cfg<SharedCfg<0, 2, 2, 2, 2, 1>>(a, 1, stream);   // 128 x (128+128), 1 workgroup / CU
+    default: return launch_shared_cfg<SharedCfg<0, 2, 2, 4, 2, 1>>(a, 1, stream);  // 256 x (128+128), 8 wavefronts
+  }
+}
+
+// K planes of the large-batch down projection: enough (row tile, channel tile, plane) triples
+// to fill two workgroups per CU, planes of at least 8 K steps.  Pure function of the shape:
+// the workspace layout depends on it.
+int shared_down_planes(int T, int d, int F) {
+  const int64_t tiles = static_cast<int64_t>((T + 127) / 128) * ((d + 127) / 128);
+  const int KT = F >> 6;
+  int planes = static_cast<int>(512 / (tiles > 0 ? tiles : 1));
+  if (planes > 8) planes = 8;
+  if (planes > KT / 8) planes = KT / 8;
+  if (planes < 1) planes = 1;
+  const int ktp = (KT + planes - 1) / planes;
+  return (KT + ktp - 1) / ktp;
 }
 
 hipError_t launch_shared_down(const uint16_t* h_s, const uint16_t* w_down, int T, int d, int F, float* y_s,
                               hipStream_t stream) {
   if (T == 0) return hipSuccess;
-  SharedGemmArgs a{h_s, w_down, nullptr, T, d, F, nullptr, y_s};
+  SharedGemmArgs a{h_s, w_down, nullptr, T, d, F, nullptr, y_s, static_cast<int64_t>(T) * d};
+  const int planes = shared_down_planes(T, d, F);
   switch (shared_variant()) {
-    case 1: return launch_shared_cfg<SharedCfg<1, 2, 4, 2, 2, 1>>(a, stream);   // 128 x 256
-    case 2: return launch_shared_cfg<SharedCfg<1, 4, 2, 2, 2, 1>>(a, stream);   // 256 x 128
-    default: return launch_shared_cfg<SharedCfg<1, 2, 2, 2, 2, 2>>(a, stream);  // 128 x 128, 2 workgroups / CU
+    case 1: return launch_shared_cfg<SharedCfg<1, 2, 4, 2, 2, 1>>(a, planes, stream);   // 128 x 256
+    case 2: return launch_shared_cfg<SharedCfg<1, 4, 2, 2, 2, 1>>(a, planes, stream);   // 256 x 128
+    default: return launch_shared_cfg<SharedCfg<1, 2, 2, 2, 2, 2>>(a, planes, stream);  // 128 x 128, 2 workgroups / CU
   }
 }
 

@@ -91,7 +91,7 @@ __device__ __forceinline__ void k_step(v16i (&acc)[Cfg::NMAT][Cfg::BM_W][Cfg::BN
 }
 
 template <typename Cfg>
-__global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_kernel(RoutedGemmArgs a, int n_ntiles) {
+__global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_kernel(RoutedGemmArgs a, int n_ntiles, int kplanes, int ktp) {
   constexpr int NMAT = Cfg::NMAT, BM_W = Cfg::BM_W, BN_W = Cfg::BN_W;
   constexpr int BM = Cfg::BM, BN = Cfg::BN, THREADS = Cfg::THREADS;
   static_assert(BM <= THREADS, "one thread per tile row publishes the row metadata");
@@ -117,6 +117,10 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
   // than 16 channel tiles, the row tiles x, x+8, ...) and walks the other index fastest:
   // the packed weights of an expert and the few activation row tiles in flight stay
   // resident in that XCD's own L2.
+  // With kplanes > 1 (down projection of small problems) the contraction is cut into planes
+  // of ktp K steps; a (channel tile, plane) pair then plays the role of a channel tile and each
+  // plane writes its own partial output that the combine kernel adds.
+  n_ntiles *= kplanes;
   const int xcd = blockIdx.x & 7;
   const int n_mtiles = a.plan.n_tiles[0];
   const bool split_n = n_ntiles >= 16;
@@ -141,15 +145,17 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
   int meta_row = 0;             // row whose beta / rowsum this thread publishes (tid < BM)
   float meta_beta = 1.0f;
   int meta_rs = 0;
-  int mt, nt, expert, row0, rows;
+  int mt, nt, kc, expert, row0, rows;
 #pragma unroll
   for (int p = 0; p < Cfg::A_PASSES; ++p) a_dst[p] = lds_a_offset(p * Cfg::ROWS_PER_PASS + (tid >> 3), tid & 7);
 
-#define MOTE_DECODE(slot_, mt_, nt_)                                            \
+#define MOTE_DECODE(slot_, mt_, nt_, kc_)                                       \
   {                                                                             \
     const int mi_ = (slot_) / xcd_ntiles, ni_ = (slot_) - mi_ * xcd_ntiles;     \
     mt_ = split_n ? mi_ : xcd + 8 * mi_;                                        \
-    nt_ = split_n ? xcd + 8 * ni_ : ni_;                                        \
+    const int ntk_ = split_n ? xcd + 8 * ni_ : ni_;                             \
+    nt_ = ntk_ / kplanes;                                                       \
+    kc_ = ntk_ - nt_ * kplanes;                                                 \
   }
 #define MOTE_GATHER(row0_, rows_)                                                                  \
   {                                                                                                \
@@ -160,15 +166,16 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
     const int mslot_ = (row0_) + min(tid < BM ? tid : 0, (rows_)-1);                               \
     meta_row = a.gather ? a.gather[mslot_] : mslot_;                                               \
   }
-#define MOTE_POINTERS(expert_, nt_)                                                                \
+#define MOTE_POINTERS(expert_, nt_, kc_)                                                           \
   {                                                                                                \
     _Pragma("unroll") for (int p = 0; p < Cfg::A_PASSES; ++p)                                      \
-      a_off[p] = static_cast<uint32_t>(src_row[p]) * static_cast<uint32_t>(K) + (tid & 7) * 16;    \
+      a_off[p] = static_cast<uint32_t>(src_row[p]) * static_cast<uint32_t>(K) + (tid & 7) * 16 +   \
+                 static_cast<uint32_t>((kc_) * ktp) * 128u;                                        \
     _Pragma("unroll") for (int f = 0; f < BN_W; ++f) {                                             \
       const int n_frag_ = (nt_) * BN + wn_u * BN_W * 32 + f * 32;                                  \
       const int nt32_ = (n_frag_ < N ? n_frag_ : 0) >> 5; /* fragments past N read tile 0 */       \
       const int64_t off_ = (static_cast<int64_t>(expert_) * expert_words +                         \
-                            static_cast<int64_t>(nt32_) * KT * 256) * 4;                           \
+                            (static_cast<int64_t>(nt32_) * KT + (kc_) * ktp) * 256) * 4;           \
       w_base[0][f] = reinterpret_cast<const unsigned char*>(a.w_gate) + off_;                      \
       if constexpr (NMAT == 2) w_base[1][f] = reinterpret_cast<const unsigned char*>(a.w_up) + off_; \
     }                                                                                              \
@@ -187,12 +194,12 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
     *reinterpret_cast<u4*>((stage_) + a_dst[p]) = a_reg[p]
 
   // ---- first tile: the whole dependent chain (plan -> gather -> rows) is paid once ----
-  MOTE_DECODE(slot, mt, nt);
+  MOTE_DECODE(slot, mt, nt, kc);
   expert = a.plan.tile_expert[mt];
   row0 = a.plan.tile_row0[mt];
   rows = a.plan.tile_rows[mt];
   MOTE_GATHER(row0, rows);
-  MOTE_POINTERS(expert, nt);
+  MOTE_POINTERS(expert, nt, kc);
   MOTE_LOAD_A(0);
   MOTE_LOAD_W(w_a, 0);
 
@@ -206,9 +213,9 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
     // (2) coordinates of the next tile of this workgroup (uniform scalar loads)
     const int nslot = slot + stride;
     const bool has_next = nslot < xcd_work;
-    int mt2 = mt, nt2 = nt, expert2 = expert, row02 = row0, rows2 = rows;
+    int mt2 = mt, nt2 = nt, kc2 = kc, expert2 = expert, row02 = row0, rows2 = rows;
     if (has_next) {
-      MOTE_DECODE(nslot, mt2, nt2);
+      MOTE_DECODE(nslot, mt2, nt2, kc2);
       expert2 = a.plan.tile_expert[mt2];
       row02 = a.plan.tile_row0[mt2];
       rows2 = a.plan.tile_rows[mt2];
@@ -220,7 +227,7 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
     v16i acc[NMAT][BM_W][BN_W];
 #pragma unroll
     for (int i = 0; i < BM_W; ++i) {
-      const int nrs = -s_rs[wm * BM_W * 32 + i * 32 + r32];
+      const int nrs = kc == 0 ? -s_rs[wm * BM_W * 32 + i * 32 + r32] : 0;   // the correction enters plane 0 only
 #pragma unroll
       for (int m = 0; m < NMAT; ++m)
 #pragma unroll
@@ -232,8 +239,9 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
     // (3) K loop.  Unrolled by two K steps so that the two weight register sets and the two
     // LDS stages are named statically (no register copies on the back-edge): while K step kt
     // is contracted, the packed weights and the activation tile of kt+1 are in flight.
+    const int ktl = min(ktp, KT - kc * ktp);   // K steps of this plane
     int kt = 0;
-    for (; kt + 1 < KT; kt += 2) {
+    for (; kt + 1 < ktl; kt += 2) {
       MOTE_LOAD_A(kt + 1);  // issued first: needed first (LDS store at the end of this half)
       MOTE_LOAD_W(w_b, kt + 1);
       __builtin_amdgcn_sched_barrier(0);  // keep the prefetch loads ahead of the contraction
@@ -241,7 +249,7 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
       __builtin_amdgcn_sched_barrier(0);
       MOTE_STORE_A(stage1);
       __syncthreads();
-      const int kn = min(kt + 2, KT - 1);  // the last prefetch of an even-length loop is a harmless repeat
+      const int kn = min(kt + 2, ktl - 1);  // the last prefetch of an even-length loop is a harmless repeat
       MOTE_LOAD_A(kn);
       MOTE_LOAD_W(w_a, kn);
       __builtin_amdgcn_sched_barrier(0);
@@ -250,13 +258,13 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
       MOTE_STORE_A(stage0);
       __syncthreads();
     }
-    if (kt < KT) k_step<Cfg>(acc, stage0, a_row_base, g, w_a);
+    if (kt < ktl) k_step<Cfg>(acc, stage0, a_row_base, g, w_a);
 
     // (4) start the next tile now: its gather indices, row scalars and first K step travel
     // while this tile runs its epilogue.
     if (has_next) {
       MOTE_GATHER(row02, rows2);
-      MOTE_POINTERS(expert2, nt2);
+      MOTE_POINTERS(expert2, nt2, kc2);
       MOTE_LOAD_A(0);
       MOTE_LOAD_W(w_a, 0);
     }
@@ -323,7 +331,7 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
         if (orow < rows && rd_n < N) {
           const int64_t o = static_cast<int64_t>(row0 + orow) * N + rd_n;
           if constexpr (Cfg::MODE == 0) *reinterpret_cast<u4*>(a.h + o) = v;
-          else *reinterpret_cast<u4*>(a.acc_out + o) = v;
+          else *reinterpret_cast<u4*>(a.acc_out + static_cast<int64_t>(kc) * a.partial_stride + o) = v;
         }
       }
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -332,7 +340,7 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
     }
     if (!has_next) break;
     __syncthreads();  // LDS (patches, row metadata) is reused by the next tile
-    slot = nslot; mt = mt2; nt = nt2; expert = expert2; row0 = row02; rows = rows2;
+    slot = nslot; mt = mt2; nt = nt2; kc = kc2; expert = expert2; row0 = row02; rows = rows2;
   }
 #undef MOTE_DECODE
 #undef MOTE_GATHER
@@ -364,12 +372,15 @@ static int resident_blocks() {
 }
 
 template <typename Cfg>
-static hipError_t launch_cfg(const RoutedGemmArgs& a, hipStream_t stream) {
+static hipError_t launch_cfg(const RoutedGemmArgs& a, int kplanes, hipStream_t stream) {
   const int n_ntiles = (a.N + Cfg::BN - 1) / Cfg::BN;
-  const int64_t tiles = static_cast<int64_t>(a.max_tiles) * n_ntiles;
+  const int KT = a.K >> 7;
+  const int ktp = (KT + kplanes - 1) / kplanes;
+  kplanes = (KT + ktp - 1) / ktp;   // every plane non-empty
+  const int64_t tiles = static_cast<int64_t>(a.max_tiles) * n_ntiles * kplanes;
   int64_t blocks = static_cast<int64_t>(device_cu_count()) * resident_blocks<Cfg>();
   if (blocks > tiles) blocks = (tiles + 7) / 8 * 8;
-  routed_gemm_kernel<Cfg><<<static_cast<unsigned>(blocks), Cfg::THREADS, 0, stream>>>(a, n_ntiles);
+  routed_gemm_kernel<Cfg><<<static_cast<unsigned>(blocks), Cfg::THREADS, 0, stream>>>(a, n_ntiles, kplanes, ktp);
   return hipGetLastError();
 }
 
@@ -393,20 +404,33 @@ int routed_tile_m(int T, int k, int E) {
 
 hipError_t launch_routed_gate_up(const RoutedGemmArgs& a, hipStream_t stream) {
   if (a.max_tiles == 0) return hipSuccess;
-  if (a.tile_m == 32) return launch_cfg<RoutedCfg<0, 1, 1, 1, 4>>(a, stream);
   switch (routed_variant()) {
-    case 1: return launch_cfg<RoutedCfg<0, 4, 1, 1, 4, 2>>(a, stream);
-    default: return launch_cfg<RoutedCfg<0, 2, 2, 2, 2, 2>>(a, stream);
+    case 1: return launch_cfg<RoutedCfg<0, 4, 1, 1, 4, 2>>(a, 1, stream);
+    default: return launch_cfg<RoutedCfg<0, 2, 2, 2, 2, 2>>(a, 1, stream);
   }
+}
+
+// K planes of the large-batch down projection (see shared_down_planes): pure function of the
+// shape, the number of row tiles is estimated as R/128 + E/2.
+int routed_down_planes(int T, int k, int E, int d, int F) {
+  const int64_t mtiles = (static_cast<int64_t>(T) * k) / 128 + (E + 1) / 2;
+  const int64_t tiles = mtiles * ((d + 127) / 128);
+  const int KT = F >> 7;
+  int planes = static_cast<int>(512 / (tiles > 0 ? tiles : 1));
+  if (planes > 8) planes = 8;
+  if (planes > KT / 4) planes = KT / 4;
+  if (planes < 1) planes = 1;
+  const int ktp = (KT + planes - 1) / planes;
+  return (KT + ktp - 1) / ktp;
 }
 
 hipError_t launch_routed_down(const RoutedGemmArgs& a, hipStream_t stream) {
   if (a.max_tiles == 0) return hipSuccess;
-  if (a.tile_m == 32) return launch_cfg<RoutedCfg<1, 1, 1, 1, 4>>(a, stream);
+  if (a.planes > 1) return launch_cfg<RoutedCfg<1, 2, 2, 2, 2, 2>>(a, a.planes, stream);   // small problem: 128 x 128 tiles
   switch (routed_variant()) {
-    case 1: return launch_cfg<RoutedCfg<1, 4, 2, 1, 4, 2>>(a, stream);
-    case 2: return launch_cfg<RoutedCfg<1, 2, 2, 2, 2, 2>>(a, stream);
-    default: return launch_cfg<RoutedCfg<1, 2, 4, 2, 2, 2>>(a, stream);
+    case 1: return launch_cfg<RoutedCfg<1, 4, 2, 1, 4, 2>>(a, 1, stream);
+    case 2: return launch_cfg<RoutedCfg<1, 2, 2, 2, 2, 2>>(a, 1, stream);
+    default: return launch_cfg<RoutedCfg<1, 2, 4, 2, 2, 2>>(a, 1, stream);
   }
 }
 
