@@ -131,6 +131,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="c2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calib-copy-mib", type=int, default=0,
+                    help="also run the library's plain copy kernel on this many MiB (three launches): the "
+                         "known-size transfer that scales rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU; the layer is token-parallel and shards without "
@@ -175,6 +178,14 @@ def main():
     M.mote_layer_forward(gp.layer, gp.x, out=out, workspace=ws, taps=taps)
     torch.cuda.synchronize()
     counts = taps["counts"].cpu().numpy()
+
+    if args.calib_copy_mib > 0:
+        src = torch.full((args.calib_copy_mib << 20,), 7, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            M.mote_calib_copy(dst, src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for i in range(args.warmup):
         M.mote_layer_forward(layers[i % n_layers], gp.x, out=out, workspace=ws)

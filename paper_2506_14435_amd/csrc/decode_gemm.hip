@@ -156,10 +156,10 @@ __global__ __launch_bounds__(kDecThreads) void routed_decode_kernel(RoutedGemmAr
           packed.x = cvt_pk_bf16(hv[0], hv[1]);
           packed.y = cvt_pk_bf16(hv[2], hv[3]);
           *reinterpret_cast<uint2*>(a.h + o) = packed;
-          if (a.tap_gate != nullptr) {
+          if (a.tap_gate != nullptr)
             *reinterpret_cast<int4*>(a.tap_gate + o) = make_int4(sum[0][0], sum[0][1], sum[0][2], sum[0][3]);
+          if (a.tap_up != nullptr)
             *reinterpret_cast<int4*>(a.tap_up + o) = make_int4(sum[1][0], sum[1][1], sum[1][2], sum[1][3]);
-          }
         } else {
           const int corr = kc == 0 ? m_rs : 0;   // the zero-point correction enters exactly one partial plane
           *reinterpret_cast<int4*>(a.acc_out + static_cast<int64_t>(kc) * a.partial_stride + o) =
@@ -278,11 +278,11 @@ __global__ __launch_bounds__(kDecThreads, 2) void routed_stream_kernel(RoutedGem
         packed.x = cvt_pk_bf16(hv[0], hv[1]);                                                             \
         packed.y = cvt_pk_bf16(hv[2], hv[3]);                                                             \
         *reinterpret_cast<uint2*>(a.h + o) = packed;                                                      \
-        if (a.tap_gate != nullptr) {                                                                      \
+        if (a.tap_gate != nullptr)                                                                        \
           *reinterpret_cast<int4*>(a.tap_gate + o) = make_int4(sum[0][0], sum[0][1], sum[0][2], sum[0][3]); \
+        if (a.tap_up != nullptr)                                                                          \
           *reinterpret_cast<int4*>(a.tap_up + o) =                                                        \
               make_int4(sum[NMAT - 1][0], sum[NMAT - 1][1], sum[NMAT - 1][2], sum[NMAT - 1][3]);          \
-        }                                                                                                 \
       } else {                                                                                            \
         *reinterpret_cast<int4*>(a.acc_out + static_cast<int64_t>(kc) * a.partial_stride + o) =           \
             make_int4(sum[0][0], sum[0][1], sum[0][2], sum[0][3]);                                        \

@@ -307,12 +307,14 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
             packed.x = cvt_pk_bf16(hv[0], hv[1]);
             packed.y = cvt_pk_bf16(hv[2], hv[3]);
             *reinterpret_cast<uint2*>(patch + r32 * PATCH_ROW + col * 2) = packed;
-            if (a.tap_gate != nullptr && rl < rows && n_wave0 + col < N) {   // parity taps (tests only)
+            if ((a.tap_gate != nullptr || a.tap_up != nullptr) && rl < rows && n_wave0 + col < N) {   // parity taps (tests only), each optional
               const int64_t o = static_cast<int64_t>(row0 + rl) * N + n_wave0 + col;
-              *reinterpret_cast<int4*>(a.tap_gate + o) = make_int4(acc[0][i][f][4 * q], acc[0][i][f][4 * q + 1],
-                                                                   acc[0][i][f][4 * q + 2], acc[0][i][f][4 * q + 3]);
-              *reinterpret_cast<int4*>(a.tap_up + o) = make_int4(acc[1][i][f][4 * q], acc[1][i][f][4 * q + 1],
-                                                                 acc[1][i][f][4 * q + 2], acc[1][i][f][4 * q + 3]);
+              if (a.tap_gate != nullptr)
+                *reinterpret_cast<int4*>(a.tap_gate + o) = make_int4(acc[0][i][f][4 * q], acc[0][i][f][4 * q + 1],
+                                                                     acc[0][i][f][4 * q + 2], acc[0][i][f][4 * q + 3]);
+              if (a.tap_up != nullptr)
+                *reinterpret_cast<int4*>(a.tap_up + o) = make_int4(acc[1][i][f][4 * q], acc[1][i][f][4 * q + 1],
+                                                                   acc[1][i][f][4 * q + 2], acc[1][i][f][4 * q + 3]);
             }
           } else {
             *reinterpret_cast<int4*>(patch + r32 * PATCH_ROW + col * 4) = make_int4(

@@ -239,6 +239,20 @@ def test_layer_zero_token_and_zero_rows_are_handled():
     assert not bits(out)[3].any() or np.abs(O.bf16_to_f32(bits(out)[3])).max() == 0
 
 
+@pytest.mark.parametrize("cfg", [W.C1, W.C1.with_tokens(300, name="c1_T300")], ids=lambda c: c.name)
+def test_layer_each_tap_is_optional_on_its_own(cfg):
+    """Every member of the tap struct may be NULL independently of the others (small-batch and
+    large-batch kernel families)."""
+    M = _m()
+    _log(f"single taps {cfg.name}")
+    gp = GpuProblem(cfg)
+    out_all, taps_all = _run_layer(gp, M.TAP_FIELDS)
+    for name in M.TAP_FIELDS:
+        out, taps = _run_layer(gp, (name,))
+        assert torch.equal(out, out_all), name
+        assert torch.equal(taps[name], taps_all[name]), name
+
+
 # ------------------------------------------------- full-size configurations (sampled)
 def _sample_tokens(ref_router, experts_allowed, n_max, seed):
     idx = ref_router
