@@ -65,31 +65,12 @@ __device__ __forceinline__ v4i unpack_codes(uint32_t w) {
 // 4-bank groups: conflict free (measured 2x faster than swizzling with row bits 0..2).
 __device__ __forceinline__ int lds_a_offset(int row, int chunk) { return row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4); }
 
-// One 128-channel K step of a wavefront: four 32-channel sub-steps; each reads BM_W
-// activation fragments from LDS and, per weight fragment, unpacks 16 codes per lane and
-// feeds BM_W MFMAs.
-template <typename Cfg>
-__device__ __forceinline__ void k_step(v16i (&acc)[Cfg::NMAT][Cfg::BM_W][Cfg::BN_W], const unsigned char* stage,
-                                       int a_row_base, int g, const u4 (&w)[Cfg::NMAT][Cfg::BN_W]) {
-  constexpr int BM_W = Cfg::BM_W, BN_W = Cfg::BN_W, NMAT = Cfg::NMAT;
-#pragma unroll
-  for (int s = 0; s < 4; ++s) {
-    v4i af[BM_W];
-#pragma unroll
-    for (int i = 0; i < BM_W; ++i)
-      af[i] = *reinterpret_cast<const v4i*>(stage + lds_a_offset(a_row_base + i * 32, 2 * s + g));
-#pragma unroll
-    for (int m = 0; m < NMAT; ++m)
-#pragma unroll
-      for (int f = 0; f < BN_W; ++f) {
-        const v4i bf = unpack_codes(w[m][f][s]);
-#pragma unroll
-        for (int i = 0; i < BM_W; ++i)
-          acc[m][i][f] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bf, af[i], acc[m][i][f], 0, 0, 0);
-      }
-  }
-}
-
+// One 128-channel K step of a wavefront is four 32-channel sub-steps; each reads BM_W
+// activation fragments from LDS and, per weight fragment, unpacks 16 codes per lane and feeds
+// BM_W MFMAs (MOTE_KSTEP in the kernel).  The global loads of the NEXT K step are spread over
+// the four sub-steps: issued in one burst right after the barrier, eight wavefronts x eight
+// 1-KiB loads fill the CU's vector-memory queue and every wavefront stalls in issue (measured:
+// about 800 cycles per K step) before it reaches its first MFMA.
 template <typename Cfg>
 __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_kernel(RoutedGemmArgs a, int n_ntiles, int kplanes, int ktp) {
   constexpr int NMAT = Cfg::NMAT, BM_W = Cfg::BM_W, BN_W = Cfg::BN_W;
@@ -240,25 +221,50 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
     // LDS stages are named statically (no register copies on the back-edge): while K step kt
     // is contracted, the packed weights and the activation tile of kt+1 are in flight.
     const int ktl = min(ktp, KT - kc * ktp);   // K steps of this plane
+    // Quarter in which each load of the next K step is issued.  Gate-up: one activation pass and one
+    // weight fragment per quarter; down: the activation passes first (their LDS store comes first).
+#define MOTE_PF_A(p) (Cfg::MODE == 0 ? ((p) & 3) : 0)
+#define MOTE_PF_W(j) ((j) & 3)
+#define MOTE_KSTEP(stage_, wc_, wn_, ktn_, PREFETCH_)                                                   \
+  {                                                                                                    \
+    v4i af_[2][BM_W];                                                                                  \
+    _Pragma("unroll") for (int i = 0; i < BM_W; ++i)                                                   \
+      af_[0][i] = *reinterpret_cast<const v4i*>((stage_) + lds_a_offset(a_row_base + i * 32, g));      \
+    _Pragma("unroll") for (int s = 0; s < 4; ++s) {                                                    \
+      if (PREFETCH_) { /* quarter s of the next K step's loads */                                      \
+        _Pragma("unroll") for (int p = 0; p < Cfg::A_PASSES; ++p)                                      \
+          if (MOTE_PF_A(p) == s) a_reg[p] = *reinterpret_cast<const u4*>(q_base + static_cast<int64_t>(ktn_) * 128 + a_off[p]); \
+        _Pragma("unroll") for (int j = 0; j < NMAT * BN_W; ++j)                                        \
+          if (MOTE_PF_W(j) == s) wn_[j / BN_W][j % BN_W] = *reinterpret_cast<const u4*>(                    \
+              w_base[j / BN_W][j % BN_W] + static_cast<int64_t>(ktn_) * 1024 + w_lane);                \
+      }                                                                                                \
+      if (s < 3) {                                                                                     \
+        _Pragma("unroll") for (int i = 0; i < BM_W; ++i)                                               \
+          af_[(s + 1) & 1][i] = *reinterpret_cast<const v4i*>((stage_) + lds_a_offset(a_row_base + i * 32, 2 * (s + 1) + g)); \
+      }                                                                                                \
+      _Pragma("unroll") for (int m = 0; m < NMAT; ++m)                                                 \
+        _Pragma("unroll") for (int f = 0; f < BN_W; ++f) {                                             \
+          const v4i bf_ = unpack_codes(wc_[m][f][s]);                                                  \
+          _Pragma("unroll") for (int i = 0; i < BM_W; ++i)                                             \
+            acc[m][i][f] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bf_, af_[s & 1][i], acc[m][i][f], 0, 0, 0); \
+        }                                                                                              \
+      __builtin_amdgcn_sched_barrier(0);  /* keep each quarter's loads with its quarter */             \
+    }                                                                                                  \
+  }
     int kt = 0;
     for (; kt + 1 < ktl; kt += 2) {
-      MOTE_LOAD_A(kt + 1);  // issued first: needed first (LDS store at the end of this half)
-      MOTE_LOAD_W(w_b, kt + 1);
-      __builtin_amdgcn_sched_barrier(0);  // keep the prefetch loads ahead of the contraction
-      k_step<Cfg>(acc, stage0, a_row_base, g, w_a);
-      __builtin_amdgcn_sched_barrier(0);
+      MOTE_KSTEP(stage0, w_a, w_b, kt + 1, true);
       MOTE_STORE_A(stage1);
       __syncthreads();
       const int kn = min(kt + 2, ktl - 1);  // the last prefetch of an even-length loop is a harmless repeat
-      MOTE_LOAD_A(kn);
-      MOTE_LOAD_W(w_a, kn);
-      __builtin_amdgcn_sched_barrier(0);
-      k_step<Cfg>(acc, stage1, a_row_base, g, w_b);
-      __builtin_amdgcn_sched_barrier(0);
+      MOTE_KSTEP(stage1, w_b, w_a, kn, true);
       MOTE_STORE_A(stage0);
       __syncthreads();
     }
-    if (kt < ktl) k_step<Cfg>(acc, stage0, a_row_base, g, w_a);
+    if (kt < ktl) MOTE_KSTEP(stage0, w_a, w_b, 0, false);
+#undef MOTE_KSTEP
+#undef MOTE_PF_A
+#undef MOTE_PF_W
 
     // (4) start the next tile now: its gather indices, row scalars and first K step travel
     // while this tile runs its epilogue.
