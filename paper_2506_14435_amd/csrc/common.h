@@ -68,4 +68,12 @@ __device__ __forceinline__ int quant_i8(float x, float s) {
   return static_cast<int>(r);
 }
 
+// Load of a wavefront-uniform value through the constant address space: a scalar load
+// (s_load, counted by lgkmcnt) instead of a vector-memory operation.  Only for memory that no
+// kernel writes while this one runs.
+template <typename T>
+__device__ __forceinline__ T load_uniform(const T* p) {
+  return *(const __attribute__((address_space(4))) T*)(p);
+}
+
 }  // namespace mote

@@ -44,6 +44,7 @@ struct RoutedGemmArgs {
   int max_tiles;            // upper bound on *plan.n_tiles known on the host
   int tile_m;               // rows per plan tile
   int K, N;                 // contraction length, output width (per matrix)
+  int64_t q_rows;           // rows of q (q_rows * K <= 2^31: 32-bit buffer offsets)
   uint16_t* h;              // gate-up: bf16 [R, N]
   int32_t* acc_out;         // down: int32 [R, N] (decode: partial planes [planes][R, N])
   int64_t partial_stride;   // elements between partial planes (down projections)

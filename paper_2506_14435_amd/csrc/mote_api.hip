@@ -30,6 +30,14 @@ struct Workspace {
   int y_planes;      // partial planes of the shared expert output
 };
 
+// Kernels address activations with 32-bit byte offsets.
+bool batch_ok(const mote_layer* l, int T) {
+  const int64_t lim = int64_t{1} << 31;
+  const int64_t R = static_cast<int64_t>(T) * l->top_k;
+  return R < (1 << 24) && static_cast<int64_t>(T) * l->d_model <= lim && R * l->d_ff_routed <= lim &&
+         static_cast<int64_t>(T) * l->d_ff_shared <= lim;
+}
+
 bool layer_shape_ok(const mote_layer* l) {
   if (l->d_model <= 0 || l->d_ff_shared <= 0 || l->d_ff_routed <= 0) return false;
   if (l->d_model % 128 || l->d_ff_shared % 128 || l->d_ff_routed % 128) return false;
@@ -150,7 +158,7 @@ mote_status mote_router_topk(const void* x, const void* w_router, const float* r
 
 size_t mote_layer_workspace_bytes(const mote_layer* layer, int T_max) {
   if (!layer || T_max < 0 || !layer_shape_ok(layer)) return 0;
-  if (static_cast<int64_t>(T_max) * layer->top_k >= (1 << 24)) return 0;
+  if (!batch_ok(layer, T_max)) return 0;
   // The kernel family (decode / large batch) and with it the number of partial planes depends
   // on T; a workspace sized for T_max must serve every T <= T_max, so take the largest layout.
   size_t need = carve(layer, T_max, nullptr).bytes;
@@ -167,7 +175,7 @@ mote_status mote_layer_forward(const mote_layer* layer, const void* x, int T, vo
                                size_t workspace_bytes, const mote_taps* taps, void* hip_stream) {
   if (!layer || T < 0) return MOTE_ERR_INVALID_ARG;
   if (!layer_shape_ok(layer)) return MOTE_ERR_UNSUPPORTED_SHAPE;
-  if (static_cast<int64_t>(T) * layer->top_k >= (1 << 24)) return MOTE_ERR_UNSUPPORTED_SHAPE;
+  if (!batch_ok(layer, T)) return MOTE_ERR_UNSUPPORTED_SHAPE;
   if (T == 0) return MOTE_OK;
   if (!x || !out || !workspace) return MOTE_ERR_INVALID_ARG;
   if (!layer->w_router || !layer->ws_gate || !layer->ws_up || !layer->ws_down || !layer->wt_gate || !layer->wt_up ||
@@ -201,7 +209,7 @@ mote_status mote_layer_forward(const mote_layer* layer, const void* x, int T, vo
   ga.q = w.q_x; ga.gather = w.tok_of; ga.beta = w.beta_x; ga.rowsum = w.rs_x;
   ga.w_gate = layer->wt_gate; ga.w_up = layer->wt_up; ga.alpha = layer->alpha;
   ga.plan = plan; ga.max_tiles = R / tile_m + E; ga.tile_m = tile_m;
-  ga.K = d; ga.N = Fr; ga.h = w.h; ga.acc_out = nullptr;
+  ga.K = d; ga.N = Fr; ga.q_rows = T; ga.h = w.h; ga.acc_out = nullptr;
   ga.tap_gate = taps ? taps->acc_gate : nullptr;
   ga.tap_up = taps ? taps->acc_up : nullptr;
   ga.partial_stride = 0; ga.planes = 1;
@@ -213,7 +221,7 @@ mote_status mote_layer_forward(const mote_layer* layer, const void* x, int T, vo
   RoutedGemmArgs gd = ga;
   gd.q = w.q_h; gd.gather = nullptr; gd.beta = w.beta_h; gd.rowsum = w.rs_h;
   gd.w_gate = layer->wt_down; gd.w_up = nullptr;
-  gd.K = Fr; gd.N = d; gd.h = nullptr; gd.acc_out = w.acc_down; gd.tap_gate = nullptr; gd.tap_up = nullptr;
+  gd.K = Fr; gd.N = d; gd.q_rows = R; gd.h = nullptr; gd.acc_out = w.acc_down; gd.tap_gate = nullptr; gd.tap_up = nullptr;
   gd.partial_stride = static_cast<int64_t>(R) * d; gd.planes = w.d_planes;
   MOTE_HIP(decode_routed ? launch_routed_decode_down(gd, stream) : launch_routed_down(gd, stream));
   MOTE_HIP(mark(5));

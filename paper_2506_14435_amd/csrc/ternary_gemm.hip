@@ -7,9 +7,10 @@
 //
 // Work decomposition: the dispatch plan lists row tiles (one expert each, BM rows); a
 // workgroup owns one row tile x one block of BN output channels and walks K in steps of
-// 128.  Activations (int8, gathered through tok_of in gate-up mode) are staged in LDS,
-// 16-byte chunks XOR-swizzled by row so that ds_read_b128 of 32 consecutive rows is
-// conflict free.  Packed weights never touch LDS: a tile of 32 rows x 128 channels is
+// 128.  Activations (int8, gathered through tok_of in gate-up mode) are loaded straight
+// into LDS (global_load_lds), 16-byte chunks XOR-swizzled by row so that ds_read_b128 of
+// 32 consecutive rows is conflict free; three stages, requested two K steps ahead.
+// Packed weights never touch LDS: a tile of 32 rows x 128 channels is
 // 1 KiB = one 16-byte load per lane, each 32-bit word expands with (w >> 2j) & 0x03030303
 // into the four operand registers of one v_mfma_i32_32x32x32_i8.  The codes are t+1, so
 // the accumulator holds sum (t+1) q; the row sum of q is subtracted in the epilogue.
@@ -20,7 +21,7 @@
 // v of lane l is output channel 8*(v/4) + 4*(l/32) + v%4 of dispatch row l%32.
 //
 // Epilogue: every wavefront transposes its result fragments through a private LDS patch so
-// that the global stores are whole rows of 128 (bf16) or 256 (int32) contiguous bytes.
+// that a global store instruction covers whole rows of a 32-row block.
 #include <stdlib.h>
 
 #include "common.h"
@@ -40,14 +41,18 @@ struct RoutedCfg {
   static constexpr int THREADS = 64 * WAVES;
   static constexpr int ROWS_PER_PASS = THREADS / 8;
   static constexpr int A_PASSES = BM / ROWS_PER_PASS;
-  static constexpr int STAGE_BYTES = BM * 128;
-  // epilogue patch of one wavefront: 32 rows x (BN_W*32 outputs) + 16 bytes of row padding
+  static constexpr int A_BYTES = BM * 128;                       // int8 activation tile of one K step
+  static constexpr int W_FRAGS = NMAT * BN / 32;                 // packed 1-KiB weight fragments of one K step
+  static constexpr int W_PER_WAVE = W_FRAGS / WAVES;
+  static constexpr int STAGE_BYTES = A_BYTES + W_FRAGS * 1024;
+  // epilogue patch of one wavefront: 32 rows x PATCH_F fragments of 32 outputs + 16 bytes of row padding
   static constexpr int OUT_BYTES = MODE_ == 0 ? 2 : 4;
-  static constexpr int PATCH_ROW = BN_W_ * 32 * OUT_BYTES + 16;
+  static constexpr int PATCH_F = MODE_ == 0 ? BN_W_ : 1;
+  static constexpr int PATCH_ROW = PATCH_F * 32 * OUT_BYTES + 16;
   static constexpr int PATCH_BYTES = 32 * PATCH_ROW;
-  static constexpr int LDS_BYTES = 2 * STAGE_BYTES > WAVES * PATCH_BYTES ? 2 * STAGE_BYTES : WAVES * PATCH_BYTES;
   static_assert(BM % ROWS_PER_PASS == 0, "activation loader covers the tile in whole passes");
-  static_assert(64 % (BN_W_ * 32 * OUT_BYTES / 16) == 0, "an epilogue read covers whole rows");
+  static_assert(W_FRAGS % WAVES == 0, "every wavefront requests the same number of weight fragments");
+  static_assert(64 % (PATCH_F * 32 * OUT_BYTES / 16) == 0, "an epilogue read covers whole rows");
 };
 
 __device__ __forceinline__ v4i unpack_codes(uint32_t w) {
@@ -67,7 +72,7 @@ __device__ __forceinline__ int lds_a_offset(int row, int chunk) { return row * 1
 
 // One 128-channel K step of a wavefront is four 32-channel sub-steps; each reads BM_W
 // activation fragments from LDS and, per weight fragment, unpacks 16 codes per lane and feeds
-// BM_W MFMAs (MOTE_KSTEP in the kernel).  The global loads of the NEXT K step are spread over
+// BM_W MFMAs (MOTE_KSTEP in the kernel).  The global loads of a later K step are spread over
 // the four sub-steps: issued in one burst right after the barrier, eight wavefronts x eight
 // 1-KiB loads fill the CU's vector-memory queue and every wavefront stalls in issue (measured:
 // about 800 cycles per K step) before it reaches its first MFMA.
@@ -75,22 +80,27 @@ template <typename Cfg>
 __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_kernel(RoutedGemmArgs a, int n_ntiles, int kplanes, int ktp) {
   constexpr int NMAT = Cfg::NMAT, BM_W = Cfg::BM_W, BN_W = Cfg::BN_W;
   constexpr int BM = Cfg::BM, BN = Cfg::BN, THREADS = Cfg::THREADS;
+  constexpr int A_BYTES = Cfg::A_BYTES, STAGE_BYTES = Cfg::STAGE_BYTES;
+  constexpr int NB = BN / 32;                       // 32-channel blocks of the tile
+  constexpr int W_PER_WAVE = Cfg::W_PER_WAVE;       // weight fragments a wavefront requests per K step
+  constexpr int NLOAD = Cfg::A_PASSES + W_PER_WAVE; // vector-memory operations a wavefront issues per K step
   static_assert(BM <= THREADS, "one thread per tile row publishes the row metadata");
-  __shared__ __attribute__((aligned(16))) unsigned char s_a[Cfg::LDS_BYTES];
-  __shared__ float s_scale[BM];
-  __shared__ int s_rs[BM];
+  static_assert(Cfg::WAVES == 4 && Cfg::ROWS_PER_PASS == 32, "a loader pass is 4 wavefronts x 8 rows");
+  static_assert(NLOAD < 16, "fits the low vmcnt field");
+  __shared__ __attribute__((aligned(16))) unsigned char s_lds[3 * STAGE_BYTES];
+  __shared__ float s_beta[2][BM];   // row metadata (absmax, integer row sum), double buffered by tile parity
+  __shared__ int s_rs[2][BM];
 
   const int K = a.K, N = a.N;
   const int KT = K >> 7;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
   const int wm = wave % Cfg::WAVES_M, wn = wave / Cfg::WAVES_M;
-  const int wn_u = __builtin_amdgcn_readfirstlane(wn);   // wavefront-uniform: keeps weight bases scalar
   const int r32 = lane & 31, g = lane >> 5;
   const int a_row_base = wm * BM_W * 32 + r32;
-  const unsigned char* const q_base = reinterpret_cast<const unsigned char*>(a.q);
   const int64_t expert_words = static_cast<int64_t>(N) * K / 16;
-  unsigned char* const stage0 = s_a;
-  unsigned char* const stage1 = s_a + Cfg::STAGE_BYTES;
+  // LDS byte address of the stage area (what M0 takes for a direct-to-LDS load)
+  const uint32_t lds0 = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) unsigned char*)s_lds);
 
   // Persistent workgroups: the grid is one wave of resident workgroups; each walks a strided
   // list of (row tile, channel tile) pairs.  Workgroups are dealt to the 8 XCDs round-robin
@@ -103,7 +113,7 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
   // plane writes its own partial output that the combine kernel adds.
   n_ntiles *= kplanes;
   const int xcd = blockIdx.x & 7;
-  const int n_mtiles = a.plan.n_tiles[0];
+  const int n_mtiles = load_uniform(a.plan.n_tiles);
   const bool split_n = n_ntiles >= 16;
   const int xcd_ntiles = split_n ? (n_ntiles - xcd + 7) >> 3 : n_ntiles;
   const int xcd_mtiles = split_n ? n_mtiles : (n_mtiles - xcd + 7) >> 3;
@@ -112,23 +122,46 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
   int slot = blockIdx.x >> 3;
   if (slot >= xcd_work) return;
 
-  // Loader state of the tile being contracted.  The same variables are refilled for the
-  // NEXT tile while the current one is still in its epilogue (see the end of the loop).
-  // Addresses are kept as uniform 64-bit bases (scalar registers) plus 32-bit per-lane byte
-  // offsets, so each global load needs one address VGPR.
-  uint32_t a_off[Cfg::A_PASSES];           // byte offset of this thread's row chunk inside q
-  int a_dst[Cfg::A_PASSES];
-  const unsigned char* w_base[NMAT][BN_W]; // uniform: first packed tile of the fragment's channel rows
+  // Loader.  Both operands travel global -> LDS directly (buffer_load ... lds, 16 bytes per
+  // lane, no register holds bytes in flight) into one of three stages, two K steps ahead of
+  // the MFMAs that consume them.
+  //   activations: a wavefront load fills 8 consecutive 128-byte tile rows; lane l lands at
+  //     byte 16*l of that 1-KiB block, so the XOR swizzle is applied on the global side (lane l
+  //     fetches chunk (l&7) ^ swizzle(row));
+  //   weights: a packed 32-channel x 128 fragment is 1 KiB = one wavefront load, stored as is.
+  // The loads are written in assembly: the compiler has no exact model of outstanding
+  // direct-to-LDS loads across this loop's control flow and would drain the queue before the
+  // LDS reads of every K step.  Vector-memory operations complete in issue order, so waiting
+  // for "all but the NLOAD youngest" retires the K step that is about to be contracted while
+  // the following one stays in flight; anything else the wavefront has issued since (stores of
+  // the previous epilogue, gather loads) only makes that wait stricter.
+  constexpr int kBufferFlags = 0x00020000;   // raw buffer, 32-bit data format
+  v4i rsrc_q;
+  {
+    const uint64_t p = reinterpret_cast<uint64_t>(a.q);
+    rsrc_q.x = static_cast<int>(static_cast<uint32_t>(p));
+    rsrc_q.y = static_cast<int>(static_cast<uint32_t>(p >> 32) & 0xFFFFu);
+    rsrc_q.z = static_cast<int>(a.q_rows * K);
+    rsrc_q.w = kBufferFlags;
+  }
+  v4i rsrc_meta;                           // beta (wavefronts 0 and 1) or rowsum (2 and 3): one 4-byte value per row of q
+  {
+    const uint64_t p = wave_u < 2 ? reinterpret_cast<uint64_t>(a.beta) : reinterpret_cast<uint64_t>(a.rowsum);
+    rsrc_meta.x = static_cast<int>(static_cast<uint32_t>(p));
+    rsrc_meta.y = static_cast<int>(static_cast<uint32_t>(p >> 32) & 0xFFFFu);
+    rsrc_meta.z = static_cast<int>(a.q_rows * 4);
+    rsrc_meta.w = kBufferFlags;
+  }
+  v4i rsrc_w[W_PER_WAVE];                  // the expert's packed matrix each of this wavefront's fragments lives in
+  uint32_t w_soff[W_PER_WAVE];             // uniform: byte offset of that fragment's first tile in the plane
+  uint32_t a_off[Cfg::A_PASSES];           // byte offset of this lane's 16 bytes inside q, K step 0 of the plane
   const uint32_t w_lane = lane * 16;
-  u4 w_a[NMAT][BN_W], w_b[NMAT][BN_W];
-  u4 a_reg[Cfg::A_PASSES];
-  int src_row[Cfg::A_PASSES];   // row of q (gathered) per loader pass
-  int meta_row = 0;             // row whose beta / rowsum this thread publishes (tid < BM)
-  float meta_beta = 1.0f;
-  int meta_rs = 0;
-  int mt, nt, kc, expert, row0, rows;
-#pragma unroll
-  for (int p = 0; p < Cfg::A_PASSES; ++p) a_dst[p] = lds_a_offset(p * Cfg::ROWS_PER_PASS + (tid >> 3), tid & 7);
+  const uint32_t a_chunk = static_cast<uint32_t>(((tid & 7) ^ ((tid >> 4) & 7)) << 4);
+  int src_row[Cfg::A_PASSES];   // row of q (gathered) per loader pass, next tile
+  int meta_row = 0;             // row of q whose beta (wavefronts 0-1) or row sum (2-3) this lane requests
+  int mt, nt, kc, expert, row0, rows, ktl;
+  int par = 0;
+  int st_cur = 0, st_nxt = STAGE_BYTES, st_nx2 = 2 * STAGE_BYTES;   // stage of K step kt, kt+1, kt+2 (byte offsets)
 
 #define MOTE_DECODE(slot_, mt_, nt_, kc_)                                       \
   {                                                                             \
@@ -138,77 +171,107 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
     nt_ = ntk_ / kplanes;                                                       \
     kc_ = ntk_ - nt_ * kplanes;                                                 \
   }
+  // gate-up rows are gathered through tok_of (a.gather), down rows are the dispatch rows themselves
 #define MOTE_GATHER(row0_, rows_)                                                                  \
   {                                                                                                \
     _Pragma("unroll") for (int p = 0; p < Cfg::A_PASSES; ++p) {                                    \
       const int rslot_ = (row0_) + min(p * Cfg::ROWS_PER_PASS + (tid >> 3), (rows_)-1);            \
-      src_row[p] = a.gather ? a.gather[rslot_] : rslot_;                                           \
+      if constexpr (Cfg::MODE == 0) src_row[p] = a.gather[rslot_];                                 \
+      else src_row[p] = rslot_;                                                                    \
     }                                                                                              \
-    const int mslot_ = (row0_) + min(tid < BM ? tid : 0, (rows_)-1);                               \
-    meta_row = a.gather ? a.gather[mslot_] : mslot_;                                               \
+    const int mslot_ = (row0_) + min(tid & (BM - 1), (rows_)-1);                                   \
+    if constexpr (Cfg::MODE == 0) meta_row = a.gather[mslot_];                                     \
+    else meta_row = mslot_;                                                                        \
   }
+  // Fragment ids of a stage: matrix m, channel block cb -> m*NB + cb.  Wavefront w requests the
+  // ids w*W_PER_WAVE ... ; every wavefront later reads the ids of its own channel blocks.
 #define MOTE_POINTERS(expert_, nt_, kc_)                                                           \
   {                                                                                                \
     _Pragma("unroll") for (int p = 0; p < Cfg::A_PASSES; ++p)                                      \
-      a_off[p] = static_cast<uint32_t>(src_row[p]) * static_cast<uint32_t>(K) + (tid & 7) * 16 +   \
+      a_off[p] = static_cast<uint32_t>(src_row[p]) * static_cast<uint32_t>(K) + a_chunk +          \
                  static_cast<uint32_t>((kc_) * ktp) * 128u;                                        \
-    _Pragma("unroll") for (int f = 0; f < BN_W; ++f) {                                             \
-      const int n_frag_ = (nt_) * BN + wn_u * BN_W * 32 + f * 32;                                  \
+    _Pragma("unroll") for (int i = 0; i < W_PER_WAVE; ++i) {                                       \
+      const int fid_ = wave_u * W_PER_WAVE + i;                                                    \
+      const int m_ = fid_ / NB, cb_ = fid_ - m_ * NB;                                              \
+      const int n_frag_ = (nt_) * BN + cb_ * 32;                                                   \
       const int nt32_ = (n_frag_ < N ? n_frag_ : 0) >> 5; /* fragments past N read tile 0 */       \
-      const int64_t off_ = (static_cast<int64_t>(expert_) * expert_words +                         \
-                            (static_cast<int64_t>(nt32_) * KT + (kc_) * ktp) * 256) * 4;           \
-      w_base[0][f] = reinterpret_cast<const unsigned char*>(a.w_gate) + off_;                      \
-      if constexpr (NMAT == 2) w_base[1][f] = reinterpret_cast<const unsigned char*>(a.w_up) + off_; \
+      w_soff[i] = static_cast<uint32_t>(nt32_ * KT + (kc_) * ktp) * 1024u;                         \
+      const uint32_t* mat_ = (NMAT == 2 && m_ == 1) ? a.w_up : a.w_gate;                           \
+      const uint64_t p_ = reinterpret_cast<uint64_t>(mat_ + static_cast<int64_t>(expert_) * expert_words); \
+      rsrc_w[i].x = static_cast<int>(static_cast<uint32_t>(p_));                                   \
+      rsrc_w[i].y = static_cast<int>(static_cast<uint32_t>(p_ >> 32) & 0xFFFFu);                   \
+      rsrc_w[i].z = static_cast<int>(expert_words * 4);                                            \
+      rsrc_w[i].w = kBufferFlags;                                                                  \
     }                                                                                              \
-    meta_beta = a.beta[meta_row];                                                                  \
-    meta_rs = a.rowsum[meta_row];                                                                  \
   }
-#define MOTE_LOAD_W(dst_, kt_)                                                  \
-  _Pragma("unroll") for (int m = 0; m < NMAT; ++m)                              \
-    _Pragma("unroll") for (int f = 0; f < BN_W; ++f)                            \
-      dst_[m][f] = *reinterpret_cast<const u4*>(w_base[m][f] + static_cast<int64_t>(kt_) * 1024 + w_lane)
-#define MOTE_LOAD_A(kt_)                                                        \
-  _Pragma("unroll") for (int p = 0; p < Cfg::A_PASSES; ++p)                     \
-    a_reg[p] = *reinterpret_cast<const u4*>(q_base + static_cast<int64_t>(kt_) * 128 + a_off[p])
-#define MOTE_STORE_A(stage_)                                                    \
-  _Pragma("unroll") for (int p = 0; p < Cfg::A_PASSES; ++p)                     \
-    *reinterpret_cast<u4*>((stage_) + a_dst[p]) = a_reg[p]
+  // one 16-byte-per-lane direct load: LDS byte address (uniform), lane offset, buffer, scalar offset
+#define MOTE_DMA(lds_, voff_, rsrc_, soff_)                                                        \
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"           \
+               :: "s"(lds_), "v"(voff_), "s"(rsrc_), "s"(soff_) : "memory")
+#define MOTE_DMA_A(stage_, ks_, p_)                                                                \
+  MOTE_DMA(lds0 + (stage_) + ((p_) * Cfg::ROWS_PER_PASS + wave_u * 8) * 128, a_off[p_], rsrc_q, (ks_) * 128)
+#define MOTE_DMA_W(stage_, ks_, i_)                                                                \
+  MOTE_DMA(lds0 + (stage_) + A_BYTES + (wave_u * W_PER_WAVE + (i_)) * 1024, w_lane, rsrc_w[i_],    \
+           w_soff[i_] + (ks_) * 1024)
+  // Row metadata of a tile into the parity buffer par_: lane l of wavefront 0/1 brings beta of
+  // tile row 64*w + l, of wavefront 2/3 the row sum of tile row 64*(w-2) + l (4 bytes per lane).
+  // Issued before the tile's first K step, so the wait for that step covers it.
+#define MOTE_DMA_META(par_)                                                                        \
+  {                                                                                                \
+    const uint32_t dst_ = wave_u < 2                                                               \
+        ? (uint32_t)(uintptr_t)((__attribute__((address_space(3))) float*)&s_beta[par_][wave_u * 64]) \
+        : (uint32_t)(uintptr_t)((__attribute__((address_space(3))) int*)&s_rs[par_][(wave_u - 2) * 64]); \
+    const uint32_t voff_ = static_cast<uint32_t>(meta_row) * 4u;                                   \
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds"           \
+                 :: "s"(dst_), "v"(voff_), "s"(rsrc_meta) : "memory");                             \
+  }
+  // all loads of one K step at once (tile start)
+#define MOTE_ISSUE_STEP(stage_, ks_)                                                               \
+  {                                                                                                \
+    _Pragma("unroll") for (int p = 0; p < Cfg::A_PASSES; ++p) MOTE_DMA_A(stage_, ks_, p);          \
+    _Pragma("unroll") for (int i = 0; i < W_PER_WAVE; ++i) MOTE_DMA_W(stage_, ks_, i);             \
+  }
+  // in_flight_: whether the loads of one more K step were issued after the ones needed now
+#define MOTE_WAIT_BARRIER(in_flight_)                                                              \
+  {                                                                                                \
+    if (in_flight_) asm volatile("s_waitcnt vmcnt(%0)" :: "n"(NLOAD) : "memory");                  \
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                                          \
+    asm volatile("s_barrier" ::: "memory");                                                        \
+  }
 
   // ---- first tile: the whole dependent chain (plan -> gather -> rows) is paid once ----
   MOTE_DECODE(slot, mt, nt, kc);
-  expert = a.plan.tile_expert[mt];
-  row0 = a.plan.tile_row0[mt];
-  rows = a.plan.tile_rows[mt];
+  expert = load_uniform(a.plan.tile_expert + mt);
+  row0 = load_uniform(a.plan.tile_row0 + mt);
+  rows = load_uniform(a.plan.tile_rows + mt);
+  ktl = min(ktp, KT - kc * ktp);
   MOTE_GATHER(row0, rows);
   MOTE_POINTERS(expert, nt, kc);
-  MOTE_LOAD_A(0);
-  MOTE_LOAD_W(w_a, 0);
+  MOTE_DMA_META(0);
+  MOTE_ISSUE_STEP(st_cur, 0);
+  if (ktl > 1) MOTE_ISSUE_STEP(st_nxt, 1);
 
   for (;;) {
-    // (1) publish this tile's row metadata and first activation K step
-    if (tid < BM) {
-      s_scale[tid] = meta_beta / 127.0f;
-      s_rs[tid] = meta_rs;
-    }
-    MOTE_STORE_A(stage0);
-    // (2) coordinates of the next tile of this workgroup (uniform scalar loads)
+    // (1) coordinates of the next tile of this workgroup (uniform scalar loads)
     const int nslot = slot + stride;
     const bool has_next = nslot < xcd_work;
     int mt2 = mt, nt2 = nt, kc2 = kc, expert2 = expert, row02 = row0, rows2 = rows;
     if (has_next) {
       MOTE_DECODE(nslot, mt2, nt2, kc2);
-      expert2 = a.plan.tile_expert[mt2];
-      row02 = a.plan.tile_row0[mt2];
-      rows2 = a.plan.tile_rows[mt2];
+      expert2 = load_uniform(a.plan.tile_expert + mt2);
+      row02 = load_uniform(a.plan.tile_row0 + mt2);
+      rows2 = load_uniform(a.plan.tile_rows + mt2);
     }
-    __syncthreads();
+    MOTE_WAIT_BARRIER(ktl > 1);   // K step 0 (and the metadata) visible to every wavefront
     const int n_wave0 = nt * BN + wn * BN_W * 32;  // first output channel of this wavefront
+    const float al0 = load_uniform(a.alpha + expert * 3 + (Cfg::MODE == 0 ? 0 : 2));
+    const float al1 = Cfg::MODE == 0 ? load_uniform(a.alpha + expert * 3 + 1) : 0.0f;
 
     // Accumulators start at -rowsum(q): the stored codes are t+1, so sum (t+1) q - sum q = sum t q.
     v16i acc[NMAT][BM_W][BN_W];
 #pragma unroll
     for (int i = 0; i < BM_W; ++i) {
-      const int nrs = kc == 0 ? -s_rs[wm * BM_W * 32 + i * 32 + r32] : 0;   // the correction enters plane 0 only
+      const int nrs = kc == 0 ? -s_rs[par][wm * BM_W * 32 + i * 32 + r32] : 0;   // the correction enters plane 0 only
 #pragma unroll
       for (int m = 0; m < NMAT; ++m)
 #pragma unroll
@@ -216,146 +279,161 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
 #pragma unroll
           for (int v = 0; v < 16; ++v) acc[m][i][f][v] = nrs;
     }
+    // row gather of the next tile: the indices are in registers when the K loop ends
+    if (has_next) MOTE_GATHER(row02, rows2);
 
-    // (3) K loop.  Unrolled by two K steps so that the two weight register sets and the two
-    // LDS stages are named statically (no register copies on the back-edge): while K step kt
-    // is contracted, the packed weights and the activation tile of kt+1 are in flight.
-    const int ktl = min(ktp, KT - kc * ktp);   // K steps of this plane
-    // Quarter in which each load of the next K step is issued.  Gate-up: one activation pass and one
-    // weight fragment per quarter; down: the activation passes first (their LDS store comes first).
-#define MOTE_PF_A(p) (Cfg::MODE == 0 ? ((p) & 3) : 0)
-#define MOTE_PF_W(j) ((j) & 3)
-#define MOTE_KSTEP(stage_, wc_, wn_, ktn_, PREFETCH_)                                                   \
-  {                                                                                                    \
-    v4i af_[2][BM_W];                                                                                  \
-    _Pragma("unroll") for (int i = 0; i < BM_W; ++i)                                                   \
-      af_[0][i] = *reinterpret_cast<const v4i*>((stage_) + lds_a_offset(a_row_base + i * 32, g));      \
-    _Pragma("unroll") for (int s = 0; s < 4; ++s) {                                                    \
-      if (PREFETCH_) { /* quarter s of the next K step's loads */                                      \
-        _Pragma("unroll") for (int p = 0; p < Cfg::A_PASSES; ++p)                                      \
-          if (MOTE_PF_A(p) == s) a_reg[p] = *reinterpret_cast<const u4*>(q_base + static_cast<int64_t>(ktn_) * 128 + a_off[p]); \
-        _Pragma("unroll") for (int j = 0; j < NMAT * BN_W; ++j)                                        \
-          if (MOTE_PF_W(j) == s) wn_[j / BN_W][j % BN_W] = *reinterpret_cast<const u4*>(                    \
-              w_base[j / BN_W][j % BN_W] + static_cast<int64_t>(ktn_) * 1024 + w_lane);                \
-      }                                                                                                \
-      if (s < 3) {                                                                                     \
-        _Pragma("unroll") for (int i = 0; i < BM_W; ++i)                                               \
-          af_[(s + 1) & 1][i] = *reinterpret_cast<const v4i*>((stage_) + lds_a_offset(a_row_base + i * 32, 2 * (s + 1) + g)); \
-      }                                                                                                \
-      _Pragma("unroll") for (int m = 0; m < NMAT; ++m)                                                 \
-        _Pragma("unroll") for (int f = 0; f < BN_W; ++f) {                                             \
-          const v4i bf_ = unpack_codes(wc_[m][f][s]);                                                  \
-          _Pragma("unroll") for (int i = 0; i < BM_W; ++i)                                             \
-            acc[m][i][f] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bf_, af_[s & 1][i], acc[m][i][f], 0, 0, 0); \
-        }                                                                                              \
-      __builtin_amdgcn_sched_barrier(0);  /* keep each quarter's loads with its quarter */             \
-    }                                                                                                  \
-  }
-    int kt = 0;
-    for (; kt + 1 < ktl; kt += 2) {
-      MOTE_KSTEP(stage0, w_a, w_b, kt + 1, true);
-      MOTE_STORE_A(stage1);
-      __syncthreads();
-      const int kn = min(kt + 2, ktl - 1);  // the last prefetch of an even-length loop is a harmless repeat
-      MOTE_KSTEP(stage1, w_b, w_a, kn, true);
-      MOTE_STORE_A(stage0);
-      __syncthreads();
+    // (2) K loop.  K step kt contracts stage st_cur while the loads of kt+2 are issued, one
+    // quarter of them per 32-channel sub-step (a burst of loads right after the barrier fills
+    // the CU's vector-memory queue and stalls every wavefront in issue), into the stage that the
+    // barrier at the end of step kt-1 released.
+    for (int kt = 0; kt < ktl; ++kt) {
+      const bool pf = kt + 2 < ktl;
+      const unsigned char* const st = s_lds + st_cur;
+      u4 wf[NMAT][BN_W];
+#pragma unroll
+      for (int m = 0; m < NMAT; ++m)
+#pragma unroll
+        for (int f = 0; f < BN_W; ++f)
+          wf[m][f] = *reinterpret_cast<const u4*>(st + A_BYTES + (m * NB + wn * BN_W + f) * 1024 + w_lane);
+      v4i af[2][BM_W];
+#pragma unroll
+      for (int i = 0; i < BM_W; ++i)
+        af[0][i] = *reinterpret_cast<const v4i*>(st + lds_a_offset(a_row_base + i * 32, g));
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        if (pf) {   // quarter s of the loads of K step kt+2
+#pragma unroll
+          for (int p = 0; p < Cfg::A_PASSES; ++p)
+            if ((p & 3) == s) MOTE_DMA_A(st_nx2, kt + 2, p);
+#pragma unroll
+          for (int i = 0; i < W_PER_WAVE; ++i)
+            if (((i + 1) & 3) == s) MOTE_DMA_W(st_nx2, kt + 2, i);
+        }
+        if (s < 3) {
+#pragma unroll
+          for (int i = 0; i < BM_W; ++i)
+            af[(s + 1) & 1][i] = *reinterpret_cast<const v4i*>(st + lds_a_offset(a_row_base + i * 32, 2 * (s + 1) + g));
+        }
+#pragma unroll
+        for (int m = 0; m < NMAT; ++m)
+#pragma unroll
+          for (int f = 0; f < BN_W; ++f) {
+            const v4i bf = unpack_codes(wf[m][f][s]);
+#pragma unroll
+            for (int i = 0; i < BM_W; ++i)
+              acc[m][i][f] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bf, af[s & 1][i], acc[m][i][f], 0, 0, 0);
+          }
+        __builtin_amdgcn_sched_barrier(0);  // keep each quarter's loads with its quarter
+      }
+      // K step kt+1 landed everywhere (kt+2 stays in flight); after the last step: every
+      // wavefront has read its last stage
+      MOTE_WAIT_BARRIER(pf);
+      const int t = st_cur; st_cur = st_nxt; st_nxt = st_nx2; st_nx2 = t;
     }
-    if (kt < ktl) MOTE_KSTEP(stage0, w_a, w_b, 0, false);
-#undef MOTE_KSTEP
-#undef MOTE_PF_A
-#undef MOTE_PF_W
 
-    // (4) start the next tile now: its gather indices, row scalars and first K step travel
-    // while this tile runs its epilogue.
+    // (3) start the next tile now: its first two K steps travel while this tile runs its
+    // epilogue.  The stage of the last K step (now st_nx2) is free until the next tile's
+    // first barrier: it holds the epilogue patches.
+    int ktl2 = ktl;
     if (has_next) {
-      MOTE_GATHER(row02, rows2);
+      ktl2 = min(ktp, KT - kc2 * ktp);
       MOTE_POINTERS(expert2, nt2, kc2);
-      MOTE_LOAD_A(0);
-      MOTE_LOAD_W(w_a, 0);
+      MOTE_DMA_META(par ^ 1);
+      MOTE_ISSUE_STEP(st_cur, 0);
+      if (ktl2 > 1) MOTE_ISSUE_STEP(st_nxt, 1);
     }
-    __syncthreads();  // every wavefront is done with the activation stages: LDS becomes epilogue space
 
     // ---- epilogue ----
     // In registers lane l owns dispatch row r32 and runs of four consecutive output channels
-    // (8q + 4g .. +3).  Each wavefront writes one 32-row fragment row into its LDS patch and
-    // reads it back row-major, 16 bytes per lane, so every global store covers whole rows.
+    // (8q + 4g .. +3).  Each wavefront writes one 32-row block of PATCH_F fragments into its
+    // private LDS patch and reads it back row-major, 16 bytes per lane, so that a global store
+    // instruction covers whole rows of the block.
+    constexpr int PATCH_F = Cfg::PATCH_F;
     constexpr int PATCH_ROW = Cfg::PATCH_ROW;
-    constexpr int OUT_ROW_BYTES = BN_W * 32 * Cfg::OUT_BYTES;   // 128 (bf16) or 256 (int32) for BN_W = 2
+    constexpr int OUT_ROW_BYTES = PATCH_F * 32 * Cfg::OUT_BYTES;
     constexpr int LANES_PER_ROW = OUT_ROW_BYTES / 16;
     constexpr int ROWS_PER_READ = 64 / LANES_PER_ROW;
-    unsigned char* const patch = s_a + wave * Cfg::PATCH_BYTES;
-    const float al0 = a.alpha[expert * 3 + (Cfg::MODE == 0 ? 0 : 2)];
-    const float al1 = Cfg::MODE == 0 ? a.alpha[expert * 3 + 1] : 0.0f;
+    static_assert(Cfg::WAVES * Cfg::PATCH_BYTES <= STAGE_BYTES, "the patches fit the free stage");
+    unsigned char* const patch = s_lds + st_nx2 + wave * Cfg::PATCH_BYTES;
     const int rd_row = lane / LANES_PER_ROW, rd_chunk = lane % LANES_PER_ROW;
-    const int rd_n = n_wave0 + rd_chunk * (16 / Cfg::OUT_BYTES);   // first output channel of this lane's 16 bytes
 #pragma unroll
     for (int i = 0; i < BM_W; ++i) {
       const int rl = wm * BM_W * 32 + i * 32 + r32;
       float sg = 0.0f, su = 0.0f;
       if constexpr (Cfg::MODE == 0) {
-        const float sx = s_scale[rl];
+        const float sx = s_beta[par][rl] / 127.0f;
         sg = sx * al0;
         su = sx * al1;
       }
 #pragma unroll
-      for (int f = 0; f < BN_W; ++f) {
+      for (int f0 = 0; f0 < BN_W; f0 += PATCH_F) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int col = f * 32 + 8 * q + 4 * g;
-          if constexpr (Cfg::MODE == 0) {
-            float hv[4];
+        for (int ff = 0; ff < PATCH_F; ++ff) {
+          const int f = f0 + ff;
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-              hv[j] = (static_cast<float>(acc[1][i][f][4 * q + j]) * su) *
-                      silu_fast(static_cast<float>(acc[0][i][f][4 * q + j]) * sg);
-            uint2 packed;
-            packed.x = cvt_pk_bf16(hv[0], hv[1]);
-            packed.y = cvt_pk_bf16(hv[2], hv[3]);
-            *reinterpret_cast<uint2*>(patch + r32 * PATCH_ROW + col * 2) = packed;
-            if ((a.tap_gate != nullptr || a.tap_up != nullptr) && rl < rows && n_wave0 + col < N) {   // parity taps (tests only), each optional
-              const int64_t o = static_cast<int64_t>(row0 + rl) * N + n_wave0 + col;
-              if (a.tap_gate != nullptr)
-                *reinterpret_cast<int4*>(a.tap_gate + o) = make_int4(acc[0][i][f][4 * q], acc[0][i][f][4 * q + 1],
-                                                                     acc[0][i][f][4 * q + 2], acc[0][i][f][4 * q + 3]);
-              if (a.tap_up != nullptr)
-                *reinterpret_cast<int4*>(a.tap_up + o) = make_int4(acc[1][i][f][4 * q], acc[1][i][f][4 * q + 1],
-                                                                   acc[1][i][f][4 * q + 2], acc[1][i][f][4 * q + 3]);
+          for (int q = 0; q < 4; ++q) {
+            const int pcol = ff * 32 + 8 * q + 4 * g;      // channel inside the patch row
+            const int col = f0 * 32 + pcol;                // channel inside the wavefront's block
+            if constexpr (Cfg::MODE == 0) {
+              float hv[4];
+#pragma unroll
+              for (int j = 0; j < 4; ++j)
+                hv[j] = (static_cast<float>(acc[1][i][f][4 * q + j]) * su) *
+                        silu_fast(static_cast<float>(acc[0][i][f][4 * q + j]) * sg);
+              uint2 packed;
+              packed.x = cvt_pk_bf16(hv[0], hv[1]);
+              packed.y = cvt_pk_bf16(hv[2], hv[3]);
+              *reinterpret_cast<uint2*>(patch + r32 * PATCH_ROW + pcol * 2) = packed;
+              if ((a.tap_gate != nullptr || a.tap_up != nullptr) && rl < rows && n_wave0 + col < N) {   // parity taps (tests only), each optional
+                const int64_t o = static_cast<int64_t>(row0 + rl) * N + n_wave0 + col;
+                if (a.tap_gate != nullptr)
+                  *reinterpret_cast<int4*>(a.tap_gate + o) = make_int4(acc[0][i][f][4 * q], acc[0][i][f][4 * q + 1],
+                                                                       acc[0][i][f][4 * q + 2], acc[0][i][f][4 * q + 3]);
+                if (a.tap_up != nullptr)
+                  *reinterpret_cast<int4*>(a.tap_up + o) = make_int4(acc[1][i][f][4 * q], acc[1][i][f][4 * q + 1],
+                                                                     acc[1][i][f][4 * q + 2], acc[1][i][f][4 * q + 3]);
+              }
+            } else {
+              *reinterpret_cast<int4*>(patch + r32 * PATCH_ROW + pcol * 4) = make_int4(
+                  acc[0][i][f][4 * q], acc[0][i][f][4 * q + 1], acc[0][i][f][4 * q + 2], acc[0][i][f][4 * q + 3]);
             }
-          } else {
-            *reinterpret_cast<int4*>(patch + r32 * PATCH_ROW + col * 4) = make_int4(
-                acc[0][i][f][4 * q], acc[0][i][f][4 * q + 1], acc[0][i][f][4 * q + 2], acc[0][i][f][4 * q + 3]);
           }
         }
-      }
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const int rd_n = n_wave0 + f0 * 32 + rd_chunk * (16 / Cfg::OUT_BYTES);   // first output channel of this lane's 16 bytes
 #pragma unroll
-      for (int p = 0; p < 32 / ROWS_PER_READ; ++p) {
-        const int pr = p * ROWS_PER_READ + rd_row;
-        const u4 v = *reinterpret_cast<const u4*>(patch + pr * PATCH_ROW + rd_chunk * 16);
-        const int orow = wm * BM_W * 32 + i * 32 + pr;
-        if (orow < rows && rd_n < N) {
-          const int64_t o = static_cast<int64_t>(row0 + orow) * N + rd_n;
-          if constexpr (Cfg::MODE == 0) *reinterpret_cast<u4*>(a.h + o) = v;
-          else *reinterpret_cast<u4*>(a.acc_out + static_cast<int64_t>(kc) * a.partial_stride + o) = v;
+        for (int p = 0; p < 32 / ROWS_PER_READ; ++p) {
+          const int pr = p * ROWS_PER_READ + rd_row;
+          const u4 v = *reinterpret_cast<const u4*>(patch + pr * PATCH_ROW + rd_chunk * 16);
+          const int orow = wm * BM_W * 32 + i * 32 + pr;
+          if (orow < rows && rd_n < N) {
+            const int64_t o = static_cast<int64_t>(row0 + orow) * N + rd_n;
+            if constexpr (Cfg::MODE == 0) *reinterpret_cast<u4*>(a.h + o) = v;
+            else *reinterpret_cast<u4*>(a.acc_out + static_cast<int64_t>(kc) * a.partial_stride + o) = v;
+          }
         }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
       }
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     }
     if (!has_next) break;
-    __syncthreads();  // LDS (patches, row metadata) is reused by the next tile
-    slot = nslot; mt = mt2; nt = nt2; kc = kc2; expert = expert2; row0 = row02; rows = rows2;
+    // No barrier here: the patches are private and their stage is not refilled before the next
+    // tile's first barrier, the metadata of the next tile went to the other parity buffer.
+    par ^= 1;
+    slot = nslot; mt = mt2; nt = nt2; kc = kc2; expert = expert2; row0 = row02; rows = rows2; ktl = ktl2;
   }
 #undef MOTE_DECODE
 #undef MOTE_GATHER
 #undef MOTE_POINTERS
-#undef MOTE_LOAD_W
-#undef MOTE_LOAD_A
-#undef MOTE_STORE_A
+#undef MOTE_DMA
+#undef MOTE_DMA_A
+#undef MOTE_DMA_META
+#undef MOTE_DMA_W
+#undef MOTE_ISSUE_STEP
+#undef MOTE_WAIT_BARRIER
 }
 
 static int device_cu_count() {
