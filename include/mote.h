@@ -145,7 +145,7 @@ size_t mote_layer_workspace_bytes(const mote_layer* layer, int T_max);
  *            ordered on one stream.
  * taps : NULL in production.
  * Limits: d, F_s, F_r % 128 == 0; 1 <= E <= 64; 1 <= k <= min(E, 8); 0 <= T; T*k < 2^24;
- *         T*d, T*F_s and T*k*F_r at most 2^31 (32-bit byte offsets inside the kernels). */
+ *         T*d, T*F_s and T*k*F_r below 2^31 (32-bit byte offsets inside the kernels). */
 mote_status mote_layer_forward(const mote_layer* layer, const void* x, int T, void* out,
                                void* workspace, size_t workspace_bytes, const mote_taps* taps,
                                void* hip_stream);

@@ -34,8 +34,8 @@ struct Workspace {
 bool batch_ok(const mote_layer* l, int T) {
   const int64_t lim = int64_t{1} << 31;
   const int64_t R = static_cast<int64_t>(T) * l->top_k;
-  return R < (1 << 24) && static_cast<int64_t>(T) * l->d_model <= lim && R * l->d_ff_routed <= lim &&
-         static_cast<int64_t>(T) * l->d_ff_shared <= lim;
+  return R < (1 << 24) && static_cast<int64_t>(T) * l->d_model < lim && R * l->d_ff_routed < lim &&
+         static_cast<int64_t>(T) * l->d_ff_shared < lim;
 }
 
 bool layer_shape_ok(const mote_layer* l) {

@@ -4,12 +4,18 @@
 //   gate-up mode : g = x W_gate^T, u = x W_up^T, h_s = bf16(u * SiLU(g))     [T, F]
 //   down mode    : y_s = h_s W_down^T (fp32)                                 [T, d]
 //
-// Both operands are K-contiguous ([rows, K] row-major), so a tile row is 64 bf16 = 128
-// bytes and the LDS geometry (8 XOR-swizzled 16-byte chunks per row) is the same for the
-// activation and the weight tiles.  MFMA operand mapping: first operand = weights (lane l:
-// output channel l%32, 8 consecutive K elements of half l/32), second = activations (lane
-// l: token row l%32); result register v of lane l is output channel 8*(v/4) + 4*(l/32) +
-// v%4 of token row l%32.
+// Both operands are K-contiguous ([rows, K] row-major) and are loaded straight into LDS
+// (buffer_load ... lds, 16 bytes per lane) in K steps of 32 elements: a tile row is 64
+// bytes = four 16-byte chunks, chunk index XOR-swizzled with bits 2..3 of the row so that a
+// ds_read_b128 of 16 consecutive rows touches every LDS bank once.  Three stages, requested
+// two K steps ahead; two workgroups of four wavefronts share a CU, so the epilogue and the
+// barrier waits of one overlap with the MFMAs of the other.  Persistent workgroups walk an
+// XCD-aware list of (row tile, channel tile, K plane) triples as the ternary GEMM does.
+//
+// MFMA operand mapping (32x32x16 bf16): first operand = weights (lane l: output channel
+// l%32, 8 consecutive K elements of half l/32), second = activations (lane l: token row
+// l%32); result register v of lane l is output channel 8*(v/4) + 4*(l/32) + v%4 of token
+// row l%32.
 #include <stdlib.h>
 
 #include "common.h"
@@ -20,24 +26,35 @@ namespace mote {
 template <int MODE_, int BM_W_, int BN_W_, int WAVES_M_, int WAVES_N_, int MIN_BLOCKS_ = 1>
 struct SharedCfg {
   static constexpr int MIN_BLOCKS = MIN_BLOCKS_;
-  static constexpr int MODE = MODE_;
+  static constexpr int MODE = MODE_;  // 0 gate-up (two matrices, SwiGLU epilogue), 1 down
   static constexpr int NMAT = MODE_ == 0 ? 2 : 1;
   static constexpr int BM_W = BM_W_, BN_W = BN_W_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
   static constexpr int BM = 32 * BM_W_ * WAVES_M_;
-  static constexpr int BN = 32 * BN_W_ * WAVES_N_;
-  static constexpr int THREADS = 64 * WAVES_M_ * WAVES_N_;
-  static constexpr int ROWS_PER_PASS = THREADS / 8;
+  static constexpr int BN = 32 * BN_W_ * WAVES_N_;   // output channels per matrix
+  static constexpr int WAVES = WAVES_M_ * WAVES_N_;
+  static constexpr int THREADS = 64 * WAVES;
+  static constexpr int KSTEP = 32;                   // bf16 elements per K step: 64-byte tile rows
+  static constexpr int ROWS_PER_PASS = 16 * WAVES;   // a wavefront load fills 16 tile rows
   static constexpr int A_PASSES = BM / ROWS_PER_PASS;
-  static constexpr int B_PASSES = BN / ROWS_PER_PASS;
-  static_assert(BM % ROWS_PER_PASS == 0 && BN % ROWS_PER_PASS == 0, "loaders cover the tiles in whole passes");
-  static constexpr int A_BYTES = BM * 128;
-  static constexpr int B_BYTES = BN * 128;
+  static constexpr int B_PASSES = NMAT * BN / ROWS_PER_PASS;
+  static constexpr int A_BYTES = BM * 64;
+  static constexpr int B_BYTES = BN * 64;            // per matrix
   static constexpr int STAGE_BYTES = A_BYTES + NMAT * B_BYTES;
+  static constexpr int OUT_BYTES = MODE_ == 0 ? 2 : 4;
+  static constexpr int PATCH_F = MODE_ == 0 ? BN_W_ : 1;   // fragments per epilogue pass (128-byte output rows for 2 / 1)
+  static constexpr int PATCH_ROW = PATCH_F * 32 * OUT_BYTES + 16;
+  static constexpr int PATCH_BYTES = 32 * PATCH_ROW;
+  static constexpr bool PATCH_IN_STAGE = WAVES * PATCH_BYTES <= STAGE_BYTES;
+  static constexpr int LDS_BYTES = 3 * STAGE_BYTES + (PATCH_IN_STAGE ? 0 : WAVES * PATCH_BYTES);
+  static_assert(BM % ROWS_PER_PASS == 0 && (NMAT * BN) % ROWS_PER_PASS == 0 && BN % ROWS_PER_PASS == 0,
+                "loaders cover the tiles in whole passes, a pass stays inside one matrix");
+  static_assert(64 % (PATCH_F * 32 * OUT_BYTES / 16) == 0, "an epilogue read covers whole rows");
+  static_assert(A_PASSES + B_PASSES < 16, "fits the low vmcnt field");
 };
 
-// 128-byte rows of eight 16-byte chunks, chunk XOR-swizzled with row bits 1..3: 16 lanes
-// reading one chunk of 16 consecutive rows cover all 64 LDS banks exactly once.
-__device__ __forceinline__ int lds_tile_offset(int row, int chunk) { return row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4); }
+// 64-byte rows of four 16-byte chunks, chunk XOR-swizzled with row bits 2..3: the 16 lanes of
+// a quarter wavefront read one chunk of 16 consecutive rows = all 64 banks exactly once.
+__device__ __forceinline__ int lds_tile_offset(int row, int chunk) { return row * 64 + ((chunk ^ ((row >> 2) & 3)) << 4); }
 
 struct SharedGemmArgs {
   const uint16_t* act;   // [M, K] bf16
@@ -50,154 +67,271 @@ struct SharedGemmArgs {
 };
 
 template <typename Cfg>
-__global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void shared_gemm_kernel(SharedGemmArgs a, int n_ntiles, int kplanes, int ktp) {
+__global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void shared_gemm_kernel(SharedGemmArgs a, int n_ntiles,
+                                                                                   int kplanes, int ktp) {
   constexpr int NMAT = Cfg::NMAT, BM_W = Cfg::BM_W, BN_W = Cfg::BN_W;
   constexpr int BM = Cfg::BM, BN = Cfg::BN;
-  extern __shared__ __attribute__((aligned(16))) unsigned char s_mem[];
+  constexpr int A_BYTES = Cfg::A_BYTES, B_BYTES = Cfg::B_BYTES, STAGE_BYTES = Cfg::STAGE_BYTES;
+  constexpr int NLOAD = Cfg::A_PASSES + Cfg::B_PASSES;   // vector-memory operations a wavefront issues per K step
+  extern __shared__ __attribute__((aligned(16))) unsigned char s_lds[];
 
-  // Workgroups go to the 8 XCDs round-robin by linear id: XCD x owns the channel tiles
-  // x, x+8, ... (the row tiles x, x+8, ... when there are fewer than 16 channel tiles) and
-  // walks the other index fastest, so its L2 keeps one slice of the weights resident.
+  const int M = a.M, N = a.N, K = a.K;
+  const int KT = K >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  const int wm = wave % Cfg::WAVES_M, wn = wave / Cfg::WAVES_M;
+  const int r32 = lane & 31, g = lane >> 5;
+  const int a_row_base = wm * BM_W * 32 + r32;
+  const int b_row_base = wn * BN_W * 32 + r32;
+  // LDS byte address of the stage area (what M0 takes for a direct-to-LDS load)
+  const uint32_t lds0 = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) unsigned char*)s_lds);
+
+  // Persistent workgroups, dealt to the 8 XCDs round-robin by linear id: XCD x owns the
+  // (channel tile, K plane) pairs x, x+8, ... (the row tiles x, x+8, ... when there are fewer
+  // than 16 pairs) and walks the other index fastest, so its L2 keeps one slice of the weights.
   // With kplanes > 1 (down projection of small problems) the contraction is cut into planes of
   // ktp K steps; each plane writes its own partial output, added later in plane order.
   n_ntiles *= kplanes;
-  const int M = a.M, N = a.N, K = a.K;
   const int n_mtiles = (M + BM - 1) / BM;
-  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int xcd = blockIdx.x & 7;
   const bool split_n = n_ntiles >= 16;
   const int xcd_ntiles = split_n ? (n_ntiles - xcd + 7) >> 3 : n_ntiles;
   const int xcd_mtiles = split_n ? n_mtiles : (n_mtiles - xcd + 7) >> 3;
-  if (slot >= xcd_ntiles * xcd_mtiles) return;
-  const int mi = slot / xcd_ntiles, ni = slot - mi * xcd_ntiles;
-  const int mt = split_n ? mi : xcd + 8 * mi;
-  const int ntk = split_n ? xcd + 8 * ni : ni;
-  const int nt = ntk / kplanes, kc = ntk - nt * kplanes;
-  const int kt0 = kc * ktp;
-  const int KT = min(ktp, (K >> 6) - kt0);   // K steps of this plane
-  const int m0 = mt * BM, n0 = nt * BN;
+  const int xcd_work = xcd_ntiles * xcd_mtiles;
+  const int stride = gridDim.x >> 3;
+  int slot = blockIdx.x >> 3;
+  if (slot >= xcd_work) return;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave % Cfg::WAVES_M, wn = wave / Cfg::WAVES_M;
-  const int r32 = lane & 31, g = lane >> 5;
-  const int chunk = tid & 7;
+  // Loader: raw buffer loads written in assembly (the compiler has no exact model of
+  // outstanding direct-to-LDS loads across this loop).  Vector-memory operations complete in
+  // issue order, so waiting for "all but the NLOAD youngest" retires the K step that is about
+  // to be contracted while the following one stays in flight; anything else issued since
+  // (stores of the previous epilogue) only makes that wait stricter.
+  constexpr int kBufferFlags = 0x00020000;   // raw buffer, 32-bit data format
+  auto make_rsrc = [&](const void* base, int64_t bytes) {
+    const uint64_t p = reinterpret_cast<uint64_t>(base);
+    v4i r;
+    r.x = static_cast<int>(static_cast<uint32_t>(p));
+    r.y = static_cast<int>(static_cast<uint32_t>(p >> 32) & 0xFFFFu);
+    r.z = static_cast<int>(bytes);
+    r.w = kBufferFlags;
+    return r;
+  };
+  const v4i rsrc_a = make_rsrc(a.act, static_cast<int64_t>(M) * K * 2);
+  const v4i rsrc_b0 = make_rsrc(a.w0, static_cast<int64_t>(N) * K * 2);
+  const v4i rsrc_b1 = make_rsrc(NMAT == 2 ? a.w1 : a.w0, static_cast<int64_t>(N) * K * 2);
+  // lane l of a wavefront load lands at byte 16*l of a 1-KiB block = tile row l/4, physical
+  // chunk l%4, and therefore fetches logical chunk (l%4) ^ swizzle(row)
+  const int ld_row = wave_u * 16 + (lane >> 2);
+  const uint32_t ld_chunk = static_cast<uint32_t>(((lane & 3) ^ ((lane >> 4) & 3)) << 4);
+  uint32_t a_off[Cfg::A_PASSES], b_off[Cfg::B_PASSES];   // byte offsets of this lane's 16 bytes, K step 0 of the plane
+  int mt, nt, kc, ktl;
+  int st_cur = 0, st_nxt = STAGE_BYTES, st_nx2 = 2 * STAGE_BYTES;   // stage of K step kt, kt+1, kt+2 (byte offsets)
 
-  const uint16_t* a_src[Cfg::A_PASSES];
-  const uint16_t* b_src[NMAT][Cfg::B_PASSES];
-  int a_dst[Cfg::A_PASSES], b_dst[Cfg::B_PASSES];
-#pragma unroll
-  for (int p = 0; p < Cfg::A_PASSES; ++p) {
-    const int r = p * Cfg::ROWS_PER_PASS + (tid >> 3);
-    a_src[p] = a.act + static_cast<int64_t>(min(m0 + r, M - 1)) * K + chunk * 8 + kt0 * 64;
-    a_dst[p] = lds_tile_offset(r, chunk);
+#define MOTE_DECODE(slot_, mt_, nt_, kc_)                                       \
+  {                                                                             \
+    const int mi_ = (slot_) / xcd_ntiles, ni_ = (slot_) - mi_ * xcd_ntiles;     \
+    mt_ = split_n ? mi_ : xcd + 8 * mi_;                                        \
+    const int ntk_ = split_n ? xcd + 8 * ni_ : ni_;                             \
+    nt_ = ntk_ / kplanes;                                                       \
+    kc_ = ntk_ - nt_ * kplanes;                                                 \
   }
-#pragma unroll
-  for (int p = 0; p < Cfg::B_PASSES; ++p) {
-    const int r = p * Cfg::ROWS_PER_PASS + (tid >> 3);
-    const int64_t off = static_cast<int64_t>(min(n0 + r, N - 1)) * K + chunk * 8 + kt0 * 64;
-    b_src[0][p] = a.w0 + off;
-    if constexpr (NMAT == 2) b_src[1][p] = a.w1 + off;
-    b_dst[p] = lds_tile_offset(r, chunk);
+#define MOTE_POINTERS(mt_, nt_, kc_)                                                               \
+  {                                                                                                \
+    const uint32_t k0_ = static_cast<uint32_t>((kc_) * ktp) * 64u + ld_chunk;                      \
+    _Pragma("unroll") for (int p = 0; p < Cfg::A_PASSES; ++p) {                                    \
+      const int row_ = min((mt_) * BM + p * Cfg::ROWS_PER_PASS + ld_row, M - 1);                   \
+      a_off[p] = static_cast<uint32_t>(row_) * static_cast<uint32_t>(K) * 2u + k0_;                \
+    }                                                                                              \
+    _Pragma("unroll") for (int p = 0; p < Cfg::B_PASSES; ++p) {                                    \
+      const int row_ = min((nt_) * BN + (p * Cfg::ROWS_PER_PASS) % BN + ld_row, N - 1);            \
+      b_off[p] = static_cast<uint32_t>(row_) * static_cast<uint32_t>(K) * 2u + k0_;                \
+    }                                                                                              \
+  }
+  // one 16-byte-per-lane direct load: LDS byte address (uniform), lane offset, buffer, scalar offset
+#define MOTE_DMA(lds_, voff_, rsrc_, soff_)                                                        \
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"           \
+               :: "s"(lds_), "v"(voff_), "s"(rsrc_), "s"(soff_) : "memory")
+#define MOTE_DMA_A(stage_, ks_, p_)                                                                \
+  MOTE_DMA(lds0 + (stage_) + ((p_) * Cfg::ROWS_PER_PASS + wave_u * 16) * 64, a_off[p_], rsrc_a, (ks_) * 64)
+  // loader pass p_ of the weights: matrix (p_*ROWS_PER_PASS)/BN, rows (p_*ROWS_PER_PASS)%BN ... of it
+#define MOTE_DMA_B(stage_, ks_, p_)                                                                \
+  MOTE_DMA(lds0 + (stage_) + A_BYTES + ((p_) * Cfg::ROWS_PER_PASS + wave_u * 16) * 64, b_off[p_],  \
+           (((p_) * Cfg::ROWS_PER_PASS) / BN == 0 ? rsrc_b0 : rsrc_b1), (ks_) * 64)
+#define MOTE_ISSUE_STEP(stage_, ks_)                                                               \
+  {                                                                                                \
+    _Pragma("unroll") for (int p = 0; p < Cfg::A_PASSES; ++p) MOTE_DMA_A(stage_, ks_, p);          \
+    _Pragma("unroll") for (int p = 0; p < Cfg::B_PASSES; ++p) MOTE_DMA_B(stage_, ks_, p);          \
+  }
+  // in_flight_: whether the loads of one more K step were issued after the ones needed now
+#define MOTE_WAIT_BARRIER(in_flight_)                                                              \
+  {                                                                                                \
+    if (in_flight_) asm volatile("s_waitcnt vmcnt(%0)" :: "n"(NLOAD) : "memory");                  \
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                                          \
+    asm volatile("s_barrier" ::: "memory");                                                        \
   }
 
-  v16f acc[NMAT][BM_W][BN_W];
-#pragma unroll
-  for (int m = 0; m < NMAT; ++m)
-#pragma unroll
-    for (int i = 0; i < BM_W; ++i)
-#pragma unroll
-      for (int f = 0; f < BN_W; ++f)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[m][i][f][v] = 0.0f;
+  // ---- first tile ----
+  MOTE_DECODE(slot, mt, nt, kc);
+  ktl = min(ktp, KT - kc * ktp);
+  MOTE_POINTERS(mt, nt, kc);
+  MOTE_ISSUE_STEP(st_cur, 0);
+  if (ktl > 1) MOTE_ISSUE_STEP(st_nxt, 1);
 
-  u4 a_reg[Cfg::A_PASSES], b_reg[NMAT][Cfg::B_PASSES];
+  for (;;) {
+    const int nslot = slot + stride;
+    const bool has_next = nslot < xcd_work;
+    int mt2 = mt, nt2 = nt, kc2 = kc;
+    if (has_next) MOTE_DECODE(nslot, mt2, nt2, kc2);
+    MOTE_WAIT_BARRIER(ktl > 1);   // K step 0 visible to every wavefront; the patches of the previous tile are done
 
-#define MOTE_GLOAD(kt_)                                                                              \
-  do {                                                                                             \
-    _Pragma("unroll") for (int p = 0; p < Cfg::A_PASSES; ++p)                                      \
-      a_reg[p] = *reinterpret_cast<const u4*>(a_src[p] + static_cast<int64_t>(kt_) * 64);        \
-    _Pragma("unroll") for (int m = 0; m < NMAT; ++m)                                               \
-      _Pragma("unroll") for (int p = 0; p < Cfg::B_PASSES; ++p)                                    \
-        b_reg[m][p] = *reinterpret_cast<const u4*>(b_src[m][p] + static_cast<int64_t>(kt_) * 64); \
-  } while (0)
-#define MOTE_LSTORE(stage_idx_)                                                                    \
-  do {                                                                                             \
-    unsigned char* st_ = s_mem + (stage_idx_) * Cfg::STAGE_BYTES;                                  \
-    _Pragma("unroll") for (int p = 0; p < Cfg::A_PASSES; ++p)                                      \
-      *reinterpret_cast<u4*>(st_ + a_dst[p]) = a_reg[p];                                        \
-    _Pragma("unroll") for (int m = 0; m < NMAT; ++m)                                               \
-      _Pragma("unroll") for (int p = 0; p < Cfg::B_PASSES; ++p)                                    \
-        *reinterpret_cast<u4*>(st_ + Cfg::A_BYTES + m * Cfg::B_BYTES + b_dst[p]) = b_reg[m][p]; \
-  } while (0)
-
-  MOTE_GLOAD(0);
-  MOTE_LSTORE(0);
-  __syncthreads();
-
-  const int a_row_base = wm * BM_W * 32 + r32;
-  const int b_row_base = wn * BN_W * 32 + r32;
-  for (int kt = 0; kt < KT; ++kt) {
-    const bool has_next = kt + 1 < KT;
-    if (has_next) MOTE_GLOAD(kt + 1);
-    __builtin_amdgcn_sched_barrier(0);  // keep the prefetch loads ahead of the contraction
-    const unsigned char* st = s_mem + (kt & 1) * Cfg::STAGE_BYTES;
+    v16f acc[NMAT][BM_W][BN_W];
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      bf16x8 af[BM_W];
+    for (int m = 0; m < NMAT; ++m)
 #pragma unroll
       for (int i = 0; i < BM_W; ++i)
-        af[i] = *reinterpret_cast<const bf16x8*>(st + lds_tile_offset(a_row_base + i * 32, 2 * s + g));
 #pragma unroll
-      for (int m = 0; m < NMAT; ++m)
+        for (int f = 0; f < BN_W; ++f)
 #pragma unroll
-        for (int f = 0; f < BN_W; ++f) {
-          const bf16x8 bf = *reinterpret_cast<const bf16x8*>(st + Cfg::A_BYTES + m * Cfg::B_BYTES +
-                                                             lds_tile_offset(b_row_base + f * 32, 2 * s + g));
+          for (int v = 0; v < 16; ++v) acc[m][i][f][v] = 0.0f;
+
+    // K loop.  K step kt contracts stage st_cur while the loads of kt+2 are issued, half of them
+    // per 16-element sub-step, into the stage that the barrier at the end of step kt-1 released.
+    for (int kt = 0; kt < ktl; ++kt) {
+      const bool pf = kt + 2 < ktl;
+      const unsigned char* const st = s_lds + st_cur;
+      // all fragments of the step are requested at once: the MFMAs of the first half run while
+      // those of the second half are still on their way
+      bf16x8 af[2][BM_W], bfr[2][NMAT][BN_W];
 #pragma unroll
-          for (int i = 0; i < BM_W; ++i)
-            acc[m][i][f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf, af[i], acc[m][i][f], 0, 0, 0);
+      for (int s = 0; s < 2; ++s) {
+#pragma unroll
+        for (int i = 0; i < BM_W; ++i)
+          af[s][i] = *reinterpret_cast<const bf16x8*>(st + lds_tile_offset(a_row_base + i * 32, 2 * s + g));
+#pragma unroll
+        for (int m = 0; m < NMAT; ++m)
+#pragma unroll
+          for (int f = 0; f < BN_W; ++f)
+            bfr[s][m][f] = *reinterpret_cast<const bf16x8*>(st + A_BYTES + m * B_BYTES +
+                                                            lds_tile_offset(b_row_base + f * 32, 2 * s + g));
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int s = 0; s < 2; ++s) {
+        if (pf) {   // half s of the loads of K step kt+2
+#pragma unroll
+          for (int p = 0; p < Cfg::A_PASSES; ++p)
+            if ((p & 1) == s) MOTE_DMA_A(st_nx2, kt + 2, p);
+#pragma unroll
+          for (int p = 0; p < Cfg::B_PASSES; ++p)
+            if ((p & 1) == s) MOTE_DMA_B(st_nx2, kt + 2, p);
         }
+#pragma unroll
+        for (int m = 0; m < NMAT; ++m)
+#pragma unroll
+          for (int f = 0; f < BN_W; ++f)
+#pragma unroll
+            for (int i = 0; i < BM_W; ++i)
+              acc[m][i][f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[s][m][f], af[s][i], acc[m][i][f], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);  // keep each half's loads with its half
+      }
+      // K step kt+1 landed everywhere (kt+2 stays in flight); after the last step: every
+      // wavefront has read its last stage
+      MOTE_WAIT_BARRIER(pf);
+      const int t = st_cur; st_cur = st_nxt; st_nxt = st_nx2; st_nx2 = t;
     }
-    __builtin_amdgcn_sched_barrier(0);
-    if (has_next) MOTE_LSTORE((kt + 1) & 1);
-    __syncthreads();
-  }
 
-#undef MOTE_GLOAD
-#undef MOTE_LSTORE
+    // Start the next tile now: its first two K steps travel while this tile runs its epilogue.
+    // The stage of the last K step (now st_nx2) is free until the next tile's first barrier.
+    int ktl2 = ktl;
+    if (has_next) {
+      ktl2 = min(ktp, KT - kc2 * ktp);
+      MOTE_POINTERS(mt2, nt2, kc2);
+      MOTE_ISSUE_STEP(st_cur, 0);
+      if (ktl2 > 1) MOTE_ISSUE_STEP(st_nxt, 1);
+    }
 
-  // Lane l owns token row r32 of every row fragment and runs of four consecutive output
-  // channels (first MFMA operand = weights).
+    // ---- epilogue ----
+    // In registers lane l owns token row r32 and runs of four consecutive output channels
+    // (8q + 4g .. +3).  Each wavefront writes one 32-row block of PATCH_F fragments into its
+    // private LDS patch and reads it back row-major, 16 bytes per lane, so that a global store
+    // instruction covers whole 128-byte rows of the block.
+    constexpr int PATCH_F = Cfg::PATCH_F;
+    constexpr int PATCH_ROW = Cfg::PATCH_ROW;
+    constexpr int OUT_ROW_BYTES = PATCH_F * 32 * Cfg::OUT_BYTES;
+    constexpr int LANES_PER_ROW = OUT_ROW_BYTES / 16;
+    constexpr int ROWS_PER_READ = 64 / LANES_PER_ROW;
+    unsigned char* const patch =
+        s_lds + (Cfg::PATCH_IN_STAGE ? st_nx2 : 3 * STAGE_BYTES) + wave * Cfg::PATCH_BYTES;
+    const int m0 = mt * BM, n_wave0 = nt * BN + wn * BN_W * 32;
+    const int rd_row = lane / LANES_PER_ROW, rd_chunk = lane % LANES_PER_ROW;
 #pragma unroll
-  for (int i = 0; i < BM_W; ++i) {
-    const int row = m0 + wm * BM_W * 32 + i * 32 + r32;
-    if (row >= M) continue;
+    for (int i = 0; i < BM_W; ++i) {
 #pragma unroll
-    for (int f = 0; f < BN_W; ++f) {
-      const int nf = n0 + wn * BN_W * 32 + f * 32;
-      if (nf >= N) continue;
+      for (int f0 = 0; f0 < BN_W; f0 += PATCH_F) {
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int64_t o = static_cast<int64_t>(row) * N + nf + 8 * q + 4 * g;
-        if constexpr (Cfg::MODE == 0) {
-          float hv[4];
+        for (int ff = 0; ff < PATCH_F; ++ff) {
+          const int f = f0 + ff;
 #pragma unroll
-          for (int j = 0; j < 4; ++j) hv[j] = acc[1][i][f][4 * q + j] * silu_fast(acc[0][i][f][4 * q + j]);
-          uint2 packed;
-          packed.x = cvt_pk_bf16(hv[0], hv[1]);
-          packed.y = cvt_pk_bf16(hv[2], hv[3]);
-          *reinterpret_cast<uint2*>(a.h_out + o) = packed;
-        } else {
-          *reinterpret_cast<float4*>(a.y_out + static_cast<int64_t>(kc) * a.plane_stride + o) = make_float4(acc[0][i][f][4 * q + 0], acc[0][i][f][4 * q + 1],
-                                                                acc[0][i][f][4 * q + 2], acc[0][i][f][4 * q + 3]);
+          for (int q = 0; q < 4; ++q) {
+            const int pcol = ff * 32 + 8 * q + 4 * g;   // channel inside the patch row
+            if constexpr (Cfg::MODE == 0) {
+              float hv[4];
+#pragma unroll
+              for (int j = 0; j < 4; ++j) hv[j] = acc[NMAT - 1][i][f][4 * q + j] * silu_fast(acc[0][i][f][4 * q + j]);
+              uint2 packed;
+              packed.x = cvt_pk_bf16(hv[0], hv[1]);
+              packed.y = cvt_pk_bf16(hv[2], hv[3]);
+              *reinterpret_cast<uint2*>(patch + r32 * PATCH_ROW + pcol * 2) = packed;
+            } else {
+              *reinterpret_cast<float4*>(patch + r32 * PATCH_ROW + pcol * 4) = make_float4(
+                  acc[0][i][f][4 * q], acc[0][i][f][4 * q + 1], acc[0][i][f][4 * q + 2], acc[0][i][f][4 * q + 3]);
+            }
+          }
         }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const int rd_n = n_wave0 + f0 * 32 + rd_chunk * (16 / Cfg::OUT_BYTES);   // first output channel of this lane's 16 bytes
+#pragma unroll
+        for (int p = 0; p < 32 / ROWS_PER_READ; ++p) {
+          const int pr = p * ROWS_PER_READ + rd_row;
+          const u4 v = *reinterpret_cast<const u4*>(patch + pr * PATCH_ROW + rd_chunk * 16);
+          const int orow = m0 + wm * BM_W * 32 + i * 32 + pr;
+          if (orow < M && rd_n < N) {
+            const int64_t o = static_cast<int64_t>(orow) * N + rd_n;
+            if constexpr (Cfg::MODE == 0) *reinterpret_cast<u4*>(a.h_out + o) = v;
+            else *reinterpret_cast<u4*>(a.y_out + static_cast<int64_t>(kc) * a.plane_stride + o) = v;
+          }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
       }
     }
+    if (!has_next) break;
+    // No barrier here: the patches are private and their stage is not refilled before the next
+    // tile's first barrier.
+    slot = nslot; mt = mt2; nt = nt2; kc = kc2; ktl = ktl2;
   }
+#undef MOTE_DECODE
+#undef MOTE_POINTERS
+#undef MOTE_DMA
+#undef MOTE_DMA_A
+#undef MOTE_DMA_B
+#undef MOTE_ISSUE_STEP
+#undef MOTE_WAIT_BARRIER
 }
 
-// Largest per-XCD tile count of the XCD-aware mapping (XCD 0 owns the most tiles).
-static int split_tiles(int n_ntiles, int n_mtiles) {
-  return n_ntiles >= 16 ? ((n_ntiles + 7) / 8) * n_mtiles : n_ntiles * ((n_mtiles + 7) / 8);
+static int shared_cu_count() {
+  static int n = 0;
+  if (n == 0) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+      n = 256;
+  }
+  return n;
 }
 
 static int shared_variant() {
@@ -209,22 +343,30 @@ static int shared_variant() {
   return v;
 }
 
+// kplanes64 / the plane length are counted in 64-element units (the workspace layout depends
+// on shared_down_planes, which predates the 32-element K step).
 template <typename Cfg>
 static hipError_t launch_shared_cfg(const SharedGemmArgs& a, int kplanes, hipStream_t stream) {
   const int n_ntiles = (a.N + Cfg::BN - 1) / Cfg::BN;
-  const int KT = a.K >> 6;
-  const int ktp = (KT + kplanes - 1) / kplanes;
+  const int KT64 = a.K >> 6;
+  const int ktp = 2 * ((KT64 + kplanes - 1) / kplanes);   // K steps of 32 per plane
   const int n_mtiles = (a.M + Cfg::BM - 1) / Cfg::BM;
-  const size_t lds = 2 * Cfg::STAGE_BYTES;
+  const size_t lds = Cfg::LDS_BYTES;
   static bool attr_set = false;
+  static int resident = Cfg::MIN_BLOCKS;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(shared_gemm_kernel<Cfg>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
     if (e != hipSuccess) return e;
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, shared_gemm_kernel<Cfg>, Cfg::THREADS, lds) == hipSuccess && n > 0)
+      resident = n;
     attr_set = true;
   }
-  const int per_xcd = split_tiles(n_ntiles * kplanes, n_mtiles);
-  shared_gemm_kernel<Cfg><<<static_cast<unsigned>(per_xcd * 8), Cfg::THREADS, lds, stream>>>(a, n_ntiles, kplanes, ktp);
+  const int64_t tiles = static_cast<int64_t>(n_mtiles) * n_ntiles * kplanes;
+  int64_t blocks = static_cast<int64_t>(shared_cu_count()) * resident;
+  if (blocks > tiles) blocks = (tiles + 7) / 8 * 8;
+  shared_gemm_kernel<Cfg><<<static_cast<unsigned>(blocks), Cfg::THREADS, lds, stream>>>(a, n_ntiles, kplanes, ktp);
   return hipGetLastError();
 }
 
@@ -232,21 +374,21 @@ hipError_t launch_shared_gate_up(const uint16_t* x, const uint16_t* w_gate, cons
                                  int F, uint16_t* h_s, hipStream_t stream) {
   if (T == 0) return hipSuccess;
   SharedGemmArgs a{x, w_gate, w_up, T, F, d, h_s, nullptr, 0};
+  // Operand traffic per flop halves with a 256 x 256 tile (one 8-wavefront workgroup per CU): the
+  // 128-row tile at two workgroups per CU saturates the L2 -> L1 path first.  Small problems keep
+  // the 128-row tile, which leaves fewer CUs idle in the last round.
   int v = shared_variant();
-  if (v == 0) {   // few 256-row tiles: the 128 x (64+64) tile at two workgroups per CU fills the chip better
-    const int64_t big_tiles = static_cast<int64_t>((T + 255) / 256) * (F / 128);
-    if (big_tiles < 2 * 256) v = 1;
-  }
+  if (v == 0) v = static_cast<int64_t>((T + 255) / 256) * ((F + 127) / 128) >= 384 ? 2 : 3;
   switch (v) {
-    case 1: return launch_shared_cfg<SharedCfg<0, 2, 1, 2, 2, 2>>(a, 1, stream);   // 128 x (64+64), 2 workgroups / CU
-    case 2: return launch_shared_cfg<SharedCfg<0, 2, 2, 2, 2, 1>>(a, 1, stream);   // 128 x (128+128), 1 workgroup / CU
-    default: return launch_shared_cfg<SharedCfg<0, 2, 2, 4, 2, 1>>(a, 1, stream);  // 256 x (128+128), 8 wavefronts
+    case 1: return launch_shared_cfg<SharedCfg<0, 2, 1, 2, 2, 2>>(a, 1, stream);   // 128 x (64+64)
+    case 2: return launch_shared_cfg<SharedCfg<0, 2, 2, 4, 2, 1>>(a, 1, stream);   // 256 x (128+128), 8 wavefronts, 1 workgroup / CU
+    default: return launch_shared_cfg<SharedCfg<0, 2, 2, 2, 2, 2>>(a, 1, stream);  // 128 x (128+128), 2 workgroups / CU
   }
 }
 
 // K planes of the large-batch down projection: enough (row tile, channel tile, plane) triples
-// to fill two workgroups per CU, planes of at least 8 K steps.  Pure function of the shape:
-// the workspace layout depends on it.
+// to fill two workgroups per CU, planes of at least 8 K steps of 64.  Pure function of the
+// shape: the workspace layout depends on it.
 int shared_down_planes(int T, int d, int F) {
   const int64_t tiles = static_cast<int64_t>((T + 127) / 128) * ((d + 127) / 128);
   const int KT = F >> 6;
@@ -263,10 +405,13 @@ hipError_t launch_shared_down(const uint16_t* h_s, const uint16_t* w_down, int T
   if (T == 0) return hipSuccess;
   SharedGemmArgs a{h_s, w_down, nullptr, T, d, F, nullptr, y_s, static_cast<int64_t>(T) * d};
   const int planes = shared_down_planes(T, d, F);
-  switch (shared_variant()) {
-    case 1: return launch_shared_cfg<SharedCfg<1, 2, 4, 2, 2, 1>>(a, planes, stream);   // 128 x 256
-    case 2: return launch_shared_cfg<SharedCfg<1, 4, 2, 2, 2, 1>>(a, planes, stream);   // 256 x 128
-    default: return launch_shared_cfg<SharedCfg<1, 2, 2, 2, 2, 2>>(a, planes, stream);  // 128 x 128, 2 workgroups / CU
+  if (planes > 1) return launch_shared_cfg<SharedCfg<1, 2, 2, 2, 2, 2>>(a, planes, stream);   // small problem: 128 x 128 tiles
+  int v = shared_variant();
+  if (v == 0) v = static_cast<int64_t>((T + 255) / 256) * ((d + 255) / 256) >= 256 ? 2 : 3;
+  switch (v) {
+    case 1: return launch_shared_cfg<SharedCfg<1, 2, 2, 2, 2, 2>>(a, 1, stream);    // 128 x 128
+    case 2: return launch_shared_cfg<SharedCfg<1, 2, 4, 4, 2, 1>>(a, 1, stream);    // 256 x 256, 8 wavefronts, 1 workgroup / CU
+    default: return launch_shared_cfg<SharedCfg<1, 2, 4, 2, 2, 2>>(a, 1, stream);   // 128 x 256
   }
 }
 
