@@ -3,6 +3,7 @@
 #include "../../include/mote.h"
 
 #include <hip/hip_runtime.h>
+#include <stdlib.h>
 
 #include "launch.h"
 
@@ -103,6 +104,42 @@ hipError_t ensure_events() {
   return hipSuccess;
 }
 
+// ---- helper stream for the shared expert (host side, created on first use per device) ----
+// The shared expert depends on x only, the routed chain (router, dispatch, two grouped GEMMs)
+// does not read its result before the combine: the two run on different streams, forked from
+// and joined back into the caller's stream with events.  Small batches do not fill the chip
+// with one kernel; there the two chains overlap, and launch gaps and kernel tails of one are
+// covered by the other.
+struct SideStream {
+  hipStream_t stream = nullptr;
+  hipEvent_t fork = nullptr, join = nullptr;
+};
+SideStream g_side[16];
+
+hipError_t side_stream(SideStream** out) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= 16) return hipErrorInvalidDevice;
+  SideStream& s = g_side[dev];
+  if (s.stream == nullptr) {
+    if ((e = hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking)) != hipSuccess) return e;
+    if ((e = hipEventCreateWithFlags(&s.fork, hipEventDisableTiming)) != hipSuccess) return e;
+    if ((e = hipEventCreateWithFlags(&s.join, hipEventDisableTiming)) != hipSuccess) return e;
+  }
+  *out = &s;
+  return hipSuccess;
+}
+
+bool fork_enabled() {
+  static int v = -1;
+  if (v < 0) {
+    const char* e = getenv("MOTE_NO_FORK");
+    v = (e && e[0] == '1') ? 0 : 1;
+  }
+  return v == 1;
+}
+
 #define MOTE_HIP(expr)                            \
   do {                                            \
     hipError_t _e = (expr);                       \
@@ -194,13 +231,31 @@ mote_status mote_layer_forward(const mote_layer* layer, const void* x, int T, vo
   if (timing) MOTE_HIP(ensure_events());
   auto mark = [&](int i) -> hipError_t { return timing ? hipEventRecord(g_ev[i], stream) : hipSuccess; };
 
+  const int tile_m = w.tile_m;
+  const bool decode_routed = tile_m == 32;
+  const bool decode_shared = T <= kSharedDecodeMaxTokens;
+  const uint16_t* sg = static_cast<const uint16_t*>(layer->ws_gate);
+  const uint16_t* su = static_cast<const uint16_t*>(layer->ws_up);
+  const uint16_t* sd = static_cast<const uint16_t*>(layer->ws_down);
+
+  // Shared expert: on the helper stream, unless stage timing wants one stage after the other.
+  SideStream* side = nullptr;
+  if (!timing && fork_enabled()) MOTE_HIP(side_stream(&side));
+  hipStream_t sstream = side ? side->stream : stream;
+  if (side) {
+    MOTE_HIP(hipEventRecord(side->fork, stream));
+    MOTE_HIP(hipStreamWaitEvent(side->stream, side->fork, 0));
+    MOTE_HIP(decode_shared ? launch_shared_decode_gate_up(xb, sg, su, T, d, Fs, w.h_s, sstream)
+                           : launch_shared_gate_up(xb, sg, su, T, d, Fs, w.h_s, sstream));
+    MOTE_HIP(decode_shared ? launch_shared_decode_down(w.h_s, sd, T, d, Fs, w.y_s, sstream)
+                           : launch_shared_down(w.h_s, sd, T, d, Fs, w.y_s, sstream));
+    MOTE_HIP(hipEventRecord(side->join, side->stream));
+  }
+
   MOTE_HIP(mark(0));
   MOTE_HIP(launch_router_quant(xb, static_cast<const uint16_t*>(layer->w_router), layer->router_bias, T, d, E, k,
                                w.topk_idx, w.topk_p, w.q_x, w.beta_x, w.rs_x, stream));
   MOTE_HIP(mark(1));
-  const int tile_m = w.tile_m;
-  const bool decode_routed = tile_m == 32;
-  const bool decode_shared = T <= kSharedDecodeMaxTokens;
   DispatchPlan plan{w.counts, w.offsets, w.row_of, w.tok_of, w.tile_expert, w.tile_row0, w.tile_rows, w.n_tiles};
   MOTE_HIP(launch_dispatch_plan(w.topk_idx, T, k, E, tile_m, plan, stream));
   MOTE_HIP(mark(2));
@@ -226,15 +281,18 @@ mote_status mote_layer_forward(const mote_layer* layer, const void* x, int T, vo
   MOTE_HIP(decode_routed ? launch_routed_decode_down(gd, stream) : launch_routed_down(gd, stream));
   MOTE_HIP(mark(5));
 
-  const uint16_t* sg = static_cast<const uint16_t*>(layer->ws_gate);
-  const uint16_t* su = static_cast<const uint16_t*>(layer->ws_up);
-  const uint16_t* sd = static_cast<const uint16_t*>(layer->ws_down);
-  MOTE_HIP(decode_shared ? launch_shared_decode_gate_up(xb, sg, su, T, d, Fs, w.h_s, stream)
-                         : launch_shared_gate_up(xb, sg, su, T, d, Fs, w.h_s, stream));
-  MOTE_HIP(mark(6));
-  MOTE_HIP(decode_shared ? launch_shared_decode_down(w.h_s, sd, T, d, Fs, w.y_s, stream)
-                         : launch_shared_down(w.h_s, sd, T, d, Fs, w.y_s, stream));
-  MOTE_HIP(mark(7));
+  if (side) {
+    MOTE_HIP(hipStreamWaitEvent(stream, side->join, 0));
+    MOTE_HIP(mark(6));
+    MOTE_HIP(mark(7));
+  } else {
+    MOTE_HIP(decode_shared ? launch_shared_decode_gate_up(xb, sg, su, T, d, Fs, w.h_s, stream)
+                           : launch_shared_gate_up(xb, sg, su, T, d, Fs, w.h_s, stream));
+    MOTE_HIP(mark(6));
+    MOTE_HIP(decode_shared ? launch_shared_decode_down(w.h_s, sd, T, d, Fs, w.y_s, stream)
+                           : launch_shared_down(w.h_s, sd, T, d, Fs, w.y_s, stream));
+    MOTE_HIP(mark(7));
+  }
   CombineArgs ca{};
   ca.y_s = w.y_s; ca.y_planes = w.y_planes; ca.y_stride = static_cast<int64_t>(T) * d;
   ca.acc_down = w.acc_down; ca.d_planes = w.d_planes; ca.d_stride = static_cast<int64_t>(R) * d;
