@@ -56,6 +56,7 @@ hipError_t launch_routed_gate_up(const RoutedGemmArgs& a, hipStream_t stream);
 hipError_t launch_routed_down(const RoutedGemmArgs& a, hipStream_t stream);
 int routed_down_planes(int T, int k, int E, int d, int F);   // large-batch down: K planes for a shape
 int shared_down_planes(int T, int d, int F);
+int tile_group_m();                      // row tiles per band of the large-batch tile order
 int routed_tile_m(int T, int k, int E);  // plan tile size chosen for a workload (32 = decode kernels)
 
 // Decode (small batch) variants: weights streamed once, K split across wavefronts and, for the

@@ -68,7 +68,7 @@ struct SharedGemmArgs {
 
 template <typename Cfg>
 __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void shared_gemm_kernel(SharedGemmArgs a, int n_ntiles,
-                                                                                   int kplanes, int ktp) {
+                                                                                   int kplanes, int ktp, int group_m) {
   constexpr int NMAT = Cfg::NMAT, BM_W = Cfg::BM_W, BN_W = Cfg::BN_W;
   constexpr int BM = Cfg::BM, BN = Cfg::BN;
   constexpr int A_BYTES = Cfg::A_BYTES, B_BYTES = Cfg::B_BYTES, STAGE_BYTES = Cfg::STAGE_BYTES;
@@ -88,7 +88,8 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void shared_gemm_ker
 
   // Persistent workgroups, dealt to the 8 XCDs round-robin by linear id: XCD x owns the
   // (channel tile, K plane) pairs x, x+8, ... (the row tiles x, x+8, ... when there are fewer
-  // than 16 pairs) and walks the other index fastest, so its L2 keeps one slice of the weights.
+  // than 16 pairs); inside an XCD the tiles are ordered in bands of group_m row tiles, row tile
+  // fastest, so the resident workgroups share both activation tiles and weight slices in L2.
   // With kplanes > 1 (down projection of small problems) the contraction is cut into planes of
   // ktp K steps; each plane writes its own partial output, added later in plane order.
   n_ntiles *= kplanes;
@@ -98,6 +99,7 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void shared_gemm_ker
   const int xcd_ntiles = split_n ? (n_ntiles - xcd + 7) >> 3 : n_ntiles;
   const int xcd_mtiles = split_n ? n_mtiles : (n_mtiles - xcd + 7) >> 3;
   const int xcd_work = xcd_ntiles * xcd_mtiles;
+  const int per_group = group_m * xcd_ntiles;   // tiles of a band of group_m row tiles
   const int stride = gridDim.x >> 3;
   int slot = blockIdx.x >> 3;
   if (slot >= xcd_work) return;
@@ -130,7 +132,10 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void shared_gemm_ker
 
 #define MOTE_DECODE(slot_, mt_, nt_, kc_)                                       \
   {                                                                             \
-    const int mi_ = (slot_) / xcd_ntiles, ni_ = (slot_) - mi_ * xcd_ntiles;     \
+    const int grp_ = (slot_) / per_group;                                       \
+    const int in_ = (slot_) - grp_ * per_group;                                 \
+    const int gsz_ = min(xcd_mtiles - grp_ * group_m, group_m);                 \
+    const int ni_ = in_ / gsz_, mi_ = grp_ * group_m + (in_ - ni_ * gsz_);      \
     mt_ = split_n ? mi_ : xcd + 8 * mi_;                                        \
     const int ntk_ = split_n ? xcd + 8 * ni_ : ni_;                             \
     nt_ = ntk_ / kplanes;                                                       \
@@ -366,7 +371,7 @@ static hipError_t launch_shared_cfg(const SharedGemmArgs& a, int kplanes, hipStr
   const int64_t tiles = static_cast<int64_t>(n_mtiles) * n_ntiles * kplanes;
   int64_t blocks = static_cast<int64_t>(shared_cu_count()) * resident;
   if (blocks > tiles) blocks = (tiles + 7) / 8 * 8;
-  shared_gemm_kernel<Cfg><<<static_cast<unsigned>(blocks), Cfg::THREADS, lds, stream>>>(a, n_ntiles, kplanes, ktp);
+  shared_gemm_kernel<Cfg><<<static_cast<unsigned>(blocks), Cfg::THREADS, lds, stream>>>(a, n_ntiles, kplanes, ktp, tile_group_m());
   return hipGetLastError();
 }
 

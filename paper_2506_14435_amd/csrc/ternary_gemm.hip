@@ -77,7 +77,7 @@ __device__ __forceinline__ int lds_a_offset(int row, int chunk) { return row * 1
 // 1-KiB loads fill the CU's vector-memory queue and every wavefront stalls in issue (measured:
 // about 800 cycles per K step) before it reaches its first MFMA.
 template <typename Cfg>
-__global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_kernel(RoutedGemmArgs a, int n_ntiles, int kplanes, int ktp) {
+__global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_kernel(RoutedGemmArgs a, int n_ntiles, int kplanes, int ktp, int group_m) {
   constexpr int NMAT = Cfg::NMAT, BM_W = Cfg::BM_W, BN_W = Cfg::BN_W;
   constexpr int BM = Cfg::BM, BN = Cfg::BN, THREADS = Cfg::THREADS;
   constexpr int A_BYTES = Cfg::A_BYTES, STAGE_BYTES = Cfg::STAGE_BYTES;
@@ -105,9 +105,10 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
   // Persistent workgroups: the grid is one wave of resident workgroups; each walks a strided
   // list of (row tile, channel tile) pairs.  Workgroups are dealt to the 8 XCDs round-robin
   // by linear id, so XCD x takes the channel tiles x, x+8, ... (or, when there are fewer
-  // than 16 channel tiles, the row tiles x, x+8, ...) and walks the other index fastest:
-  // the packed weights of an expert and the few activation row tiles in flight stay
-  // resident in that XCD's own L2.
+  // than 16 channel tiles, the row tiles x, x+8, ...).  Inside an XCD the pairs are ordered in
+  // bands of group_m row tiles, row tile fastest: the workgroups resident at one time then
+  // cover about group_m row tiles x (resident / group_m) channel tiles, so every activation
+  // tile and every weight slice fetched into that XCD's L2 is used by several of them.
   // With kplanes > 1 (down projection of small problems) the contraction is cut into planes
   // of ktp K steps; a (channel tile, plane) pair then plays the role of a channel tile and each
   // plane writes its own partial output that the combine kernel adds.
@@ -118,6 +119,7 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
   const int xcd_ntiles = split_n ? (n_ntiles - xcd + 7) >> 3 : n_ntiles;
   const int xcd_mtiles = split_n ? n_mtiles : (n_mtiles - xcd + 7) >> 3;
   const int xcd_work = xcd_ntiles * xcd_mtiles;
+  const int per_group = group_m * xcd_ntiles;   // tiles of a band of group_m row tiles
   const int stride = gridDim.x >> 3;
   int slot = blockIdx.x >> 3;
   if (slot >= xcd_work) return;
@@ -165,7 +167,10 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
 
 #define MOTE_DECODE(slot_, mt_, nt_, kc_)                                       \
   {                                                                             \
-    const int mi_ = (slot_) / xcd_ntiles, ni_ = (slot_) - mi_ * xcd_ntiles;     \
+    const int grp_ = (slot_) / per_group;                                       \
+    const int in_ = (slot_) - grp_ * per_group;                                 \
+    const int gsz_ = min(xcd_mtiles - grp_ * group_m, group_m);                 \
+    const int ni_ = in_ / gsz_, mi_ = grp_ * group_m + (in_ - ni_ * gsz_);      \
     mt_ = split_n ? mi_ : xcd + 8 * mi_;                                        \
     const int ntk_ = split_n ? xcd + 8 * ni_ : ni_;                             \
     nt_ = ntk_ / kplanes;                                                       \
@@ -457,6 +462,18 @@ static int resident_blocks() {
   return n;
 }
 
+// Row tiles per band of the tile order (environment variable MOTE_GROUP_M, read once; a value
+// larger than the number of row tiles gives the plain row-tile-fastest sweep).
+int tile_group_m() {
+  static int v = -1;
+  if (v < 0) {
+    const char* e = getenv("MOTE_GROUP_M");
+    v = e ? atoi(e) : 8;
+    if (v < 1) v = 8;
+  }
+  return v;
+}
+
 template <typename Cfg>
 static hipError_t launch_cfg(const RoutedGemmArgs& a, int kplanes, hipStream_t stream) {
   const int n_ntiles = (a.N + Cfg::BN - 1) / Cfg::BN;
@@ -466,7 +483,7 @@ static hipError_t launch_cfg(const RoutedGemmArgs& a, int kplanes, hipStream_t s
   const int64_t tiles = static_cast<int64_t>(a.max_tiles) * n_ntiles * kplanes;
   int64_t blocks = static_cast<int64_t>(device_cu_count()) * resident_blocks<Cfg>();
   if (blocks > tiles) blocks = (tiles + 7) / 8 * 8;
-  routed_gemm_kernel<Cfg><<<static_cast<unsigned>(blocks), Cfg::THREADS, 0, stream>>>(a, n_ntiles, kplanes, ktp);
+  routed_gemm_kernel<Cfg><<<static_cast<unsigned>(blocks), Cfg::THREADS, 0, stream>>>(a, n_ntiles, kplanes, ktp, tile_group_m());
   return hipGetLastError();
 }
 
