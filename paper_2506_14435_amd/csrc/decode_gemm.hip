@@ -18,6 +18,8 @@
 // MFMA operand mapping as in the large-batch kernels: first operand = weights (lane l:
 // output channel l%32, K half l/32), second = activations (lane l: row l%32); result
 // register v of lane l is output channel 8*(v/4) + 4*(l/32) + v%4 of row l%32.
+#include <stdlib.h>
+
 #include "common.h"
 #include "launch.h"
 
@@ -72,8 +74,8 @@ __global__ __launch_bounds__(kDecThreads) void routed_decode_kernel(RoutedGemmAr
 #pragma unroll
     for (int j = 0; j < PD; ++j) {
       if (j < nsteps) {
-        wr[j][0] = *reinterpret_cast<const u4*>(wg + j * 1024);
-        if constexpr (NMAT == 2) wr[j][1] = *reinterpret_cast<const u4*>(wu + j * 1024);
+        wr[j][0] = __builtin_nontemporal_load(reinterpret_cast<const u4*>(wg + j * 1024));
+        if constexpr (NMAT == 2) wr[j][1] = __builtin_nontemporal_load(reinterpret_cast<const u4*>(wu + j * 1024));
       }
     }
     // activation rows: lane (r32, g) reads 16 bytes per 32-channel sub-step
@@ -110,8 +112,8 @@ __global__ __launch_bounds__(kDecThreads) void routed_decode_kernel(RoutedGemmAr
           }
           const int nx = base + j + PD;
           if (nx < nsteps) {
-            wr[j][0] = *reinterpret_cast<const u4*>(wg + static_cast<int64_t>(nx) * 1024);
-            if constexpr (NMAT == 2) wr[j][1] = *reinterpret_cast<const u4*>(wu + static_cast<int64_t>(nx) * 1024);
+            wr[j][0] = __builtin_nontemporal_load(reinterpret_cast<const u4*>(wg + static_cast<int64_t>(nx) * 1024));
+            if constexpr (NMAT == 2) wr[j][1] = __builtin_nontemporal_load(reinterpret_cast<const u4*>(wu + static_cast<int64_t>(nx) * 1024));
 #pragma unroll
             for (int s = 0; s < 4; ++s)
               ar[j][s] = *reinterpret_cast<const v4i*>(ap + static_cast<int64_t>(nx) * 128 + s * 32);
@@ -215,7 +217,7 @@ __global__ __launch_bounds__(kDecThreads, 2) void routed_stream_kernel(RoutedGem
 #define MOTE_LOADW(dst_, nf_)                                                               \
   _Pragma("unroll") for (int m = 0; m < NMAT; ++m)                                          \
     _Pragma("unroll") for (int s = 0; s < 4; ++s)                                           \
-      if (s < nsteps) dst_[m][s] = *reinterpret_cast<const u4*>(wb[m] + (nf_) * frag_bytes + s * 1024)
+      if (s < nsteps) dst_[m][s] = __builtin_nontemporal_load(reinterpret_cast<const u4*>(wb[m] + (nf_) * frag_bytes + s * 1024))
     MOTE_LOADW(w_a, nf0);
     if (nf0 + 1 < nf_end) { MOTE_LOADW(w_b, nf0 + 1); }
 
@@ -299,6 +301,171 @@ __global__ __launch_bounds__(kDecThreads, 2) void routed_stream_kernel(RoutedGem
   }
 }
 
+// Wave-streaming variant for many (tile, fragment) units: the int8 activation rows of one
+// (row tile, K plane of 16 steps) sit in LDS (64 KiB, loaded directly from global memory),
+// and every wavefront of the workgroup owns whole output fragments of that tile: it streams the
+// packed weights of its fragment through a register ring of eight K steps, crossing into its
+// next fragment without a bubble, and finishes the fragment alone - no barrier, no cross-wave
+// reduction in the steady state.  Loads are raw buffer loads issued unconditionally (a lane
+// offset beyond the buffer turns one into a no-op), so the number of loads in flight is the
+// same on every path and the compiler's wait counts stay exact.  A plane shorter than 16 steps
+// is padded with zero activations.
+template <int MODE>
+__global__ __launch_bounds__(kDecThreads, 2) void routed_wave_kernel(RoutedGemmArgs a, int n_frags, int kc_count) {
+  constexpr int NMAT = MODE == 0 ? 2 : 1;
+  constexpr int D = 8;                                    // K steps of packed weights in flight per wavefront
+  constexpr int kBufferFlags = 0x00020000;                // raw buffer, 32-bit data format
+  constexpr int kWeightAux = 2;                           // weight loads are non-temporal: every byte is used once (measured: 42 -> 39.5 us)
+  constexpr uint32_t kOutOfRange = 0x80000000u;           // lane offset past any buffer of <= 2 GiB
+  // activations of the plane: [K step 16][16-byte chunk 8][row 32][16 bytes]; a quarter wavefront
+  // reads 16 consecutive rows of one chunk = 256 contiguous bytes
+  __shared__ __attribute__((aligned(16))) unsigned char s_a[16 * 8 * 32 * 16];
+
+  const int K = a.K, N = a.N, KT = K >> 7;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int r32 = lane & 31, g = lane >> 5;
+  const int64_t expert_words = static_cast<int64_t>(N) * K / 16;
+  const uint32_t lds0 = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) unsigned char*)s_a);
+  auto make_rsrc = [&](const void* base, int64_t bytes) {
+    const uint64_t p = reinterpret_cast<uint64_t>(base);
+    v4i r;
+    r.x = static_cast<int>(static_cast<uint32_t>(p));
+    r.y = static_cast<int>(static_cast<uint32_t>(p >> 32) & 0xFFFFu);
+    r.z = static_cast<int>(bytes);
+    r.w = kBufferFlags;
+    return r;
+  };
+  const v4i rsrc_q = make_rsrc(a.q, a.q_rows * K);
+  const int64_t total = static_cast<int64_t>(load_uniform(a.plan.n_tiles)) * kc_count * n_frags;
+  int64_t u = blockIdx.x * total / gridDim.x;
+  const int64_t hi = (blockIdx.x + 1) * total / gridDim.x;
+
+  while (u < hi) {
+    const int grp = static_cast<int>(u / n_frags);          // (row tile, K plane)
+    const int nf0 = static_cast<int>(u - static_cast<int64_t>(grp) * n_frags);
+    const int nf_end = static_cast<int>(min(static_cast<int64_t>(n_frags), nf0 + (hi - u)));
+    const int mt = grp / kc_count, kc = grp - mt * kc_count;
+    const int expert = load_uniform(a.plan.tile_expert + mt);
+    const int row0 = load_uniform(a.plan.tile_row0 + mt);
+    const int rows = load_uniform(a.plan.tile_rows + mt);
+    const int step0 = kc * 16;
+    const int nsteps = min(16, KT - step0);
+
+    // ---- weight ring first: it depends on the plan only, not on the row gather ----
+    __amdgpu_buffer_rsrc_t rw[NMAT];
+    rw[0] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(a.w_gate) + expert * expert_words, 0,
+                                              static_cast<int>(expert_words * 4), kBufferFlags);
+    if constexpr (NMAT == 2)
+      rw[1] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(a.w_up) + expert * expert_words, 0,
+                                                static_cast<int>(expert_words * 4), kBufferFlags);
+    const uint32_t w_lane = lane * 16;
+    u4 wr[D][NMAT];
+    int nf = nf0 + wave;   // this wavefront's fragments: nf0 + wave, + 4, ...
+    {   // the first D steps of the first fragment (out of range if this wavefront has none)
+      const uint32_t oob = nf < nf_end ? 0u : kOutOfRange;
+#pragma unroll
+      for (int j = 0; j < D; ++j)
+#pragma unroll
+        for (int m = 0; m < NMAT; ++m)
+          wr[j][m] = __builtin_amdgcn_raw_buffer_load_b128(rw[m], w_lane + oob, (nf * KT + step0 + j) * 1024, kWeightAux);
+    }
+
+    // ---- activation plane into LDS ----
+    const int slot = row0 + min(r32, rows - 1);
+    const int src = a.gather ? a.gather[slot] : slot;
+    __syncthreads();   // every wavefront is done with the previous plane
+    {
+      const uint32_t voff = static_cast<uint32_t>(src) * static_cast<uint32_t>(K) + step0 * 128 + g * 16;
+      // load i covers K step i/4, chunks 2*(i%4) and 2*(i%4)+1 (lane l: chunk + l/32, row l%32)
+      for (int i = wave; i < nsteps * 4; i += 4) {
+        const uint32_t dst = lds0 + static_cast<uint32_t>(((i >> 2) * 8 + 2 * (i & 3)) * 512);
+        const int soff = (i >> 2) * 128 + (i & 3) * 32;
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                     :: "s"(dst), "v"(voff), "s"(rsrc_q), "s"(soff) : "memory");
+      }
+      // steps past the end of the contraction contribute nothing: zero activations
+      for (int i = nsteps * 256 + tid; i < 16 * 256; i += kDecThreads)   // 256 x 16 bytes per K step
+        *reinterpret_cast<u4*>(s_a + i * 16) = u4{0u, 0u, 0u, 0u};
+    }
+    const float m_beta = a.beta[src];
+    const int m_rs = a.rowsum[src];
+    float sg = 0.0f, su = 0.0f;
+    if constexpr (MODE == 0) {
+      const float sx = m_beta / 127.0f;
+      sg = sx * load_uniform(a.alpha + expert * 3 + 0);
+      su = sx * load_uniform(a.alpha + expert * 3 + 1);
+    }
+    const int corr = (MODE == 0 || kc == 0) ? m_rs : 0;   // zero-point correction enters one plane only
+    const __amdgpu_buffer_rsrc_t r_out = __builtin_amdgcn_make_buffer_rsrc(
+        MODE == 0 ? static_cast<void*>(a.h) : static_cast<void*>(a.acc_out + static_cast<int64_t>(kc) * a.partial_stride), 0,
+        static_cast<int>(a.out_rows * N * (MODE == 0 ? 2 : 4)), kBufferFlags);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the plane (and everything else requested so far) has landed
+    __syncthreads();
+
+    for (; nf < nf_end; nf += 4) {
+      const uint32_t oob_next = nf + 4 < nf_end ? 0u : kOutOfRange;
+      v16i acc[NMAT];
+#pragma unroll
+      for (int m = 0; m < NMAT; ++m)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[m][v] = 0;
+#pragma unroll
+      for (int kt = 0; kt < 16; ++kt) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          const v4i af = *reinterpret_cast<const v4i*>(s_a + ((kt * 8 + 2 * s + g) * 32 + r32) * 16);
+#pragma unroll
+          for (int m = 0; m < NMAT; ++m)
+            acc[m] = __builtin_amdgcn_mfma_i32_32x32x32_i8(unpack_codes_dec(wr[kt % D][m][s]), af, acc[m], 0, 0, 0);
+        }
+        // refill the slot: step kt + D of this fragment, or step kt + D - 16 of the next one
+#pragma unroll
+        for (int m = 0; m < NMAT; ++m) {
+          if (kt + D < 16)
+            wr[kt % D][m] = __builtin_amdgcn_raw_buffer_load_b128(rw[m], w_lane, (nf * KT + step0 + kt + D) * 1024, kWeightAux);
+          else
+            wr[kt % D][m] = __builtin_amdgcn_raw_buffer_load_b128(rw[m], w_lane + oob_next,
+                                                                  ((nf + 4) * KT + step0 + kt + D - 16) * 1024, kWeightAux);
+        }
+        __builtin_amdgcn_sched_barrier(0);   // one K step at a time: the LDS reads of later steps would pile up in registers
+      }
+      // ---- epilogue of the fragment: lane l owns row r32 and channels 8q + 4g .. +3 ----
+      const bool row_ok = r32 < rows;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const uint32_t o = static_cast<uint32_t>(row0 + r32) * static_cast<uint32_t>(N) + nf * 32 + 8 * q + 4 * g;
+        int sum[NMAT][4];
+#pragma unroll
+        for (int m = 0; m < NMAT; ++m)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) sum[m][j] = acc[m][4 * q + j] - corr;
+        if constexpr (MODE == 0) {
+          float hv[4];
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            hv[j] = (static_cast<float>(sum[NMAT - 1][j]) * su) * silu_fast(static_cast<float>(sum[0][j]) * sg);
+          typedef unsigned u2v __attribute__((ext_vector_type(2)));
+          u2v packed;
+          packed.x = cvt_pk_bf16(hv[0], hv[1]);
+          packed.y = cvt_pk_bf16(hv[2], hv[3]);
+          __builtin_amdgcn_raw_buffer_store_b64(packed, r_out, row_ok ? o * 2u : kOutOfRange, 0, 0);
+          if (row_ok && a.tap_gate != nullptr)
+            *reinterpret_cast<int4*>(a.tap_gate + o) = make_int4(sum[0][0], sum[0][1], sum[0][2], sum[0][3]);
+          if (row_ok && a.tap_up != nullptr)
+            *reinterpret_cast<int4*>(a.tap_up + o) =
+                make_int4(sum[NMAT - 1][0], sum[NMAT - 1][1], sum[NMAT - 1][2], sum[NMAT - 1][3]);
+        } else {
+          const u4 d4 = {static_cast<unsigned>(sum[0][0]), static_cast<unsigned>(sum[0][1]),
+                         static_cast<unsigned>(sum[0][2]), static_cast<unsigned>(sum[0][3])};
+          __builtin_amdgcn_raw_buffer_store_b128(d4, r_out, row_ok ? o * 4u : kOutOfRange, 0, 0);
+        }
+      }
+    }
+    u += nf_end - nf0;
+  }
+}
+
 static int device_cus() {
   static int n = 0;
   if (n == 0) {
@@ -312,6 +479,23 @@ static int device_cus() {
 
 int routed_decode_down_planes(int K) { return ((K >> 7) + 15) / 16; }
 
+// The wave-streaming kernel wants whole 16-step planes (a ragged last plane is padded with
+// zero activations) and enough units to give every wavefront of the grid a fragment.
+static bool use_wave_kernel(const RoutedGemmArgs& a, int n_frags, int kc) {
+  static int forced = -2;
+  if (forced == -2) {
+    const char* e = getenv("MOTE_DECODE_VARIANT");
+    forced = e ? atoi(e) : -1;
+  }
+  if (forced >= 0) return forced == 1;
+  const int KT = a.K >> 7;
+  const int padded = kc * 16;
+  if (padded * 3 > KT * 4) return false;                                 // more than a third of the MFMA work would be padding
+  if (static_cast<int64_t>(a.q_rows) * a.K >= (int64_t{1} << 31)) return false;
+  // few dispatch rows = few row tiles: the K-split kernel keeps all four wavefronts of a workgroup busy then
+  return a.out_rows >= 64 && static_cast<int64_t>(n_frags) * kc >= 256;
+}
+
 hipError_t launch_routed_decode_gate_up(const RoutedGemmArgs& a, hipStream_t stream) {
   if (a.max_tiles == 0) return hipSuccess;
   const int n_frags = a.N / 32, KT = a.K >> 7;
@@ -319,7 +503,10 @@ hipError_t launch_routed_decode_gate_up(const RoutedGemmArgs& a, hipStream_t str
   int64_t blocks = static_cast<int64_t>(device_cus()) * 4;
   if (blocks > max_units) blocks = max_units;
   if (KT <= 16) {
-    routed_stream_kernel<0><<<device_cus() * 2, kDecThreads, 0, stream>>>(a, n_frags, 1);
+    if (use_wave_kernel(a, n_frags, 1))
+      routed_wave_kernel<0><<<device_cus() * 2, kDecThreads, 0, stream>>>(a, n_frags, 1);
+    else
+      routed_stream_kernel<0><<<device_cus() * 2, kDecThreads, 0, stream>>>(a, n_frags, 1);
     return hipGetLastError();
   }
   routed_decode_kernel<0><<<static_cast<unsigned>(blocks), kDecThreads, 0, stream>>>(a, n_frags, 1, (KT + 3) / 4);
@@ -330,11 +517,10 @@ hipError_t launch_routed_decode_down(const RoutedGemmArgs& a, hipStream_t stream
   if (a.max_tiles == 0) return hipSuccess;
   const int n_frags = a.N / 32;
   const int kc = routed_decode_down_planes(a.K);
-  const int64_t max_units = static_cast<int64_t>(a.max_tiles) * n_frags * kc;
-  int64_t blocks = static_cast<int64_t>(device_cus()) * 4;
-  if (blocks > max_units) blocks = max_units;
-  (void)blocks;
-  routed_stream_kernel<1><<<device_cus() * 3, kDecThreads, 0, stream>>>(a, n_frags, kc);
+  if (use_wave_kernel(a, n_frags, kc))
+    routed_wave_kernel<1><<<device_cus() * 2, kDecThreads, 0, stream>>>(a, n_frags, kc);
+  else
+    routed_stream_kernel<1><<<device_cus() * 3, kDecThreads, 0, stream>>>(a, n_frags, kc);
   return hipGetLastError();
 }
 

@@ -45,6 +45,7 @@ struct RoutedGemmArgs {
   int tile_m;               // rows per plan tile
   int K, N;                 // contraction length, output width (per matrix)
   int64_t q_rows;           // rows of q (q_rows * K <= 2^31: 32-bit buffer offsets)
+  int64_t out_rows;         // rows of the output (dispatch rows R)
   uint16_t* h;              // gate-up: bf16 [R, N]
   int32_t* acc_out;         // down: int32 [R, N] (decode: partial planes [planes][R, N])
   int64_t partial_stride;   // elements between partial planes (down projections)

@@ -264,7 +264,7 @@ mote_status mote_layer_forward(const mote_layer* layer, const void* x, int T, vo
   ga.q = w.q_x; ga.gather = w.tok_of; ga.beta = w.beta_x; ga.rowsum = w.rs_x;
   ga.w_gate = layer->wt_gate; ga.w_up = layer->wt_up; ga.alpha = layer->alpha;
   ga.plan = plan; ga.max_tiles = R / tile_m + E; ga.tile_m = tile_m;
-  ga.K = d; ga.N = Fr; ga.q_rows = T; ga.h = w.h; ga.acc_out = nullptr;
+  ga.K = d; ga.N = Fr; ga.q_rows = T; ga.out_rows = R; ga.h = w.h; ga.acc_out = nullptr;
   ga.tap_gate = taps ? taps->acc_gate : nullptr;
   ga.tap_up = taps ? taps->acc_up : nullptr;
   ga.partial_stride = 0; ga.planes = 1;
