@@ -648,12 +648,194 @@ __global__ __launch_bounds__(kDecThreads) void shared_decode_kernel(SharedDecode
   }
 }
 
+// Wave-streaming shared expert for T <= 64: one wavefront = one workgroup owns a 32-channel
+// fragment (both matrices in gate-up mode) over its whole K range (a K plane in down mode) and
+// streams weight rows AND token rows straight into a private LDS ring of 64-element K steps
+// (buffer_load ... lds: a wavefront load covers 8 rows x 128 bytes = whole cache lines, the
+// register-operand layout of the MFMA would touch 32 lines per load).  Nothing synchronises:
+// the wavefront waits on its own load counter, S-1 steps (48 KiB) stay in flight, which is what
+// a few hundred wavefronts need to keep HBM busy.  LDS rows are 128 bytes, chunk XOR-swizzled
+// with row bits 1..3 (conflict-free ds_read_b128 of 32 rows).
+// wait until at most min(ahead, MAXA) * L of this wavefront's loads are outstanding
+template <int L, int MAXA>
+__device__ __forceinline__ void wait_steps_ahead(int ahead) {
+  if constexpr (MAXA > 0) {
+    if (ahead >= MAXA) {
+      asm volatile("s_waitcnt vmcnt(%0)" :: "n"(MAXA * L) : "memory");
+      return;
+    }
+    wait_steps_ahead<L, MAXA - 1>(ahead);
+  } else {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  }
+}
+
+// AL = 1-KiB loads of token rows per K step (8 rows each): 1, 2, 4 or 8 for T <= 8, 16, 32, 64.
+// Token rows beyond the batch are never loaded: the MFMA reads whatever the ring holds there
+// and the output rows it produces from it are not stored.
+template <int MODE, int AL>
+struct SharedWaveCfg {
+  static constexpr int NMAT = MODE == 0 ? 2 : 1;
+  static constexpr int MFR = AL > 4 ? 2 : 1;                // 32-row fragments of tokens
+  static constexpr int W_LOADS = NMAT * 4, L = W_LOADS + AL;   // 1-KiB loads per K step
+  static constexpr int A_OFF = W_LOADS * 1024;              // token rows follow the weight rows in a slot
+  static constexpr int SLOT = L * 1024;                     // only the loaded rows: reads of the other token rows run into the next slot
+  static constexpr int TAIL = (MFR * 4 - AL) * 1024;        // ... or, in the last slot, into this much padding
+  static constexpr int S_LDS = (65536 - TAIL) / SLOT, S_CNT = 2 + 63 / L;
+  static constexpr int S = S_LDS < S_CNT ? S_LDS : S_CNT;   // ring slots: LDS and the 6-bit load counter bound it
+  static constexpr int LDS = S * SLOT + TAIL;
+};
+
+template <int MODE, int AL>
+__global__ __launch_bounds__(64) void shared_wave_kernel(SharedDecodeArgs a, int kc_count, int steps_per_plane) {
+  using Cfg = SharedWaveCfg<MODE, AL>;
+  constexpr int NMAT = Cfg::NMAT, MFR = Cfg::MFR, L = Cfg::L, SLOT = Cfg::SLOT, S = Cfg::S, A_LOADS = AL;
+  constexpr int kBufferFlags = 0x00020000;
+  extern __shared__ __attribute__((aligned(16))) unsigned char s_ring[];
+  const int M = a.M, N = a.N, K = a.K, KT = K >> 6;
+  const int lane = threadIdx.x, r32 = lane & 31, g = lane >> 5;
+  const int kc = blockIdx.x % kc_count, nf = blockIdx.x / kc_count;
+  const int step0 = kc * steps_per_plane;
+  const int nsteps = min(steps_per_plane, KT - step0);
+  const uint32_t lds0 = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) unsigned char*)s_ring);
+  auto make_rsrc = [&](const void* base, int64_t bytes) {
+    const uint64_t p = reinterpret_cast<uint64_t>(base);
+    v4i r;
+    r.x = static_cast<int>(static_cast<uint32_t>(p));
+    r.y = static_cast<int>(static_cast<uint32_t>(p >> 32) & 0xFFFFu);
+    r.z = static_cast<int>(bytes);
+    r.w = kBufferFlags;
+    return r;
+  };
+  const v4i rsrc_a = make_rsrc(a.act, static_cast<int64_t>(M) * K * 2);
+  const v4i rsrc_w0 = make_rsrc(a.w0, static_cast<int64_t>(N) * K * 2);
+  const v4i rsrc_w1 = make_rsrc(NMAT == 2 ? a.w1 : a.w0, static_cast<int64_t>(N) * K * 2);
+  // load i of a 32-row block covers rows 8i .. 8i+7: lane l lands at row 8i + l/8, physical chunk l%8
+  const int ld_row = lane >> 3;
+  uint32_t w_voff[4], a_voff[A_LOADS];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int chunk = (lane & 7) ^ ((4 * i + (ld_row >> 1)) & 7);
+    w_voff[i] = static_cast<uint32_t>(nf * 32 + 8 * i + ld_row) * static_cast<uint32_t>(K) * 2u + step0 * 128 + chunk * 16;
+  }
+#pragma unroll
+  for (int i = 0; i < A_LOADS; ++i) {
+    const int chunk = (lane & 7) ^ ((4 * i + (ld_row >> 1)) & 7);
+    a_voff[i] = static_cast<uint32_t>(min(8 * i + ld_row, M - 1)) * static_cast<uint32_t>(K) * 2u + step0 * 128 + chunk * 16;
+  }
+#define MOTE_DMA(lds_, voff_, rsrc_, soff_)                                                        \
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"           \
+               :: "s"(lds_), "v"(voff_), "s"(rsrc_), "s"(soff_) : "memory")
+#define MOTE_ISSUE(step_, slot_)                                                                   \
+  {                                                                                                \
+    const uint32_t base_ = lds0 + (slot_) * SLOT;                                                  \
+    const int soff_ = (step_) * 128;                                                               \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i) MOTE_DMA(base_ + i * 1024, w_voff[i], rsrc_w0, soff_);            \
+    if constexpr (NMAT == 2) {                                                                     \
+      _Pragma("unroll") for (int i = 0; i < 4; ++i) MOTE_DMA(base_ + 4096 + i * 1024, w_voff[i], rsrc_w1, soff_);   \
+    }                                                                                              \
+    _Pragma("unroll") for (int i = 0; i < A_LOADS; ++i)                                            \
+      MOTE_DMA(base_ + Cfg::A_OFF + i * 1024, a_voff[i], rsrc_a, soff_);                          \
+  }
+
+  v16f acc[NMAT][MFR];
+#pragma unroll
+  for (int m = 0; m < NMAT; ++m)
+#pragma unroll
+    for (int f = 0; f < MFR; ++f)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[m][f][v] = 0.0f;
+
+  for (int j = 0; j < S - 1 && j < nsteps; ++j) MOTE_ISSUE(j, j);
+  const int rd = r32 * 128, sw = (r32 >> 1) & 7;
+  int slot = 0, slot_fill = S - 1;
+  for (int j = 0; j < nsteps; ++j) {
+    // steps j+1 .. min(j+S-2, nsteps-1) may stay in flight
+    wait_steps_ahead<L, S - 2>(nsteps - 1 - j);
+    const unsigned char* const st = s_ring + slot * SLOT;
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4) {
+      const int co = ((2 * s4 + g) ^ sw) << 4;
+      bf16x8 af[MFR];
+#pragma unroll
+      for (int f = 0; f < MFR; ++f) af[f] = *reinterpret_cast<const bf16x8*>(st + Cfg::A_OFF + f * 4096 + rd + co);
+#pragma unroll
+      for (int m = 0; m < NMAT; ++m) {
+        const bf16x8 wf = *reinterpret_cast<const bf16x8*>(st + m * 4096 + rd + co);
+#pragma unroll
+        for (int f = 0; f < MFR; ++f) acc[m][f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, af[f], acc[m][f], 0, 0, 0);
+      }
+    }
+    // refill the slot that was consumed one step ago with step j + S - 1
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    if (j + S - 1 < nsteps) MOTE_ISSUE(j + S - 1, slot_fill);
+    slot_fill = slot;
+    slot = slot + 1 == S ? 0 : slot + 1;
+  }
+#undef MOTE_DMA
+#undef MOTE_ISSUE
+
+  // lane l owns token row r32 of every row fragment and channels 8q + 4g .. +3 of the fragment
+#pragma unroll
+  for (int f = 0; f < MFR; ++f) {
+    const int row = f * 32 + r32;
+    if (row >= M) continue;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int64_t o = static_cast<int64_t>(row) * N + nf * 32 + 8 * q + 4 * g;
+      if constexpr (MODE == 0) {
+        uint2 packed;
+        packed.x = cvt_pk_bf16(acc[1][f][4 * q] * silu_fast(acc[0][f][4 * q]), acc[1][f][4 * q + 1] * silu_fast(acc[0][f][4 * q + 1]));
+        packed.y = cvt_pk_bf16(acc[1][f][4 * q + 2] * silu_fast(acc[0][f][4 * q + 2]), acc[1][f][4 * q + 3] * silu_fast(acc[0][f][4 * q + 3]));
+        *reinterpret_cast<uint2*>(a.h_out + o) = packed;
+      } else {
+        *reinterpret_cast<float4*>(a.y_out + static_cast<int64_t>(kc) * a.plane_stride + o) =
+            make_float4(acc[0][f][4 * q], acc[0][f][4 * q + 1], acc[0][f][4 * q + 2], acc[0][f][4 * q + 3]);
+      }
+    }
+  }
+}
+
 int shared_decode_down_planes(int K) { return ((K >> 6) + 31) / 32; }
+
+static int shared_decode_variant() {
+  static int v = -2;
+  if (v == -2) {
+    const char* e = getenv("MOTE_SHARED_DECODE_VARIANT");
+    v = e ? atoi(e) : -1;
+  }
+  return v;
+}
+
+template <int MODE, int AL>
+static hipError_t launch_shared_wave_al(const SharedDecodeArgs& a, int n_frags, int kc, int steps_per_plane, hipStream_t stream) {
+  constexpr int lds = SharedWaveCfg<MODE, AL>::LDS;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(shared_wave_kernel<MODE, AL>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  shared_wave_kernel<MODE, AL><<<n_frags * kc, 64, lds, stream>>>(a, kc, steps_per_plane);
+  return hipGetLastError();
+}
+
+template <int MODE>
+static hipError_t launch_shared_wave(const SharedDecodeArgs& a, int n_frags, int kc, int steps_per_plane, hipStream_t stream) {
+  if (a.M <= 8) return launch_shared_wave_al<MODE, 1>(a, n_frags, kc, steps_per_plane, stream);
+  if (a.M <= 16) return launch_shared_wave_al<MODE, 2>(a, n_frags, kc, steps_per_plane, stream);
+  if (a.M <= 32) return launch_shared_wave_al<MODE, 4>(a, n_frags, kc, steps_per_plane, stream);
+  return launch_shared_wave_al<MODE, 8>(a, n_frags, kc, steps_per_plane, stream);
+}
 
 hipError_t launch_shared_decode_gate_up(const uint16_t* x, const uint16_t* w_gate, const uint16_t* w_up, int T, int d,
                                         int F, uint16_t* h_s, hipStream_t stream) {
   SharedDecodeArgs a{x, w_gate, w_up, T, F, d, h_s, nullptr, 0};
   const int n_frags = F / 32, KT = d >> 6;
+  if (shared_decode_variant() != 0) {
+    return launch_shared_wave<0>(a, n_frags, 1, KT, stream);
+  }
   const int spw = (KT + 3) / 4;
   if (T <= 32) shared_decode_kernel<0, 1, 2><<<n_frags, kDecThreads, 0, stream>>>(a, 1, spw);
   else shared_decode_kernel<0, 2, 2><<<n_frags, kDecThreads, 0, stream>>>(a, 1, spw);
@@ -665,6 +847,9 @@ hipError_t launch_shared_decode_down(const uint16_t* h_s, const uint16_t* w_down
   SharedDecodeArgs a{h_s, w_down, nullptr, T, d, F, nullptr, y_s, static_cast<int64_t>(T) * d};
   const int n_frags = d / 32;
   const int kc = shared_decode_down_planes(F);
+  if (shared_decode_variant() != 0) {
+    return launch_shared_wave<1>(a, n_frags, kc, 32, stream);
+  }
   if (T <= 32) shared_decode_kernel<1, 1, 4><<<n_frags * kc, kDecThreads, 0, stream>>>(a, kc, 8);
   else shared_decode_kernel<1, 2, 2><<<n_frags * kc, kDecThreads, 0, stream>>>(a, kc, 8);
   return hipGetLastError();
