@@ -197,6 +197,8 @@ SMALL_CASES = [
     W.MoteConfig("ragged_mid", 384, 640, 8, 2, 211, seed=11, outlier_channels=2),
     W.MoteConfig("e16_skew", 256, 384, 16, 2, 500, seed=12, bias_kind="zipf", zipf_tau=0.8),
     W.MoteConfig("decode_like", 512, 1408, 16, 2, 16, seed=13, bias_kind="subset", bias_subset=4),
+    W.C1.with_tokens(24, name="c1_T24"),                                              # 17..32 tokens: its own shared decode variant
+    W.MoteConfig("one_k_step", 128, 256, 4, 2, 200, seed=14),                        # d = 128: a single 128-channel K step
 ]
 
 
