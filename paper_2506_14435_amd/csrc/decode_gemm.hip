@@ -376,7 +376,9 @@ __global__ __launch_bounds__(kDecThreads, 2) void routed_wave_kernel(RoutedGemmA
     const int src = a.gather ? a.gather[slot] : slot;
     __syncthreads();   // every wavefront is done with the previous plane
     {
-      const uint32_t voff = static_cast<uint32_t>(src) * static_cast<uint32_t>(K) + step0 * 128 + g * 16;
+      // rows past the end of the tile are not fetched (their accumulator rows are never stored)
+      const uint32_t voff = r32 < rows ? static_cast<uint32_t>(src) * static_cast<uint32_t>(K) + step0 * 128 + g * 16
+                                       : kOutOfRange;
       // load i covers K step i/4, chunks 2*(i%4) and 2*(i%4)+1 (lane l: chunk + l/32, row l%32)
       for (int i = wave; i < nsteps * 4; i += 4) {
         const uint32_t dst = lds0 + static_cast<uint32_t>(((i >> 2) * 8 + 2 * (i & 3)) * 512);
