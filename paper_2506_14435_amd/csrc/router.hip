@@ -60,8 +60,6 @@ __global__ __launch_bounds__(64 * NW) void router_quant_kernel(
   constexpr int kWaves = NW;               // wavefronts that split the channels of one token group
   constexpr int kThreads = 64 * NW;
   __shared__ double s_logit[kWaves][64];
-  __shared__ double s_total[64];
-  __shared__ float s_prob[64];
   __shared__ float s_amax[kWaves][TPW];
   __shared__ int s_rsum[kWaves][TPW];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -81,12 +79,18 @@ __global__ __launch_bounds__(64 * NW) void router_quant_kernel(
 #pragma unroll
   for (int t = 0; t < TPW; ++t) amax[t] = 0.0f;
 
+  // with at most one chunk per lane the token values stay in registers for the quantisation pass
+  const bool single_pass = n_chunks <= kThreads;
+  u4 xkeep[TPW];   // plain register vectors
+#pragma unroll
+  for (int t = 0; t < TPW; ++t) xkeep[t] = u4{0u, 0u, 0u, 0u};
   for (int ch = wave * kWave + lane; ch < n_chunks; ch += kThreads) {
     const int c0 = ch << 3;
     float xf[TPW][8];
 #pragma unroll
     for (int t = 0; t < TPW; ++t) {
       const uint4 p = *reinterpret_cast<const uint4*>(xrow[t] + c0);
+      xkeep[t] = u4{p.x, p.y, p.z, p.w};
       xf[t][0] = bf16_lo(p.x); xf[t][1] = bf16_hi(p.x); xf[t][2] = bf16_lo(p.y); xf[t][3] = bf16_hi(p.y);
       xf[t][4] = bf16_lo(p.z); xf[t][5] = bf16_hi(p.z); xf[t][6] = bf16_lo(p.w); xf[t][7] = bf16_hi(p.w);
 #pragma unroll
@@ -129,8 +133,32 @@ __global__ __launch_bounds__(64 * NW) void router_quant_kernel(
     float sum = ex;
 #pragma unroll
     for (int off = EMAX / 2; off > 0; off >>= 1) sum += __shfl_xor(sum, off, kWave);
-    s_total[lane] = l;
-    s_prob[lane] = ex / sum;
+    const float pr = ex / sum;
+    // top-k: k rounds of an arg-max butterfly over the EMAX lanes of a token.  Every lane of the
+    // group ends a round with the winner (largest logit, ties to the lower expert index); the
+    // winner's own lane then leaves the contest.
+    double cur = l;                      // invalid experts sit at -1e300, taken ones go below that
+    const int tok = lane / EMAX;
+    for (int j = 0; j < k; ++j) {
+      double bl = cur;
+      int be = e;
+      float bp = pr;
+#pragma unroll
+      for (int off = EMAX / 2; off > 0; off >>= 1) {
+        const double ol = __shfl_xor(bl, off, kWave);
+        const int oe = __shfl_xor(be, off, kWave);
+        const float op = __shfl_xor(bp, off, kWave);
+        const bool take = (ol > bl) || (ol == bl && oe < be);
+        bl = take ? ol : bl;
+        be = take ? oe : be;
+        bp = take ? op : bp;
+      }
+      if (be == e) cur = -1.7e300;
+      if (e == 0 && t0 + tok < T) {
+        topk_idx[static_cast<int64_t>(t0 + tok) * k + j] = be;
+        topk_p[static_cast<int64_t>(t0 + tok) * k + j] = bp;
+      }
+    }
   }
 #pragma unroll
   for (int t = 0; t < TPW; ++t) {
@@ -138,28 +166,6 @@ __global__ __launch_bounds__(64 * NW) void router_quant_kernel(
 #pragma unroll
     for (int w = 1; w < kWaves; ++w) m = fmaxf(m, s_amax[w][t]);
     amax[t] = m;
-  }
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-
-  // Softmax over all E logits and top-k: one lane per token, serial over E <= 64.
-  if (wave == 0 && lane < TPW && t0 + lane < T) {
-    const double* l = &s_total[lane * EMAX];
-    const float* pr = &s_prob[lane * EMAX];
-    uint64_t taken = 0;
-    for (int j = 0; j < k; ++j) {
-      int best = -1;
-      double lb = 0.0;
-      for (int e = 0; e < E; ++e) {
-        if ((taken >> e) & 1ull) continue;
-        const double le = l[e];
-        if (best < 0 || le > lb) { best = e; lb = le; }   // strict >: ties keep the lower index
-      }
-      taken |= 1ull << best;
-      topk_idx[static_cast<int64_t>(t0 + lane) * k + j] = best;
-      topk_p[static_cast<int64_t>(t0 + lane) * k + j] = pr[best];
-    }
   }
 
   if (q_x == nullptr) return;
@@ -176,7 +182,7 @@ __global__ __launch_bounds__(64 * NW) void router_quant_kernel(
     const int c0 = ch << 3;
 #pragma unroll
     for (int t = 0; t < TPW; ++t) {
-      const uint4 p = *reinterpret_cast<const uint4*>(xrow[t] + c0);
+      const u4 p = single_pass ? xkeep[t] : *reinterpret_cast<const u4*>(xrow[t] + c0);
       const int q0 = quant_i8(bf16_lo(p.x), scale[t]), q1 = quant_i8(bf16_hi(p.x), scale[t]);
       const int q2 = quant_i8(bf16_lo(p.y), scale[t]), q3 = quant_i8(bf16_hi(p.y), scale[t]);
       const int q4 = quant_i8(bf16_lo(p.z), scale[t]), q5 = quant_i8(bf16_hi(p.z), scale[t]);
