@@ -180,9 +180,14 @@ __global__ __launch_bounds__(64 * NW) void router_quant_kernel(
   }
   for (int ch = wave * kWave + lane; ch < n_chunks; ch += kThreads) {
     const int c0 = ch << 3;
+    // all token rows are in registers before the first store: a wait for a load would otherwise
+    // also wait for the stores issued before it (one counter for both)
+    u4 px[TPW];
+#pragma unroll
+    for (int t = 0; t < TPW; ++t) px[t] = single_pass ? xkeep[t] : *reinterpret_cast<const u4*>(xrow[t] + c0);
 #pragma unroll
     for (int t = 0; t < TPW; ++t) {
-      const u4 p = single_pass ? xkeep[t] : *reinterpret_cast<const u4*>(xrow[t] + c0);
+      const u4 p = px[t];
       const int q0 = quant_i8(bf16_lo(p.x), scale[t]), q1 = quant_i8(bf16_hi(p.x), scale[t]);
       const int q2 = quant_i8(bf16_lo(p.y), scale[t]), q3 = quant_i8(bf16_hi(p.y), scale[t]);
       const int q4 = quant_i8(bf16_lo(p.z), scale[t]), q5 = quant_i8(bf16_hi(p.z), scale[t]);
