@@ -34,7 +34,7 @@ struct RoutedCfg {
   static constexpr int MODE = MODE_;  // 0 gate-up (two matrices, SwiGLU epilogue), 1 down
   static constexpr int NMAT = MODE_ == 0 ? 2 : 1;
   static constexpr int BM_W = BM_W_, BN_W = BN_W_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
-  static constexpr int MIN_BLOCKS = MIN_BLOCKS_;  // workgroups per CU the register budget must allow
+  static constexpr int MIN_BLOCKS = MIN_BLOCKS_;  // wavefronts per SIMD the register budget must allow (2 workgroups per CU)
   static constexpr int BM = 32 * BM_W_ * WAVES_M_;
   static constexpr int BN = 32 * BN_W_ * WAVES_N_;
   static constexpr int WAVES = WAVES_M_ * WAVES_N_;
@@ -85,7 +85,7 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
   constexpr int W_PER_WAVE = Cfg::W_PER_WAVE;       // weight fragments a wavefront requests per K step
   constexpr int NLOAD = Cfg::A_PASSES + W_PER_WAVE; // vector-memory operations a wavefront issues per K step
   static_assert(BM <= THREADS, "one thread per tile row publishes the row metadata");
-  static_assert(Cfg::WAVES == 4 && Cfg::ROWS_PER_PASS == 32, "a loader pass is 4 wavefronts x 8 rows");
+  static_assert((Cfg::WAVES == 4 || Cfg::WAVES == 8) && Cfg::ROWS_PER_PASS == 8 * Cfg::WAVES, "a loader pass is 8 rows per wavefront");
   static_assert(NLOAD < 16, "fits the low vmcnt field");
   __shared__ __attribute__((aligned(16))) unsigned char s_lds[3 * STAGE_BYTES];
   __shared__ float s_beta[2][BM];   // row metadata (absmax, integer row sum), double buffered by tile parity
@@ -222,7 +222,7 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
   // tile row 64*w + l, of wavefront 2/3 the row sum of tile row 64*(w-2) + l (4 bytes per lane).
   // Issued before the tile's first K step, so the wait for that step covers it.
 #define MOTE_DMA_META(par_)                                                                        \
-  {                                                                                                \
+  if (wave_u < 4) {                                                                                \
     const uint32_t dst_ = wave_u < 2                                                               \
         ? (uint32_t)(uintptr_t)((__attribute__((address_space(3))) float*)&s_beta[par_][wave_u * 64]) \
         : (uint32_t)(uintptr_t)((__attribute__((address_space(3))) int*)&s_rs[par_][(wave_u - 2) * 64]); \
@@ -508,8 +508,9 @@ int routed_tile_m(int T, int k, int E) {
 hipError_t launch_routed_gate_up(const RoutedGemmArgs& a, hipStream_t stream) {
   if (a.max_tiles == 0) return hipSuccess;
   switch (routed_variant()) {
-    case 1: return launch_cfg<RoutedCfg<0, 4, 1, 1, 4, 2>>(a, 1, stream);
-    default: return launch_cfg<RoutedCfg<0, 2, 2, 2, 2, 2>>(a, 1, stream);
+    case 1: return launch_cfg<RoutedCfg<0, 4, 1, 1, 4, 2>>(a, 1, stream);   // 4 wavefronts of 128 x (32+32)
+    case 2: return launch_cfg<RoutedCfg<0, 2, 2, 2, 2, 2>>(a, 1, stream);   // 4 wavefronts of 64 x (64+64)
+    default: return launch_cfg<RoutedCfg<0, 2, 1, 2, 4, 4>>(a, 1, stream);  // 8 wavefronts of 64 x (32+32): four per SIMD (2-3 % faster)
   }
 }
 
