@@ -131,6 +131,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="c2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay a captured HIP graph of the forward instead of launching its kernels eagerly")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run the library's plain copy kernel on this many MiB (three launches): the "
                          "known-size transfer that scales rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings")
@@ -187,12 +189,24 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    # One step = one forward, launched eagerly.  --graph replays a HIP graph captured from the
+    # same call instead (same kernels, one launch); measured 3-15 % slower than eager launches
+    # on every workload, because the gaps between graph nodes exceed those between queued kernels.
+    launch = "eager"
+    steps = [lambda l=l: M.mote_layer_forward(l, gp.x, out=out, workspace=ws) for l in layers]
+    if args.graph:
+        try:
+            graphs = [M.ForwardGraph(l, gp.x, out, ws) for l in layers]
+            steps = [g.replay for g in graphs]
+            launch = "hip_graph"
+        except Exception as exc:  # noqa: BLE001
+            print(f"bench.py: graph capture failed ({exc}); launching eagerly", file=sys.stderr)
     for i in range(args.warmup):
-        M.mote_layer_forward(layers[i % n_layers], gp.x, out=out, workspace=ws)
+        steps[i % n_layers]()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        M.mote_layer_forward(layers[i % n_layers], gp.x, out=out, workspace=ws)
+        steps[i % n_layers]()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed * 1e3 / args.steps
@@ -229,7 +243,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "i8+bf16",
         "data": "synthetic",
         "config": {"workload": cfg.name, "d_model": cfg.d_model, "d_ff": cfg.d_ff, "n_experts": cfg.n_experts,
-                   "top_k": cfg.top_k, "tokens": cfg.n_tokens, "expert_loads": counts.tolist(), "weight_copies_rotated": n_layers},
+                   "top_k": cfg.top_k, "tokens": cfg.n_tokens, "expert_loads": counts.tolist(), "weight_copies_rotated": n_layers, "launch": launch},
         "roofline": roofline,
         "stages": stages,
     }

@@ -233,6 +233,26 @@ def mote_layer_forward(layer: MoteLayer, x: torch.Tensor, out: torch.Tensor = No
     return out
 
 
+class ForwardGraph:
+    """One mote_layer_forward call (fixed layer, x, out and workspace buffers) captured into a HIP
+    graph: replay() re-runs the same kernels with one launch instead of eight plus the fork/join
+    events.  The buffers must stay alive and keep their addresses; x may be refilled in place."""
+
+    def __init__(self, layer: MoteLayer, x: torch.Tensor, out: torch.Tensor, workspace: torch.Tensor):
+        self.layer, self.x, self.out, self.workspace = layer, x, out, workspace
+        # one eager call first: everything the library sets up lazily (helper stream, kernel
+        # attributes) must exist before the capture starts
+        mote_layer_forward(layer, x, out=out, workspace=workspace)
+        torch.cuda.synchronize()
+        self.graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(self.graph):
+            mote_layer_forward(layer, x, out=out, workspace=workspace)
+
+    def replay(self) -> torch.Tensor:
+        self.graph.replay()
+        return self.out
+
+
 def mote_stage_timing(enable: bool) -> None:
     _check(load_library().mote_stage_timing(1 if enable else 0), "mote_stage_timing")
 

@@ -398,6 +398,36 @@ def test_bad_arguments_are_rejected_before_any_launch():
     torch.cuda.synchronize()
 
 
+@pytest.mark.parametrize("cfg", [W.C1, W.C1.with_tokens(300, name="c1_T300")], ids=lambda c: c.name)
+def test_forward_graph_replays_match_eager(cfg):
+    """The forward captured into a HIP graph (helper stream included) gives the eager result on
+    every replay, with eager work and synchronisations between the replays."""
+    M = _m()
+    _log(f"graph {cfg.name}")
+    gp = GpuProblem(cfg)
+    want = M.mote_layer_forward(gp.layer, gp.x).clone()
+    torch.cuda.synchronize()
+    x = gp.x.clone()
+    out = torch.empty_like(x)
+    ws = gp.layer.workspace(cfg.n_tokens)
+    fg = M.ForwardGraph(gp.layer, x, out, ws)
+    for it in range(4):
+        out.zero_()
+        torch.cuda.synchronize()
+        got = fg.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(got, want), it
+        eager = M.mote_layer_forward(gp.layer, gp.x)          # eager work between the replays
+        torch.cuda.synchronize()
+        assert torch.equal(eager, want), it
+    # new input in the captured buffer: the replay follows it
+    x.copy_(gp.x.flip(0))
+    want2 = M.mote_layer_forward(gp.layer, gp.x.flip(0).contiguous())
+    got2 = fg.replay()
+    torch.cuda.synchronize()
+    assert torch.equal(got2, want2)
+
+
 def test_stage_timing_reports_every_stage():
     M = _m()
     gp = GpuProblem(W.C1)
