@@ -27,7 +27,9 @@ struct DispatchPlan {
   int32_t* tile_row0;   // [max_tiles]
   int32_t* tile_rows;   // [max_tiles]
   int32_t* n_tiles;     // [1]
+  int32_t* sched;       // [16 * kSchedStride] tile counters of the two grouped GEMMs (8 lists each, one cache line per counter), zeroed with the plan
 };
+constexpr int kSchedStride = 32;   // ints between two counters
 hipError_t launch_dispatch_plan(const int32_t* topk_idx, int T, int k, int E, int tile_m, const DispatchPlan& plan,
                                 hipStream_t stream);
 

@@ -16,7 +16,7 @@ inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Workspace {
   // dispatch
-  int32_t* topk_idx; float* topk_p; int32_t* counts; int32_t* offsets; int32_t* n_tiles;
+  int32_t* topk_idx; float* topk_p; int32_t* counts; int32_t* offsets; int32_t* n_tiles; int32_t* sched;
   int32_t* row_of; int32_t* tok_of; int32_t* tile_expert; int32_t* tile_row0; int32_t* tile_rows;
   // Q_a(x)
   int8_t* q_x; float* beta_x; int32_t* rs_x;
@@ -69,6 +69,7 @@ Workspace carve(const mote_layer* l, int T, char* base) {
   w.counts = reinterpret_cast<int32_t*>(take(64 * 4));
   w.offsets = reinterpret_cast<int32_t*>(take(65 * 4));
   w.n_tiles = reinterpret_cast<int32_t*>(take(4));
+  w.sched = reinterpret_cast<int32_t*>(take(16 * kSchedStride * 4));
   w.row_of = reinterpret_cast<int32_t*>(take(R * 4));
   w.tok_of = reinterpret_cast<int32_t*>(take(R * 4));
   w.tile_expert = reinterpret_cast<int32_t*>(take(static_cast<size_t>(w.max_tiles) * 4));
@@ -256,7 +257,7 @@ mote_status mote_layer_forward(const mote_layer* layer, const void* x, int T, vo
   MOTE_HIP(launch_router_quant(xb, static_cast<const uint16_t*>(layer->w_router), layer->router_bias, T, d, E, k,
                                w.topk_idx, w.topk_p, w.q_x, w.beta_x, w.rs_x, stream));
   MOTE_HIP(mark(1));
-  DispatchPlan plan{w.counts, w.offsets, w.row_of, w.tok_of, w.tile_expert, w.tile_row0, w.tile_rows, w.n_tiles};
+  DispatchPlan plan{w.counts, w.offsets, w.row_of, w.tok_of, w.tile_expert, w.tile_row0, w.tile_rows, w.n_tiles, w.sched};
   MOTE_HIP(launch_dispatch_plan(w.topk_idx, T, k, E, tile_m, plan, stream));
   MOTE_HIP(mark(2));
 

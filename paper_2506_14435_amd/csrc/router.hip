@@ -258,6 +258,7 @@ __global__ __launch_bounds__(kPlanThreads) void dispatch_plan_kernel(const int32
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int e = blockIdx.x;
   if (tid < 64) s_cnt[tid] = 0;
+  if (e == 0 && tid < 16 * kSchedStride) plan.sched[tid] = 0;
   __syncthreads();
   for (int i = tid; i < R; i += kPlanThreads) atomicAdd(&s_cnt[topk_idx[i]], 1);
   __syncthreads();

@@ -24,6 +24,7 @@
 // that a global store instruction covers whole rows of a 32-row block.
 #include <stdlib.h>
 
+#include <algorithm>
 #include "common.h"
 #include "launch.h"
 
@@ -64,6 +65,13 @@ __device__ __forceinline__ v4i unpack_codes(uint32_t w) {
   return b;
 }
 
+#ifdef MOTE_TRACE
+__device__ unsigned long long g_trace[1024 * 32 * 8];
+#define MOTE_TP(k_) if (Cfg::MODE == MOTE_TRACE && tid == 0 && tile_it < 32) g_trace[(blockIdx.x * 32 + tile_it) * 8 + (k_)] = __builtin_readcyclecounter();
+#else
+#define MOTE_TP(k_)
+#endif
+
 // LDS tile geometry: 128-byte rows of eight 16-byte chunks, chunk index XOR-swizzled with
 // bits 1..3 of the row.  Two consecutive rows span the 64 banks once, so 16 lanes that read
 // the same chunk of 16 consecutive rows (one quarter of a ds_read_b128) hit 16 distinct
@@ -77,7 +85,7 @@ __device__ __forceinline__ int lds_a_offset(int row, int chunk) { return row * 1
 // 1-KiB loads fill the CU's vector-memory queue and every wavefront stalls in issue (measured:
 // about 800 cycles per K step) before it reaches its first MFMA.
 template <typename Cfg>
-__global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_kernel(RoutedGemmArgs a, int n_ntiles, int kplanes, int ktp, int group_m) {
+__global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_kernel(RoutedGemmArgs a, int n_ntiles, int kplanes, int ktp, int group_m, int n_static) {
   constexpr int NMAT = Cfg::NMAT, BM_W = Cfg::BM_W, BN_W = Cfg::BN_W;
   constexpr int BM = Cfg::BM, BN = Cfg::BN, THREADS = Cfg::THREADS;
   constexpr int A_BYTES = Cfg::A_BYTES, STAGE_BYTES = Cfg::STAGE_BYTES;
@@ -102,27 +110,84 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
   // LDS byte address of the stage area (what M0 takes for a direct-to-LDS load)
   const uint32_t lds0 = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) unsigned char*)s_lds);
 
-  // Persistent workgroups: the grid is one wave of resident workgroups; each walks a strided
-  // list of (row tile, channel tile) pairs.  Workgroups are dealt to the 8 XCDs round-robin
-  // by linear id, so XCD x takes the channel tiles x, x+8, ... (or, when there are fewer
-  // than 16 channel tiles, the row tiles x, x+8, ...).  Inside an XCD the pairs are ordered in
+  // Persistent workgroups: the grid is one wave of resident workgroups that take (row tile,
+  // channel tile) pairs until none is left.  Workgroups are dealt to the 8 XCDs round-robin by
+  // linear id; XCD x owns the list of the channel tiles x, x+8, ... (or, when there are fewer
+  // than 16 channel tiles, of the row tiles x, x+8, ...).  Inside a list the pairs are ordered in
   // bands of group_m row tiles, row tile fastest: the workgroups resident at one time then
   // cover about group_m row tiles x (resident / group_m) channel tiles, so every activation
   // tile and every weight slice fetched into that XCD's L2 is used by several of them.
   // With kplanes > 1 (down projection of small problems) the contraction is cut into planes
   // of ktp K steps; a (channel tile, plane) pair then plays the role of a channel tile and each
   // plane writes its own partial output that the combine kernel adds.
+  //
+  // The first n_static pairs of a workgroup are fixed (list positions b, b + stride, ... of its
+  // own XCD); every later one is drawn from a counter per list (plan.sched, one cache line each,
+  // zeroed by the dispatch plan kernel), first from the own XCD's list and, once that is empty,
+  // from the others'.  Two workgroups share a CU and the hardware favours the older one: with
+  // fixed shares only, the favoured half of the grid finished its tiles at 60 % of the kernel's
+  // time (measured, 23 tiles per workgroup) and the other half ran the rest alone, one
+  // workgroup per CU.  A draw is a device-wide atomic that costs microseconds when the whole
+  // grid draws at once, so problems of a few tiles per workgroup keep fixed shares
+  // (n_static = kAllStatic).  A ticket is slot * 8 + list.
   n_ntiles *= kplanes;
-  const int xcd = blockIdx.x & 7;
+  const int own = blockIdx.x & 7;
   const int n_mtiles = load_uniform(a.plan.n_tiles);
   const bool split_n = n_ntiles >= 16;
-  const int xcd_ntiles = split_n ? (n_ntiles - xcd + 7) >> 3 : n_ntiles;
-  const int xcd_mtiles = split_n ? n_mtiles : (n_mtiles - xcd + 7) >> 3;
-  const int xcd_work = xcd_ntiles * xcd_mtiles;
-  const int per_group = group_m * xcd_ntiles;   // tiles of a band of group_m row tiles
   const int stride = gridDim.x >> 3;
-  int slot = blockIdx.x >> 3;
-  if (slot >= xcd_work) return;
+  auto list_ntiles = [&](int x) { return split_n ? (n_ntiles - x + 7) >> 3 : n_ntiles; };
+  auto list_mtiles = [&](int x) { return split_n ? n_mtiles : (n_mtiles - x + 7) >> 3; };
+  auto list_work = [&](int x) { return list_ntiles(x) * list_mtiles(x); };
+  int32_t* const sched = a.plan.sched + (Cfg::MODE == 0 ? 0 : 8 * kSchedStride);
+  // thread 0's scheduler state: 0 = the own list may still have pairs, 1 = take from the other lists, 8 = all empty
+  __shared__ int s_sched[1];
+  // Thread 0 only.  One draw from the own list while it lasts; afterwards a look at all eight
+  // counters picks a list that still has pairs (one round trip even when every list is empty).
+  auto fetch_ticket = [&](int& cur) -> int {
+    if (cur == 0) {
+      const int sl = n_static * stride + __hip_atomic_fetch_add(sched + own * kSchedStride, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (sl < list_work(own)) return (sl << 3) | own;
+      cur = 1;
+    }
+    while (cur < 8) {
+      int seen[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) seen[i] = __hip_atomic_load(sched + i * kSchedStride, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      int pick = -1;
+#pragma unroll
+      for (int i = 7; i >= 1; --i) {
+        const int x = (own + i) & 7;
+        int c = 0;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) c = j == x ? seen[j] : c;
+        if (n_static * stride + c < list_work(x)) pick = x;
+      }
+      if (pick < 0) { cur = 8; break; }
+      const int sl = n_static * stride + __hip_atomic_fetch_add(sched + pick * kSchedStride, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (sl < list_work(pick)) return (sl << 3) | pick;
+    }
+    return -1;
+  };
+  // ticket of this workgroup's j-th tile (thread 0 only)
+  auto next_ticket = [&](int& cur, int j) -> int {
+    if (j < n_static) {
+      const int sl = (blockIdx.x >> 3) + j * stride;
+      if (sl < list_work(own)) return (sl << 3) | own;
+      if (cur == 0) cur = 1;   // the own list ends within its fixed part
+    }
+    return fetch_ticket(cur);
+  };
+  __shared__ int s_ticket[2];   // ticket of tile i lives in s_ticket[i & 1]
+  if (tid == 0) {
+    // list 0 is the longest: if it ends within the fixed pairs there is nothing to draw anywhere
+    int cur = list_work(0) <= n_static * stride ? 8 : 0;
+    s_ticket[0] = next_ticket(cur, 0);
+    s_sched[0] = cur;
+  }
+  __syncthreads();
+  int ticket = __builtin_amdgcn_readfirstlane(s_ticket[0]);
+  if (ticket < 0) return;
+  int tile_i = 0;
 
   // Loader.  Both operands travel global -> LDS directly (buffer_load ... lds, 16 bytes per
   // lane, no register holds bytes in flight) into one of three stages, two K steps ahead of
@@ -165,14 +230,17 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
   int par = 0;
   int st_cur = 0, st_nxt = STAGE_BYTES, st_nx2 = 2 * STAGE_BYTES;   // stage of K step kt, kt+1, kt+2 (byte offsets)
 
-#define MOTE_DECODE(slot_, mt_, nt_, kc_)                                       \
+#define MOTE_DECODE(ticket_, mt_, nt_, kc_)                                     \
   {                                                                             \
-    const int grp_ = (slot_) / per_group;                                       \
-    const int in_ = (slot_) - grp_ * per_group;                                 \
-    const int gsz_ = min(xcd_mtiles - grp_ * group_m, group_m);                 \
+    const int x_ = (ticket_) & 7, slot_ = (ticket_) >> 3;                       \
+    const int xm_ = list_mtiles(x_);                                            \
+    const int per_group_ = group_m * list_ntiles(x_);                           \
+    const int grp_ = slot_ / per_group_;                                        \
+    const int in_ = slot_ - grp_ * per_group_;                                  \
+    const int gsz_ = min(xm_ - grp_ * group_m, group_m);                        \
     const int ni_ = in_ / gsz_, mi_ = grp_ * group_m + (in_ - ni_ * gsz_);      \
-    mt_ = split_n ? mi_ : xcd + 8 * mi_;                                        \
-    const int ntk_ = split_n ? xcd + 8 * ni_ : ni_;                             \
+    mt_ = split_n ? mi_ : x_ + 8 * mi_;                                         \
+    const int ntk_ = split_n ? x_ + 8 * ni_ : ni_;                              \
     nt_ = ntk_ / kplanes;                                                       \
     kc_ = ntk_ - nt_ * kplanes;                                                 \
   }
@@ -245,7 +313,7 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
   }
 
   // ---- first tile: the whole dependent chain (plan -> gather -> rows) is paid once ----
-  MOTE_DECODE(slot, mt, nt, kc);
+  MOTE_DECODE(ticket, mt, nt, kc);
   expert = load_uniform(a.plan.tile_expert + mt);
   row0 = load_uniform(a.plan.tile_row0 + mt);
   rows = load_uniform(a.plan.tile_rows + mt);
@@ -255,19 +323,34 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
   MOTE_DMA_META(0);
   MOTE_ISSUE_STEP(st_cur, 0);
   if (ktl > 1) MOTE_ISSUE_STEP(st_nxt, 1);
+  if (tid == 0) {   // second ticket, drawn while the first loads travel
+    int cur = s_sched[0];
+    const int t = next_ticket(cur, 1);
+    s_sched[0] = cur;
+    s_ticket[1] = t;
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  }
 
+#ifdef MOTE_TRACE
+  int tile_it = 0;
+#endif
   for (;;) {
+    MOTE_TP(0)
+#ifdef MOTE_TRACE
+    if (Cfg::MODE == MOTE_TRACE && tid == 0 && tile_it < 32) g_trace[(blockIdx.x * 32 + tile_it) * 8 + 6] = wall_clock64();
+#endif
+    MOTE_WAIT_BARRIER(ktl > 1);   // K step 0 (and the metadata) visible to every wavefront; so is the next ticket
     // (1) coordinates of the next tile of this workgroup (uniform scalar loads)
-    const int nslot = slot + stride;
-    const bool has_next = nslot < xcd_work;
+    const int nticket = __builtin_amdgcn_readfirstlane(s_ticket[(tile_i + 1) & 1]);
+    const bool has_next = nticket >= 0;
     int mt2 = mt, nt2 = nt, kc2 = kc, expert2 = expert, row02 = row0, rows2 = rows;
     if (has_next) {
-      MOTE_DECODE(nslot, mt2, nt2, kc2);
+      MOTE_DECODE(nticket, mt2, nt2, kc2);
       expert2 = load_uniform(a.plan.tile_expert + mt2);
       row02 = load_uniform(a.plan.tile_row0 + mt2);
       rows2 = load_uniform(a.plan.tile_rows + mt2);
     }
-    MOTE_WAIT_BARRIER(ktl > 1);   // K step 0 (and the metadata) visible to every wavefront
+    MOTE_TP(1)
     const int n_wave0 = nt * BN + wn * BN_W * 32;  // first output channel of this wavefront
     const float al0 = load_uniform(a.alpha + expert * 3 + (Cfg::MODE == 0 ? 0 : 2));
     const float al1 = Cfg::MODE == 0 ? load_uniform(a.alpha + expert * 3 + 1) : 0.0f;
@@ -336,6 +419,7 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
       const int t = st_cur; st_cur = st_nxt; st_nxt = st_nx2; st_nx2 = t;
     }
 
+    MOTE_TP(2)
     // (3) start the next tile now: its first two K steps travel while this tile runs its
     // epilogue.  The stage of the last K step (now st_nx2) is free until the next tile's
     // first barrier: it holds the epilogue patches.
@@ -348,6 +432,7 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
       if (ktl2 > 1) MOTE_ISSUE_STEP(st_nxt, 1);
     }
 
+    MOTE_TP(3)
     // ---- epilogue ----
     // In registers lane l owns dispatch row r32 and runs of four consecutive output channels
     // (8q + 4g .. +3).  Each wavefront writes one 32-row block of PATCH_F fragments into its
@@ -424,12 +509,31 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
       }
     }
+    MOTE_TP(4)
+#ifdef MOTE_TRACE
+    if (Cfg::MODE == MOTE_TRACE && tid == 0 && tile_it < 32) g_trace[(blockIdx.x * 32 + tile_it) * 8 + 7] = wall_clock64();
+    if (Cfg::MODE == MOTE_TRACE && tid == 0 && tile_it < 32) g_trace[(blockIdx.x * 32 + tile_it) * 8 + 5] = (unsigned long long)mt << 32 | (unsigned)nt;
+    ++tile_it;
+#endif
     if (!has_next) break;
+    // Thread 0 draws the ticket of tile i + 2; the others read it after the next tile's first
+    // barrier.  The draw is waited for here: the other wavefronts spend that time at the barrier
+    // in any case, until the next tile's first K step has landed.
+    if (tid == 0) {
+      int cur = s_sched[0];
+      const int t = next_ticket(cur, tile_i + 2);
+      s_sched[0] = cur;
+      s_ticket[tile_i & 1] = t;
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    }
     // No barrier here: the patches are private and their stage is not refilled before the next
     // tile's first barrier, the metadata of the next tile went to the other parity buffer.
     par ^= 1;
-    slot = nslot; mt = mt2; nt = nt2; kc = kc2; expert = expert2; row0 = row02; rows = rows2; ktl = ktl2;
+    ticket = nticket; ++tile_i; mt = mt2; nt = nt2; kc = kc2; expert = expert2; row0 = row02; rows = rows2; ktl = ktl2;
   }
+#ifdef MOTE_TRACE
+  if (Cfg::MODE == MOTE_TRACE && tid == 0 && tile_it < 32) g_trace[(blockIdx.x * 32 + tile_it) * 8 + 4] = 0;
+#endif
 #undef MOTE_DECODE
 #undef MOTE_GATHER
 #undef MOTE_POINTERS
@@ -440,6 +544,13 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
 #undef MOTE_ISSUE_STEP
 #undef MOTE_WAIT_BARRIER
 }
+
+#ifdef MOTE_TRACE
+extern "C" int mote_debug_trace(void* dst, size_t bytes, int clear) {
+  if (clear) { void* p; hipGetSymbolAddress(&p, HIP_SYMBOL(g_trace)); return (int)hipMemset(p, 0, sizeof(g_trace)); }
+  return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_trace), bytes);
+}
+#endif
 
 static int device_cu_count() {
   static int n = 0;
@@ -474,6 +585,20 @@ int tile_group_m() {
   return v;
 }
 
+constexpr int kAllStatic = 1 << 20;   // n_static of a launch that never draws
+
+// Tiles per workgroup from which the tiles are drawn dynamically (environment variable
+// MOTE_DYNAMIC_ROUNDS, read once).
+static int routed_dynamic_rounds() {
+  static int v = -1;
+  if (v < 0) {
+    const char* e = getenv("MOTE_DYNAMIC_ROUNDS");
+    v = e ? atoi(e) : 4;
+    if (v < 1) v = 1;
+  }
+  return v;
+}
+
 template <typename Cfg>
 static hipError_t launch_cfg(const RoutedGemmArgs& a, int kplanes, hipStream_t stream) {
   const int n_ntiles = (a.N + Cfg::BN - 1) / Cfg::BN;
@@ -483,7 +608,11 @@ static hipError_t launch_cfg(const RoutedGemmArgs& a, int kplanes, hipStream_t s
   const int64_t tiles = static_cast<int64_t>(a.max_tiles) * n_ntiles * kplanes;
   int64_t blocks = static_cast<int64_t>(device_cu_count()) * resident_blocks<Cfg>();
   if (blocks > tiles) blocks = (tiles + 7) / 8 * 8;
-  routed_gemm_kernel<Cfg><<<static_cast<unsigned>(blocks), Cfg::THREADS, 0, stream>>>(a, n_ntiles, kplanes, ktp, tile_group_m());
+  // tiles drawn from the counters once a workgroup sees several of them, fixed shares otherwise
+  // (max_tiles bounds the row tiles for any routing; the expected number is rows / tile_m plus a few)
+  const int64_t expected = std::min<int64_t>(a.max_tiles, a.out_rows / a.tile_m + 8) * n_ntiles * kplanes;
+  const int n_static = expected >= routed_dynamic_rounds() * blocks ? 1 : kAllStatic;
+  routed_gemm_kernel<Cfg><<<static_cast<unsigned>(blocks), Cfg::THREADS, 0, stream>>>(a, n_ntiles, kplanes, ktp, tile_group_m(), n_static);
   return hipGetLastError();
 }
 
