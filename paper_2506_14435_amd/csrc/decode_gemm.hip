@@ -368,7 +368,8 @@ __global__ __launch_bounds__(kDecThreads, 2) void routed_wave_kernel(RoutedGemmA
       for (int j = 0; j < D; ++j)
 #pragma unroll
         for (int m = 0; m < NMAT; ++m)
-          wr[j][m] = __builtin_amdgcn_raw_buffer_load_b128(rw[m], w_lane + oob, (nf * KT + step0 + j) * 1024, kWeightAux);
+          wr[j][m] = __builtin_amdgcn_raw_buffer_load_b128(rw[m], w_lane + (j < nsteps ? oob : kOutOfRange),
+                                                           (nf * KT + step0 + j) * 1024, kWeightAux);
     }
 
     // ---- activation plane into LDS ----
@@ -424,10 +425,12 @@ __global__ __launch_bounds__(kDecThreads, 2) void routed_wave_kernel(RoutedGemmA
         // refill the slot: step kt + D of this fragment, or step kt + D - 16 of the next one
 #pragma unroll
         for (int m = 0; m < NMAT; ++m) {
+          // steps of the padding are not fetched (a lane offset out of range: no traffic, zeros back)
           if (kt + D < 16)
-            wr[kt % D][m] = __builtin_amdgcn_raw_buffer_load_b128(rw[m], w_lane, (nf * KT + step0 + kt + D) * 1024, kWeightAux);
+            wr[kt % D][m] = __builtin_amdgcn_raw_buffer_load_b128(rw[m], w_lane + (kt + D < nsteps ? 0u : kOutOfRange),
+                                                                  (nf * KT + step0 + kt + D) * 1024, kWeightAux);
           else
-            wr[kt % D][m] = __builtin_amdgcn_raw_buffer_load_b128(rw[m], w_lane + oob_next,
+            wr[kt % D][m] = __builtin_amdgcn_raw_buffer_load_b128(rw[m], w_lane + (kt + D - 16 < nsteps ? oob_next : kOutOfRange),
                                                                   ((nf + 4) * KT + step0 + kt + D - 16) * 1024, kWeightAux);
         }
         __builtin_amdgcn_sched_barrier(0);   // one K step at a time: the LDS reads of later steps would pile up in registers

@@ -137,7 +137,13 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
   const int stride = gridDim.x >> 3;
   auto list_ntiles = [&](int x) { return split_n ? (n_ntiles - x + 7) >> 3 : n_ntiles; };
   auto list_mtiles = [&](int x) { return split_n ? n_mtiles : (n_mtiles - x + 7) >> 3; };
-  auto list_work = [&](int x) { return list_ntiles(x) * list_mtiles(x); };
+  // When the lists are short, their uneven lengths (whole row or channel tiles per XCD) can cost
+  // a whole extra round of tiles; the pairs are then dealt to the XCDs one by one instead
+  // (pair p = row tile * n_ntiles + channel tile goes to list p % 8).
+  const int n_pairs = n_mtiles * n_ntiles;
+  const int band_longest = (split_n ? ((n_ntiles + 7) >> 3) * n_mtiles : ((n_mtiles + 7) >> 3) * n_ntiles);
+  const bool flat = (((n_pairs + 7) >> 3) + stride - 1) / stride < (band_longest + stride - 1) / stride;
+  auto list_work = [&](int x) { return flat ? (n_pairs - x + 7) >> 3 : list_ntiles(x) * list_mtiles(x); };
   int32_t* const sched = a.plan.sched + (Cfg::MODE == 0 ? 0 : 8 * kSchedStride);
   // thread 0's scheduler state: 0 = the own list may still have pairs, 1 = take from the other lists, 8 = all empty
   __shared__ int s_sched[1];
@@ -233,14 +239,20 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
 #define MOTE_DECODE(ticket_, mt_, nt_, kc_)                                     \
   {                                                                             \
     const int x_ = (ticket_) & 7, slot_ = (ticket_) >> 3;                       \
-    const int xm_ = list_mtiles(x_);                                            \
-    const int per_group_ = group_m * list_ntiles(x_);                           \
-    const int grp_ = slot_ / per_group_;                                        \
-    const int in_ = slot_ - grp_ * per_group_;                                  \
-    const int gsz_ = min(xm_ - grp_ * group_m, group_m);                        \
-    const int ni_ = in_ / gsz_, mi_ = grp_ * group_m + (in_ - ni_ * gsz_);      \
-    mt_ = split_n ? mi_ : x_ + 8 * mi_;                                         \
-    const int ntk_ = split_n ? x_ + 8 * ni_ : ni_;                              \
+    int ntk_;                                                                   \
+    if (flat) {                                                                 \
+      mt_ = (ticket_) / n_ntiles;                                               \
+      ntk_ = (ticket_) - mt_ * n_ntiles;                                        \
+    } else {                                                                    \
+      const int xm_ = list_mtiles(x_);                                          \
+      const int per_group_ = group_m * list_ntiles(x_);                         \
+      const int grp_ = slot_ / per_group_;                                      \
+      const int in_ = slot_ - grp_ * per_group_;                                \
+      const int gsz_ = min(xm_ - grp_ * group_m, group_m);                      \
+      const int ni_ = in_ / gsz_, mi_ = grp_ * group_m + (in_ - ni_ * gsz_);    \
+      mt_ = split_n ? mi_ : x_ + 8 * mi_;                                       \
+      ntk_ = split_n ? x_ + 8 * ni_ : ni_;                                      \
+    }                                                                           \
     nt_ = ntk_ / kplanes;                                                       \
     kc_ = ntk_ - nt_ * kplanes;                                                 \
   }
@@ -660,7 +672,8 @@ int routed_down_planes(int T, int k, int E, int d, int F) {
 hipError_t launch_routed_down(const RoutedGemmArgs& a, hipStream_t stream) {
   if (a.max_tiles == 0) return hipSuccess;
   if (a.planes > 1) return launch_cfg<RoutedCfg<1, 2, 2, 2, 2, 2>>(a, a.planes, stream);   // small problem: 128 x 128 tiles
-  switch (routed_variant()) {
+  static const int down_variant = getenv("MOTE_ROUTED_DOWN_VARIANT") ? atoi(getenv("MOTE_ROUTED_DOWN_VARIANT")) : routed_variant();
+  switch (down_variant) {
     case 1: return launch_cfg<RoutedCfg<1, 4, 2, 1, 4, 2>>(a, 1, stream);
     case 2: return launch_cfg<RoutedCfg<1, 2, 2, 2, 2, 2>>(a, 1, stream);
     default: return launch_cfg<RoutedCfg<1, 2, 4, 2, 2, 2>>(a, 1, stream);
