@@ -107,7 +107,8 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
       const float sc = (a.beta_h[row] / 127.0f) * a.alpha[e * 3 + 2];
       const int64_t ro = static_cast<int64_t>(row) * d + c0;
       int dsum[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-      for (int pl = 0; pl < a.d_planes; ++pl) {
+      const int d_planes = a.row_planes ? 1 + ((a.row_planes[row] >> (2 * (c0 / a.d_tile_n))) & 3) : a.d_planes;
+      for (int pl = 0; pl < d_planes; ++pl) {
         const int4 d0 = *reinterpret_cast<const int4*>(a.acc_down + pl * a.d_stride + ro);
         const int4 d1 = *reinterpret_cast<const int4*>(a.acc_down + pl * a.d_stride + ro + 4);
         dsum[0] += d0.x; dsum[1] += d0.y; dsum[2] += d0.z; dsum[3] += d0.w;

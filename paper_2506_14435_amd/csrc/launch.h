@@ -27,9 +27,11 @@ struct DispatchPlan {
   int32_t* tile_row0;   // [max_tiles]
   int32_t* tile_rows;   // [max_tiles]
   int32_t* n_tiles;     // [1]
+  int32_t* row_planes;  // [T*k] per dispatch row: 2 bits per channel tile of the down projection, partial planes - 1 of its accumulators
   int32_t* sched;       // [16 * kSchedStride] tile counters of the two grouped GEMMs (8 lists each, one cache line per counter), zeroed with the plan
 };
 constexpr int kSchedStride = 32;   // ints between two counters
+constexpr int kSplitMaxPlanes = 4;  // K planes a pair of the last round of the down projection may be cut into
 hipError_t launch_dispatch_plan(const int32_t* topk_idx, int T, int k, int E, int tile_m, const DispatchPlan& plan,
                                 hipStream_t stream);
 
@@ -52,11 +54,13 @@ struct RoutedGemmArgs {
   int32_t* acc_out;         // down: int32 [R, N] (decode: partial planes [planes][R, N])
   int64_t partial_stride;   // elements between partial planes (down projections)
   int planes;               // K planes of the large-batch down projection (1: none)
+  int split_max;            // planes a pair of the last round may be cut into (down projection with planes == 1; <= 1: never)
   int32_t* tap_gate;        // optional int32 [R, N]
   int32_t* tap_up;
 };
 hipError_t launch_routed_gate_up(const RoutedGemmArgs& a, hipStream_t stream);
 hipError_t launch_routed_down(const RoutedGemmArgs& a, hipStream_t stream);
+int routed_down_tile_n(int planes);
 int routed_down_planes(int T, int k, int E, int d, int F);   // large-batch down: K planes for a shape
 int shared_down_planes(int T, int d, int F);
 int tile_group_m();                      // row tiles per band of the large-batch tile order
@@ -89,6 +93,8 @@ hipError_t launch_shared_down(const uint16_t* h_s, const uint16_t* w_down, int T
 struct CombineArgs {
   const float* y_s; int y_planes; int64_t y_stride;
   const int32_t* acc_down; int d_planes; int64_t d_stride;
+  const int32_t* row_planes;   // plan.row_planes, or null: d_planes for every row and channel
+  int d_tile_n;                // channels per channel tile of row_planes
   const float* beta_h; const float* alpha;
   const int32_t* topk_idx; const float* topk_p; const int32_t* row_of;
   int T, d, k;

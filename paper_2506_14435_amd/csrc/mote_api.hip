@@ -6,6 +6,7 @@
 #include <stdlib.h>
 
 #include "launch.h"
+#include <algorithm>
 
 namespace {
 
@@ -16,7 +17,7 @@ inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Workspace {
   // dispatch
-  int32_t* topk_idx; float* topk_p; int32_t* counts; int32_t* offsets; int32_t* n_tiles; int32_t* sched;
+  int32_t* topk_idx; float* topk_p; int32_t* counts; int32_t* offsets; int32_t* n_tiles; int32_t* sched; int32_t* row_planes;
   int32_t* row_of; int32_t* tok_of; int32_t* tile_expert; int32_t* tile_row0; int32_t* tile_rows;
   // Q_a(x)
   int8_t* q_x; float* beta_x; int32_t* rs_x;
@@ -27,7 +28,8 @@ struct Workspace {
   size_t bytes;
   int max_tiles;
   int tile_m;        // 32: decode kernels, else large-batch kernels
-  int d_planes;      // partial planes of the routed down accumulators
+  int d_planes;      // uniform partial planes of the routed down accumulators
+  int d_split;       // planes a tile of the last round may be cut into instead (large batch, d_planes == 1)
   int y_planes;      // partial planes of the shared expert output
 };
 
@@ -62,6 +64,7 @@ Workspace carve(const mote_layer* l, int T, char* base) {
   w.tile_m = routed_tile_m(T, l->top_k, l->n_experts);
   w.d_planes = w.tile_m == 32 ? routed_decode_down_planes(l->d_ff_routed)
                               : routed_down_planes(T, l->top_k, l->n_experts, l->d_model, l->d_ff_routed);
+  w.d_split = (w.tile_m != 32 && w.d_planes == 1) ? kSplitMaxPlanes : 1;
   w.y_planes = T <= kSharedDecodeMaxTokens ? shared_decode_down_planes(l->d_ff_shared)
                                            : shared_down_planes(T, l->d_model, l->d_ff_shared);
   w.topk_idx = reinterpret_cast<int32_t*>(take(R * 4));
@@ -70,6 +73,7 @@ Workspace carve(const mote_layer* l, int T, char* base) {
   w.offsets = reinterpret_cast<int32_t*>(take(65 * 4));
   w.n_tiles = reinterpret_cast<int32_t*>(take(4));
   w.sched = reinterpret_cast<int32_t*>(take(16 * kSchedStride * 4));
+  w.row_planes = reinterpret_cast<int32_t*>(take(R * 4));
   w.row_of = reinterpret_cast<int32_t*>(take(R * 4));
   w.tok_of = reinterpret_cast<int32_t*>(take(R * 4));
   w.tile_expert = reinterpret_cast<int32_t*>(take(static_cast<size_t>(w.max_tiles) * 4));
@@ -82,7 +86,7 @@ Workspace carve(const mote_layer* l, int T, char* base) {
   w.q_h = reinterpret_cast<int8_t*>(take(R * Fr));
   w.beta_h = reinterpret_cast<float*>(take(R * 4));
   w.rs_h = reinterpret_cast<int32_t*>(take(R * 4));
-  w.acc_down = reinterpret_cast<int32_t*>(take(R * d * 4 * static_cast<size_t>(w.d_planes)));
+  w.acc_down = reinterpret_cast<int32_t*>(take(R * d * 4 * static_cast<size_t>(std::max(w.d_planes, w.d_split))));
   w.h_s = reinterpret_cast<uint16_t*>(take(static_cast<size_t>(T) * Fs * 2));
   w.y_s = reinterpret_cast<float*>(take(static_cast<size_t>(T) * d * 4 * static_cast<size_t>(w.y_planes)));
   w.bytes = off;
@@ -257,7 +261,7 @@ mote_status mote_layer_forward(const mote_layer* layer, const void* x, int T, vo
   MOTE_HIP(launch_router_quant(xb, static_cast<const uint16_t*>(layer->w_router), layer->router_bias, T, d, E, k,
                                w.topk_idx, w.topk_p, w.q_x, w.beta_x, w.rs_x, stream));
   MOTE_HIP(mark(1));
-  DispatchPlan plan{w.counts, w.offsets, w.row_of, w.tok_of, w.tile_expert, w.tile_row0, w.tile_rows, w.n_tiles, w.sched};
+  DispatchPlan plan{w.counts, w.offsets, w.row_of, w.tok_of, w.tile_expert, w.tile_row0, w.tile_rows, w.n_tiles, w.row_planes, w.sched};
   MOTE_HIP(launch_dispatch_plan(w.topk_idx, T, k, E, tile_m, plan, stream));
   MOTE_HIP(mark(2));
 
@@ -268,7 +272,7 @@ mote_status mote_layer_forward(const mote_layer* layer, const void* x, int T, vo
   ga.K = d; ga.N = Fr; ga.q_rows = T; ga.out_rows = R; ga.h = w.h; ga.acc_out = nullptr;
   ga.tap_gate = taps ? taps->acc_gate : nullptr;
   ga.tap_up = taps ? taps->acc_up : nullptr;
-  ga.partial_stride = 0; ga.planes = 1;
+  ga.partial_stride = 0; ga.planes = 1; ga.split_max = 1;
   MOTE_HIP(decode_routed ? launch_routed_decode_gate_up(ga, stream) : launch_routed_gate_up(ga, stream));
   MOTE_HIP(mark(3));
   MOTE_HIP(launch_quant_rows(w.h, R, Fr, w.q_h, w.beta_h, w.rs_h, stream));
@@ -278,7 +282,7 @@ mote_status mote_layer_forward(const mote_layer* layer, const void* x, int T, vo
   gd.q = w.q_h; gd.gather = nullptr; gd.beta = w.beta_h; gd.rowsum = w.rs_h;
   gd.w_gate = layer->wt_down; gd.w_up = nullptr;
   gd.K = Fr; gd.N = d; gd.q_rows = R; gd.h = nullptr; gd.acc_out = w.acc_down; gd.tap_gate = nullptr; gd.tap_up = nullptr;
-  gd.partial_stride = static_cast<int64_t>(R) * d; gd.planes = w.d_planes;
+  gd.partial_stride = static_cast<int64_t>(R) * d; gd.planes = w.d_planes; gd.split_max = w.d_split;
   MOTE_HIP(decode_routed ? launch_routed_decode_down(gd, stream) : launch_routed_down(gd, stream));
   MOTE_HIP(mark(5));
 
@@ -297,6 +301,8 @@ mote_status mote_layer_forward(const mote_layer* layer, const void* x, int T, vo
   CombineArgs ca{};
   ca.y_s = w.y_s; ca.y_planes = w.y_planes; ca.y_stride = static_cast<int64_t>(T) * d;
   ca.acc_down = w.acc_down; ca.d_planes = w.d_planes; ca.d_stride = static_cast<int64_t>(R) * d;
+  ca.row_planes = w.d_split > 1 ? w.row_planes : nullptr;
+  ca.d_tile_n = routed_down_tile_n(w.d_planes);
   ca.beta_h = w.beta_h; ca.alpha = layer->alpha;
   ca.topk_idx = w.topk_idx; ca.topk_p = w.topk_p; ca.row_of = w.row_of;
   ca.T = T; ca.d = d; ca.k = k;

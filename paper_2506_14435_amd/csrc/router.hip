@@ -298,6 +298,7 @@ __global__ __launch_bounds__(kPlanThreads) void dispatch_plan_kernel(const int32
       const int slot = my_off + running + wave_off + prefix;
       plan.row_of[i] = slot;
       plan.tok_of[slot] = i / k;
+      plan.row_planes[slot] = 0;
     }
     running += total;
     __syncthreads();

@@ -84,6 +84,8 @@ __device__ __forceinline__ int lds_a_offset(int row, int chunk) { return row * 1
 // the four sub-steps: issued in one burst right after the barrier, eight wavefronts x eight
 // 1-KiB loads fill the CU's vector-memory queue and every wavefront stalls in issue (measured:
 // about 800 cycles per K step) before it reaches its first MFMA.
+constexpr int kFixedShares = 1 << 20;   // n_static from which every tile of a workgroup is fixed
+
 template <typename Cfg>
 __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_kernel(RoutedGemmArgs a, int n_ntiles, int kplanes, int ktp, int group_m, int n_static) {
   constexpr int NMAT = Cfg::NMAT, BM_W = Cfg::BM_W, BN_W = Cfg::BN_W;
@@ -129,7 +131,19 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
   // time (measured, 23 tiles per workgroup) and the other half ran the rest alone, one
   // workgroup per CU.  A draw is a device-wide atomic that costs microseconds when the whole
   // grid draws at once, so problems of a few tiles per workgroup keep fixed shares
-  // (n_static = kAllStatic).  A ticket is slot * 8 + list.
+  // (n_static = kAllStatic).
+  //
+  // With fixed shares the last round of a list is often nearly empty (C3 down projection: 136
+  // pairs on 64 workgroups, so 8 workgroups ran a third tile while 56 idled: 40 % of the
+  // kernel's time).  If at most half of the workgroups would have a pair in that round, each
+  // pair of the round is cut into up to a.split_max K planes that go to different workgroups
+  // (measured 316 -> 299 us; the favoured workgroups of the first rounds still finish early.
+  // Cutting the last pairs of drawn lists the same way was slower: the combine kernel then adds
+  // four planes for a quarter of the rows);
+  // plane kc writes partial plane kc of the output, and the pair's plane count goes into the
+  // rows' words of plan.row_planes (2 bits per channel tile, hence at most 16 channel tiles)
+  // for the combine kernel (down projection with a single uniform plane only).
+  // A ticket packs list (3 bits), planes of the pair (3), plane (2) and the slot in the list.
   n_ntiles *= kplanes;
   const int own = blockIdx.x & 7;
   const int n_mtiles = load_uniform(a.plan.n_tiles);
@@ -147,12 +161,14 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
   int32_t* const sched = a.plan.sched + (Cfg::MODE == 0 ? 0 : 8 * kSchedStride);
   // thread 0's scheduler state: 0 = the own list may still have pairs, 1 = take from the other lists, 8 = all empty
   __shared__ int s_sched[1];
+  auto make_ticket = [](int slot, int x, int kc, int planes) { return (slot << 8) | (kc << 6) | (planes << 3) | x; };
+  const bool may_split = Cfg::MODE == 1 && kplanes == 1 && n_ntiles <= 16;
   // Thread 0 only.  One draw from the own list while it lasts; afterwards a look at all eight
   // counters picks a list that still has pairs (one round trip even when every list is empty).
   auto fetch_ticket = [&](int& cur) -> int {
     if (cur == 0) {
       const int sl = n_static * stride + __hip_atomic_fetch_add(sched + own * kSchedStride, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (sl < list_work(own)) return (sl << 3) | own;
+      if (sl < list_work(own)) return make_ticket(sl, own, 0, 1);
       cur = 1;
     }
     while (cur < 8) {
@@ -170,15 +186,23 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
       }
       if (pick < 0) { cur = 8; break; }
       const int sl = n_static * stride + __hip_atomic_fetch_add(sched + pick * kSchedStride, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (sl < list_work(pick)) return (sl << 3) | pick;
+      if (sl < list_work(pick)) return make_ticket(sl, pick, 0, 1);
     }
     return -1;
   };
   // ticket of this workgroup's j-th tile (thread 0 only)
   auto next_ticket = [&](int& cur, int j) -> int {
     if (j < n_static) {
-      const int sl = (blockIdx.x >> 3) + j * stride;
-      if (sl < list_work(own)) return (sl << 3) | own;
+      const int b = blockIdx.x >> 3;
+      const int w = list_work(own);
+      const int full = w / stride, last = w - full * stride;   // whole rounds, pairs of the last partial round
+      if (j < full) return make_ticket(b + j * stride, own, 0, 1);
+      if (j == full && last > 0) {
+        int planes = 1;
+        if (may_split && n_static >= kFixedShares && 2 * last <= stride)
+          planes = max(1, min(min(a.split_max, stride / last), KT >> 3));
+        if (b < last * planes) return make_ticket(full * stride + b / planes, own, b % planes, planes);
+      }
       if (cur == 0) cur = 1;   // the own list ends within its fixed part
     }
     return fetch_ticket(cur);
@@ -232,17 +256,19 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
   const uint32_t a_chunk = static_cast<uint32_t>(((tid & 7) ^ ((tid >> 4) & 7)) << 4);
   int src_row[Cfg::A_PASSES];   // row of q (gathered) per loader pass, next tile
   int meta_row = 0;             // row of q whose beta (wavefronts 0-1) or row sum (2-3) this lane requests
-  int mt, nt, kc, expert, row0, rows, ktl;
+  int mt, nt, kc, expert, row0, rows, ktl, ktp_t, planes_t;   // ktp_t: K steps per plane of this tile, planes_t: its planes
   int par = 0;
   int st_cur = 0, st_nxt = STAGE_BYTES, st_nx2 = 2 * STAGE_BYTES;   // stage of K step kt, kt+1, kt+2 (byte offsets)
 
-#define MOTE_DECODE(ticket_, mt_, nt_, kc_)                                     \
+#define MOTE_DECODE(ticket_, mt_, nt_, kc_, ktp_, planes_)                      \
   {                                                                             \
-    const int x_ = (ticket_) & 7, slot_ = (ticket_) >> 3;                       \
+    const int x_ = (ticket_) & 7, slot_ = (ticket_) >> 8;                       \
+    planes_ = ((ticket_) >> 3) & 7;                                             \
     int ntk_;                                                                   \
     if (flat) {                                                                 \
-      mt_ = (ticket_) / n_ntiles;                                               \
-      ntk_ = (ticket_) - mt_ * n_ntiles;                                        \
+      const int p_ = slot_ * 8 + x_;                                            \
+      mt_ = p_ / n_ntiles;                                                      \
+      ntk_ = p_ - mt_ * n_ntiles;                                               \
     } else {                                                                    \
       const int xm_ = list_mtiles(x_);                                          \
       const int per_group_ = group_m * list_ntiles(x_);                         \
@@ -253,8 +279,15 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
       mt_ = split_n ? mi_ : x_ + 8 * mi_;                                       \
       ntk_ = split_n ? x_ + 8 * ni_ : ni_;                                      \
     }                                                                           \
-    nt_ = ntk_ / kplanes;                                                       \
-    kc_ = ntk_ - nt_ * kplanes;                                                 \
+    if (kplanes > 1) {                                                          \
+      nt_ = ntk_ / kplanes;                                                     \
+      kc_ = ntk_ - nt_ * kplanes;                                               \
+      ktp_ = ktp;                                                               \
+    } else {                                                                    \
+      nt_ = ntk_;                                                               \
+      kc_ = ((ticket_) >> 6) & 3;                                               \
+      ktp_ = (KT + planes_ - 1) / planes_;                                      \
+    }                                                                           \
   }
   // gate-up rows are gathered through tok_of (a.gather), down rows are the dispatch rows themselves
 #define MOTE_GATHER(row0_, rows_)                                                                  \
@@ -270,17 +303,17 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
   }
   // Fragment ids of a stage: matrix m, channel block cb -> m*NB + cb.  Wavefront w requests the
   // ids w*W_PER_WAVE ... ; every wavefront later reads the ids of its own channel blocks.
-#define MOTE_POINTERS(expert_, nt_, kc_)                                                           \
+#define MOTE_POINTERS(expert_, nt_, kc_, ktp_)                                                           \
   {                                                                                                \
     _Pragma("unroll") for (int p = 0; p < Cfg::A_PASSES; ++p)                                      \
       a_off[p] = static_cast<uint32_t>(src_row[p]) * static_cast<uint32_t>(K) + a_chunk +          \
-                 static_cast<uint32_t>((kc_) * ktp) * 128u;                                        \
+                 static_cast<uint32_t>((kc_) * (ktp_)) * 128u;                                        \
     _Pragma("unroll") for (int i = 0; i < W_PER_WAVE; ++i) {                                       \
       const int fid_ = wave_u * W_PER_WAVE + i;                                                    \
       const int m_ = fid_ / NB, cb_ = fid_ - m_ * NB;                                              \
       const int n_frag_ = (nt_) * BN + cb_ * 32;                                                   \
       const int nt32_ = (n_frag_ < N ? n_frag_ : 0) >> 5; /* fragments past N read tile 0 */       \
-      w_soff[i] = static_cast<uint32_t>(nt32_ * KT + (kc_) * ktp) * 1024u;                         \
+      w_soff[i] = static_cast<uint32_t>(nt32_ * KT + (kc_) * (ktp_)) * 1024u;                         \
       const uint32_t* mat_ = (NMAT == 2 && m_ == 1) ? a.w_up : a.w_gate;                           \
       const uint64_t p_ = reinterpret_cast<uint64_t>(mat_ + static_cast<int64_t>(expert_) * expert_words); \
       rsrc_w[i].x = static_cast<int>(static_cast<uint32_t>(p_));                                   \
@@ -325,13 +358,13 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
   }
 
   // ---- first tile: the whole dependent chain (plan -> gather -> rows) is paid once ----
-  MOTE_DECODE(ticket, mt, nt, kc);
+  MOTE_DECODE(ticket, mt, nt, kc, ktp_t, planes_t);
   expert = load_uniform(a.plan.tile_expert + mt);
   row0 = load_uniform(a.plan.tile_row0 + mt);
   rows = load_uniform(a.plan.tile_rows + mt);
-  ktl = min(ktp, KT - kc * ktp);
+  ktl = min(ktp_t, KT - kc * ktp_t);
   MOTE_GATHER(row0, rows);
-  MOTE_POINTERS(expert, nt, kc);
+  MOTE_POINTERS(expert, nt, kc, ktp_t);
   MOTE_DMA_META(0);
   MOTE_ISSUE_STEP(st_cur, 0);
   if (ktl > 1) MOTE_ISSUE_STEP(st_nxt, 1);
@@ -355,9 +388,9 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
     // (1) coordinates of the next tile of this workgroup (uniform scalar loads)
     const int nticket = __builtin_amdgcn_readfirstlane(s_ticket[(tile_i + 1) & 1]);
     const bool has_next = nticket >= 0;
-    int mt2 = mt, nt2 = nt, kc2 = kc, expert2 = expert, row02 = row0, rows2 = rows;
+    int mt2 = mt, nt2 = nt, kc2 = kc, expert2 = expert, row02 = row0, rows2 = rows, ktp2 = ktp_t, planes2 = planes_t;
     if (has_next) {
-      MOTE_DECODE(nticket, mt2, nt2, kc2);
+      MOTE_DECODE(nticket, mt2, nt2, kc2, ktp2, planes2);
       expert2 = load_uniform(a.plan.tile_expert + mt2);
       row02 = load_uniform(a.plan.tile_row0 + mt2);
       rows2 = load_uniform(a.plan.tile_rows + mt2);
@@ -437,8 +470,8 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
     // first barrier: it holds the epilogue patches.
     int ktl2 = ktl;
     if (has_next) {
-      ktl2 = min(ktp, KT - kc2 * ktp);
-      MOTE_POINTERS(expert2, nt2, kc2);
+      ktl2 = min(ktp2, KT - kc2 * ktp2);
+      MOTE_POINTERS(expert2, nt2, kc2, ktp2);
       MOTE_DMA_META(par ^ 1);
       MOTE_ISSUE_STEP(st_cur, 0);
       if (ktl2 > 1) MOTE_ISSUE_STEP(st_nxt, 1);
@@ -456,6 +489,9 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
     constexpr int LANES_PER_ROW = OUT_ROW_BYTES / 16;
     constexpr int ROWS_PER_READ = 64 / LANES_PER_ROW;
     static_assert(Cfg::WAVES * Cfg::PATCH_BYTES <= STAGE_BYTES, "the patches fit the free stage");
+    if constexpr (Cfg::MODE == 1) {   // a pair cut into K planes: tell the combine kernel how many to add for these rows and channels
+      if (planes_t > 1 && kc == 0 && tid < rows) atomicOr(a.plan.row_planes + row0 + tid, (planes_t - 1) << (2 * nt));
+    }
     unsigned char* const patch = s_lds + st_nx2 + wave * Cfg::PATCH_BYTES;
     const int rd_row = lane / LANES_PER_ROW, rd_chunk = lane % LANES_PER_ROW;
 #pragma unroll
@@ -541,7 +577,7 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
     // No barrier here: the patches are private and their stage is not refilled before the next
     // tile's first barrier, the metadata of the next tile went to the other parity buffer.
     par ^= 1;
-    ticket = nticket; ++tile_i; mt = mt2; nt = nt2; kc = kc2; expert = expert2; row0 = row02; rows = rows2; ktl = ktl2;
+    ticket = nticket; ++tile_i; mt = mt2; nt = nt2; kc = kc2; expert = expert2; row0 = row02; rows = rows2; ktl = ktl2; ktp_t = ktp2; planes_t = planes2;
   }
 #ifdef MOTE_TRACE
   if (Cfg::MODE == MOTE_TRACE && tid == 0 && tile_it < 32) g_trace[(blockIdx.x * 32 + tile_it) * 8 + 4] = 0;
@@ -597,7 +633,7 @@ int tile_group_m() {
   return v;
 }
 
-constexpr int kAllStatic = 1 << 20;   // n_static of a launch that never draws
+constexpr int kAllStatic = kFixedShares;   // n_static of a launch that never draws
 
 // Tiles per workgroup from which the tiles are drawn dynamically (environment variable
 // MOTE_DYNAMIC_ROUNDS, read once).
@@ -669,11 +705,25 @@ int routed_down_planes(int T, int k, int E, int d, int F) {
   return (KT + ktp - 1) / ktp;
 }
 
+static int routed_down_variant() {
+  static const int v = getenv("MOTE_ROUTED_DOWN_VARIANT") ? atoi(getenv("MOTE_ROUTED_DOWN_VARIANT")) : routed_variant();
+  return v;
+}
+
+// Channels per tile of the large-batch down projection (the unit of plan.row_planes).
+int routed_down_tile_n(int planes) {
+  if (planes > 1) return RoutedCfg<1, 2, 2, 2, 2, 2>::BN;
+  switch (routed_down_variant()) {
+    case 1: return RoutedCfg<1, 4, 2, 1, 4, 2>::BN;
+    case 2: return RoutedCfg<1, 2, 2, 2, 2, 2>::BN;
+    default: return RoutedCfg<1, 2, 4, 2, 2, 2>::BN;
+  }
+}
+
 hipError_t launch_routed_down(const RoutedGemmArgs& a, hipStream_t stream) {
   if (a.max_tiles == 0) return hipSuccess;
   if (a.planes > 1) return launch_cfg<RoutedCfg<1, 2, 2, 2, 2, 2>>(a, a.planes, stream);   // small problem: 128 x 128 tiles
-  static const int down_variant = getenv("MOTE_ROUTED_DOWN_VARIANT") ? atoi(getenv("MOTE_ROUTED_DOWN_VARIANT")) : routed_variant();
-  switch (down_variant) {
+  switch (routed_down_variant()) {
     case 1: return launch_cfg<RoutedCfg<1, 4, 2, 1, 4, 2>>(a, 1, stream);
     case 2: return launch_cfg<RoutedCfg<1, 2, 2, 2, 2, 2>>(a, 1, stream);
     default: return launch_cfg<RoutedCfg<1, 2, 4, 2, 2, 2>>(a, 1, stream);

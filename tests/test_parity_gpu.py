@@ -317,6 +317,22 @@ def _check_sampled(cfg, n_sample, n_allowed_experts, out, taps, op):
     return ref
 
 
+def _check_down_rows(cfg, op, taps, rows):
+    """Down accumulators of the given dispatch rows against W_down . q_h (exact), whatever tile or K plane computed them."""
+    k = cfg.top_k
+    row_of = taps["row_of"].cpu().numpy().reshape(-1)
+    idx = taps["topk_idx"].cpu().numpy().reshape(-1)
+    flat_of_row = np.empty_like(row_of)
+    flat_of_row[row_of] = np.arange(row_of.size)
+    e_of_row = idx[flat_of_row[rows]]
+    rows_t = torch.from_numpy(rows.astype(np.int64)).cuda()
+    q_h = taps["q_h"][rows_t].cpu().numpy()
+    acc_down = taps["acc_down"][rows_t].cpu().numpy()
+    for e in np.unique(e_of_row):
+        sel = np.flatnonzero(e_of_row == e)
+        assert np.array_equal(acc_down[sel], O.ternary_matmul_int(op.experts(int(e))[4], q_h[sel])), f"expert {e}"
+
+
 FULL_TAPS = ("topk_idx", "topk_p", "counts", "row_of", "tok_of", "q_x", "beta_x", "acc_gate", "acc_up", "h", "q_h",
              "beta_h", "acc_down")
 
@@ -339,6 +355,13 @@ def test_layer_config3_prefill_sampled():
     gp, op = GpuProblem(cfg), OracleProblem(cfg)
     out, taps = _run_layer(gp, FULL_TAPS)
     _check_sampled(cfg, 48, 3, out, taps, op)
+    # The last round of the down projection's tile lists is nearly empty at this shape: its row
+    # tiles (the last ones in dispatch order) are cut into K planes.  Rows of the first and of
+    # the last tiles, all channels.
+    R = cfg.n_tokens * cfg.top_k
+    rng = np.random.default_rng(7)
+    rows = np.concatenate([rng.choice(1024, 16, replace=False), R - 1 - rng.choice(1400, 48, replace=False)])
+    _check_down_rows(cfg, op, taps, np.sort(rows))
 
 
 @pytest.mark.parametrize("T,n", [(1, 2), (4, 4), (16, 8), (64, 16)])
