@@ -309,11 +309,27 @@ __global__ __launch_bounds__(kDecThreads, 2) void routed_stream_kernel(RoutedGem
 // reduction in the steady state.  Loads are raw buffer loads issued unconditionally (a lane
 // offset beyond the buffer turns one into a no-op), so the number of loads in flight is the
 // same on every path and the compiler's wait counts stay exact.  A plane shorter than 16 steps
-// is padded with zero activations.
+// is padded with zero activations (the weights of the padding are not fetched).
+// The grid is two workgroups per CU; each (row tile, K plane) group is shared evenly by
+// floor(grid / groups) workgroups, so a workgroup stays with one plane (changing it cost a drained
+// load queue and two barriers) and every CU streams about the same number of bytes.  That
+// balance matters more than an equal number of fragments per wavefront: a CU serves its own
+// requests in order at its share of the HBM bandwidth, and with 352 equal workgroups on 256 CUs
+// the CUs that held two finished at 37 us, the others at 23 us (measured).
+// The plane is requested before the first weights: vector-memory operations complete in issue
+// order, so "all but the ring's loads" retires the plane while the weights keep streaming.
+#ifdef MOTE_TRACE_DEC
+__device__ unsigned long long g_dtrace[1024 * 4 * 24];
+#define MOTE_DTP(k_) if (MODE == MOTE_TRACE_DEC && lane == 0 && (k_) < 24) g_dtrace[(blockIdx.x * 4 + wave) * 24 + (k_)] = wall_clock64();
+extern "C" int mote_debug_dtrace(void* dst, size_t bytes) { return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_dtrace), bytes); }
+#else
+#define MOTE_DTP(k_)
+#endif
+
 template <int MODE>
 __global__ __launch_bounds__(kDecThreads, 2) void routed_wave_kernel(RoutedGemmArgs a, int n_frags, int kc_count) {
   constexpr int NMAT = MODE == 0 ? 2 : 1;
-  constexpr int D = 8;                                    // K steps of packed weights in flight per wavefront
+  constexpr int D = 8;                                    // K steps of packed weights in flight per wavefront (16 measured no faster)
   constexpr int kBufferFlags = 0x00020000;                // raw buffer, 32-bit data format
   constexpr int kWeightAux = 2;                           // weight loads are non-temporal: every byte is used once (measured: 42 -> 39.5 us)
   constexpr uint32_t kOutOfRange = 0x80000000u;           // lane offset past any buffer of <= 2 GiB
@@ -337,14 +353,18 @@ __global__ __launch_bounds__(kDecThreads, 2) void routed_wave_kernel(RoutedGemmA
     return r;
   };
   const v4i rsrc_q = make_rsrc(a.q, a.q_rows * K);
-  const int64_t total = static_cast<int64_t>(load_uniform(a.plan.n_tiles)) * kc_count * n_frags;
-  int64_t u = blockIdx.x * total / gridDim.x;
-  const int64_t hi = (blockIdx.x + 1) * total / gridDim.x;
-
-  while (u < hi) {
-    const int grp = static_cast<int>(u / n_frags);          // (row tile, K plane)
-    const int nf0 = static_cast<int>(u - static_cast<int64_t>(grp) * n_frags);
-    const int nf_end = static_cast<int>(min(static_cast<int64_t>(n_frags), nf0 + (hi - u)));
+  const int groups = load_uniform(a.plan.n_tiles) * kc_count;
+  const int bpg = max(1, static_cast<int>(gridDim.x) / max(groups, 1));   // workgroups per (row tile, K plane) group
+  const int gstride = gridDim.x / bpg;                                     // groups in flight
+  const int g0 = blockIdx.x / bpg, part = blockIdx.x - g0 * bpg;
+  if (g0 >= gstride) return;                                               // left-over workgroups
+  const int nf0 = part * n_frags / bpg;
+  const int nf_end = (part + 1) * n_frags / bpg;
+  int tp = 0;
+  MOTE_DTP(tp) ++tp;
+  for (int grp = g0; grp < groups; grp += gstride) {
+    // every wavefront is done with the previous plane (a plain barrier: the loads in flight stay in flight)
+    if (grp != g0) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     const int mt = grp / kc_count, kc = grp - mt * kc_count;
     const int expert = load_uniform(a.plan.tile_expert + mt);
     const int row0 = load_uniform(a.plan.tile_row0 + mt);
@@ -352,7 +372,25 @@ __global__ __launch_bounds__(kDecThreads, 2) void routed_wave_kernel(RoutedGemmA
     const int step0 = kc * 16;
     const int nsteps = min(16, KT - step0);
 
-    // ---- weight ring first: it depends on the plan only, not on the row gather ----
+    // ---- activation plane into LDS, requested first ----
+    const int slot = row0 + min(r32, rows - 1);
+    const int src = a.gather ? a.gather[slot] : slot;
+    {
+      // rows past the end of the tile are not fetched (their accumulator rows are never stored)
+      const uint32_t voff = r32 < rows ? static_cast<uint32_t>(src) * static_cast<uint32_t>(K) + step0 * 128 + g * 16
+                                       : kOutOfRange;
+      // load i covers K step i/4, chunks 2*(i%4) and 2*(i%4)+1 (lane l: chunk + l/32, row l%32)
+      for (int i = wave; i < nsteps * 4; i += 4) {
+        const uint32_t dst = lds0 + static_cast<uint32_t>(((i >> 2) * 8 + 2 * (i & 3)) * 512);
+        const int soff = (i >> 2) * 128 + (i & 3) * 32;
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                     :: "s"(dst), "v"(voff), "s"(rsrc_q), "s"(soff) : "memory");
+      }
+    }
+    const float m_beta = a.beta[src];
+    const int m_rs = a.rowsum[src];
+
+    // ---- weight ring ----
     __amdgpu_buffer_rsrc_t rw[NMAT];
     rw[0] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(a.w_gate) + expert * expert_words, 0,
                                               static_cast<int>(expert_words * 4), kBufferFlags);
@@ -372,27 +410,9 @@ __global__ __launch_bounds__(kDecThreads, 2) void routed_wave_kernel(RoutedGemmA
                                                            (nf * KT + step0 + j) * 1024, kWeightAux);
     }
 
-    // ---- activation plane into LDS ----
-    const int slot = row0 + min(r32, rows - 1);
-    const int src = a.gather ? a.gather[slot] : slot;
-    __syncthreads();   // every wavefront is done with the previous plane
-    {
-      // rows past the end of the tile are not fetched (their accumulator rows are never stored)
-      const uint32_t voff = r32 < rows ? static_cast<uint32_t>(src) * static_cast<uint32_t>(K) + step0 * 128 + g * 16
-                                       : kOutOfRange;
-      // load i covers K step i/4, chunks 2*(i%4) and 2*(i%4)+1 (lane l: chunk + l/32, row l%32)
-      for (int i = wave; i < nsteps * 4; i += 4) {
-        const uint32_t dst = lds0 + static_cast<uint32_t>(((i >> 2) * 8 + 2 * (i & 3)) * 512);
-        const int soff = (i >> 2) * 128 + (i & 3) * 32;
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-                     :: "s"(dst), "v"(voff), "s"(rsrc_q), "s"(soff) : "memory");
-      }
-      // steps past the end of the contraction contribute nothing: zero activations
-      for (int i = nsteps * 256 + tid; i < 16 * 256; i += kDecThreads)   // 256 x 16 bytes per K step
-        *reinterpret_cast<u4*>(s_a + i * 16) = u4{0u, 0u, 0u, 0u};
-    }
-    const float m_beta = a.beta[src];
-    const int m_rs = a.rowsum[src];
+    // steps past the end of the contraction contribute nothing: zero activations
+    for (int i = nsteps * 256 + tid; i < 16 * 256; i += kDecThreads)   // 256 x 16 bytes per K step
+      *reinterpret_cast<u4*>(s_a + i * 16) = u4{0u, 0u, 0u, 0u};
     float sg = 0.0f, su = 0.0f;
     if constexpr (MODE == 0) {
       const float sx = m_beta / 127.0f;
@@ -403,8 +423,11 @@ __global__ __launch_bounds__(kDecThreads, 2) void routed_wave_kernel(RoutedGemmA
     const __amdgpu_buffer_rsrc_t r_out = __builtin_amdgcn_make_buffer_rsrc(
         MODE == 0 ? static_cast<void*>(a.h) : static_cast<void*>(a.acc_out + static_cast<int64_t>(kc) * a.partial_stride), 0,
         static_cast<int>(a.out_rows * N * (MODE == 0 ? 2 : 4)), kBufferFlags);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the plane (and everything else requested so far) has landed
-    __syncthreads();
+    MOTE_DTP(tp) ++tp;
+    // the plane and the row metadata (everything requested before the ring) have landed; the ring stays in flight
+    // (a plain barrier: __syncthreads() would also drain the ring)
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" :: "n"(D * NMAT) : "memory");
+    MOTE_DTP(tp) ++tp;
 
     for (; nf < nf_end; nf += 4) {
       const uint32_t oob_next = nf + 4 < nf_end ? 0u : kOutOfRange;
@@ -466,9 +489,11 @@ __global__ __launch_bounds__(kDecThreads, 2) void routed_wave_kernel(RoutedGemmA
           __builtin_amdgcn_raw_buffer_store_b128(d4, r_out, row_ok ? o * 4u : kOutOfRange, 0, 0);
         }
       }
+      MOTE_DTP(tp) ++tp;
     }
-    u += nf_end - nf0;
   }
+  MOTE_DTP(tp) ++tp;
+  MOTE_DTP(23)
 }
 
 static int device_cus() {
