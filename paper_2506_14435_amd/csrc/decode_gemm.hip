@@ -20,6 +20,7 @@
 // register v of lane l is output channel 8*(v/4) + 4*(l/32) + v%4 of row l%32.
 #include <stdlib.h>
 
+#include <algorithm>
 #include "common.h"
 #include "launch.h"
 
@@ -724,7 +725,16 @@ __global__ __launch_bounds__(64) void shared_wave_kernel(SharedDecodeArgs a, int
   extern __shared__ __attribute__((aligned(16))) unsigned char s_ring[];
   const int M = a.M, N = a.N, K = a.K, KT = K >> 6;
   const int lane = threadIdx.x, r32 = lane & 31, g = lane >> 5;
-  const int kc = blockIdx.x % kc_count, nf = blockIdx.x / kc_count;
+  // Down projection: workgroup = (32-channel fragment, K plane).  Gate-up (no K planes: the
+  // epilogue needs the whole sums): the channels are cut into gridDim.x nearly equal runs of
+  // whole quads, at most 32 channels each, so that every CU streams the same number of weight
+  // rows (with whole 32-channel fragments 344 workgroups on 256 CUs left a third of the CUs
+  // with twice the bytes of the others; a CU serves its requests in order at its share of the
+  // HBM bandwidth).  Rows of the fragment past the run are not fetched and not stored.
+  const int kc = MODE == 1 ? blockIdx.x % kc_count : 0;
+  const int quads = N >> 2;
+  const int c0 = MODE == 1 ? (blockIdx.x / kc_count) * 32 : static_cast<int>(static_cast<int64_t>(blockIdx.x) * quads / gridDim.x) * 4;
+  const int c1 = MODE == 1 ? c0 + 32 : static_cast<int>(static_cast<int64_t>(blockIdx.x + 1) * quads / gridDim.x) * 4;
   const int step0 = kc * steps_per_plane;
   const int nsteps = min(steps_per_plane, KT - step0);
   const uint32_t lds0 = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) unsigned char*)s_ring);
@@ -746,7 +756,9 @@ __global__ __launch_bounds__(64) void shared_wave_kernel(SharedDecodeArgs a, int
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int chunk = (lane & 7) ^ ((4 * i + (ld_row >> 1)) & 7);
-    w_voff[i] = static_cast<uint32_t>(nf * 32 + 8 * i + ld_row) * static_cast<uint32_t>(K) * 2u + step0 * 128 + chunk * 16;
+    const int wrow = c0 + 8 * i + ld_row;
+    w_voff[i] = wrow < c1 ? static_cast<uint32_t>(wrow) * static_cast<uint32_t>(K) * 2u + step0 * 128 + chunk * 16
+                          : 0x80000000u;   // out of range: nothing is fetched
   }
 #pragma unroll
   for (int i = 0; i < A_LOADS; ++i) {
@@ -812,7 +824,9 @@ __global__ __launch_bounds__(64) void shared_wave_kernel(SharedDecodeArgs a, int
     if (row >= M) continue;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-      const int64_t o = static_cast<int64_t>(row) * N + nf * 32 + 8 * q + 4 * g;
+      const int ch = c0 + 8 * q + 4 * g;
+      if (ch >= c1) continue;
+      const int64_t o = static_cast<int64_t>(row) * N + ch;
       if constexpr (MODE == 0) {
         uint2 packed;
         packed.x = cvt_pk_bf16(acc[1][f][4 * q] * silu_fast(acc[0][f][4 * q]), acc[1][f][4 * q + 1] * silu_fast(acc[0][f][4 * q + 1]));
@@ -826,8 +840,6 @@ __global__ __launch_bounds__(64) void shared_wave_kernel(SharedDecodeArgs a, int
   }
 }
 
-int shared_decode_down_planes(int K) { return ((K >> 6) + 31) / 32; }
-
 static int shared_decode_variant() {
   static int v = -2;
   if (v == -2) {
@@ -836,6 +848,30 @@ static int shared_decode_variant() {
   }
   return v;
 }
+
+// K planes of the decode down projection: (fragments x planes) workgroups should fill two
+// slots per CU evenly, with planes of at least 8 K steps of 64.  The second value is the plane length.
+static void shared_decode_down_split(int d, int K, int* kc_out, int* steps_out) {
+  const int KT = K >> 6, n_frags = d / 32;
+  if (shared_decode_variant() == 0) {   // the older kernel wants planes of 32 steps
+    *kc_out = (KT + 31) / 32;
+    *steps_out = 32;
+    return;
+  }
+  int kc = (device_cus() * 2 + n_frags / 2) / (n_frags > 0 ? n_frags : 1);
+  if (kc > KT / 8) kc = KT / 8;
+  if (kc < 1) kc = 1;
+  const int steps = (KT + kc - 1) / kc;
+  *kc_out = (KT + steps - 1) / steps;
+  *steps_out = steps;
+}
+
+int shared_decode_down_planes(int d, int K) {
+  int kc, steps;
+  shared_decode_down_split(d, K, &kc, &steps);
+  return kc;
+}
+
 
 template <int MODE, int AL>
 static hipError_t launch_shared_wave_al(const SharedDecodeArgs& a, int n_frags, int kc, int steps_per_plane, hipStream_t stream) {
@@ -864,7 +900,9 @@ hipError_t launch_shared_decode_gate_up(const uint16_t* x, const uint16_t* w_gat
   SharedDecodeArgs a{x, w_gate, w_up, T, F, d, h_s, nullptr, 0};
   const int n_frags = F / 32, KT = d >> 6;
   if (shared_decode_variant() != 0) {
-    return launch_shared_wave<0>(a, n_frags, 1, KT, stream);
+    // channel runs instead of fragments: see the kernel
+    const int runs = std::max(device_cus() * 2, n_frags);
+    return launch_shared_wave<0>(a, std::min(runs, F / 4), 1, KT, stream);
   }
   const int spw = (KT + 3) / 4;
   if (T <= 32) shared_decode_kernel<0, 1, 2><<<n_frags, kDecThreads, 0, stream>>>(a, 1, spw);
@@ -876,9 +914,10 @@ hipError_t launch_shared_decode_down(const uint16_t* h_s, const uint16_t* w_down
                                      hipStream_t stream) {
   SharedDecodeArgs a{h_s, w_down, nullptr, T, d, F, nullptr, y_s, static_cast<int64_t>(T) * d};
   const int n_frags = d / 32;
-  const int kc = shared_decode_down_planes(F);
+  int kc, steps;
+  shared_decode_down_split(d, F, &kc, &steps);
   if (shared_decode_variant() != 0) {
-    return launch_shared_wave<1>(a, n_frags, kc, 32, stream);
+    return launch_shared_wave<1>(a, n_frags, kc, steps, stream);
   }
   if (T <= 32) shared_decode_kernel<1, 1, 4><<<n_frags * kc, kDecThreads, 0, stream>>>(a, kc, 8);
   else shared_decode_kernel<1, 2, 2><<<n_frags * kc, kDecThreads, 0, stream>>>(a, kc, 8);

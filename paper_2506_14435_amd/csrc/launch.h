@@ -76,7 +76,7 @@ hipError_t launch_shared_decode_gate_up(const uint16_t* x, const uint16_t* w_gat
                                         int F, uint16_t* h_s, hipStream_t stream);
 hipError_t launch_shared_decode_down(const uint16_t* h_s, const uint16_t* w_down, int T, int d, int F, float* y_s,
                                      hipStream_t stream);
-int shared_decode_down_planes(int K);
+int shared_decode_down_planes(int d, int K);
 
 // Q_a(h): per dispatch row absmax int8 of the bf16 hidden activation.
 hipError_t launch_quant_rows(const uint16_t* h, int rows, int F, int8_t* q, float* beta, int32_t* rowsum,

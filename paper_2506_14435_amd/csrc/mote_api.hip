@@ -65,7 +65,7 @@ Workspace carve(const mote_layer* l, int T, char* base) {
   w.d_planes = w.tile_m == 32 ? routed_decode_down_planes(l->d_ff_routed)
                               : routed_down_planes(T, l->top_k, l->n_experts, l->d_model, l->d_ff_routed);
   w.d_split = (w.tile_m != 32 && w.d_planes == 1) ? kSplitMaxPlanes : 1;
-  w.y_planes = T <= kSharedDecodeMaxTokens ? shared_decode_down_planes(l->d_ff_shared)
+  w.y_planes = T <= kSharedDecodeMaxTokens ? shared_decode_down_planes(l->d_model, l->d_ff_shared)
                                            : shared_down_planes(T, l->d_model, l->d_ff_shared);
   w.topk_idx = reinterpret_cast<int32_t*>(take(R * 4));
   w.topk_p = reinterpret_cast<float*>(take(R * 4));
