@@ -29,8 +29,27 @@ __device__ __forceinline__ int block_sum(int v, int* s_buf) {
   return r;
 }
 
-// One workgroup per dispatch row: absmax over the bf16 row, then a second sweep (L2 hits)
-// that writes the int8 row and accumulates its integer sum.
+// One workgroup per dispatch row.  Rows of up to kRowThreads * kRowChunks 8-element chunks are
+// read once: every thread requests all its chunks before it looks at the first (the loads are in
+// flight together), takes the absmax, and quantises out of registers.  Longer rows take a second
+// sweep (L2 hits) for the part that did not fit.
+constexpr int kRowChunks = 6;
+
+__device__ __forceinline__ float chunk_absmax(const uint4& p) {
+  return fmaxf(fmaxf(fmaxf(fabsf(bf16_lo(p.x)), fabsf(bf16_hi(p.x))), fmaxf(fabsf(bf16_lo(p.y)), fabsf(bf16_hi(p.y)))),
+               fmaxf(fmaxf(fabsf(bf16_lo(p.z)), fabsf(bf16_hi(p.z))), fmaxf(fabsf(bf16_lo(p.w)), fabsf(bf16_hi(p.w)))));
+}
+
+__device__ __forceinline__ int chunk_quant(const uint4& p, float s, uint2* o) {
+  const int q0 = quant_i8(bf16_lo(p.x), s), q1 = quant_i8(bf16_hi(p.x), s);
+  const int q2 = quant_i8(bf16_lo(p.y), s), q3 = quant_i8(bf16_hi(p.y), s);
+  const int q4 = quant_i8(bf16_lo(p.z), s), q5 = quant_i8(bf16_hi(p.z), s);
+  const int q6 = quant_i8(bf16_lo(p.w), s), q7 = quant_i8(bf16_hi(p.w), s);
+  o->x = (q0 & 0xFF) | ((q1 & 0xFF) << 8) | ((q2 & 0xFF) << 16) | (static_cast<uint32_t>(q3 & 0xFF) << 24);
+  o->y = (q4 & 0xFF) | ((q5 & 0xFF) << 8) | ((q6 & 0xFF) << 16) | (static_cast<uint32_t>(q7 & 0xFF) << 24);
+  return q0 + q1 + q2 + q3 + q4 + q5 + q6 + q7;
+}
+
 __global__ __launch_bounds__(kRowThreads) void quant_rows_kernel(const uint16_t* __restrict__ h, int F,
                                                                  int8_t* __restrict__ q, float* __restrict__ beta,
                                                                  int32_t* __restrict__ rowsum) {
@@ -39,25 +58,33 @@ __global__ __launch_bounds__(kRowThreads) void quant_rows_kernel(const uint16_t*
   const int64_t row = blockIdx.x;
   const uint16_t* hp = h + row * F;
   const int n_chunks = F >> 3;
-  float amax = 0.0f;
-  for (int ch = threadIdx.x; ch < n_chunks; ch += kRowThreads) {
-    const uint4 p = *reinterpret_cast<const uint4*>(hp + ch * 8);
-    amax = fmaxf(amax, fmaxf(fmaxf(fabsf(bf16_lo(p.x)), fabsf(bf16_hi(p.x))), fmaxf(fabsf(bf16_lo(p.y)), fabsf(bf16_hi(p.y)))));
-    amax = fmaxf(amax, fmaxf(fmaxf(fabsf(bf16_lo(p.z)), fabsf(bf16_hi(p.z))), fmaxf(fabsf(bf16_lo(p.w)), fabsf(bf16_hi(p.w)))));
+  uint4 keep[kRowChunks];
+#pragma unroll
+  for (int i = 0; i < kRowChunks; ++i) {
+    const int ch = threadIdx.x + i * kRowThreads;
+    keep[i] = ch < n_chunks ? *reinterpret_cast<const uint4*>(hp + ch * 8) : make_uint4(0u, 0u, 0u, 0u);
   }
+  float amax = 0.0f;
+#pragma unroll
+  for (int i = 0; i < kRowChunks; ++i) amax = fmaxf(amax, chunk_absmax(keep[i]));
+  for (int ch = threadIdx.x + kRowChunks * kRowThreads; ch < n_chunks; ch += kRowThreads)
+    amax = fmaxf(amax, chunk_absmax(*reinterpret_cast<const uint4*>(hp + ch * 8)));
   const float b = fmaxf(block_max(amax, s_f), kEps);
   const float s = 127.0f / b;
   int rs = 0;
-  for (int ch = threadIdx.x; ch < n_chunks; ch += kRowThreads) {
-    const uint4 p = *reinterpret_cast<const uint4*>(hp + ch * 8);
-    const int q0 = quant_i8(bf16_lo(p.x), s), q1 = quant_i8(bf16_hi(p.x), s);
-    const int q2 = quant_i8(bf16_lo(p.y), s), q3 = quant_i8(bf16_hi(p.y), s);
-    const int q4 = quant_i8(bf16_lo(p.z), s), q5 = quant_i8(bf16_hi(p.z), s);
-    const int q6 = quant_i8(bf16_lo(p.w), s), q7 = quant_i8(bf16_hi(p.w), s);
-    rs += q0 + q1 + q2 + q3 + q4 + q5 + q6 + q7;
+#pragma unroll
+  for (int i = 0; i < kRowChunks; ++i) {
+    const int ch = threadIdx.x + i * kRowThreads;
     uint2 o;
-    o.x = (q0 & 0xFF) | ((q1 & 0xFF) << 8) | ((q2 & 0xFF) << 16) | (static_cast<uint32_t>(q3 & 0xFF) << 24);
-    o.y = (q4 & 0xFF) | ((q5 & 0xFF) << 8) | ((q6 & 0xFF) << 16) | (static_cast<uint32_t>(q7 & 0xFF) << 24);
+    const int part = chunk_quant(keep[i], s, &o);
+    if (ch < n_chunks) {
+      rs += part;
+      *reinterpret_cast<uint2*>(q + row * F + ch * 8) = o;
+    }
+  }
+  for (int ch = threadIdx.x + kRowChunks * kRowThreads; ch < n_chunks; ch += kRowThreads) {
+    uint2 o;
+    rs += chunk_quant(*reinterpret_cast<const uint4*>(hp + ch * 8), s, &o);
     *reinterpret_cast<uint2*>(q + row * F + ch * 8) = o;
   }
   const int total = block_sum(rs, s_i);
@@ -87,12 +114,25 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
   const int t = static_cast<int>(gid / chunks);
   const int c0 = static_cast<int>(gid - static_cast<int64_t>(t) * chunks) << 3;
   const int64_t yo = static_cast<int64_t>(t) * d + c0;
+  // Partial planes are requested four at a time (the loads of a batch are in flight together: a
+  // plane-by-plane loop pays one memory round trip per plane) and added in plane order.
   float o[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  for (int pl = 0; pl < a.y_planes; ++pl) {
-    const float4 s0 = *reinterpret_cast<const float4*>(a.y_s + pl * a.y_stride + yo);
-    const float4 s1 = *reinterpret_cast<const float4*>(a.y_s + pl * a.y_stride + yo + 4);
-    o[0] += s0.x; o[1] += s0.y; o[2] += s0.z; o[3] += s0.w;
-    o[4] += s1.x; o[5] += s1.y; o[6] += s1.z; o[7] += s1.w;
+  for (int p0 = 0; p0 < a.y_planes; p0 += 4) {
+    float4 s0[4], s1[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (p0 + u < a.y_planes) {
+        s0[u] = *reinterpret_cast<const float4*>(a.y_s + (p0 + u) * a.y_stride + yo);
+        s1[u] = *reinterpret_cast<const float4*>(a.y_s + (p0 + u) * a.y_stride + yo + 4);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (p0 + u < a.y_planes) {
+        o[0] += s0[u].x; o[1] += s0[u].y; o[2] += s0[u].z; o[3] += s0[u].w;
+        o[4] += s1[u].x; o[5] += s1[u].y; o[6] += s1[u].z; o[7] += s1[u].w;
+      }
+    }
   }
   if (a.tap_y_s) {
     *reinterpret_cast<float4*>(a.tap_y_s + yo) = make_float4(o[0], o[1], o[2], o[3]);
@@ -108,11 +148,22 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
       const int64_t ro = static_cast<int64_t>(row) * d + c0;
       int dsum[8] = {0, 0, 0, 0, 0, 0, 0, 0};
       const int d_planes = a.row_planes ? 1 + ((a.row_planes[row] >> (2 * (c0 / a.d_tile_n))) & 3) : a.d_planes;
-      for (int pl = 0; pl < d_planes; ++pl) {
-        const int4 d0 = *reinterpret_cast<const int4*>(a.acc_down + pl * a.d_stride + ro);
-        const int4 d1 = *reinterpret_cast<const int4*>(a.acc_down + pl * a.d_stride + ro + 4);
-        dsum[0] += d0.x; dsum[1] += d0.y; dsum[2] += d0.z; dsum[3] += d0.w;
-        dsum[4] += d1.x; dsum[5] += d1.y; dsum[6] += d1.z; dsum[7] += d1.w;
+      for (int p0 = 0; p0 < d_planes; p0 += 4) {
+        int4 d0[4], d1[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          if (p0 + u < d_planes) {
+            d0[u] = *reinterpret_cast<const int4*>(a.acc_down + (p0 + u) * a.d_stride + ro);
+            d1[u] = *reinterpret_cast<const int4*>(a.acc_down + (p0 + u) * a.d_stride + ro + 4);
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          if (p0 + u < d_planes) {
+            dsum[0] += d0[u].x; dsum[1] += d0[u].y; dsum[2] += d0[u].z; dsum[3] += d0[u].w;
+            dsum[4] += d1[u].x; dsum[5] += d1[u].y; dsum[6] += d1[u].z; dsum[7] += d1[u].w;
+          }
+        }
       }
       if (a.tap_acc_down) {
         *reinterpret_cast<int4*>(a.tap_acc_down + ro) = make_int4(dsum[0], dsum[1], dsum[2], dsum[3]);

@@ -15,8 +15,8 @@
 namespace mote {
 
 
-template <int OFF>
-__device__ __forceinline__ void reduce_scatter_step(double (&v)[64], int lane) {
+template <int OFF, int N>
+__device__ __forceinline__ void reduce_scatter_step(double (&v)[N], int lane) {
   constexpr int kHalf = OFF;  // values kept after this step == OFF (64 -> 32 -> ... -> 1)
   const bool up = (lane & OFF) != 0;
 #pragma unroll
@@ -25,7 +25,7 @@ __device__ __forceinline__ void reduce_scatter_step(double (&v)[64], int lane) {
     const double send = up ? v[i] : v[i + kHalf];
     v[i] = keep + __shfl_xor(send, OFF, kWave);
   }
-  if constexpr (OFF > 1) reduce_scatter_step<OFF / 2>(v, lane);
+  if constexpr (OFF > 1) reduce_scatter_step<OFF / 2, N>(v, lane);
 }
 
 template <int EMAX>
@@ -56,7 +56,8 @@ __global__ __launch_bounds__(64 * NW) void router_quant_kernel(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ w_router, const float* __restrict__ bias, int T,
     int d, int E, int k, int32_t* __restrict__ topk_idx, float* __restrict__ topk_p, int8_t* __restrict__ q_x,
     float* __restrict__ beta_x, int32_t* __restrict__ rowsum_x) {
-  static_assert(EMAX * TPW == 64, "one finished logit per lane");
+  constexpr int NV = EMAX * TPW;           // logits of a token group; lane l ends up with logit l % NV
+  static_assert(NV <= 64 && 64 % NV == 0, "at most one finished logit per lane");
   constexpr int kWaves = NW;               // wavefronts that split the channels of one token group
   constexpr int kThreads = 64 * NW;
   __shared__ double s_logit[kWaves][64];
@@ -72,9 +73,9 @@ __global__ __launch_bounds__(64 * NW) void router_quant_kernel(
 #pragma unroll
   for (int t = 0; t < TPW; ++t) xrow[t] = x + static_cast<int64_t>(min(t0 + t, T - 1)) * d;
 
-  double acc[64];
+  double acc[NV];
 #pragma unroll
-  for (int i = 0; i < 64; ++i) acc[i] = 0.0;
+  for (int i = 0; i < NV; ++i) acc[i] = 0.0;
   float amax[TPW];
 #pragma unroll
   for (int t = 0; t < TPW; ++t) amax[t] = 0.0f;
@@ -109,7 +110,11 @@ __global__ __launch_bounds__(64 * NW) void router_quant_kernel(
     }
   }
 
-  reduce_scatter_step<32>(acc, lane);  // lane l holds this wavefront's share of logit(token l / EMAX, expert l % EMAX)
+  // lane l holds this wavefront's share of logit(token (l % NV) / EMAX, expert l % EMAX): reduce-scatter
+  // over the low lane bits, then (fewer than 64 logits) a butterfly sum over the remaining ones
+  if constexpr (NV > 1) reduce_scatter_step<NV / 2, NV>(acc, lane);
+#pragma unroll
+  for (int off = NV; off < 64; off <<= 1) acc[0] += __shfl_xor(acc[0], off, kWave);
   s_logit[wave][lane] = acc[0];
 #pragma unroll
   for (int t = 0; t < TPW; ++t) {
@@ -138,7 +143,7 @@ __global__ __launch_bounds__(64 * NW) void router_quant_kernel(
     // group ends a round with the winner (largest logit, ties to the lower expert index); the
     // winner's own lane then leaves the contest.
     double cur = l;                      // invalid experts sit at -1e300, taken ones go below that
-    const int tok = lane / EMAX;
+    const int tok = (lane % NV) / EMAX;
     for (int j = 0; j < k; ++j) {
       double bl = cur;
       int be = e;
@@ -154,7 +159,7 @@ __global__ __launch_bounds__(64 * NW) void router_quant_kernel(
         bp = take ? op : bp;
       }
       if (be == e) cur = -1.7e300;
-      if (e == 0 && t0 + tok < T) {
+      if (e == 0 && lane < NV && t0 + tok < T) {
         topk_idx[static_cast<int64_t>(t0 + tok) * k + j] = be;
         topk_p[static_cast<int64_t>(t0 + tok) * k + j] = bp;
       }
@@ -217,6 +222,9 @@ __global__ __launch_bounds__(64 * NW) void router_quant_kernel(
   }
 }
 
+// Up to this many tokens every token gets a workgroup of its own (environment variable MOTE_ROUTER_TOKEN_BLOCKS).
+static const int kRouterTokenBlocks = getenv("MOTE_ROUTER_TOKEN_BLOCKS") ? atoi(getenv("MOTE_ROUTER_TOKEN_BLOCKS")) : 256;
+
 hipError_t launch_router_quant(const uint16_t* x, const uint16_t* w_router, const float* bias, int T, int d,
                                int E, int k, int32_t* topk_idx, float* topk_p, int8_t* q_x, float* beta_x,
                                int32_t* rowsum_x, hipStream_t stream) {
@@ -227,7 +235,10 @@ hipError_t launch_router_quant(const uint16_t* x, const uint16_t* w_router, cons
   if (E <= 16) {
     constexpr int kTpw = 4;
     const int blocks = (T + kTpw - 1) / kTpw;
-    if (coop)
+    if (T <= kRouterTokenBlocks)   // a few tokens: one token per workgroup, a quarter of the arithmetic and of the reduction per lane
+      router_quant_kernel<16, 1, 4><<<T, 256, 0, stream>>>(x, w_router, bias, T, d, E, k, topk_idx, topk_p, q_x, beta_x,
+                                                           rowsum_x);
+    else if (coop)
       router_quant_kernel<16, kTpw, 4><<<blocks, 256, 0, stream>>>(x, w_router, bias, T, d, E, k, topk_idx, topk_p, q_x,
                                                                    beta_x, rowsum_x);
     else
