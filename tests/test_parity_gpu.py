@@ -199,6 +199,12 @@ SMALL_CASES = [
     W.MoteConfig("decode_like", 512, 1408, 16, 2, 16, seed=13, bias_kind="subset", bias_subset=4),
     W.C1.with_tokens(24, name="c1_T24"),                                              # 17..32 tokens: its own shared decode variant
     W.MoteConfig("one_k_step", 128, 256, 4, 2, 200, seed=14),                        # d = 128: a single 128-channel K step
+    # 34 row tiles x 64 channel tiles on 512 workgroups: the gate-up tiles are drawn from the
+    # counters (and taken from other XCDs' lists at the end); every output is checked
+    W.MoteConfig("drawn_tiles", 256, 8192, 4, 2, 2048, seed=15),
+    # 76 row tiles x 8 channel tiles of the down projection on 512 workgroups with fixed shares:
+    # the 8-16 pairs left for the last round of each XCD's list are cut into two K planes
+    W.MoteConfig("split_last_round", 2048, 2048, 8, 2, 4608, seed=16),
 ]
 
 
