@@ -492,11 +492,16 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
     if constexpr (Cfg::MODE == 1) {   // a pair cut into K planes: tell the combine kernel how many to add for these rows and channels
       if (planes_t > 1 && kc == 0 && tid < rows) atomicOr(a.plan.row_planes + row0 + tid, (planes_t - 1) << (2 * nt));
     }
+    // The lane id is read afresh so that the epilogue's lane-dependent addresses are computed here
+    // and not held in registers across the K loop (10-30 registers per configuration).
+    int lane_e;
+    asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(lane_e));
+    const int r32e = lane_e & 31, ge = lane_e >> 5;
     unsigned char* const patch = s_lds + st_nx2 + wave * Cfg::PATCH_BYTES;
-    const int rd_row = lane / LANES_PER_ROW, rd_chunk = lane % LANES_PER_ROW;
+    const int rd_row = lane_e / LANES_PER_ROW, rd_chunk = lane_e % LANES_PER_ROW;
 #pragma unroll
     for (int i = 0; i < BM_W; ++i) {
-      const int rl = wm * BM_W * 32 + i * 32 + r32;
+      const int rl = wm * BM_W * 32 + i * 32 + r32e;
       float sg = 0.0f, su = 0.0f;
       if constexpr (Cfg::MODE == 0) {
         const float sx = s_beta[par][rl] / 127.0f;
@@ -510,7 +515,7 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
           const int f = f0 + ff;
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
-            const int pcol = ff * 32 + 8 * q + 4 * g;      // channel inside the patch row
+            const int pcol = ff * 32 + 8 * q + 4 * ge;      // channel inside the patch row
             const int col = f0 * 32 + pcol;                // channel inside the wavefront's block
             if constexpr (Cfg::MODE == 0) {
               float hv[4];
@@ -521,7 +526,7 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
               uint2 packed;
               packed.x = cvt_pk_bf16(hv[0], hv[1]);
               packed.y = cvt_pk_bf16(hv[2], hv[3]);
-              *reinterpret_cast<uint2*>(patch + r32 * PATCH_ROW + pcol * 2) = packed;
+              *reinterpret_cast<uint2*>(patch + r32e * PATCH_ROW + pcol * 2) = packed;
               if ((a.tap_gate != nullptr || a.tap_up != nullptr) && rl < rows && n_wave0 + col < N) {   // parity taps (tests only), each optional
                 const int64_t o = static_cast<int64_t>(row0 + rl) * N + n_wave0 + col;
                 if (a.tap_gate != nullptr)
@@ -532,7 +537,7 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
                                                                      acc[1][i][f][4 * q + 2], acc[1][i][f][4 * q + 3]);
               }
             } else {
-              *reinterpret_cast<int4*>(patch + r32 * PATCH_ROW + pcol * 4) = make_int4(
+              *reinterpret_cast<int4*>(patch + r32e * PATCH_ROW + pcol * 4) = make_int4(
                   acc[0][i][f][4 * q], acc[0][i][f][4 * q + 1], acc[0][i][f][4 * q + 2], acc[0][i][f][4 * q + 3]);
             }
           }
