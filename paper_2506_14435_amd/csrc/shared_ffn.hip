@@ -381,12 +381,13 @@ hipError_t launch_shared_gate_up(const uint16_t* x, const uint16_t* w_gate, cons
   SharedGemmArgs a{x, w_gate, w_up, T, F, d, h_s, nullptr, 0};
   // Operand traffic per flop halves with a 256 x 256 tile (one 8-wavefront workgroup per CU): the
   // 128-row tile at two workgroups per CU saturates the L2 -> L1 path first.  Small problems keep
-  // the 128-row tile, which leaves fewer CUs idle in the last round.
+  // the 128-row tile, which leaves fewer CUs idle in the last round (eight wavefronts of 64 x (32+32), four per SIMD).
   int v = shared_variant();
-  if (v == 0) v = static_cast<int64_t>((T + 255) / 256) * ((F + 127) / 128) >= 384 ? 2 : 3;
+  if (v == 0) v = static_cast<int64_t>((T + 255) / 256) * ((F + 127) / 128) >= 384 ? 2 : 4;
   switch (v) {
     case 1: return launch_shared_cfg<SharedCfg<0, 2, 1, 2, 2, 2>>(a, 1, stream);   // 128 x (64+64)
     case 2: return launch_shared_cfg<SharedCfg<0, 2, 2, 4, 2, 1>>(a, 1, stream);   // 256 x (128+128), 8 wavefronts, 1 workgroup / CU
+    case 4: return launch_shared_cfg<SharedCfg<0, 2, 1, 2, 4, 4>>(a, 1, stream);   // 128 x (128+128), 8 wavefronts of 64 x (32+32), 2 workgroups / CU (C2: 49.7 -> 47.8 us against case 3)
     default: return launch_shared_cfg<SharedCfg<0, 2, 2, 2, 2, 2>>(a, 1, stream);  // 128 x (128+128), 2 workgroups / CU
   }
 }
