@@ -1,23 +1,28 @@
 // Small-batch (decode) GEMMs of the MoTE layer: the weights are streamed from HBM exactly
 // once and every design choice serves bytes in flight, not MFMA rate.
 //
-//   routed_decode_kernel<0>: ternary gate-up (Eq.6) for the <= 32 rows of one expert tile
-//   routed_decode_kernel<1>: ternary down (Eq.5), K split across workgroups, int32 partials
-//   shared_decode_kernel<0/1>: bf16 shared expert (Eq.2) for T <= 64 tokens
+//   routed_wave_kernel<0/1>:   ternary gate-up (Eq.6) / down (Eq.5) when there are enough (row tile,
+//                              fragment) units for every wavefront of the chip: activation plane in
+//                              LDS, each wavefront streams whole fragments through a register ring
+//   routed_stream_kernel<0/1>: the same for fewer rows: the four wavefronts of a workgroup split K
+//   routed_decode_kernel<0/1>: register-ring fallback for d_model > 2048 (gate-up planes longer
+//                              than 16 K steps)
+//   shared_wave_kernel<0/1>:   bf16 shared expert (Eq.2) for T <= 64 tokens, one wavefront per
+//                              workgroup with a private LDS ring
 //
-// A workgroup of four wavefronts owns one 32-channel fragment of the output (both matrices
-// in gate-up mode) and splits the contraction length four ways.  A wavefront keeps a ring of
-// PD K steps in registers: the weight loads (one 16-byte load per lane = 1 KiB per packed
-// ternary tile, 64 contiguous bytes per lane for a bf16 row) and the matching activation
-// fragments are issued PD steps ahead of the MFMAs that consume them, nothing is staged in
-// LDS and there is no barrier in the K loop.  The four partial accumulators meet in LDS,
-// where the epilogue of the large-batch kernels is applied.  Cross-workgroup K splits (down
-// projections) are written as separate partial planes that the combine kernel adds in a
-// fixed order, so the result does not depend on scheduling.
+// Cross-workgroup K splits (down projections) are written as separate partial planes that the
+// combine kernel adds in a fixed order, so the result does not depend on scheduling.
 //
 // MFMA operand mapping as in the large-batch kernels: first operand = weights (lane l:
 // output channel l%32, K half l/32), second = activations (lane l: row l%32); result
 // register v of lane l is output channel 8*(v/4) + 4*(l/32) + v%4 of row l%32.
+//
+// routed_decode_kernel: a workgroup of four wavefronts owns one 32-channel fragment of the output
+// (both matrices in gate-up mode) and splits the contraction length four ways.  A wavefront keeps
+// a ring of PD K steps in registers: the weight loads (one 16-byte load per lane = 1 KiB per
+// packed ternary tile) and the matching activation fragments are issued PD steps ahead of the
+// MFMAs that consume them, nothing is staged in LDS and there is no barrier in the K loop.  The
+// four partial accumulators meet in LDS, where the epilogue of the large-batch kernels is applied.
 #include <stdlib.h>
 
 #include <algorithm>
@@ -566,119 +571,6 @@ struct SharedDecodeArgs {
   int64_t plane_stride;
 };
 
-// K steps are 64 bf16 elements; lane (n, g) reads the 64 contiguous bytes [64 g, 64 g + 64) of
-// its weight row in a step and uses them as four MFMA operands; the activation lane reads the
-// same byte range of its token row, so both operands agree on the channel order.
-template <int MODE, int MFR, int PD>
-__global__ __launch_bounds__(kDecThreads) void shared_decode_kernel(SharedDecodeArgs a, int kc_count,
-                                                                    int steps_per_wave) {
-  constexpr int NMAT = MODE == 0 ? 2 : 1;
-  __shared__ float s_part[4 * NMAT * MFR * 16 * 64];
-  const int M = a.M, N = a.N, K = a.K, KT = K >> 6;
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int r32 = lane & 31, g = lane >> 5;
-  const int kc = blockIdx.x % kc_count;
-  const int nf = blockIdx.x / kc_count;
-  const int step0 = (kc * 4 + wave) * steps_per_wave;
-  const int nsteps = max(0, min(steps_per_wave, KT - step0));
-
-  const unsigned char* wp[NMAT];
-  wp[0] = reinterpret_cast<const unsigned char*>(a.w0) + (static_cast<int64_t>(nf * 32 + r32) * K + step0 * 64) * 2 + g * 64;
-  if constexpr (NMAT == 2)
-    wp[1] = reinterpret_cast<const unsigned char*>(a.w1) + (static_cast<int64_t>(nf * 32 + r32) * K + step0 * 64) * 2 + g * 64;
-  const unsigned char* ap[MFR];
-#pragma unroll
-  for (int i = 0; i < MFR; ++i)
-    ap[i] = reinterpret_cast<const unsigned char*>(a.act) +
-            (static_cast<int64_t>(min(i * 32 + r32, M - 1)) * K + step0 * 64) * 2 + g * 64;
-
-  bf16x8 wr[PD][NMAT][4], ar[PD][MFR][4];
-#pragma unroll
-  for (int j = 0; j < PD; ++j) {
-    if (j < nsteps) {
-#pragma unroll
-      for (int m = 0; m < NMAT; ++m)
-#pragma unroll
-        for (int s = 0; s < 4; ++s) wr[j][m][s] = *reinterpret_cast<const bf16x8*>(wp[m] + j * 128 + s * 16);
-#pragma unroll
-      for (int i = 0; i < MFR; ++i)
-#pragma unroll
-        for (int s = 0; s < 4; ++s) ar[j][i][s] = *reinterpret_cast<const bf16x8*>(ap[i] + j * 128 + s * 16);
-    }
-  }
-  v16f acc[NMAT][MFR];
-#pragma unroll
-  for (int m = 0; m < NMAT; ++m)
-#pragma unroll
-    for (int i = 0; i < MFR; ++i)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[m][i][v] = 0.0f;
-
-  for (int base = 0; base < nsteps; base += PD) {
-#pragma unroll
-    for (int j = 0; j < PD; ++j) {
-      if (base + j < nsteps) {
-#pragma unroll
-        for (int s = 0; s < 4; ++s)
-#pragma unroll
-          for (int m = 0; m < NMAT; ++m)
-#pragma unroll
-            for (int i = 0; i < MFR; ++i)
-              acc[m][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[j][m][s], ar[j][i][s], acc[m][i], 0, 0, 0);
-        const int nx = base + j + PD;
-        if (nx < nsteps) {
-#pragma unroll
-          for (int m = 0; m < NMAT; ++m)
-#pragma unroll
-            for (int s = 0; s < 4; ++s)
-              wr[j][m][s] = *reinterpret_cast<const bf16x8*>(wp[m] + static_cast<int64_t>(nx) * 128 + s * 16);
-#pragma unroll
-          for (int i = 0; i < MFR; ++i)
-#pragma unroll
-            for (int s = 0; s < 4; ++s)
-              ar[j][i][s] = *reinterpret_cast<const bf16x8*>(ap[i] + static_cast<int64_t>(nx) * 128 + s * 16);
-        }
-      }
-    }
-  }
-
-#pragma unroll
-  for (int m = 0; m < NMAT; ++m)
-#pragma unroll
-    for (int i = 0; i < MFR; ++i)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) s_part[(((wave * NMAT + m) * MFR + i) * 16 + v) * 64 + lane] = acc[m][i][v];
-  __syncthreads();
-  const int q = tid >> 6;
-#pragma unroll
-  for (int i = 0; i < MFR; ++i) {
-    float sum[NMAT][4];
-#pragma unroll
-    for (int m = 0; m < NMAT; ++m)
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        float t = 0.0f;
-#pragma unroll
-        for (int w = 0; w < 4; ++w) t += s_part[(((w * NMAT + m) * MFR + i) * 16 + 4 * q + j) * 64 + lane];
-        sum[m][j] = t;
-      }
-    const int row = i * 32 + r32;
-    if (row < M) {
-      const int64_t o = static_cast<int64_t>(row) * N + nf * 32 + 8 * q + 4 * g;
-      if constexpr (MODE == 0) {
-        uint2 packed;
-        packed.x = cvt_pk_bf16(sum[1][0] * silu_fast(sum[0][0]), sum[1][1] * silu_fast(sum[0][1]));
-        packed.y = cvt_pk_bf16(sum[1][2] * silu_fast(sum[0][2]), sum[1][3] * silu_fast(sum[0][3]));
-        *reinterpret_cast<uint2*>(a.h_out + o) = packed;
-      } else {
-        *reinterpret_cast<float4*>(a.y_out + static_cast<int64_t>(kc) * a.plane_stride + o) =
-            make_float4(sum[0][0], sum[0][1], sum[0][2], sum[0][3]);
-      }
-    }
-  }
-}
-
 // Wave-streaming shared expert for T <= 64: one wavefront = one workgroup owns a 32-channel
 // fragment (both matrices in gate-up mode) over its whole K range (a K plane in down mode) and
 // streams weight rows AND token rows straight into a private LDS ring of 64-element K steps
@@ -840,24 +732,10 @@ __global__ __launch_bounds__(64) void shared_wave_kernel(SharedDecodeArgs a, int
   }
 }
 
-static int shared_decode_variant() {
-  static int v = -2;
-  if (v == -2) {
-    const char* e = getenv("MOTE_SHARED_DECODE_VARIANT");
-    v = e ? atoi(e) : -1;
-  }
-  return v;
-}
-
 // K planes of the decode down projection: (fragments x planes) workgroups should fill two
 // slots per CU evenly, with planes of at least 8 K steps of 64.  The second value is the plane length.
 static void shared_decode_down_split(int d, int K, int* kc_out, int* steps_out) {
   const int KT = K >> 6, n_frags = d / 32;
-  if (shared_decode_variant() == 0) {   // the older kernel wants planes of 32 steps
-    *kc_out = (KT + 31) / 32;
-    *steps_out = 32;
-    return;
-  }
   int kc = (device_cus() * 2 + n_frags / 2) / (n_frags > 0 ? n_frags : 1);
   if (kc > KT / 8) kc = KT / 8;
   if (kc < 1) kc = 1;
@@ -899,15 +777,9 @@ hipError_t launch_shared_decode_gate_up(const uint16_t* x, const uint16_t* w_gat
                                         int F, uint16_t* h_s, hipStream_t stream) {
   SharedDecodeArgs a{x, w_gate, w_up, T, F, d, h_s, nullptr, 0};
   const int n_frags = F / 32, KT = d >> 6;
-  if (shared_decode_variant() != 0) {
-    // channel runs instead of fragments: see the kernel
-    const int runs = std::max(device_cus() * 2, n_frags);
-    return launch_shared_wave<0>(a, std::min(runs, F / 4), 1, KT, stream);
-  }
-  const int spw = (KT + 3) / 4;
-  if (T <= 32) shared_decode_kernel<0, 1, 2><<<n_frags, kDecThreads, 0, stream>>>(a, 1, spw);
-  else shared_decode_kernel<0, 2, 2><<<n_frags, kDecThreads, 0, stream>>>(a, 1, spw);
-  return hipGetLastError();
+  // channel runs instead of fragments: see the kernel
+  const int runs = std::max(device_cus() * 2, n_frags);
+  return launch_shared_wave<0>(a, std::min(runs, F / 4), 1, KT, stream);
 }
 
 hipError_t launch_shared_decode_down(const uint16_t* h_s, const uint16_t* w_down, int T, int d, int F, float* y_s,
@@ -916,12 +788,7 @@ hipError_t launch_shared_decode_down(const uint16_t* h_s, const uint16_t* w_down
   const int n_frags = d / 32;
   int kc, steps;
   shared_decode_down_split(d, F, &kc, &steps);
-  if (shared_decode_variant() != 0) {
-    return launch_shared_wave<1>(a, n_frags, kc, steps, stream);
-  }
-  if (T <= 32) shared_decode_kernel<1, 1, 4><<<n_frags * kc, kDecThreads, 0, stream>>>(a, kc, 8);
-  else shared_decode_kernel<1, 2, 2><<<n_frags * kc, kDecThreads, 0, stream>>>(a, kc, 8);
-  return hipGetLastError();
+  return launch_shared_wave<1>(a, n_frags, kc, steps, stream);
 }
 
 }  // namespace mote

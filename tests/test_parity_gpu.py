@@ -198,6 +198,7 @@ SMALL_CASES = [
     W.MoteConfig("e16_skew", 256, 384, 16, 2, 500, seed=12, bias_kind="zipf", zipf_tau=0.8),
     W.MoteConfig("decode_like", 512, 1408, 16, 2, 16, seed=13, bias_kind="subset", bias_subset=4),
     W.C1.with_tokens(24, name="c1_T24"),                                              # 17..32 tokens: its own shared decode variant
+    W.MoteConfig("decode_wide", 2560, 1280, 8, 2, 12, seed=17),                     # decode with d > 2048: register-ring gate-up kernel
     W.MoteConfig("one_k_step", 128, 256, 4, 2, 200, seed=14),                        # d = 128: a single 128-channel K step
     # 34 row tiles x 64 channel tiles on 512 workgroups: the gate-up tiles are drawn from the
     # counters (and taken from other XCDs' lists at the end); every output is checked
