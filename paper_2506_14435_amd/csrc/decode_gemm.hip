@@ -375,8 +375,10 @@ __global__ __launch_bounds__(kDecThreads, 2) void routed_wave_kernel(RoutedGemmA
     const int expert = load_uniform(a.plan.tile_expert + mt);
     const int row0 = load_uniform(a.plan.tile_row0 + mt);
     const int rows = load_uniform(a.plan.tile_rows + mt);
-    const int step0 = kc * 16;
-    const int nsteps = min(16, KT - step0);
+    // the K planes share the contraction evenly (at most 16 steps each): with planes of 16 steps and
+    // a short last one, the workgroups of the last plane had a third of the bytes of the others
+    const int step0 = kc * KT / kc_count;
+    const int nsteps = (kc + 1) * KT / kc_count - step0;
 
     // ---- activation plane into LDS, requested first ----
     const int slot = row0 + min(r32, rows - 1);
