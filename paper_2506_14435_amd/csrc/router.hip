@@ -263,15 +263,27 @@ constexpr int kPlanThreads = 1024;
 // expert in ascending flat order t*k + j: the dispatch order is deterministic and stable.
 __global__ __launch_bounds__(kPlanThreads) void dispatch_plan_kernel(const int32_t* __restrict__ topk_idx, int R,
                                                                      int k, int E, int tile_m, DispatchPlan plan) {
+  constexpr int kItems = 4;                       // indices per thread and pass: they stay in registers
+  constexpr int kPass = kItems * kPlanThreads;
+  constexpr int kPlanWaves = kPlanThreads / kWave;
   __shared__ int s_cnt[64];
-  __shared__ int s_wave[kPlanThreads / kWave];
+  __shared__ int s_wave[kItems][kPlanWaves];
   __shared__ int s_off, s_tile_base;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int e = blockIdx.x;
   if (tid < 64) s_cnt[tid] = 0;
   if (e == 0 && tid < 16 * kSchedStride) plan.sched[tid] = 0;
   __syncthreads();
-  for (int i = tid; i < R; i += kPlanThreads) atomicAdd(&s_cnt[topk_idx[i]], 1);
+  int first[kItems];                              // the first pass is kept for the compaction
+#pragma unroll
+  for (int j = 0; j < kItems; ++j) {
+    const int i = j * kPlanThreads + tid;
+    first[j] = i < R ? topk_idx[i] : -1;
+  }
+#pragma unroll
+  for (int j = 0; j < kItems; ++j)
+    if (first[j] >= 0) atomicAdd(&s_cnt[first[j]], 1);
+  for (int i = kPass + tid; i < R; i += kPlanThreads) atomicAdd(&s_cnt[topk_idx[i]], 1);
   __syncthreads();
   if (tid == 0) {
     int off = 0, tiles = 0;
@@ -290,26 +302,42 @@ __global__ __launch_bounds__(kPlanThreads) void dispatch_plan_kernel(const int32
     plan.tile_row0[tile_base + m] = my_off + m * tile_m;
     plan.tile_rows[tile_base + m] = min(tile_m, my_cnt - m * tile_m);
   }
+  // Compaction, kItems * kPlanThreads indices per pass: index j * kPlanThreads + tid of the pass is
+  // item j of this thread, so (item, wavefront, lane) order is ascending flat order.
   int running = 0;
-  for (int base = 0; base < R; base += kPlanThreads) {
-    const int i = base + tid;
-    const bool flag = (i < R) && (topk_idx[i] == e);
-    const uint64_t mask = __ballot(flag);
-    const int prefix = __popcll(mask & ((1ull << lane) - 1ull));
-    if (lane == 0) s_wave[wave] = __popcll(mask);
-    __syncthreads();
-    int wave_off = 0, total = 0;
+  for (int base = 0; base < R; base += kPass) {
+    bool flag[kItems];
+    int prefix[kItems];
 #pragma unroll
-    for (int w = 0; w < kPlanThreads / kWave; ++w) {
-      const int c = s_wave[w];
-      if (w < wave) wave_off += c;
-      total += c;
+    for (int j = 0; j < kItems; ++j) {
+      const int i = base + j * kPlanThreads + tid;
+      const int v = base == 0 ? first[j] : (i < R ? topk_idx[i] : -1);
+      flag[j] = v == e;
+      const uint64_t mask = __ballot(flag[j]);
+      prefix[j] = __popcll(mask & ((1ull << lane) - 1ull));
+      if (lane == 0) s_wave[j][wave] = __popcll(mask);
     }
-    if (flag) {
-      const int slot = my_off + running + wave_off + prefix;
-      plan.row_of[i] = slot;
-      plan.tok_of[slot] = i / k;
-      plan.row_planes[slot] = 0;
+    __syncthreads();
+    int before[kItems], total = 0;
+#pragma unroll
+    for (int j = 0; j < kItems; ++j) {
+      before[j] = total;
+#pragma unroll
+      for (int w = 0; w < kPlanWaves; ++w) {
+        const int c = s_wave[j][w];
+        if (w < wave) before[j] += c;
+        total += c;
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < kItems; ++j) {
+      if (flag[j]) {
+        const int i = base + j * kPlanThreads + tid;
+        const int slot = my_off + running + before[j] + prefix[j];
+        plan.row_of[i] = slot;
+        plan.tok_of[slot] = i / k;
+        plan.row_planes[slot] = 0;
+      }
     }
     running += total;
     __syncthreads();
