@@ -1,5 +1,6 @@
 // Row quantiser Q_a(h) (Eq.8-10 applied to the hidden activation of Eq.5), the weighted
 // combine of Eq.2 + Eq.4, and the calibration copy kernel.
+#include <stdlib.h>
 #include "common.h"
 #include "launch.h"
 
@@ -7,24 +8,26 @@ namespace mote {
 
 constexpr int kRowThreads = 256;
 
+template <int THREADS>
 __device__ __forceinline__ float block_max(float v, float* s_buf) {
   v = wave_max(v);
   if ((threadIdx.x & 63) == 0) s_buf[threadIdx.x >> 6] = v;
   __syncthreads();
   float r = s_buf[0];
 #pragma unroll
-  for (int i = 1; i < kRowThreads / kWave; ++i) r = fmaxf(r, s_buf[i]);
+  for (int i = 1; i < THREADS / kWave; ++i) r = fmaxf(r, s_buf[i]);
   __syncthreads();
   return r;
 }
 
+template <int THREADS>
 __device__ __forceinline__ int block_sum(int v, int* s_buf) {
   v = wave_sum(v);
   if ((threadIdx.x & 63) == 0) s_buf[threadIdx.x >> 6] = v;
   __syncthreads();
   int r = 0;
 #pragma unroll
-  for (int i = 0; i < kRowThreads / kWave; ++i) r += s_buf[i];
+  for (int i = 0; i < THREADS / kWave; ++i) r += s_buf[i];
   __syncthreads();
   return r;
 }
@@ -50,9 +53,11 @@ __device__ __forceinline__ int chunk_quant(const uint4& p, float s, uint2* o) {
   return q0 + q1 + q2 + q3 + q4 + q5 + q6 + q7;
 }
 
-__global__ __launch_bounds__(kRowThreads) void quant_rows_kernel(const uint16_t* __restrict__ h, int F,
-                                                                 int8_t* __restrict__ q, float* __restrict__ beta,
-                                                                 int32_t* __restrict__ rowsum) {
+template <int THREADS>
+__global__ __launch_bounds__(THREADS) void quant_rows_kernel(const uint16_t* __restrict__ h, int F,
+                                                             int8_t* __restrict__ q, float* __restrict__ beta,
+                                                             int32_t* __restrict__ rowsum) {
+  constexpr int kRowThreads = THREADS;
   __shared__ float s_f[kRowThreads / kWave];
   __shared__ int s_i[kRowThreads / kWave];
   const int64_t row = blockIdx.x;
@@ -69,7 +74,7 @@ __global__ __launch_bounds__(kRowThreads) void quant_rows_kernel(const uint16_t*
   for (int i = 0; i < kRowChunks; ++i) amax = fmaxf(amax, chunk_absmax(keep[i]));
   for (int ch = threadIdx.x + kRowChunks * kRowThreads; ch < n_chunks; ch += kRowThreads)
     amax = fmaxf(amax, chunk_absmax(*reinterpret_cast<const uint4*>(hp + ch * 8)));
-  const float b = fmaxf(block_max(amax, s_f), kEps);
+  const float b = fmaxf(block_max<THREADS>(amax, s_f), kEps);
   const float s = 127.0f / b;
   int rs = 0;
 #pragma unroll
@@ -87,7 +92,7 @@ __global__ __launch_bounds__(kRowThreads) void quant_rows_kernel(const uint16_t*
     rs += chunk_quant(*reinterpret_cast<const uint4*>(hp + ch * 8), s, &o);
     *reinterpret_cast<uint2*>(q + row * F + ch * 8) = o;
   }
-  const int total = block_sum(rs, s_i);
+  const int total = block_sum<THREADS>(rs, s_i);
   if (threadIdx.x == 0) {
     beta[row] = b;
     rowsum[row] = total;
@@ -97,7 +102,10 @@ __global__ __launch_bounds__(kRowThreads) void quant_rows_kernel(const uint16_t*
 hipError_t launch_quant_rows(const uint16_t* h, int rows, int F, int8_t* q, float* beta, int32_t* rowsum,
                              hipStream_t stream) {
   if (rows == 0) return hipSuccess;
-  quant_rows_kernel<<<rows, kRowThreads, 0, stream>>>(h, F, q, beta, rowsum);
+  // short rows: half the threads per row still read a row in one sweep, and twice as many rows are resident
+  static const bool narrow = getenv("MOTE_QUANT_WIDE") == nullptr;
+  if (narrow && (F >> 3) <= 128 * kRowChunks) quant_rows_kernel<128><<<rows, 128, 0, stream>>>(h, F, q, beta, rowsum);
+  else quant_rows_kernel<kRowThreads><<<rows, kRowThreads, 0, stream>>>(h, F, q, beta, rowsum);
   return hipGetLastError();
 }
 
