@@ -23,9 +23,10 @@
 
 namespace mote {
 
-template <int MODE_, int BM_W_, int BN_W_, int WAVES_M_, int WAVES_N_, int MIN_BLOCKS_ = 1>
+template <int MODE_, int BM_W_, int BN_W_, int WAVES_M_, int WAVES_N_, int MIN_BLOCKS_ = 1, int STAGES_ = 3>
 struct SharedCfg {
   static constexpr int MIN_BLOCKS = MIN_BLOCKS_;
+  static constexpr int STAGES = STAGES_;   // LDS ring: 3, or 4 with the fragment reads of a K step moved half a step ahead
   static constexpr int MODE = MODE_;  // 0 gate-up (two matrices, SwiGLU epilogue), 1 down
   static constexpr int NMAT = MODE_ == 0 ? 2 : 1;
   static constexpr int BM_W = BM_W_, BN_W = BN_W_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
@@ -45,7 +46,11 @@ struct SharedCfg {
   static constexpr int PATCH_ROW = PATCH_F * 32 * OUT_BYTES + 16;
   static constexpr int PATCH_BYTES = 32 * PATCH_ROW;
   static constexpr bool PATCH_IN_STAGE = WAVES * PATCH_BYTES <= STAGE_BYTES;
-  static constexpr int LDS_BYTES = 3 * STAGE_BYTES + (PATCH_IN_STAGE ? 0 : WAVES * PATCH_BYTES);
+  // ring of four: two stages are free during the epilogue, each takes the patches of half the wavefronts
+  static constexpr bool PATCH_IN_TWO = STAGES_ == 4 && (WAVES / 2) * PATCH_BYTES <= STAGE_BYTES;
+  static constexpr int LDS_BYTES = STAGES * STAGE_BYTES + ((PATCH_IN_STAGE || PATCH_IN_TWO) ? 0 : WAVES * PATCH_BYTES);
+  static_assert(STAGES == 3 || STAGES == 4, "ring of three or four stages");
+  static_assert(STAGES == 3 || PATCH_IN_TWO, "the ring of four keeps the epilogue patches in its two free stages");
   static_assert(BM % ROWS_PER_PASS == 0 && (NMAT * BN) % ROWS_PER_PASS == 0 && BN % ROWS_PER_PASS == 0,
                 "loaders cover the tiles in whole passes, a pass stays inside one matrix");
   static_assert(64 % (PATCH_F * 32 * OUT_BYTES / 16) == 0, "an epilogue read covers whole rows");
@@ -129,6 +134,7 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void shared_gemm_ker
   uint32_t a_off[Cfg::A_PASSES], b_off[Cfg::B_PASSES];   // byte offsets of this lane's 16 bytes, K step 0 of the plane
   int mt, nt, kc, ktl;
   int st_cur = 0, st_nxt = STAGE_BYTES, st_nx2 = 2 * STAGE_BYTES;   // stage of K step kt, kt+1, kt+2 (byte offsets)
+  int st_nx3 = 3 * STAGE_BYTES;                                      // ... and kt+3 (ring of four stages only)
 
 #define MOTE_DECODE(slot_, mt_, nt_, kc_)                                       \
   {                                                                             \
@@ -189,6 +195,9 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void shared_gemm_ker
     int mt2 = mt, nt2 = nt, kc2 = kc;
     if (has_next) MOTE_DECODE(nslot, mt2, nt2, kc2);
     MOTE_WAIT_BARRIER(ktl > 1);   // K step 0 visible to every wavefront; the patches of the previous tile are done
+    if constexpr (Cfg::STAGES == 4) {   // the third K step goes where patches of the previous tile were
+      if (ktl > 2) MOTE_ISSUE_STEP(st_nx2, 2);
+    }
 
     v16f acc[NMAT][BM_W][BN_W];
 #pragma unroll
@@ -200,50 +209,113 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void shared_gemm_ker
 #pragma unroll
           for (int v = 0; v < 16; ++v) acc[m][i][f][v] = 0.0f;
 
-    // K loop.  K step kt contracts stage st_cur while the loads of kt+2 are issued, half of them
-    // per 16-element sub-step, into the stage that the barrier at the end of step kt-1 released.
-    for (int kt = 0; kt < ktl; ++kt) {
-      const bool pf = kt + 2 < ktl;
-      const unsigned char* const st = s_lds + st_cur;
-      // all fragments of the step are requested at once: the MFMAs of the first half run while
-      // those of the second half are still on their way
-      bf16x8 af[2][BM_W], bfr[2][NMAT][BN_W];
-#pragma unroll
-      for (int s = 0; s < 2; ++s) {
-#pragma unroll
-        for (int i = 0; i < BM_W; ++i)
-          af[s][i] = *reinterpret_cast<const bf16x8*>(st + lds_tile_offset(a_row_base + i * 32, 2 * s + g));
-#pragma unroll
-        for (int m = 0; m < NMAT; ++m)
-#pragma unroll
-          for (int f = 0; f < BN_W; ++f)
-            bfr[s][m][f] = *reinterpret_cast<const bf16x8*>(st + A_BYTES + m * B_BYTES +
-                                                            lds_tile_offset(b_row_base + f * 32, 2 * s + g));
+    if constexpr (Cfg::STAGES == 4) {
+      // Ring of four stages, loads three K steps ahead, ONE barrier per K step placed in the middle
+      // of the step: after it the next step's stage is visible, and its first-half fragments are
+      // read while the MFMAs of this step's second half run; the second-half fragments of a step
+      // are read at its start, under the MFMAs of the first half.  The wavefronts of the single
+      // workgroup of a CU all stop at the same barrier, so without this every K step began with
+      // the matrix pipe idle for an LDS round trip.
+      constexpr int NH0 = (Cfg::A_PASSES + 1) / 2 + (Cfg::B_PASSES + 1) / 2;   // loads issued in the first half of a step
+      bf16x8 af0[BM_W], bf0[NMAT][BN_W], af1[BM_W], bf1[NMAT][BN_W];
+#define MOTE_READ_HALF(af_, bf_, stage_, s_)                                                              \
+      {                                                                                                   \
+        const unsigned char* const st_ = s_lds + (stage_);                                                \
+        _Pragma("unroll") for (int i = 0; i < BM_W; ++i)                                                  \
+          af_[i] = *reinterpret_cast<const bf16x8*>(st_ + lds_tile_offset(a_row_base + i * 32, 2 * (s_) + g)); \
+        _Pragma("unroll") for (int m = 0; m < NMAT; ++m)                                                  \
+          _Pragma("unroll") for (int f = 0; f < BN_W; ++f)                                                \
+            bf_[m][f] = *reinterpret_cast<const bf16x8*>(st_ + A_BYTES + m * B_BYTES +                    \
+                                                         lds_tile_offset(b_row_base + f * 32, 2 * (s_) + g)); \
       }
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int s = 0; s < 2; ++s) {
-        if (pf) {   // half s of the loads of K step kt+2
+#define MOTE_MFMA_HALF(af_, bf_)                                                                          \
+      _Pragma("unroll") for (int m = 0; m < NMAT; ++m)                                                    \
+        _Pragma("unroll") for (int f = 0; f < BN_W; ++f)                                                  \
+          _Pragma("unroll") for (int i = 0; i < BM_W; ++i)                                                \
+            acc[m][i][f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf_[m][f], af_[i], acc[m][i][f], 0, 0, 0);
+      MOTE_READ_HALF(af0, bf0, st_cur, 0);
+      for (int kt = 0; kt < ktl; ++kt) {
+        const bool pf = kt + 3 < ktl;
+        MOTE_READ_HALF(af1, bf1, st_cur, 1);
+        if (pf) {   // first half of the loads of K step kt+3, into the stage that step kt-1 used
 #pragma unroll
           for (int p = 0; p < Cfg::A_PASSES; ++p)
-            if ((p & 1) == s) MOTE_DMA_A(st_nx2, kt + 2, p);
+            if ((p & 1) == 0) MOTE_DMA_A(st_nx3, kt + 3, p);
 #pragma unroll
           for (int p = 0; p < Cfg::B_PASSES; ++p)
-            if ((p & 1) == s) MOTE_DMA_B(st_nx2, kt + 2, p);
+            if ((p & 1) == 0) MOTE_DMA_B(st_nx3, kt + 3, p);
         }
+        __builtin_amdgcn_sched_barrier(0);
+        MOTE_MFMA_HALF(af0, bf0);
+        __builtin_amdgcn_sched_barrier(0);
+        // K step kt+1 has landed everywhere (kt+2 and the half of kt+3 stay in flight); every
+        // wavefront has finished its reads of this step's stage
+        if (pf) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" :: "n"(NLOAD + NH0) : "memory");
+        else if (kt + 2 < ktl) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" :: "n"(NLOAD) : "memory");
+        else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+        asm volatile("s_barrier" ::: "memory");
+        if (kt + 1 < ktl) MOTE_READ_HALF(af0, bf0, st_nxt, 0);
+        if (pf) {
 #pragma unroll
-        for (int m = 0; m < NMAT; ++m)
+          for (int p = 0; p < Cfg::A_PASSES; ++p)
+            if ((p & 1) == 1) MOTE_DMA_A(st_nx3, kt + 3, p);
 #pragma unroll
-          for (int f = 0; f < BN_W; ++f)
-#pragma unroll
-            for (int i = 0; i < BM_W; ++i)
-              acc[m][i][f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[s][m][f], af[s][i], acc[m][i][f], 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);  // keep each half's loads with its half
+          for (int p = 0; p < Cfg::B_PASSES; ++p)
+            if ((p & 1) == 1) MOTE_DMA_B(st_nx3, kt + 3, p);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        MOTE_MFMA_HALF(af1, bf1);
+        __builtin_amdgcn_sched_barrier(0);
+        const int t = st_cur; st_cur = st_nxt; st_nxt = st_nx2; st_nx2 = st_nx3; st_nx3 = t;
       }
-      // K step kt+1 landed everywhere (kt+2 stays in flight); after the last step: every
-      // wavefront has read its last stage
-      MOTE_WAIT_BARRIER(pf);
-      const int t = st_cur; st_cur = st_nxt; st_nxt = st_nx2; st_nx2 = t;
+#undef MOTE_READ_HALF
+#undef MOTE_MFMA_HALF
+    } else {
+      // K loop.  K step kt contracts stage st_cur while the loads of kt+2 are issued, half of them
+      // per 16-element sub-step, into the stage that the barrier at the end of step kt-1 released.
+      for (int kt = 0; kt < ktl; ++kt) {
+        const bool pf = kt + 2 < ktl;
+        const unsigned char* const st = s_lds + st_cur;
+        // all fragments of the step are requested at once: the MFMAs of the first half run while
+        // those of the second half are still on their way
+        bf16x8 af[2][BM_W], bfr[2][NMAT][BN_W];
+  #pragma unroll
+        for (int s = 0; s < 2; ++s) {
+  #pragma unroll
+          for (int i = 0; i < BM_W; ++i)
+            af[s][i] = *reinterpret_cast<const bf16x8*>(st + lds_tile_offset(a_row_base + i * 32, 2 * s + g));
+  #pragma unroll
+          for (int m = 0; m < NMAT; ++m)
+  #pragma unroll
+            for (int f = 0; f < BN_W; ++f)
+              bfr[s][m][f] = *reinterpret_cast<const bf16x8*>(st + A_BYTES + m * B_BYTES +
+                                                              lds_tile_offset(b_row_base + f * 32, 2 * s + g));
+        }
+        __builtin_amdgcn_sched_barrier(0);
+  #pragma unroll
+        for (int s = 0; s < 2; ++s) {
+          if (pf) {   // half s of the loads of K step kt+2
+  #pragma unroll
+            for (int p = 0; p < Cfg::A_PASSES; ++p)
+              if ((p & 1) == s) MOTE_DMA_A(st_nx2, kt + 2, p);
+  #pragma unroll
+            for (int p = 0; p < Cfg::B_PASSES; ++p)
+              if ((p & 1) == s) MOTE_DMA_B(st_nx2, kt + 2, p);
+          }
+  #pragma unroll
+          for (int m = 0; m < NMAT; ++m)
+  #pragma unroll
+            for (int f = 0; f < BN_W; ++f)
+  #pragma unroll
+              for (int i = 0; i < BM_W; ++i)
+                acc[m][i][f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[s][m][f], af[s][i], acc[m][i][f], 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);  // keep each half's loads with its half
+        }
+        // K step kt+1 landed everywhere (kt+2 stays in flight); after the last step: every
+        // wavefront has read its last stage
+        MOTE_WAIT_BARRIER(pf);
+        const int t = st_cur; st_cur = st_nxt; st_nxt = st_nx2; st_nx2 = t;
+      }
     }
 
     // Start the next tile now: its first two K steps travel while this tile runs its epilogue.
@@ -267,7 +339,8 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void shared_gemm_ker
     constexpr int LANES_PER_ROW = OUT_ROW_BYTES / 16;
     constexpr int ROWS_PER_READ = 64 / LANES_PER_ROW;
     unsigned char* const patch =
-        s_lds + (Cfg::PATCH_IN_STAGE ? st_nx2 : 3 * STAGE_BYTES) + wave * Cfg::PATCH_BYTES;
+        Cfg::PATCH_IN_TWO ? s_lds + (wave < Cfg::WAVES / 2 ? st_nx2 : st_nx3) + (wave % (Cfg::WAVES / 2)) * Cfg::PATCH_BYTES
+                          : s_lds + (Cfg::PATCH_IN_STAGE ? st_nx2 : Cfg::STAGES * STAGE_BYTES) + wave * Cfg::PATCH_BYTES;
     const int m0 = mt * BM, n_wave0 = nt * BN + wn * BN_W * 32;
     const int rd_row = lane / LANES_PER_ROW, rd_chunk = lane % LANES_PER_ROW;
 #pragma unroll
@@ -383,10 +456,11 @@ hipError_t launch_shared_gate_up(const uint16_t* x, const uint16_t* w_gate, cons
   // 128-row tile at two workgroups per CU saturates the L2 -> L1 path first.  Small problems keep
   // the 128-row tile, which leaves fewer CUs idle in the last round (eight wavefronts of 64 x (32+32), four per SIMD).
   int v = shared_variant();
-  if (v == 0) v = static_cast<int64_t>((T + 255) / 256) * ((F + 127) / 128) >= 384 ? 2 : 4;
+  if (v == 0) v = static_cast<int64_t>((T + 255) / 256) * ((F + 127) / 128) >= 384 ? 5 : 4;
   switch (v) {
     case 1: return launch_shared_cfg<SharedCfg<0, 2, 1, 2, 2, 2>>(a, 1, stream);   // 128 x (64+64)
     case 2: return launch_shared_cfg<SharedCfg<0, 2, 2, 4, 2, 1>>(a, 1, stream);   // 256 x (128+128), 8 wavefronts, 1 workgroup / CU
+    case 5: return launch_shared_cfg<SharedCfg<0, 2, 2, 4, 2, 1, 4>>(a, 1, stream);   // the same with the ring of four stages (C5 4.08 -> 4.02 ms)
     case 4: return launch_shared_cfg<SharedCfg<0, 2, 1, 2, 4, 4>>(a, 1, stream);   // 128 x (128+128), 8 wavefronts of 64 x (32+32), 2 workgroups / CU (C2: 49.7 -> 47.8 us against case 3)
     default: return launch_shared_cfg<SharedCfg<0, 2, 2, 2, 2, 2>>(a, 1, stream);  // 128 x (128+128), 2 workgroups / CU
   }
@@ -413,10 +487,11 @@ hipError_t launch_shared_down(const uint16_t* h_s, const uint16_t* w_down, int T
   const int planes = shared_down_planes(T, d, F);
   if (planes > 1) return launch_shared_cfg<SharedCfg<1, 2, 2, 2, 2, 2>>(a, planes, stream);   // small problem: 128 x 128 tiles
   int v = shared_variant();
-  if (v == 0) v = static_cast<int64_t>((T + 255) / 256) * ((d + 255) / 256) >= 256 ? 2 : 3;
+  if (v == 0) v = static_cast<int64_t>((T + 255) / 256) * ((d + 255) / 256) >= 256 ? 5 : 3;
   switch (v) {
     case 1: return launch_shared_cfg<SharedCfg<1, 2, 2, 2, 2, 2>>(a, 1, stream);    // 128 x 128
     case 2: return launch_shared_cfg<SharedCfg<1, 2, 4, 4, 2, 1>>(a, 1, stream);    // 256 x 256, 8 wavefronts, 1 workgroup / CU
+    case 5: return launch_shared_cfg<SharedCfg<1, 2, 4, 4, 2, 1, 4>>(a, 1, stream);    // the same with the ring of four stages (C5 2.15 -> 2.09 ms)
     default: return launch_shared_cfg<SharedCfg<1, 2, 4, 2, 2, 2>>(a, 1, stream);   // 128 x 256
   }
 }
