@@ -223,6 +223,35 @@ def test_layer_stagewise_small(cfg):
     assert torch.equal(out, out2)
 
 
+@pytest.mark.parametrize("T", [3, 64, 300, 2048])
+def test_dispatch_plan_follows_the_input_on_a_reused_workspace(T):
+    """Alternating two inputs on one workspace, the dispatch plan of every call is the stable
+    expert-major order of that call's own top-k indices (nothing of the call before survives in
+    the plan arrays, counters or caches)."""
+    M = _m()
+    cfg = W.C1.with_tokens(T, name=f"c1_T{T}")
+    _log(f"plan on reused workspace {cfg.name}")
+    gp = GpuProblem(cfg)
+    xs = [gp.x.clone(), gp.x.flip(0).contiguous() * 0.5 + gp.x * 0.5]
+    seen = []
+    for it in range(6):
+        x = xs[it & 1]
+        taps = M.alloc_taps(gp.layer, T, ("topk_idx", "counts", "row_of", "tok_of"))
+        M.mote_layer_forward(gp.layer, x, taps=taps)
+        torch.cuda.synchronize()
+        idx = taps["topk_idx"].cpu().numpy().reshape(-1)
+        order = np.argsort(idx, kind="stable")
+        row_of = np.empty_like(order)
+        row_of[order] = np.arange(order.size)
+        assert np.array_equal(taps["row_of"].cpu().numpy().reshape(-1), row_of), it
+        assert np.array_equal(taps["tok_of"].cpu().numpy(), order // cfg.top_k), it
+        assert np.array_equal(taps["counts"].cpu().numpy(), np.bincount(idx, minlength=cfg.n_experts)), it
+        seen.append(idx)
+    assert np.array_equal(seen[0], seen[2]) and np.array_equal(seen[1], seen[3])
+    if T > 3:
+        assert not np.array_equal(seen[0], seen[1])
+
+
 def test_layer_pack_parity_config1_all_experts():
     cfg = W.C1
     gp, op = GpuProblem(cfg), OracleProblem(cfg)
