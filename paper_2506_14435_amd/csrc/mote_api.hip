@@ -245,10 +245,17 @@ mote_status mote_layer_forward(const mote_layer* layer, const void* x, int T, vo
 
   // Shared expert: on the helper stream, unless stage timing wants one stage after the other.
   // Forking and joining costs the host about 40 us per call (two event records, two stream waits)
-  // and the GPU a few us at the join: a forward of little work is faster on one stream (measured:
-  // C1 0.040 vs 0.045-0.065 ms, decode T=1 0.076 vs 0.086 ms, T=16 0.118 vs 0.122 ms; decode T=64
-  // 0.125 vs 0.1215 ms and C2 0.208 vs 0.192 ms the other way round).
-  const bool fork_pays = static_cast<int64_t>(T) * d * Fs >= (int64_t{1} << 29);
+  // and the GPU a few us at the join, and two kernels that stream weights at the same time share
+  // the HBM.  Measured in steady state (ms per forward, one stream vs forked): C1 0.040 vs 0.055,
+  // decode shape T=16 0.1155 vs 0.1206 the one way; T=1 0.075 vs 0.0695, T=4 0.089 vs 0.081 (few
+  // routed experts stream, the shared expert's weights dominate), T=32 0.1157 vs 0.112, T=64
+  // 0.1229 vs 0.1155, C2 0.1896 vs 0.1644 the other.  Hence: fork when the shared expert has
+  // real work (T*d*F >= 2^29), or at most 8 tokens meet a shared expert of >= 2^24 weights per
+  // matrix.  MOTE_FORK_MIN_LOG2 moves the first threshold (tuning switch).
+  static const int fork_log2 = getenv("MOTE_FORK_MIN_LOG2") ? atoi(getenv("MOTE_FORK_MIN_LOG2")) : 29;
+  const int64_t shared_weights = static_cast<int64_t>(d) * Fs;
+  const bool fork_pays = T * shared_weights >= (int64_t{1} << fork_log2) ||
+                         (T <= 8 && shared_weights >= (int64_t{1} << 24) && fork_log2 <= 29);
   SideStream* side = nullptr;
   if (!timing && fork_enabled() && fork_pays) MOTE_HIP(side_stream(&side));
   hipStream_t sstream = side ? side->stream : stream;
