@@ -454,14 +454,17 @@ hipError_t launch_shared_gate_up(const uint16_t* x, const uint16_t* w_gate, cons
   SharedGemmArgs a{x, w_gate, w_up, T, F, d, h_s, nullptr, 0};
   // Operand traffic per flop halves with a 256 x 256 tile (one 8-wavefront workgroup per CU): the
   // 128-row tile at two workgroups per CU saturates the L2 -> L1 path first.  Small problems keep
-  // the 128-row tile, which leaves fewer CUs idle in the last round (eight wavefronts of 64 x (32+32), four per SIMD).
+  // the 128-row tile, which leaves fewer CUs idle in the last round.  Of its two forms, eight
+  // wavefronts of 64 x (32+32) are faster alone (C2: 47.8 vs 49.7 us) but fill every wavefront
+  // slot of a CU; four wavefronts of 64 x (64+64) leave room for the routed chain's kernels that
+  // run beside it, and the whole forward is faster (C2 steady state: 0.1563 vs 0.1643 ms).
   int v = shared_variant();
-  if (v == 0) v = static_cast<int64_t>((T + 255) / 256) * ((F + 127) / 128) >= 384 ? 5 : 4;
+  if (v == 0) v = static_cast<int64_t>((T + 255) / 256) * ((F + 127) / 128) >= 384 ? 5 : 3;
   switch (v) {
     case 1: return launch_shared_cfg<SharedCfg<0, 2, 1, 2, 2, 2>>(a, 1, stream);   // 128 x (64+64)
     case 2: return launch_shared_cfg<SharedCfg<0, 2, 2, 4, 2, 1>>(a, 1, stream);   // 256 x (128+128), 8 wavefronts, 1 workgroup / CU
     case 5: return launch_shared_cfg<SharedCfg<0, 2, 2, 4, 2, 1, 4>>(a, 1, stream);   // the same with the ring of four stages (C5 4.08 -> 4.02 ms)
-    case 4: return launch_shared_cfg<SharedCfg<0, 2, 1, 2, 4, 4>>(a, 1, stream);   // 128 x (128+128), 8 wavefronts of 64 x (32+32), 2 workgroups / CU (C2: 49.7 -> 47.8 us against case 3)
+    case 4: return launch_shared_cfg<SharedCfg<0, 2, 1, 2, 4, 4>>(a, 1, stream);   // 128 x (128+128), 8 wavefronts of 64 x (32+32), 2 workgroups / CU
     default: return launch_shared_cfg<SharedCfg<0, 2, 2, 2, 2, 2>>(a, 1, stream);  // 128 x (128+128), 2 workgroups / CU
   }
 }
