@@ -130,9 +130,7 @@ def main():
     ap.add_argument("--steps", type=int, default=None,
                     help="timed forwards (default: about 0.3 s of them, between 50 and 2000)")
     ap.add_argument("--warmup", type=int, default=None,
-                    help="untimed forwards before the timed ones (default: about 0.1 s of them, between 10 and "
-                         "1000: the GPU needs some 50 ms of continuous work to reach its steady clocks; with 10 "
-                         "warm-up forwards C2 reads 0.19 ms per forward, with 300 or more 0.166 ms)")
+                    help="untimed forwards before the timed ones (default: about 0.1 s of them, between 10 and 1000)")
     ap.add_argument("--workload", default="c2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true",
@@ -205,17 +203,22 @@ def main():
             launch = "hip_graph"
         except Exception as exc:  # noqa: BLE001
             print(f"bench.py: graph capture failed ({exc}); launching eagerly", file=sys.stderr)
-    if args.steps is None or args.warmup is None:   # size the defaults from a probe of a few forwards
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
+    # Conditioning: an idle GPU needs some 50 ms of continuous work to reach its steady clocks (C2
+    # reads 0.19 ms per forward right after start-up and 0.16 ms from then on), so forwards are
+    # run for 0.1 s before the W warm-up steps, whatever W is; the probe also sizes the defaults.
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    conditioning = 0
+    while conditioning < 5 or (time.perf_counter() - t0 < 0.1 and conditioning < 5000):
         for i in range(5):
-            steps[i % n_layers]()
+            steps[(conditioning + i) % n_layers]()
+        conditioning += 5
         torch.cuda.synchronize()
-        probe_ms = (time.perf_counter() - t0) * 1e3 / 5
-        if args.warmup is None:
-            args.warmup = int(min(1000, max(10, 100.0 / probe_ms)))
-        if args.steps is None:
-            args.steps = int(min(2000, max(50, 300.0 / probe_ms)))
+    probe_ms = (time.perf_counter() - t0) * 1e3 / conditioning
+    if args.warmup is None:
+        args.warmup = int(min(1000, max(10, 100.0 / probe_ms)))
+    if args.steps is None:
+        args.steps = int(min(2000, max(50, 300.0 / probe_ms)))
     for i in range(args.warmup):
         steps[i % n_layers]()
     torch.cuda.synchronize()
@@ -259,7 +262,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "i8+bf16",
         "data": "synthetic",
         "config": {"workload": cfg.name, "d_model": cfg.d_model, "d_ff": cfg.d_ff, "n_experts": cfg.n_experts,
-                   "top_k": cfg.top_k, "tokens": cfg.n_tokens, "expert_loads": counts.tolist(), "weight_copies_rotated": n_layers, "launch": launch},
+                   "top_k": cfg.top_k, "tokens": cfg.n_tokens, "expert_loads": counts.tolist(), "weight_copies_rotated": n_layers, "launch": launch, "conditioning_forwards": conditioning},
         "roofline": roofline,
         "stages": stages,
     }
