@@ -13,11 +13,12 @@
  *   - Every data pointer is a DEVICE pointer into memory the CALLER owns, 16-byte aligned.
  *     The library never allocates or frees device memory and never synchronises inside these
  *     calls; all work is ordered on the HIP stream passed as `hip_stream` (a hipStream_t cast
- *     to void*, NULL is the default stream).  mote_layer_forward runs the shared expert on a
- *     helper stream of its own (created on first use, default priority) that it forks from and
- *     joins back into `hip_stream` with events, so to the caller the call behaves like work on
- *     `hip_stream` alone; the environment variable MOTE_NO_FORK=1 keeps everything on one
- *     stream.  Host-side state (helper stream, timing events) is not thread-safe.
+ *     to void*, NULL is the default stream).  For batches where it pays, mote_layer_forward
+ *     runs the shared expert on a helper stream of its own (created on first use, default
+ *     priority) that it forks from and joins back into `hip_stream` with events, so to the
+ *     caller the call behaves like work on `hip_stream` alone; the environment variable
+ *     MOTE_NO_FORK=1 keeps everything on one stream.  Host-side state (helper stream, timing
+ *     events) is not thread-safe.
  *     Inputs and outputs must not alias.
  *   - Matrices are row-major.  A weight matrix is [n_out, n_in] and acts on a column
  *     vector of n_in channels (Section 3.1, sentence after Eq.10).
