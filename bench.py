@@ -34,6 +34,8 @@ def pick_config(name: str):
         return W.C3
     if name == "c5":
         return W.C5
+    if name in ("p05", "p15", "p3"):   # the paper's own layer: E = 4, top-1, T = 2048
+        return {"p05": W.P05, "p15": W.P15, "p3": W.P3}[name]
     if name.startswith("c4"):
         n_tok, n_distinct = 64, 16
         for part in name.split("_")[1:]:

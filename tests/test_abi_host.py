@@ -69,7 +69,8 @@ def test_shape_validation_happens_on_the_host(lib):
 def test_workloads_are_seeded_and_shaped():
     import torch
     import workloads as W
-    assert [c.name for c in (W.C1, W.C2, W.C3, W.C4, W.C5)] == list(W.CONFIGS)
+    assert [c.name for c in (W.C1, W.C2, W.C3, W.C4, W.C5, W.P05, W.P15, W.P3)] == list(W.CONFIGS)
+    assert all((c.n_experts, c.top_k, c.n_tokens) == (4, 1, 2048) for c in (W.P05, W.P15, W.P3))   # Section 4.1
     a, b = W.make_x(W.C1), W.make_x(W.C1)
     assert torch.equal(a, b) and a.dtype == torch.bfloat16 and a.shape == (64, 256)
     assert W.make_router(W.C2).shape == (896, 8)

@@ -402,6 +402,16 @@ def test_layer_config3_prefill_sampled():
     _check_down_rows(cfg, op, taps, np.sort(rows))
 
 
+@pytest.mark.parametrize("cfg", [W.P05, W.P15, W.P3], ids=lambda c: c.name)
+def test_layer_paper_shape_top1_sampled(cfg):
+    """The paper's own layer (Section 4.1): four routed experts, top-1 gating (the combine weight is
+    the raw softmax probability), 2048 tokens, at the 0.5B / 1.5B / 3B widths."""
+    _log(f"layer {cfg.name}")
+    gp, op = GpuProblem(cfg), OracleProblem(cfg)
+    out, taps = _run_layer(gp, FULL_TAPS)
+    _check_sampled(cfg, 32, 4, out, taps, op)
+
+
 @pytest.mark.parametrize("T,n", [(1, 2), (4, 4), (16, 8), (64, 16)])
 def test_layer_config4_decode(T, n):
     cfg = W.decode_config(T, n)

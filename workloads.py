@@ -49,7 +49,13 @@ C4 = MoteConfig("c4_qwen3b_decode", 2048, 11008, 16, 2, 64, seed=2, sigma_shared
                 bias_kind="subset", bias_subset=16)
 C5 = MoteConfig("c5_qwen7b_skew", 3584, 18944, 16, 2, 16384, seed=4, sigma_shared=0.01,
                 bias_kind="zipf", zipf_tau=0.45)
-CONFIGS = {c.name: c for c in (C1, C2, C3, C4, C5)}
+# The paper's own layer (Section 4.1, Figure 1): four routed ternary experts, top-1 gating, one
+# shared expert, sequences of 2048 tokens, at the Qwen2.5-0.5B / 1.5B / 3B widths.
+P05 = MoteConfig("paper_0.5b_top1", 896, 4864, 4, 1, 2048, seed=21, sigma_shared=0.012)
+P15 = MoteConfig("paper_1.5b_top1", 1536, 8960, 4, 1, 2048, seed=22, sigma_shared=0.012)
+P3 = MoteConfig("paper_3b_top1", 2048, 11008, 4, 1, 2048, seed=23, sigma_shared=0.012)
+
+CONFIGS = {c.name: c for c in (C1, C2, C3, C4, C5, P05, P15, P3)}
 
 
 # x seeds for which the decode batch really touches all n_distinct selectable experts
