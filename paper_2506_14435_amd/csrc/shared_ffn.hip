@@ -470,17 +470,17 @@ hipError_t launch_shared_gate_up(const uint16_t* x, const uint16_t* w_gate, cons
 }
 
 // K planes of the large-batch down projection: enough (row tile, channel tile, plane) triples
-// for about one workgroup per CU (two as long as the tiles alone do not fill the CUs), planes of
-// at least 8 K steps of 64.  More planes than that only add fp32 partial output (C2: four planes
-// 42 us, two planes 35 us, and a faster combine).  Pure function of the shape: the workspace
-// layout depends on it.
+// for two workgroups per CU, but planes of at least 2048 channels: every further plane adds an
+// fp32 partial output that is written here and read by the combine (C2, F = 4864: four planes
+// 42 us, two planes 35 us and a faster combine; the 3B width with T = 2048, F = 11008: one plane
+// on 128 of 512 workgroup slots 220 us).  Pure function of the shape: the workspace layout
+// depends on it.
 int shared_down_planes(int T, int d, int F) {
   const int64_t tiles = static_cast<int64_t>((T + 127) / 128) * ((d + 127) / 128);
   const int KT = F >> 6;
-  int planes = static_cast<int>(256 / (tiles > 0 ? tiles : 1));
-  if (planes < 2 && tiles < 256) planes = 2;
+  int planes = tiles > 0 ? static_cast<int>(512 / tiles) : 1;   // rounded down: a third plane at the 1.5B width (192 tiles) cost 5 %
+  if (planes > F / 2048) planes = F / 2048;
   if (planes > 8) planes = 8;
-  if (planes > KT / 8) planes = KT / 8;
   if (planes < 1) planes = 1;
   const int ktp = (KT + planes - 1) / planes;
   return (KT + ktp - 1) / ktp;

@@ -702,9 +702,9 @@ int routed_down_planes(int T, int k, int E, int d, int F) {
   const int64_t mtiles = (static_cast<int64_t>(T) * k) / 128 + (E + 1) / 2;
   const int64_t tiles = mtiles * ((d + 127) / 128);
   const int KT = F >> 7;
-  int planes = static_cast<int>(512 / (tiles > 0 ? tiles : 1));
+  int planes = tiles > 0 ? static_cast<int>((512 + tiles / 2) / tiles) : 1;
+  if (planes > F / 2048) planes = F / 2048;   // every plane adds an int32 partial output (C2, F = 4864: 2 planes 30 us, 3 planes 41 us)
   if (planes > 8) planes = 8;
-  if (planes > KT / 4) planes = KT / 4;
   if (planes < 1) planes = 1;
   const int ktp = (KT + planes - 1) / planes;
   return (KT + ktp - 1) / ktp;
