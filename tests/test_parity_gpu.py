@@ -254,6 +254,34 @@ def test_dispatch_plan_follows_the_input_on_a_reused_workspace(T):
         assert not np.array_equal(seen[0], seen[1])
 
 
+def _random_config(seed):
+    rng = np.random.default_rng(1000 + seed)
+    d = int(rng.choice([128, 256, 384, 512, 640, 1024]))
+    f = int(rng.choice([128, 256, 384, 640, 896, 1152]))
+    e = int(rng.integers(1, 17))
+    k = int(rng.integers(1, min(e, 4) + 1))
+    t = int(rng.choice([1, 2, 3, 7, 17, 40, 65, 129, 260, 511, 700]))
+    kind = ["none", "zipf", "subset"][int(rng.integers(0, 3))]
+    kw = {}
+    if kind == "zipf":
+        kw = dict(bias_kind="zipf", zipf_tau=float(rng.uniform(0.3, 1.0)))
+    elif kind == "subset" and e > 1:
+        kw = dict(bias_kind="subset", bias_subset=int(rng.integers(max(k, 1), e + 1)))
+    return W.MoteConfig(f"random_{seed}_d{d}_F{f}_E{e}_k{k}_T{t}_{kind}", d, f, e, k, t, seed=200 + seed, **kw)
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_layer_random_shapes(seed):
+    """Seeded random small shapes (widths, expert counts, top-k, batch sizes from one token to a few
+    hundred, uniform / skewed / restricted routing): every output against the oracle, stage by stage."""
+    cfg = _random_config(seed)
+    _log(f"layer {cfg.name}")
+    M = _m()
+    gp, op = GpuProblem(cfg), OracleProblem(cfg)
+    out, taps = _run_layer(gp, M.TAP_FIELDS)
+    _check_stagewise(cfg, gp, op, op.forward(), out, taps)
+
+
 def test_layer_pack_parity_config1_all_experts():
     cfg = W.C1
     gp, op = GpuProblem(cfg), OracleProblem(cfg)
