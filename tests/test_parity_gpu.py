@@ -440,6 +440,34 @@ def test_layer_paper_shape_top1_sampled(cfg):
     _check_sampled(cfg, 32, 4, out, taps, op)
 
 
+def _random_mid_config(seed):
+    rng = np.random.default_rng(5000 + seed)
+    d = int(rng.choice([512, 768, 1024, 1536, 2048]))
+    f = int(rng.choice([1024, 1536, 2048, 3072, 4096]))
+    e = int(rng.choice([2, 4, 6, 8, 12]))
+    k = int(rng.integers(1, min(e, 3) + 1))
+    t = int(rng.choice([1000, 1537, 2048, 3000, 4100, 6000]))
+    kw = dict(bias_kind="zipf", zipf_tau=float(rng.uniform(0.2, 0.8))) if rng.integers(0, 2) else {}
+    return W.MoteConfig(f"random_mid_{seed}_d{d}_F{f}_E{e}_k{k}_T{t}", d, f, e, k, t, seed=300 + seed,
+                        sigma_shared=0.012, **kw)
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_layer_random_mid_size_sampled(seed):
+    """Seeded random mid-size shapes on the large-batch kernels (fixed and drawn tile shares, K planes,
+    cut last rounds): routing and dispatch for every token, the experts on sampled tokens, and the
+    down accumulators of the first and last dispatch rows on every channel."""
+    cfg = _random_mid_config(seed)
+    _log(f"layer {cfg.name}")
+    gp, op = GpuProblem(cfg), OracleProblem(cfg)
+    out, taps = _run_layer(gp, FULL_TAPS)
+    _check_sampled(cfg, 24, min(cfg.n_experts, 3 + 2 * cfg.top_k), out, taps, op)
+    R = cfg.n_tokens * cfg.top_k
+    rng = np.random.default_rng(seed)
+    rows = np.unique(np.concatenate([rng.choice(256, 8, replace=False), R - 1 - rng.choice(600, 24, replace=False)]))
+    _check_down_rows(cfg, op, taps, rows)
+
+
 @pytest.mark.parametrize("T,n", [(1, 2), (4, 4), (16, 8), (64, 16)])
 def test_layer_config4_decode(T, n):
     cfg = W.decode_config(T, n)
