@@ -480,6 +480,11 @@ int shared_down_planes(int T, int d, int F) {
   const int KT = F >> 6;
   int planes = tiles > 0 ? static_cast<int>(512 / tiles) : 1;   // rounded down: a third plane at the 1.5B width (192 tiles) cost 5 %
   if (planes > F / 2048) planes = F / 2048;
+  // few tiles (small T): the partial outputs are small then, and an empty CU costs more than a
+  // plane; up to one workgroup per CU, planes of at least 8 K steps of 64
+  int fill = tiles > 0 ? static_cast<int>(256 / tiles) : 1;
+  if (fill > KT / 8) fill = KT / 8;
+  if (planes < fill) planes = fill;
   if (planes > 8) planes = 8;
   if (planes < 1) planes = 1;
   const int ktp = (KT + planes - 1) / planes;

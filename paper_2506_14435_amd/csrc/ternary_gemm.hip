@@ -704,6 +704,9 @@ int routed_down_planes(int T, int k, int E, int d, int F) {
   const int KT = F >> 7;
   int planes = tiles > 0 ? static_cast<int>((512 + tiles / 2) / tiles) : 1;
   if (planes > F / 2048) planes = F / 2048;   // every plane adds an int32 partial output (C2, F = 4864: 2 planes 30 us, 3 planes 41 us)
+  int fill = tiles > 0 ? static_cast<int>(256 / tiles) : 1;   // few tiles: up to one workgroup per CU, planes of at least 4 K steps
+  if (fill > KT / 4) fill = KT / 4;
+  if (planes < fill) planes = fill;
   if (planes > 8) planes = 8;
   if (planes < 1) planes = 1;
   const int ktp = (KT + planes - 1) / planes;
