@@ -200,6 +200,9 @@ SMALL_CASES = [
     W.C1.with_tokens(24, name="c1_T24"),                                              # 17..32 tokens: its own shared decode variant
     W.MoteConfig("decode_wide", 2560, 1280, 8, 2, 12, seed=17),                     # decode with d > 2048: register-ring gate-up kernel
     W.MoteConfig("one_k_step", 128, 256, 4, 2, 200, seed=14),                        # d = 128: a single 128-channel K step
+    # about 75 rows per expert: just above the decode kernels' range, 128-row tiles mostly half empty
+    W.MoteConfig("rows75", 512, 640, 8, 2, 300, seed=20),
+    W.MoteConfig("rows75_skew_wide", 1024, 2048, 16, 2, 600, seed=21, bias_kind="zipf", zipf_tau=0.5),
     W.MoteConfig("e64_k8", 256, 256, 64, 8, 100, seed=18),                           # the largest expert count and top-k the library takes
     W.MoteConfig("e32_k4_large_batch", 256, 384, 32, 4, 1200, seed=19, bias_kind="zipf", zipf_tau=0.6),   # 64-expert router variant, large-batch kernels, empty experts likely
     # 34 row tiles x 64 channel tiles on 512 workgroups: the gate-up tiles are drawn from the
