@@ -82,3 +82,24 @@ def test_workloads_are_seeded_and_shaped():
     assert z.max() == 0 and z.min() < -1.0
     x2 = W.make_x(W.C2).float()
     assert (x2.abs().amax(0) > 40).sum() == 4                       # the four outlier channels
+
+
+def test_bench_refuses_more_than_one_gpu_and_names_every_workload():
+    """`bench.py --gpus N` with N > 1 exits with a message before anything touches a GPU; the
+    workload names of the benchmark definition and of the paper's own layer resolve to configs."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout == ""
+    sys.path.insert(0, root)
+    import bench
+    import workloads as W
+    assert bench.pick_config("c2") is W.C2 and bench.pick_config("p15") is W.P15
+    dec = bench.pick_config("c4_T16_n8")
+    assert (dec.n_tokens, dec.bias_subset, dec.d_model) == (16, 8, W.C4.d_model)
+    work = bench.stage_work(W.C2, __import__("numpy").full(8, 512))
+    # algorithmic work of the dominant kernel: 2 * R * 2 * d * F integer operations against the int8 MFMA peak
+    bound, amount, unit, peak = work["routed_gate_up"]
+    assert bound == "mfma" and peak == 5000.0 and amount == 2 * 4096 * 2 * 896 * 4864
