@@ -558,6 +558,31 @@ def test_forward_graph_replays_match_eager(cfg):
     assert torch.equal(got2, want2)
 
 
+@pytest.mark.parametrize("cfg", [W.C1, W.C1.with_tokens(300, name="c1_T300"), W.decode_config(4, 4)], ids=lambda c: c.name)
+def test_forward_on_a_caller_stream_and_changing_batch_sizes(cfg):
+    """The forward is ordered on the caller's stream (a non-default one here, with work queued before
+    and after it on that stream), and one layer serves batches of different sizes one after the other."""
+    M = _m()
+    _log(f"caller stream {cfg.name}")
+    gp = GpuProblem(cfg)
+    want = M.mote_layer_forward(gp.layer, gp.x).clone()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        x = torch.zeros_like(gp.x)
+        x.copy_(gp.x, non_blocking=True)                 # producer of x on the same stream
+        got = M.mote_layer_forward(gp.layer, x)
+        doubled = got.float() * 2                         # consumer on the same stream
+    side.synchronize()
+    assert torch.equal(got, want)
+    assert torch.equal(doubled, want.float() * 2)
+    T = cfg.n_tokens
+    for t in (max(1, T // 3), T, max(1, T - 1)):          # smaller, equal, ragged: same workspace object
+        part = M.mote_layer_forward(gp.layer, gp.x[:t].contiguous())
+        torch.cuda.synchronize()
+        assert torch.equal(part, want[:t]), t
+
+
 def test_stage_timing_reports_every_stage():
     M = _m()
     gp = GpuProblem(W.C1)
