@@ -129,8 +129,15 @@ hipError_t side_stream(SideStream** out) {
   SideStream& s = g_side[dev];
   if (s.stream == nullptr) {
     if ((e = hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking)) != hipSuccess) return e;
-    if ((e = hipEventCreateWithFlags(&s.fork, hipEventDisableTiming)) != hipSuccess) return e;
-    if ((e = hipEventCreateWithFlags(&s.join, hipEventDisableTiming)) != hipSuccess) return e;
+    // The two events order work between two streams of this device only, so they carry no
+    // system-scope fence (nothing here has to become visible to the host or to another device at
+    // the fork or the join; the kernels' own device-scope release and acquire order the data).
+    // Measured: C2 0.1572 -> 0.1552 ms, decode T=64 0.1155 -> 0.1129 ms per forward.
+    // MOTE_EVENT_FENCE=1 (tuning switch) creates them with the fence.
+    static const bool fence = getenv("MOTE_EVENT_FENCE") && atoi(getenv("MOTE_EVENT_FENCE")) == 1;
+    const unsigned f = hipEventDisableTiming | (fence ? 0u : hipEventDisableSystemFence);
+    if ((e = hipEventCreateWithFlags(&s.fork, f)) != hipSuccess) return e;
+    if ((e = hipEventCreateWithFlags(&s.join, f)) != hipSuccess) return e;
   }
   *out = &s;
   return hipSuccess;

@@ -583,6 +583,28 @@ def test_forward_on_a_caller_stream_and_changing_batch_sizes(cfg):
         assert torch.equal(part, want[:t]), t
 
 
+@pytest.mark.parametrize("cfg,n", [(W.C2, 60), (W.decode_config(64, 16), 120), (W.decode_config(4, 4), 120),
+                                   (W.C1.with_tokens(300, name="c1_T300"), 120)], ids=lambda c: getattr(c, "name", str(c)))
+def test_back_to_back_forwards_with_alternating_inputs(cfg, n):
+    """Forwards queued back to back, without a synchronisation between them and with two inputs
+    taking turns on one workspace: every output equals the one of a forward that was waited for
+    (the fork and join between the caller's stream and the helper stream order all data)."""
+    M = _m()
+    _log(f"back to back {cfg.name}")
+    gp = GpuProblem(cfg)
+    xs = [gp.x, (gp.x.flip(0) * 0.5 + gp.x * 0.5).contiguous()]
+    refs = []
+    for x in xs:
+        refs.append(M.mote_layer_forward(gp.layer, x).clone())
+        torch.cuda.synchronize()
+    assert not torch.equal(refs[0], refs[1])
+    outs = [torch.empty_like(gp.x) for _ in range(n)]
+    for i in range(n):
+        M.mote_layer_forward(gp.layer, xs[i & 1], out=outs[i])
+    torch.cuda.synchronize()
+    assert [i for i in range(n) if not torch.equal(outs[i], refs[i & 1])] == []
+
+
 def test_stage_timing_reports_every_stage():
     M = _m()
     gp = GpuProblem(W.C1)
