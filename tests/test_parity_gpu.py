@@ -605,6 +605,28 @@ def test_back_to_back_forwards_with_alternating_inputs(cfg, n):
     assert [i for i in range(n) if not torch.equal(outs[i], refs[i & 1])] == []
 
 
+@pytest.mark.parametrize("cfg,n", [(W.C2, 30), (W.decode_config(4, 4), 60)], ids=lambda c: getattr(c, "name", str(c)))
+def test_forward_after_async_host_to_device_copy(cfg, n):
+    """x is refilled from pinned host memory by an asynchronous copy on the caller's stream right
+    before each forward (three inputs taking turns): the helper stream, too, sees the new x."""
+    M = _m()
+    _log(f"host copy {cfg.name}")
+    gp = GpuProblem(cfg)
+    xs = [gp.x.clone(), (gp.x.flip(0) * 0.5 + gp.x * 0.5).contiguous(), (gp.x * 0.25).contiguous()]
+    refs = []
+    for x in xs:
+        refs.append(M.mote_layer_forward(gp.layer, x).clone())
+        torch.cuda.synchronize()
+    hosts = [x.cpu().pin_memory() for x in xs]
+    xdev = torch.empty_like(gp.x)
+    outs = [torch.empty_like(gp.x) for _ in range(n)]
+    for i in range(n):
+        xdev.copy_(hosts[i % 3], non_blocking=True)
+        M.mote_layer_forward(gp.layer, xdev, out=outs[i])
+    torch.cuda.synchronize()
+    assert [i for i in range(n) if not torch.equal(outs[i], refs[i % 3])] == []
+
+
 def test_stage_timing_reports_every_stage():
     M = _m()
     gp = GpuProblem(W.C1)
