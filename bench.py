@@ -4,7 +4,11 @@ One step = one pass of the whole hot path (router + Q_a(x), dispatch, routed gat
 with SwiGLU, Q_a(h), routed down GEMM, shared FFN, combine) over one batch of synthetic
 tokens whose inputs and weights already sit in HBM.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c5|c4_T<T>_n<n>]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload headline|c2|c3|c5|c4_T<T>_n<n>]
+
+Without --workload the timed workload is the prefill shape (c3: d=2048, F=11008, E=16, top-2,
+T=8192); the decode shapes (c4) and the skewed shape (c5) are measured after it and ride along in
+the same JSON line under "decode" and "c5".
 """
 from __future__ import annotations
 
@@ -100,15 +104,17 @@ def cpu_baseline(cfg, budget_s=20.0):
     t0 = time.perf_counter()
     op.forward(tokens=tokens)
     t_small = time.perf_counter() - t0
-    n = int(min(cfg.n_tokens, max(n_probe, n_probe * budget_s / max(t_small, 1e-3))))
-    if n > n_probe and t_probe < 120:
+    # The probe's time is mostly fixed cost (router on all tokens), so the sample is grown until a
+    # pass takes at least half the budget or covers the whole workload.
+    n = len(tokens)
+    while t_probe < 120 and n < cfg.n_tokens and t_small < 0.5 * budget_s:
+        n = int(min(cfg.n_tokens, max(2 * n, n * 0.8 * budget_s / max(t_small, 1e-3))))
         stride = max(cfg.n_tokens // n, 1)
         tokens = np.arange(0, cfg.n_tokens, stride)[:n]
+        n = len(tokens)
         t0 = time.perf_counter()
         op.forward(tokens=tokens)
         t_small = time.perf_counter() - t0
-    else:
-        n = len(tokens)
     reps = 1
     if t_small < 0.5 * budget_s and n == cfg.n_tokens:     # whole workload fits: repeat it to fill the budget
         reps = int(min(50, max(1, 0.5 * budget_s / t_small)))
@@ -126,35 +132,14 @@ def cpu_baseline(cfg, budget_s=20.0):
                       f"experts already ternarised; {reps} pass(es) of {t_small:.2f} s"}
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=None,
-                    help="timed forwards (default: about 0.3 s of them, between 50 and 2000)")
-    ap.add_argument("--warmup", type=int, default=None,
-                    help="untimed forwards before the timed ones (default: about 0.1 s of them, between 10 and 1000)")
-    ap.add_argument("--workload", default="c2")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--graph", action="store_true",
-                    help="replay a captured HIP graph of the forward instead of launching its kernels eagerly")
-    ap.add_argument("--calib-copy-mib", type=int, default=0,
-                    help="also run the library's plain copy kernel on this many MiB (three launches): the "
-                         "known-size transfer that scales rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings")
-    args = ap.parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build measures one GPU; the layer is token-parallel and shards without "
-              "communication, so no multi-GPU figure is produced (run with --gpus 1).", file=sys.stderr)
-        raise SystemExit(2)
-
-    import numpy as np
+def measure(workload: str, steps, warmup, graph: bool, calib_copy_mib: int, stage_steps_max: int = 200):
+    """Times one workload: whole forwards, then per-stage durations.  Returns the result dict
+    (without cpu_baseline) and the config."""
     import torch
     import paper_2506_14435_amd as M
     from tests.mote_testlib import GpuProblem
 
-    if not torch.cuda.is_available():
-        raise SystemExit("bench.py needs a GPU; there is no CPU fallback")
-    M.load_library()
-    cfg = pick_config(args.workload)
+    cfg = pick_config(workload)
     dev = torch.device("cuda:0")
     gen = torch.Generator(device=dev).manual_seed(cfg.seed + 977)
 
@@ -170,10 +155,10 @@ def main():
     # Decode shapes are HBM-bound and touch less than the 256 MB memory-side cache: rotate
     # over distinct copies of all weights so that every step really streams from HBM.
     layers = [gp.layer]
-    if args.workload.startswith("c4"):
+    keep = []
+    if workload.startswith("c4"):
         step_bytes = sum(t.numel() * t.element_size() for t in (*gp.shared, *gp.wt))
         n_copies = max(2, int(-(-(1536 << 20) // step_bytes)))
-        keep = []
         for _ in range(n_copies - 1):
             sh = tuple(t.clone() for t in gp.shared)
             wt = [t.clone() for t in gp.wt]
@@ -185,8 +170,8 @@ def main():
     torch.cuda.synchronize()
     counts = taps["counts"].cpu().numpy()
 
-    if args.calib_copy_mib > 0:
-        src = torch.full((args.calib_copy_mib << 20,), 7, dtype=torch.uint8, device=dev)
+    if calib_copy_mib > 0:
+        src = torch.full((calib_copy_mib << 20,), 7, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)
         for _ in range(3):
             M.mote_calib_copy(dst, src)
@@ -197,11 +182,11 @@ def main():
     # same call instead (same kernels, one launch); measured 3-15 % slower than eager launches
     # on every workload, because the gaps between graph nodes exceed those between queued kernels.
     launch = "eager"
-    steps = [lambda l=l: M.mote_layer_forward(l, gp.x, out=out, workspace=ws) for l in layers]
-    if args.graph:
+    fns = [lambda l=l: M.mote_layer_forward(l, gp.x, out=out, workspace=ws) for l in layers]
+    if graph:
         try:
             graphs = [M.ForwardGraph(l, gp.x, out, ws) for l in layers]
-            steps = [g.replay for g in graphs]
+            fns = [g.replay for g in graphs]
             launch = "hip_graph"
         except Exception as exc:  # noqa: BLE001
             print(f"bench.py: graph capture failed ({exc}); launching eagerly", file=sys.stderr)
@@ -213,29 +198,29 @@ def main():
     conditioning = 0
     while conditioning < 5 or (time.perf_counter() - t0 < 0.1 and conditioning < 5000):
         for i in range(5):
-            steps[(conditioning + i) % n_layers]()
+            fns[(conditioning + i) % n_layers]()
         conditioning += 5
         torch.cuda.synchronize()
     probe_ms = (time.perf_counter() - t0) * 1e3 / conditioning
-    if args.warmup is None:
-        args.warmup = int(min(1000, max(10, 100.0 / probe_ms)))
-    if args.steps is None:
-        args.steps = int(min(2000, max(50, 300.0 / probe_ms)))
-    for i in range(args.warmup):
-        steps[i % n_layers]()
+    if warmup is None:
+        warmup = int(min(1000, max(10, 100.0 / probe_ms)))
+    if steps is None:
+        steps = int(min(2000, max(50, 300.0 / probe_ms)))
+    for i in range(warmup):
+        fns[i % n_layers]()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
-        steps[i % n_layers]()
+    for i in range(steps):
+        fns[i % n_layers]()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    ms_per_step = elapsed * 1e3 / args.steps
-    tokens_per_s = cfg.n_tokens * args.steps / elapsed
+    ms_per_step = elapsed * 1e3 / steps
+    tokens_per_s = cfg.n_tokens * steps / elapsed
 
     # per-kernel durations: HIP events recorded by the library on the launch stream
     M.mote_stage_timing(True)
     acc = {n: 0.0 for n in M.STAGE_NAMES}
-    stage_steps = min(args.steps, 200)
+    stage_steps = min(steps, stage_steps_max)
     for i in range(stage_steps):
         M.mote_layer_forward(layers[i % n_layers], gp.x, out=out, workspace=ws)
         for n, v in M.mote_stage_times().items():
@@ -255,19 +240,99 @@ def main():
     bound, amount, unit, peak = work[dom]
     achieved = amount / (stage_ms[dom] * 1e-3) / (1e9 if unit == "GB/s" else 1e12)
     roofline = {"kernel": dom, "bound": bound, "achieved": round(achieved, 2), "peak": peak, "unit": unit,
-                "frac": round(achieved / peak, 4), "traffic": read_traffic(dom, args.workload),
+                "frac": round(achieved / peak, 4), "traffic": read_traffic(dom, workload),
                 "avg_launch_ms": round(stage_ms[dom], 5)}
+    # The two figures the metric names: the routed GEMM pair against the int8 MFMA peak (large
+    # batches) or its packed-weight stream against the HBM peak (decode).
+    pair_ms = stage_ms["routed_gate_up"] + stage_ms["routed_down"]
+    pair_amount = work["routed_gate_up"][1] + work["routed_down"][1]
+    pair_peak = work["routed_gate_up"][3]
+    pair_div = 1e9 if work["routed_gate_up"][2] == "GB/s" else 1e12
+    routed_pair = {"bound": work["routed_gate_up"][0], "ms": round(pair_ms, 5),
+                   "achieved": round(pair_amount / (pair_ms * 1e-3) / pair_div, 2),
+                   "unit": work["routed_gate_up"][2], "peak": pair_peak,
+                   "frac": round(pair_amount / (pair_ms * 1e-3) / pair_div / pair_peak, 4)}
 
     result = {
         "metric": "MoTE-layer tokens/s", "value": round(tokens_per_s, 1), "unit": "tokens/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(ms_per_step, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "i8+bf16",
         "data": "synthetic",
         "config": {"workload": cfg.name, "d_model": cfg.d_model, "d_ff": cfg.d_ff, "n_experts": cfg.n_experts,
-                   "top_k": cfg.top_k, "tokens": cfg.n_tokens, "expert_loads": counts.tolist(), "weight_copies_rotated": n_layers, "launch": launch, "conditioning_forwards": conditioning},
+                   "top_k": cfg.top_k, "tokens": cfg.n_tokens, "expert_loads": counts.tolist(),
+                   "weight_copies_rotated": n_layers, "launch": launch, "conditioning_forwards": conditioning},
         "roofline": roofline,
+        "routed_gemms": routed_pair,
         "stages": stages,
     }
+    del fns, layers, keep, gp, out, ws, taps
+    torch.cuda.empty_cache()
+    return result, cfg
+
+
+def brief(result):
+    """The part of a workload's result that rides along in the headline line."""
+    keep = ("value", "unit", "steps", "warmup", "ms_per_step", "roofline", "routed_gemms")
+    b = {k: result[k] for k in keep}
+    b["workload"] = result["config"]["workload"]
+    b["tokens"] = result["config"]["tokens"]
+    b["expert_loads"] = result["config"]["expert_loads"]
+    b["weight_copies_rotated"] = result["config"]["weight_copies_rotated"]
+    b["stage_frac"] = {n: s["frac"] for n, s in result["stages"].items()
+                       if n in ("routed_gate_up", "routed_down", "shared_gate_up", "shared_down")}
+    b["stage_ms"] = {n: s["ms"] for n, s in result["stages"].items()}
+    return b
+
+
+# decode batches of the benchmark definition: T tokens touching n distinct experts
+DECODE_POINTS = ((1, 2), (4, 4), (16, 8), (64, 16))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None,
+                    help="timed forwards (default: about 0.3 s of them, between 50 and 2000)")
+    ap.add_argument("--warmup", type=int, default=None,
+                    help="untimed forwards before the timed ones (default: about 0.1 s of them, between 10 and 1000)")
+    ap.add_argument("--workload", default="headline",
+                    help="headline (default): the prefill shape c3 as the timed workload, with the decode shapes "
+                         "c4 (T = 1, 4, 16, 64) and the skewed shape c5 measured after it and carried in the same "
+                         "JSON line; or one of c1 | c2 | c3 | c5 | c4_T<T>_n<n> | p05 | p15 | p3")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay a captured HIP graph of the forward instead of launching its kernels eagerly")
+    ap.add_argument("--calib-copy-mib", type=int, default=0,
+                    help="also run the library's plain copy kernel on this many MiB (three launches): the "
+                         "known-size transfer that scales rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU; the layer is token-parallel and shards without "
+              "communication, so no multi-GPU figure is produced (run with --gpus 1).", file=sys.stderr)
+        raise SystemExit(2)
+
+    import torch
+    import paper_2506_14435_amd as M
+
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU; there is no CPU fallback")
+    M.load_library()
+    headline = args.workload == "headline"
+    main_workload = "c3" if headline else args.workload
+    result, cfg = measure(main_workload, args.steps, args.warmup, args.graph, args.calib_copy_mib)
+    if headline:
+        # The metric names three figures: tokens/s of the layer, the decode shapes' packed-weight
+        # stream against the HBM peak and the prefill shape's routed GEMMs against the int8 MFMA
+        # peak.  The timed workload of this line is the prefill shape; the other shapes are
+        # measured after it with their own default step counts.
+        result["decode"] = [brief(measure(f"c4_T{t}_n{n}", None, None, args.graph, 0)[0]) for t, n in DECODE_POINTS]
+        result["c5"] = brief(measure("c5", None, None, args.graph, 0)[0])
+        d64 = result["decode"][-1]
+        result["targets"] = {
+            "prefill_routed_i8_frac": result["routed_gemms"]["frac"], "prefill_target": 0.5,
+            "decode_routed_hbm_frac_T64": d64["routed_gemms"]["frac"],
+            "decode_routed_gate_up_hbm_frac_T64": d64["stage_frac"]["routed_gate_up"],
+            "decode_routed_down_hbm_frac_T64": d64["stage_frac"]["routed_down"], "decode_target": 0.7}
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg)
     print(json.dumps(result))
