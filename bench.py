@@ -305,6 +305,8 @@ def main():
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run the library's plain copy kernel on this many MiB (three launches): the "
                          "known-size transfer that scales rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings")
+    ap.add_argument("--tune", action="append", default=[], metavar="KNOB=VALUE",
+                    help="experiment knob of the library (mote_tuning_set), e.g. --tune no_fork=1")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU; the layer is token-parallel and shards without "
@@ -317,6 +319,9 @@ def main():
     if not torch.cuda.is_available():
         raise SystemExit("bench.py needs a GPU; there is no CPU fallback")
     M.load_library()
+    for kv in args.tune:
+        name, _, val = kv.partition("=")
+        M.mote_tuning_set(name, int(val))
     headline = args.workload == "headline"
     main_workload = "c3" if headline else args.workload
     result, cfg = measure(main_workload, args.steps, args.warmup, args.graph, args.calib_copy_mib)

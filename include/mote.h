@@ -16,9 +16,9 @@
  *     to void*, NULL is the default stream).  For batches where it pays, mote_layer_forward
  *     runs the shared expert on a helper stream of its own (created on first use, default
  *     priority) that it forks from and joins back into `hip_stream` with events, so to the
- *     caller the call behaves like work on `hip_stream` alone; the environment variable
- *     MOTE_NO_FORK=1 keeps everything on one stream.  Host-side state (helper stream, timing
- *     events) is not thread-safe.
+ *     caller the call behaves like work on `hip_stream` alone; mote_tuning_set(MOTE_KNOB_NO_FORK, 1)
+ *     keeps everything on one stream.  The library reads no environment variable.  Host-side
+ *     state (helper stream, timing events, knobs) is not thread-safe.
  *     Inputs and outputs must not alias.
  *   - Matrices are row-major.  A weight matrix is [n_out, n_in] and acts on a column
  *     vector of n_in channels (Section 3.1, sentence after Eq.10).
@@ -52,7 +52,7 @@ const char* mote_status_string(int status);
 int mote_version(void);
 
 /* ---------------------------------------------------------------------------------------
- * Q_w + INT2 pack  (Eq.7, Eq.9, Eq.10; "stores ... ternary weight in INT2 format", end of
+ * Q_w + INT2 pack  (Eq.7, Eq.9, Eq.10; INT2 storage of the ternary weights, end of
  * Section 3.1).  Offline, once per weight matrix.
  *
  *   alpha  = max( fp32( sum|W| (fp64) / (n_out*n_in) ), 1e-5 )
@@ -81,7 +81,7 @@ mote_status mote_pack_ternary(const void* w, int w_dtype, int64_t n_out, int64_t
 
 /* ---------------------------------------------------------------------------------------
  * Router: gate softmax of Eq.3 and GShard-style top-k selection (Section 3.1; Section 4.1
- * "top-1 gating").
+ * uses top-1 routing).
  *
  *   logits[t,e] = sum_c x[t,c] * w_router[c,e] (+ router_bias[e]),   fp64 accumulation
  *   P = softmax over all E logits; the k largest logits are selected, in descending order,
@@ -138,9 +138,9 @@ typedef struct {
   float* out_f32;      /* [T, d]  layer output before the final bf16 rounding             */
 } mote_taps;
 
-/* Bytes of scratch mote_layer_forward needs for a batch of T_max tokens (0 on a bad shape).
- * The layout (kernel family, K-split partial planes) depends on the batch size: a caller that
- * runs several batch sizes takes the largest value over the sizes it uses. */
+/* Bytes of scratch that serve mote_layer_forward for every batch of 1..T_max tokens (0 on a bad
+ * shape): the largest layout over those batch sizes (the kernel family and the number of K-split
+ * partial planes depend on the batch size, not monotonically). */
 size_t mote_layer_workspace_bytes(const mote_layer* layer, int T_max);
 
 /* out = FFN(x) + MoE(x)  (Eq.2 + Eq.4; no residual add, no LayerNorm).
@@ -178,6 +178,27 @@ mote_status mote_stage_timing(int enable);
 /* Waits for the last timed forward and writes the MOTE_N_STAGES stage durations in
  * milliseconds to host memory `ms`; a stage that did not run reports 0. */
 mote_status mote_stage_times(float* ms_host);
+
+/* Tuning knobs for experiments (the defaults are what the measurements chose; the library reads
+ * nothing from the environment).  Host-side state, not thread-safe.  Some knobs change the
+ * workspace layout: set them before mote_layer_workspace_bytes and keep them until the forwards
+ * that use that workspace have been enqueued. */
+enum {
+  MOTE_KNOB_NO_FORK = 0,             /* 1: shared expert on the caller's stream (default 0)            */
+  MOTE_KNOB_FORK_MIN_LOG2 = 1,       /* log2 of T*d*F_s from which the forward forks (29)              */
+  MOTE_KNOB_EVENT_FENCE = 2,         /* 1: fork/join events with a system-scope fence; before the first
+                                        forked forward (0)                                             */
+  MOTE_KNOB_QUANT_WIDE = 3,          /* 1: 256-thread row quantiser for every row length (0)           */
+  MOTE_KNOB_ROUTED_VARIANT = 4,      /* tile configuration of the large-batch routed gate-up GEMM (0)  */
+  MOTE_KNOB_ROUTED_DOWN_VARIANT = 5, /* ... of the routed down GEMM (-1: as gate-up)                   */
+  MOTE_KNOB_SHARED_VARIANT = 6,      /* ... of the shared GEMMs (0: chosen by shape)                   */
+  MOTE_KNOB_GROUP_M = 7,             /* row tiles per band of the tile order (2)                       */
+  MOTE_KNOB_DYNAMIC_ROUNDS = 8,      /* tiles per workgroup from which tiles are drawn (4)             */
+  MOTE_KNOB_DECODE_VARIANT = 9,      /* 1 / 0 forces / forbids the wave-streaming decode kernel (-1)   */
+  MOTE_KNOB_ROUTER_TOKEN_BLOCKS = 10,/* largest T with one token per router workgroup (256)            */
+  MOTE_N_KNOBS = 11
+};
+mote_status mote_tuning_set(int knob, int value);
 
 /* dst[i] = src[i] for n_bytes (multiple of 16) with a plain grid-stride copy kernel: the
  * known-size transfer used to calibrate HBM byte counters. */

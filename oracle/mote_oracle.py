@@ -259,7 +259,9 @@ def layer_forward(x_bf16, w_router_bf16, bias, k, shared, experts, tokens=None):
     xs_bits = x_bf16[sel]
     xs = bf16_to_f32(xs_bits)
     d = xs.shape[1]
-    f_dim = shared[0].shape[0]
+    idx_s = idx[sel]
+    # hidden width of the routed experts (the shared expert may have another one)
+    f_dim = experts(int(idx_s.flat[0]))[0].shape[0] if idx_s.size else shared[0].shape[0]
     ns = len(sel)
     out = dict(logits=logits, p=p, idx=idx, w=w, counts=counts, row_of=row_of, tok_of=tok_of,
                tokens=sel)
@@ -272,7 +274,6 @@ def layer_forward(x_bf16, w_router_bf16, bias, k, shared, experts, tokens=None):
     beta_h = np.zeros((ns, k), dtype=np.float32)
     acc_down = np.zeros((ns, k, d), dtype=np.int32)
     y = np.zeros((ns, k, d), dtype=np.float32)
-    idx_s = idx[sel]
     for e in np.unique(idx_s):
         ii, jj = np.nonzero(idx_s == e)
         r = ternary_expert(xs[ii], *experts(int(e)))

@@ -21,7 +21,9 @@ STAGE_NAMES = ("router_quant", "dispatch", "routed_gate_up", "quant_h", "routed_
 # every symbol include/mote.h declares
 EXPORTS = ("mote_status_string", "mote_version", "mote_packed_bytes", "mote_pack_ternary",
            "mote_router_topk", "mote_layer_workspace_bytes", "mote_layer_forward",
-           "mote_stage_timing", "mote_stage_times", "mote_calib_copy")
+           "mote_stage_timing", "mote_stage_times", "mote_tuning_set", "mote_calib_copy")
+KNOBS = ("no_fork", "fork_min_log2", "event_fence", "quant_wide", "routed_variant", "routed_down_variant",
+         "shared_variant", "group_m", "dynamic_rounds", "decode_variant", "router_token_blocks")
 
 
 class MoteError(RuntimeError):
@@ -76,6 +78,8 @@ def load_library() -> ctypes.CDLL:
     lib.mote_stage_timing.argtypes = [c_int]
     lib.mote_stage_times.restype = c_int
     lib.mote_stage_times.argtypes = [POINTER(c_float)]
+    lib.mote_tuning_set.restype = c_int
+    lib.mote_tuning_set.argtypes = [c_int, c_int]
     lib.mote_calib_copy.restype = c_int
     lib.mote_calib_copy.argtypes = [c_void_p, c_void_p, c_size_t, c_void_p]
     _lib = lib
@@ -261,6 +265,12 @@ def mote_stage_times() -> dict:
     buf = (c_float * len(STAGE_NAMES))()
     _check(load_library().mote_stage_times(buf), "mote_stage_times")
     return {n: float(buf[i]) for i, n in enumerate(STAGE_NAMES)}
+
+
+def mote_tuning_set(knob, value: int) -> None:
+    """knob: a name from KNOBS or its number."""
+    kid = KNOBS.index(knob) if isinstance(knob, str) else int(knob)
+    _check(load_library().mote_tuning_set(kid, int(value)), "mote_tuning_set")
 
 
 def mote_calib_copy(dst: torch.Tensor, src: torch.Tensor) -> None:

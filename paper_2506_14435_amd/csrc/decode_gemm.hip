@@ -520,11 +520,7 @@ int routed_decode_down_planes(int K) { return ((K >> 7) + 15) / 16; }
 // The wave-streaming kernel wants whole 16-step planes (a ragged last plane is padded with
 // zero activations) and enough units to give every wavefront of the grid a fragment.
 static bool use_wave_kernel(const RoutedGemmArgs& a, int n_frags, int kc) {
-  static int forced = -2;
-  if (forced == -2) {
-    const char* e = getenv("MOTE_DECODE_VARIANT");
-    forced = e ? atoi(e) : -1;
-  }
+  const int forced = knob(kKnobDecodeVariant);
   if (forced >= 0) return forced == 1;
   const int KT = a.K >> 7;
   const int padded = kc * 16;

@@ -103,7 +103,7 @@ hipError_t launch_quant_rows(const uint16_t* h, int rows, int F, int8_t* q, floa
                              hipStream_t stream) {
   if (rows == 0) return hipSuccess;
   // short rows: half the threads per row still read a row in one sweep, and twice as many rows are resident
-  static const bool narrow = getenv("MOTE_QUANT_WIDE") == nullptr;
+  const bool narrow = knob(kKnobQuantWide) != 1;
   if (narrow && (F >> 3) <= 128 * kRowChunks) quant_rows_kernel<128><<<rows, 128, 0, stream>>>(h, F, q, beta, rowsum);
   else quant_rows_kernel<kRowThreads><<<rows, kRowThreads, 0, stream>>>(h, F, q, beta, rowsum);
   return hipGetLastError();

@@ -5,6 +5,24 @@
 
 namespace mote {
 
+// Tuning knobs (experiments only; set through mote_tuning_set, never read from the environment).
+// The values are plain ints in one table of mote_api.hip; -1 means "the library's own choice".
+enum Knob {
+  kKnobNoFork = 0,           // 1: shared expert on the caller's stream
+  kKnobForkMinLog2,          // log2 of T*d*F_s from which the forward forks
+  kKnobEventFence,           // 1: fork / join events carry a system-scope fence
+  kKnobQuantWide,            // 1: 256-thread row quantiser for every row length
+  kKnobRoutedVariant,        // tile configuration of the large-batch routed gate-up GEMM
+  kKnobRoutedDownVariant,    // ... of the routed down GEMM (-1: same as gate-up)
+  kKnobSharedVariant,        // ... of the shared GEMMs (0: by shape)
+  kKnobGroupM,               // row tiles per band of the tile order
+  kKnobDynamicRounds,        // tiles per workgroup from which tiles are drawn
+  kKnobDecodeVariant,        // 1 / 0 forces / forbids the wave-streaming routed decode kernel
+  kKnobRouterTokenBlocks,    // largest T with one token per router workgroup
+  kKnobCount
+};
+int knob(int id);
+
 hipError_t launch_pack_ternary(const void* w, bool is_bf16, int64_t n_out, int64_t n_in, uint32_t* packed,
                                float* alpha, hipStream_t stream);
 

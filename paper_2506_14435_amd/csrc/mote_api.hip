@@ -3,10 +3,18 @@
 #include "../../include/mote.h"
 
 #include <hip/hip_runtime.h>
-#include <stdlib.h>
 
 #include "launch.h"
 #include <algorithm>
+
+namespace mote {
+// Tuning knobs: defaults are what the measurements chose; mote_tuning_set overwrites them.
+static int g_knobs[kKnobCount] = {
+    /* NoFork */ 0, /* ForkMinLog2 */ 29, /* EventFence */ 0, /* QuantWide */ 0, /* RoutedVariant */ 0,
+    /* RoutedDownVariant */ -1, /* SharedVariant */ 0, /* GroupM */ 2, /* DynamicRounds */ 4,
+    /* DecodeVariant */ -1, /* RouterTokenBlocks */ 256};
+int knob(int id) { return (id >= 0 && id < kKnobCount) ? g_knobs[id] : -1; }
+}  // namespace mote
 
 namespace {
 
@@ -133,8 +141,8 @@ hipError_t side_stream(SideStream** out) {
     // system-scope fence (nothing here has to become visible to the host or to another device at
     // the fork or the join; the kernels' own device-scope release and acquire order the data).
     // Measured: C2 0.1572 -> 0.1552 ms, decode T=64 0.1155 -> 0.1129 ms per forward.
-    // MOTE_EVENT_FENCE=1 (tuning switch) creates them with the fence.
-    static const bool fence = getenv("MOTE_EVENT_FENCE") && atoi(getenv("MOTE_EVENT_FENCE")) == 1;
+    // The knob kKnobEventFence = 1, set before the first forked forward, creates them with the fence.
+    const bool fence = knob(kKnobEventFence) == 1;
     const unsigned f = hipEventDisableTiming | (fence ? 0u : hipEventDisableSystemFence);
     if ((e = hipEventCreateWithFlags(&s.fork, f)) != hipSuccess) return e;
     if ((e = hipEventCreateWithFlags(&s.join, f)) != hipSuccess) return e;
@@ -143,14 +151,7 @@ hipError_t side_stream(SideStream** out) {
   return hipSuccess;
 }
 
-bool fork_enabled() {
-  static int v = -1;
-  if (v < 0) {
-    const char* e = getenv("MOTE_NO_FORK");
-    v = (e && e[0] == '1') ? 0 : 1;
-  }
-  return v == 1;
-}
+bool fork_enabled() { return knob(kKnobNoFork) != 1; }
 
 #define MOTE_HIP(expr)                            \
   do {                                            \
@@ -208,15 +209,28 @@ mote_status mote_router_topk(const void* x, const void* w_router, const float* r
 size_t mote_layer_workspace_bytes(const mote_layer* layer, int T_max) {
   if (!layer || T_max < 0 || !layer_shape_ok(layer)) return 0;
   if (!batch_ok(layer, T_max)) return 0;
-  // The kernel family (decode / large batch) and with it the number of partial planes depends
-  // on T; a workspace sized for T_max must serve every T <= T_max, so take the largest layout.
-  size_t need = carve(layer, T_max, nullptr).bytes;
-  const int t_shared = T_max < kSharedDecodeMaxTokens ? T_max : kSharedDecodeMaxTokens;
-  const int t_routed_cap = 48 * layer->n_experts / layer->top_k;
-  const int t_routed = T_max < t_routed_cap ? T_max : t_routed_cap;
-  const size_t a = carve(layer, t_shared, nullptr).bytes, b = carve(layer, t_routed, nullptr).bytes;
-  if (a > need) need = a;
-  if (b > need) need = b;
+  // The kernel family (decode / large batch) and the number of K-split partial planes depend on
+  // T, and not monotonically (fewer tokens can mean more planes).  A workspace sized for T_max
+  // must serve every T <= T_max, so the result is the largest layout over them.  Between two
+  // batch sizes at which a plane count or the kernel family can change, the layout grows with
+  // T; those sizes are: the family switches, every T at which floor(T*k/128) steps (routed row
+  // tiles) and every multiple of 128 (shared row tiles).  Only the last T before each is tried.
+  const int k = layer->top_k, E = layer->n_experts;
+  size_t need = 0;
+  auto consider = [&](int64_t t) {
+    if (t < 1 || t > T_max) return;
+    const size_t b = carve(layer, static_cast<int>(t), nullptr).bytes;
+    if (b > need) need = b;
+  };
+  need = carve(layer, T_max, nullptr).bytes;
+  consider(kSharedDecodeMaxTokens);
+  consider(int64_t{48} * E / k);
+  for (int64_t m = 1;; ++m) {   // largest T with floor(T*k/128) == m - 1
+    const int64_t t = (128 * m - 1) / k;
+    if (t > T_max) break;
+    consider(t);
+  }
+  for (int64_t t = 128; t <= T_max; t += 128) consider(t);
   return need;
 }
 
@@ -258,8 +272,8 @@ mote_status mote_layer_forward(const mote_layer* layer, const void* x, int T, vo
   // routed experts stream, the shared expert's weights dominate), T=32 0.1157 vs 0.112, T=64
   // 0.1229 vs 0.1155, C2 0.1896 vs 0.1644 the other.  Hence: fork when the shared expert has
   // real work (T*d*F >= 2^29), or at most 8 tokens meet a shared expert of >= 2^24 weights per
-  // matrix.  MOTE_FORK_MIN_LOG2 moves the first threshold (tuning switch).
-  static const int fork_log2 = getenv("MOTE_FORK_MIN_LOG2") ? atoi(getenv("MOTE_FORK_MIN_LOG2")) : 29;
+  // matrix.  The knob kKnobForkMinLog2 moves the first threshold.
+  const int fork_log2 = knob(kKnobForkMinLog2);
   const int64_t shared_weights = static_cast<int64_t>(d) * Fs;
   const bool fork_pays = T * shared_weights >= (int64_t{1} << fork_log2) ||
                          (T <= 8 && shared_weights >= (int64_t{1} << 24) && fork_log2 <= 29);
@@ -366,6 +380,12 @@ mote_status mote_stage_times(float* ms_host) {
   if (!g_timed_run) return MOTE_OK;
   MOTE_HIP(hipEventSynchronize(g_ev[MOTE_N_STAGES]));
   for (int i = 0; i < MOTE_N_STAGES; ++i) MOTE_HIP(hipEventElapsedTime(&ms_host[i], g_ev[i], g_ev[i + 1]));
+  return MOTE_OK;
+}
+
+mote_status mote_tuning_set(int knob_id, int value) {
+  if (knob_id < 0 || knob_id >= mote::kKnobCount) return MOTE_ERR_INVALID_ARG;
+  mote::g_knobs[knob_id] = value;
   return MOTE_OK;
 }
 

@@ -97,7 +97,8 @@ __global__ __launch_bounds__(64 * NW) void router_quant_kernel(
 #pragma unroll
       for (int i = 0; i < 8; ++i) amax[t] = fmaxf(amax[t], fabsf(xf[t][i]));
     }
-#pragma unroll(EMAX > 16 ? 1 : 2)
+    constexpr int kRowUnroll = EMAX > 16 ? 1 : 2;
+#pragma unroll kRowUnroll
     for (int i = 0; i < 8; ++i) {
       double w[EMAX];
       load_router_row<EMAX>(w_router + static_cast<int64_t>(c0 + i) * E, E, vec_ok, w);
@@ -129,16 +130,21 @@ __global__ __launch_bounds__(64 * NW) void router_quant_kernel(
     const int e = lane % EMAX;
     const bool valid = e < E;
     if (bias != nullptr && valid) l += static_cast<double>(bias[e]);
+    // A non-finite hidden state must not be able to select a padding lane: NaN and -inf logits
+    // are ranked as the lowest finite value, still above the padding (-1e300) and the taken
+    // (-1.7e300) lanes, so the k winners are always experts below E.
+    if (!(l > -1.0e299)) l = -1.0e299;
     if (!valid) l = -1.0e300;
     // gate softmax (Eq.3) over the EMAX lanes of a token: max and sum by xor shuffles
     double mx = l;
 #pragma unroll
     for (int off = EMAX / 2; off > 0; off >>= 1) mx = fmax(mx, __shfl_xor(mx, off, kWave));
-    const float ex = valid ? expf(static_cast<float>(l - mx)) : 0.0f;
-    float sum = ex;
+    // fp64 like the logits; P is rounded to fp32 once
+    const double ex = valid ? exp(l - mx) : 0.0;
+    double sum = ex;
 #pragma unroll
     for (int off = EMAX / 2; off > 0; off >>= 1) sum += __shfl_xor(sum, off, kWave);
-    const float pr = ex / sum;
+    const float pr = static_cast<float>(ex / sum);
     // top-k: k rounds of an arg-max butterfly over the EMAX lanes of a token.  Every lane of the
     // group ends a round with the winner (largest logit, ties to the lower expert index); the
     // winner's own lane then leaves the contest.
@@ -222,8 +228,8 @@ __global__ __launch_bounds__(64 * NW) void router_quant_kernel(
   }
 }
 
-// Up to this many tokens every token gets a workgroup of its own (environment variable MOTE_ROUTER_TOKEN_BLOCKS).
-static const int kRouterTokenBlocks = getenv("MOTE_ROUTER_TOKEN_BLOCKS") ? atoi(getenv("MOTE_ROUTER_TOKEN_BLOCKS")) : 256;
+// Up to this many tokens every token gets a workgroup of its own.
+static int router_token_blocks() { return knob(kKnobRouterTokenBlocks); }
 
 hipError_t launch_router_quant(const uint16_t* x, const uint16_t* w_router, const float* bias, int T, int d,
                                int E, int k, int32_t* topk_idx, float* topk_p, int8_t* q_x, float* beta_x,
@@ -235,7 +241,7 @@ hipError_t launch_router_quant(const uint16_t* x, const uint16_t* w_router, cons
   if (E <= 16) {
     constexpr int kTpw = 4;
     const int blocks = (T + kTpw - 1) / kTpw;
-    if (T <= kRouterTokenBlocks)   // a few tokens: one token per workgroup, a quarter of the arithmetic and of the reduction per lane
+    if (T <= router_token_blocks())   // a few tokens: one token per workgroup, a quarter of the arithmetic and of the reduction per lane
       router_quant_kernel<16, 1, 4><<<T, 256, 0, stream>>>(x, w_router, bias, T, d, E, k, topk_idx, topk_p, q_x, beta_x,
                                                            rowsum_x);
     else if (coop)

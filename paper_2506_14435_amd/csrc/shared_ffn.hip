@@ -412,14 +412,7 @@ static int shared_cu_count() {
   return n;
 }
 
-static int shared_variant() {
-  static int v = -1;
-  if (v < 0) {
-    const char* e = getenv("MOTE_SHARED_VARIANT");
-    v = e ? atoi(e) : 0;
-  }
-  return v;
-}
+static int shared_variant() { return knob(kKnobSharedVariant); }
 
 // kplanes64 / the plane length are counted in 64-element units (the workspace layout depends
 // on shared_down_planes, which predates the 32-element K step).

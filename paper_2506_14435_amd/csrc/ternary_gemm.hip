@@ -10,10 +10,11 @@
 // 128.  Activations (int8, gathered through tok_of in gate-up mode) are loaded straight
 // into LDS (global_load_lds), 16-byte chunks XOR-swizzled by row so that ds_read_b128 of
 // 32 consecutive rows is conflict free; three stages, requested two K steps ahead.
-// Packed weights never touch LDS: a tile of 32 rows x 128 channels is
-// 1 KiB = one 16-byte load per lane, each 32-bit word expands with (w >> 2j) & 0x03030303
-// into the four operand registers of one v_mfma_i32_32x32x32_i8.  The codes are t+1, so
-// the accumulator holds sum (t+1) q; the row sum of q is subtracted in the epilogue.
+// Packed weights take the same road (global -> LDS directly, ring of three stages) and stay
+// packed in LDS: a tile of 32 rows x 128 channels is 1 KiB = one 16-byte LDS read per lane,
+// each 32-bit word expands in registers with (w >> 2j) & 0x03030303 into the four operand
+// registers of one v_mfma_i32_32x32x32_i8.  The codes are t+1, so the accumulator holds
+// sum (t+1) q; it starts at minus the row sum of q.
 //
 // MFMA operand mapping (32x32x32 i8): first operand = weights, lane l supplies output
 // channel l%32 and 16 consecutive input channels of half l/32; second operand =
@@ -322,7 +323,11 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
       rsrc_w[i].w = kBufferFlags;                                                                  \
     }                                                                                              \
   }
-  // one 16-byte-per-lane direct load: LDS byte address (uniform), lane offset, buffer, scalar offset
+  // one 16-byte-per-lane direct load: LDS byte address (uniform), lane offset, buffer, scalar offset.
+  // M0 is written inside the statement and not listed as a clobber: the AMDGPU backend reserves M0
+  // (it never keeps a value of its own there across instructions; it writes M0 itself directly
+  // before each instruction of its own that reads it), and it rejects reserved registers in clobber
+  // lists with a warning.  The same holds for the other direct-load statements of this library.
 #define MOTE_DMA(lds_, voff_, rsrc_, soff_)                                                        \
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"           \
                :: "s"(lds_), "v"(voff_), "s"(rsrc_), "s"(soff_) : "memory")
@@ -629,27 +634,17 @@ static int resident_blocks() {
 // Row tiles per band of the tile order (environment variable MOTE_GROUP_M, read once; a value
 // larger than the number of row tiles gives the plain row-tile-fastest sweep).
 int tile_group_m() {
-  static int v = -1;
-  if (v < 0) {
-    const char* e = getenv("MOTE_GROUP_M");
-    v = e ? atoi(e) : 2;   // steady state, 2 against 8: T = 2048 at the 3B width 0.464 vs 0.474 ms, C5 11.60 vs 11.65 ms, C2 equal; 1 costs 3 % at the 0.5B width
-    if (v < 1) v = 2;
-  }
-  return v;
+  // default 2; steady state, 2 against 8: T = 2048 at the 3B width 0.464 vs 0.474 ms, C5 11.60 vs 11.65 ms, C2 equal; 1 costs 3 % at the 0.5B width
+  const int v = knob(kKnobGroupM);
+  return v < 1 ? 2 : v;
 }
 
 constexpr int kAllStatic = kFixedShares;   // n_static of a launch that never draws
 
-// Tiles per workgroup from which the tiles are drawn dynamically (environment variable
-// MOTE_DYNAMIC_ROUNDS, read once).
+// Tiles per workgroup from which the tiles are drawn dynamically.
 static int routed_dynamic_rounds() {
-  static int v = -1;
-  if (v < 0) {
-    const char* e = getenv("MOTE_DYNAMIC_ROUNDS");
-    v = e ? atoi(e) : 4;
-    if (v < 1) v = 1;
-  }
-  return v;
+  const int v = knob(kKnobDynamicRounds);
+  return v < 1 ? 1 : v;
 }
 
 template <typename Cfg>
@@ -671,14 +666,7 @@ static hipError_t launch_cfg(const RoutedGemmArgs& a, int kplanes, hipStream_t s
 
 // Tuning switch (environment variable MOTE_ROUTED_VARIANT, read once): selects the tile
 // configuration of the large-batch kernels.
-static int routed_variant() {
-  static int v = -1;
-  if (v < 0) {
-    const char* e = getenv("MOTE_ROUTED_VARIANT");
-    v = e ? atoi(e) : 0;
-  }
-  return v;
-}
+static int routed_variant() { return knob(kKnobRoutedVariant); }
 
 // Plan tile height: 32-row tiles when experts see few rows (decode), else 128.
 int routed_tile_m(int T, int k, int E) {
@@ -714,8 +702,8 @@ int routed_down_planes(int T, int k, int E, int d, int F) {
 }
 
 static int routed_down_variant() {
-  static const int v = getenv("MOTE_ROUTED_DOWN_VARIANT") ? atoi(getenv("MOTE_ROUTED_DOWN_VARIANT")) : routed_variant();
-  return v;
+  const int v = knob(kKnobRoutedDownVariant);
+  return v < 0 ? routed_variant() : v;
 }
 
 // Channels per tile of the large-batch down projection (the unit of plan.row_planes).

@@ -103,3 +103,28 @@ def test_bench_refuses_more_than_one_gpu_and_names_every_workload():
     # algorithmic work of the dominant kernel: 2 * R * 2 * d * F integer operations against the int8 MFMA peak
     bound, amount, unit, peak = work["routed_gate_up"]
     assert bound == "mfma" and peak == 5000.0 and amount == 2 * 4096 * 2 * 896 * 4864
+
+
+@pytest.mark.parametrize("d,F,E,k,T_max", [(896, 4864, 8, 2, 300), (2048, 11008, 16, 2, 520),
+                                            (1536, 8960, 4, 1, 2100), (256, 512, 4, 3, 700)])
+def test_workspace_for_T_max_serves_every_smaller_batch(lib, d, F, E, k, T_max):
+    """mote_layer_workspace_bytes(T) is what a forward of exactly T tokens needs at least, and the
+    value for T_max must serve every T <= T_max although the number of K-split partial planes
+    goes up when the batch gets smaller (the 0.5B shape needs more at T = 255 than at T = 256)."""
+    L = M.binding.MoteLayerStruct(d, F, F, E, k, *([None] * 9))
+    sizes = [lib.mote_layer_workspace_bytes(ctypes.byref(L), t) for t in range(1, T_max + 1)]
+    assert all(s > 0 for s in sizes)
+    assert all(a <= b for a, b in zip(sizes, sizes[1:]))      # a maximum over all smaller batches
+    assert sizes[-1] == max(sizes)
+
+
+def test_tuning_knobs_are_validated(lib):
+    assert lib.mote_tuning_set(-1, 0) == 1
+    assert lib.mote_tuning_set(len(M.KNOBS), 0) == 1
+    assert lib.mote_tuning_set(M.KNOBS.index("group_m"), 2) == 0
+    with pytest.raises(ValueError):
+        M.mote_tuning_set("no_such_knob", 1)
+    # the library's behaviour does not depend on the environment
+    srcs = os.path.join(ROOT, "paper_2506_14435_amd", "csrc")
+    for f in os.listdir(srcs):
+        assert "getenv" not in open(os.path.join(srcs, f)).read(), f

@@ -110,6 +110,33 @@ def test_router_exact_ties_lower_index_and_empty_batch():
     assert idx.shape == (0, 2)
 
 
+def test_router_non_finite_hidden_states_select_valid_experts():
+    """NaN and infinite logits (from non-finite hidden states) still select k distinct experts
+    below E: an index beyond E would send the later stages out of bounds.  Only the router entry
+    point runs here; it writes the k indices per token and reads nothing through them."""
+    M = _m()
+    for E, k in ((2, 2), (4, 2), (5, 3), (16, 2), (3, 3)):
+        d = 256
+        g = torch.Generator().manual_seed(40 + E)
+        x = torch.randn(6, d, generator=g).to(torch.bfloat16)
+        wr = (torch.randn(d, E, generator=g) * d ** -0.5).to(torch.bfloat16)
+        x[1, 3] = float("nan")
+        x[2, 7] = float("inf")
+        x[3, 9] = float("-inf")
+        x[4, :] = float("nan")
+        bias = torch.zeros(E)
+        bias[E - 1] = float("nan")
+        for b in (None, bias.cuda()):
+            idx, p, _ = M.mote_router_topk(x.cuda(), wr.cuda(), k, router_bias=b, want_counts=False)
+            idx = idx.cpu().numpy()
+            assert idx.min() >= 0 and idx.max() < E, (E, k, idx)
+            assert all(len(set(row)) == k for row in idx.tolist()), (E, k, idx)
+        # finite tokens are untouched by their neighbours
+        ref = O.router(W.bf16_bits(x[:1]), W.bf16_bits(wr), None, k)
+        idx, p, _ = M.mote_router_topk(x.cuda(), wr.cuda(), k, want_counts=False)
+        assert np.array_equal(idx.cpu().numpy()[:1], ref[2])
+
+
 # ------------------------------------------------------------------------ whole layer
 def _run_layer(gp, taps_names):
     M = _m()
@@ -211,6 +238,11 @@ SMALL_CASES = [
     # 76 row tiles x 8 channel tiles of the down projection on 512 workgroups with fixed shares:
     # the 8-16 pairs left for the last round of each XCD's list are cut into two K planes
     W.MoteConfig("split_last_round", 2048, 2048, 8, 2, 4608, seed=16),
+    # shared and routed experts of different hidden widths (the boundary keeps two fields): decode
+    # kernels, mid-size and large-batch kernels
+    W.MoteConfig("shared_wider_T9", 256, 384, 4, 2, 9, seed=31, d_ff_shared=640),
+    W.MoteConfig("shared_narrower_T150", 384, 640, 8, 2, 150, seed=32, d_ff_shared=256),
+    W.MoteConfig("shared_wider_T1100", 256, 512, 4, 2, 1100, seed=33, d_ff_shared=1152),
 ]
 
 

@@ -35,6 +35,11 @@ class MoteConfig:
     zipf_s: float = 1.2            # "zipf": exponent
     zipf_tau: float = 1.0          # "zipf": temperature on the log-rank bias
     x_seed: int = -1               # >= 0: draw x from this seed instead of `seed` (weights unchanged)
+    d_ff_shared: int = 0           # hidden width of the shared expert; 0: the same as d_ff (all benchmark shapes)
+
+    @property
+    def f_shared(self) -> int:
+        return self.d_ff_shared or self.d_ff
 
     def with_tokens(self, n_tokens: int, **kw) -> "MoteConfig":
         return replace(self, n_tokens=n_tokens, **kw)
@@ -117,7 +122,7 @@ def make_router_bias(cfg: MoteConfig):
 
 def make_shared(cfg: MoteConfig):
     """Shared expert, bf16: W_gate [F,d], W_up [F,d], W_down [d,F], N(0, sigma_shared)."""
-    shapes = [(cfg.d_ff, cfg.d_model), (cfg.d_ff, cfg.d_model), (cfg.d_model, cfg.d_ff)]
+    shapes = [(cfg.f_shared, cfg.d_model), (cfg.f_shared, cfg.d_model), (cfg.d_model, cfg.f_shared)]
     return tuple(
         (torch.randn(*s, generator=_gen(cfg, "shared", m), dtype=torch.float32) * cfg.sigma_shared)
         .to(torch.bfloat16) for m, s in enumerate(shapes))
