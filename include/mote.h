@@ -156,6 +156,22 @@ mote_status mote_layer_forward(const mote_layer* layer, const void* x, int T, vo
                                void* workspace, size_t workspace_bytes, const mote_taps* taps,
                                void* hip_stream);
 
+/* The same forward for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The scratch is a
+ * static device array of the library, MOTE_STATIC_WORKSPACE_BYTES per GPU, held from the time the
+ * library is loaded until the process ends.  The call allocates and frees nothing (no device
+ * memory, no stream, no event): every kernel, the shared expert included, runs on `hip_stream`,
+ * and stage timing does not apply.  Arguments, limits and results are those of
+ * mote_layer_forward (the results are bit-identical).  A batch whose layout needs more than the
+ * array (mote_layer_workspace_bytes(layer, T) > MOTE_STATIC_WORKSPACE_BYTES) is refused with
+ * MOTE_ERR_WORKSPACE_TOO_SMALL before anything is launched; 64 MiB serve the 3B-width layer
+ * (d = 2048, F = 11008, 16 experts, top-2) up to 256 tokens and the 7B width up to 128.  All calls
+ * on one GPU share that GPU's array, which keeps the previous call's contents: calls must be
+ * ordered on one stream (or otherwise not overlap), two that overlap on one GPU race. */
+#define MOTE_STATIC_WORKSPACE_BYTES (64u << 20)
+mote_status mote_layer_forward_static(const mote_layer* layer, const void* x, int T, void* out,
+                                      const mote_taps* taps, void* hip_stream);
+
 /* ---------------------------------------------------------------------------------------
  * Measurement support (not part of the layer's mathematics).
  */

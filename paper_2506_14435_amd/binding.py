@@ -20,7 +20,7 @@ STAGE_NAMES = ("router_quant", "dispatch", "routed_gate_up", "quant_h", "routed_
                "shared_gate_up", "shared_down", "combine")
 # every symbol include/mote.h declares
 EXPORTS = ("mote_status_string", "mote_version", "mote_packed_bytes", "mote_pack_ternary",
-           "mote_router_topk", "mote_layer_workspace_bytes", "mote_layer_forward",
+           "mote_router_topk", "mote_layer_workspace_bytes", "mote_layer_forward", "mote_layer_forward_static",
            "mote_stage_timing", "mote_stage_times", "mote_tuning_set", "mote_calib_copy")
 KNOBS = ("no_fork", "fork_min_log2", "event_fence", "quant_wide", "routed_variant", "routed_down_variant",
          "shared_variant", "group_m", "dynamic_rounds", "decode_variant", "router_token_blocks")
@@ -74,6 +74,9 @@ def load_library() -> ctypes.CDLL:
     lib.mote_layer_forward.restype = c_int
     lib.mote_layer_forward.argtypes = [POINTER(MoteLayerStruct), c_void_p, c_int, c_void_p, c_void_p,
                                        c_size_t, POINTER(MoteTapsStruct), c_void_p]
+    lib.mote_layer_forward_static.restype = c_int
+    lib.mote_layer_forward_static.argtypes = [POINTER(MoteLayerStruct), c_void_p, c_int, c_void_p,
+                                              POINTER(MoteTapsStruct), c_void_p]
     lib.mote_stage_timing.restype = c_int
     lib.mote_stage_timing.argtypes = [c_int]
     lib.mote_stage_times.restype = c_int
@@ -234,6 +237,26 @@ def mote_layer_forward(layer: MoteLayer, x: torch.Tensor, out: torch.Tensor = No
     _check(lib.mote_layer_forward(ctypes.byref(layer.struct), _ptr(x), n_tok, _ptr(out), _ptr(workspace),
                                   workspace.numel(), ctypes.byref(ts) if ts is not None else None, _stream()),
            "mote_layer_forward")
+    return out
+
+
+STATIC_WORKSPACE_BYTES = 64 << 20
+
+
+def mote_layer_forward_static(layer: MoteLayer, x: torch.Tensor, out: torch.Tensor, taps: dict = None) -> torch.Tensor:
+    """mote_layer_forward on the library's static scratch array: allocates nothing, so `out` is
+    required; batches whose layout exceeds STATIC_WORKSPACE_BYTES raise."""
+    lib = load_library()
+    _dev(x, torch.bfloat16, "x")
+    _dev(out, torch.bfloat16, "out")
+    if x.shape[1] != layer.d_model or out.shape != x.shape:
+        raise MoteError("x / out have the wrong shape")
+    ts = None
+    if taps is not None:
+        ts = MoteTapsStruct(*[taps[n].data_ptr() if n in taps else None for n in TAP_FIELDS])
+    _check(lib.mote_layer_forward_static(ctypes.byref(layer.struct), _ptr(x), x.shape[0], _ptr(out),
+                                         ctypes.byref(ts) if ts is not None else None, _stream()),
+           "mote_layer_forward_static")
     return out
 
 

@@ -234,8 +234,14 @@ size_t mote_layer_workspace_bytes(const mote_layer* layer, int T_max) {
   return need;
 }
 
-mote_status mote_layer_forward(const mote_layer* layer, const void* x, int T, void* out, void* workspace,
-                               size_t workspace_bytes, const mote_taps* taps, void* hip_stream) {
+}  // extern "C"
+
+namespace {
+
+// The forward pass behind both entry points.  one_stream: everything on the caller's stream and
+// no host-side object is created (no helper stream, no events).
+mote_status forward_impl(const mote_layer* layer, const void* x, int T, void* out, void* workspace,
+                         size_t workspace_bytes, const mote_taps* taps, void* hip_stream, bool one_stream) {
   if (!layer || T < 0) return MOTE_ERR_INVALID_ARG;
   if (!layer_shape_ok(layer)) return MOTE_ERR_UNSUPPORTED_SHAPE;
   if (!batch_ok(layer, T)) return MOTE_ERR_UNSUPPORTED_SHAPE;
@@ -253,7 +259,7 @@ mote_status mote_layer_forward(const mote_layer* layer, const void* x, int T, vo
   const int E = layer->n_experts, k = layer->top_k;
   const int R = T * k;
   const uint16_t* xb = static_cast<const uint16_t*>(x);
-  const bool timing = g_timing;
+  const bool timing = g_timing && !one_stream;
   if (timing) MOTE_HIP(ensure_events());
   auto mark = [&](int i) -> hipError_t { return timing ? hipEventRecord(g_ev[i], stream) : hipSuccess; };
 
@@ -278,7 +284,7 @@ mote_status mote_layer_forward(const mote_layer* layer, const void* x, int T, vo
   const bool fork_pays = T * shared_weights >= (int64_t{1} << fork_log2) ||
                          (T <= 8 && shared_weights >= (int64_t{1} << 24) && fork_log2 <= 29);
   SideStream* side = nullptr;
-  if (!timing && fork_enabled() && fork_pays) MOTE_HIP(side_stream(&side));
+  if (!timing && !one_stream && fork_enabled() && fork_pays) MOTE_HIP(side_stream(&side));
   hipStream_t sstream = side ? side->stream : stream;
   if (side) {
     MOTE_HIP(hipEventRecord(side->fork, stream));
@@ -366,6 +372,49 @@ mote_status mote_layer_forward(const mote_layer* layer, const void* x, int T, vo
     MOTE_HIP(tap(taps->h_s, w.h_s, Tz * Fs * 2));
   }
   return MOTE_OK;
+}
+
+// ---- scratch of mote_layer_forward_static: one array per device, held until the process ends ----
+__device__ __align__(256) unsigned char scratch[MOTE_STATIC_WORKSPACE_BYTES];
+void* g_scratch_ptr[16] = {};   // device address of `scratch` on each device (the array's name is
+                                // only a host-side handle: never passed to a kernel or a copy)
+
+hipError_t static_scratch(void** out) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= 16) return hipErrorInvalidDevice;
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* p = nullptr;
+    if ((e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch))) != hipSuccess) return e;
+    if (p == nullptr) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
+
+}  // namespace
+
+extern "C" {
+
+mote_status mote_layer_forward(const mote_layer* layer, const void* x, int T, void* out, void* workspace,
+                               size_t workspace_bytes, const mote_taps* taps, void* hip_stream) {
+  return forward_impl(layer, x, T, out, workspace, workspace_bytes, taps, hip_stream, false);
+}
+
+mote_status mote_layer_forward_static(const mote_layer* layer, const void* x, int T, void* out,
+                                      const mote_taps* taps, void* hip_stream) {
+  if (!layer || T < 0) return MOTE_ERR_INVALID_ARG;
+  if (!layer_shape_ok(layer) || !batch_ok(layer, T)) return MOTE_ERR_UNSUPPORTED_SHAPE;
+  if (T == 0) return MOTE_OK;
+  // size check first: a batch that does not fit is refused before anything touches the device
+  if (carve(layer, T, nullptr).bytes > MOTE_STATIC_WORKSPACE_BYTES) return MOTE_ERR_WORKSPACE_TOO_SMALL;
+  void* ws = nullptr;
+  MOTE_HIP(static_scratch(&ws));
+  // Nothing in the array has to start at zero: the dispatch plan kernel of every forward zeroes
+  // the tile counters and the plane words it uses, everything else is written before it is read.
+  return forward_impl(layer, x, T, out, ws, MOTE_STATIC_WORKSPACE_BYTES, taps, hip_stream, true);
 }
 
 mote_status mote_stage_timing(int enable) {
