@@ -8,7 +8,8 @@ It shares no code, table or helper with the HIP kernels.
 Every function cites the passage of the MoTE paper (arXiv 2506.14435) it follows.
 Equation numbers count the displayed equations of Section 3 in order of appearance:
 Eq.1-2 block forward, Eq.3 gate softmax, Eq.4 MoE sum, Eq.5-6 ternary expert,
-Eq.7 Q_w, Eq.8 Q_a, Eq.9 alpha / beta, Eq.10 RoundClip.
+Eq.7 Q_w, Eq.8 Q_a, Eq.9 alpha / beta, Eq.10 RoundClip, Eq.11 language-modelling loss,
+Eq.12 load-balancing loss, Eq.13 total loss.
 
 Conventions
 -----------
@@ -24,12 +25,16 @@ Conventions
 * Readings of points the paper leaves open (rounding mode, evaluation order,
   zero scales, precision of h) are listed next to the function that takes them.
 
-Parity pins (tests/test_oracle_pins.py): every function below is pinned against
-something other than itself -- closed forms, hand-worked exact cases, library
-routines, brute force on tiny inputs, and the expert-memory figures of Table 1.
+Parity pins (tests/test_oracle_pins.py, tests/test_oracle_pins_next.py): every function
+below is pinned against something other than itself -- closed forms, hand-worked exact
+cases, library routines, brute force on tiny inputs, and the expert-memory figures of
+Table 1 and Table 3.
 The paper prints no worked numerical example of the layer, so the readings R1-R3
 (rounding mode, evaluation order, epsilon clamp) are pinned only against their
 written statement here: "parity unpinned" with respect to the authors' own code.
+The same holds for the readings taken beyond Section 3.1: the granularity and rounding
+of the RTN shared expert (Section 4.3 names the method only), RMSNorm as the LN of
+Eq.1-2, the count t_i in Eq.12, and sign(0) = +1 of the 1-bit quantiser.
 """
 from __future__ import annotations
 
@@ -238,11 +243,154 @@ def shared_expert(x_bf16, wg_bf16, wu_bf16, wd_bf16):
     return h_bits, y
 
 
+# ------------------------------------- post-training quantised shared expert (Section 4.3)
+def rtn_quantize(w_bf16: np.ndarray, n_bits: int):
+    """Round-to-nearest weight quantisation of a shared-expert matrix to INT8 or INT4
+    (Section 4.3 and Table 3: the shared expert is quantised with RTN).
+
+    The paper names the method only.  Reading: weight-only, symmetric, one scale per output
+    channel (row of W [out, in]), the vector-wise absmax scheme of the work it cites for RTN:
+        amax_n = max(max_c |W[n, c]|, 1e-5),  s_n = amax_n / qmax   (fp32 divide),
+        q[n, c] = RoundClip(W[n, c] / s_n, -qmax, qmax)             (fp32 divide, Eq.10's RoundClip),
+    qmax = 127 (INT8) or 7 (INT4); activations stay bf16; dequantised weight = s_n * q.
+    Returns (q int8 [N, K], s fp32 [N])."""
+    assert n_bits in (8, 4)
+    qmax = np.float32(127.0 if n_bits == 8 else 7.0)
+    w = bf16_to_f32(w_bf16)
+    amax = np.maximum(np.max(np.abs(w), axis=1, keepdims=True), EPS).astype(np.float32)
+    s = (amax / qmax).astype(np.float32)
+    q = round_clip((w / s).astype(np.float32), -float(qmax), float(qmax)).astype(np.int8)
+    return q, s[:, 0]
+
+
+def rtn_packed_bytes(n_rows: int, n_cols: int, n_bits: int) -> int:
+    """Bytes of the integer codes of an RTN matrix (the fp32 row scales, 4 * n_rows bytes,
+    come on top and are what Table 3's rounding hides)."""
+    return n_rows * n_cols * n_bits // 8
+
+
+def rtn_channel_order(n_cols: int, n_bits: int) -> np.ndarray:
+    """Storage order of the input channels inside a packed RTN row (this library's layout; the
+    paper fixes none).  order[p] is the channel stored at position p.
+
+    INT8: groups of 32 channels; position 16*g + 8*a + i holds channel 16*a + 8*g + i of the group
+    (g, a in {0,1}, i in 0..7).  INT4: groups of 64 channels; position 32*g + 8*s + i holds channel
+    16*s + 8*g + i of the group (g in {0,1}, s in 0..3, i in 0..7)."""
+    grp = 32 if n_bits == 8 else 64
+    assert n_cols % grp == 0
+    pos = np.arange(grp)
+    if n_bits == 8:
+        g, a, i = pos // 16, (pos // 8) % 2, pos % 8
+        ch = 16 * a + 8 * g + i
+    else:
+        g, s4, i = pos // 32, (pos // 8) % 4, pos % 8
+        ch = 16 * s4 + 8 * g + i
+    return (np.arange(0, n_cols, grp)[:, None] + ch[None, :]).reshape(-1)
+
+
+def pack_rtn(q: np.ndarray, n_bits: int) -> np.ndarray:
+    """RTN codes [N, K] int8 -> bytes, row-major over rows, channels in rtn_channel_order.
+    INT8: one two's-complement byte per weight.  INT4: two's-complement nibbles, the code at
+    storage position p of a row in byte p // 2, bits 4*(p % 2) .. 4*(p % 2) + 3."""
+    n_rows, n_cols = q.shape
+    qs = q[:, rtn_channel_order(n_cols, n_bits)]
+    if n_bits == 8:
+        return qs.astype(np.int8).view(np.uint8).reshape(-1).copy()
+    nib = (qs.astype(np.int16) & 0xF).astype(np.uint8)
+    return (nib[:, 0::2] | (nib[:, 1::2] << 4)).astype(np.uint8).reshape(-1)
+
+
+def unpack_rtn(raw: np.ndarray, n_rows: int, n_cols: int, n_bits: int) -> np.ndarray:
+    """Inverse of pack_rtn (plain loops)."""
+    raw = np.asarray(raw, dtype=np.uint8)
+    order = rtn_channel_order(n_cols, n_bits)
+    q = np.empty((n_rows, n_cols), dtype=np.int8)
+    for n in range(n_rows):
+        for p in range(n_cols):
+            if n_bits == 8:
+                v = int(raw[n * n_cols + p])
+                v = v - 256 if v >= 128 else v
+            else:
+                b = int(raw[(n * n_cols + p) // 2])
+                v = (b >> (4 * (p % 2))) & 0xF
+                v = v - 16 if v >= 8 else v
+            q[n, order[p]] = v
+    return q
+
+
+def shared_expert_rtn(x_bf16, qg, sg, qu, su, qd, sd):
+    """FFN(x) of Eq.2 with the three matrices replaced by their RTN dequantisations s_n * q
+    (exact in fp64); bf16 activations, fp64 accumulation, bf16 hidden activation, as in
+    shared_expert.  Returns (h_s bf16 bits [T,F], y_s fp64 [T,d])."""
+    x = bf16_to_f32(x_bf16).astype(np.float64)
+    wg = sg.astype(np.float64)[:, None] * qg.astype(np.float64)
+    wu = su.astype(np.float64)[:, None] * qu.astype(np.float64)
+    wd = sd.astype(np.float64)[:, None] * qd.astype(np.float64)
+    g = x @ wg.T
+    u = x @ wu.T
+    h = u * (g / (1.0 + np.exp(-g)))
+    h_bits = f32_to_bf16(h.astype(np.float32))
+    y = bf16_to_f32(h_bits).astype(np.float64) @ wd.T
+    return h_bits, y
+
+
+# ------------------------------------------------- normalisation of Eq.1-2 (block prologue)
+def rms_norm(x_bf16, gamma_bf16, eps: float) -> np.ndarray:
+    """LN(.) of Eq.1-2 for a base model whose normalisation is RMSNorm (the Qwen2.5 models the
+    paper up-cycles): y = x / sqrt(mean_c x^2 + eps) * gamma, in fp64, rounded once to bf16
+    (the normalised hidden state is a bf16 tensor like every activation between modules)."""
+    x = bf16_to_f32(x_bf16).astype(np.float64)
+    g = bf16_to_f32(gamma_bf16).astype(np.float64)
+    y = x / np.sqrt(np.mean(x * x, axis=-1, keepdims=True) + eps) * g
+    return f32_to_bf16(y.astype(np.float32))
+
+
+def layer_norm(x_bf16, gamma_bf16, beta_bf16, eps: float) -> np.ndarray:
+    """LN(.) of Eq.1-2 taken literally as layer normalisation: (x - mean) / sqrt(var + eps) *
+    gamma + beta over the channels (biased variance), fp64, rounded once to bf16."""
+    x = bf16_to_f32(x_bf16).astype(np.float64)
+    g = bf16_to_f32(gamma_bf16).astype(np.float64)
+    b = bf16_to_f32(beta_bf16).astype(np.float64)
+    mu = np.mean(x, axis=-1, keepdims=True)
+    var = np.mean((x - mu) ** 2, axis=-1, keepdims=True)
+    y = (x - mu) / np.sqrt(var + eps) * g + b
+    return f32_to_bf16(y.astype(np.float32))
+
+
+# ------------------------------------------------------- load balancing (Section 3.3, Eq.12)
+def load_balance(p: np.ndarray, idx: np.ndarray):
+    """Eq.12 as printed: L_balance = E / |X| * sum_i sum_x t_i * P(x)_i, with t_i the number of
+    tokens routed to expert i (over all k slots) and P(x)_i the gate softmax of Eq.3.
+
+    p [T, E] gate probabilities, idx [T, k] selected experts.
+    Returns (t int64 [E], s fp64 [E] = sum_x P(x)_i, loss fp64).  The loss of the work the paper
+    follows here divides by |X| once more (t_i as a fraction of the tokens): loss / T."""
+    n_tok, n_exp = p.shape
+    t = np.bincount(idx.reshape(-1), minlength=n_exp).astype(np.int64)
+    s = p.astype(np.float64).sum(axis=0)
+    loss = float(n_exp) / float(n_tok) * float(np.sum(t.astype(np.float64) * s))
+    return t, s, loss
+
+
+# ------------------------------------------------ 1-bit routed experts (Section 4.4, Table 5)
+def binarize(w: np.ndarray):
+    """The 1-bit weight quantiser of the routed-expert ablation (binary weight network of the
+    work cited there): W_b = alpha * sign(W), alpha = ||W||_1 / (n m) as in Eq.9.
+    Reading: sign(0) = +1 (a binary code has no zero); alpha clamped to >= 1e-5 like Q_w.
+    Returns (t int8 in {-1, +1}, alpha fp32)."""
+    w32 = np.asarray(w, dtype=np.float32)
+    alpha = absmean_scale(w32)
+    t = np.where(w32 < 0, -1, 1).astype(np.int8)
+    return t, alpha
+
+
 # ----------------------------------------------------------------- whole layer
 def layer_forward(x_bf16, w_router_bf16, bias, k, shared, experts, tokens=None):
     """MoE(x) + FFN(x) of Eq.2 (no residual, no LayerNorm: those are the outer terms).
 
-    shared  = (W_gate, W_up, W_down) bf16 bits, [F,d], [F,d], [d,F]
+    shared  = (W_gate, W_up, W_down) bf16 bits, [F,d], [F,d], [d,F]; or, for a post-training
+              quantised shared expert (Section 4.3), (q_gate, s_gate, q_up, s_up, q_down, s_down)
+              as returned by rtn_quantize
     experts = callable e -> (t_gate, a_gate, t_up, a_up, t_down, a_down) (ternary int8
               matrices [F,d], [F,d], [d,F] with their fp32 absmean scales), called
               only for experts that receive at least one of the evaluated tokens
@@ -280,11 +428,31 @@ def layer_forward(x_bf16, w_router_bf16, bias, k, shared, experts, tokens=None):
         acc_gate[ii, jj], acc_up[ii, jj], h[ii, jj] = r["acc_gate"], r["acc_up"], r["h"]
         q_h[ii, jj], beta_h[ii, jj] = r["q_h"], r["beta_h"]
         acc_down[ii, jj], y[ii, jj] = r["acc_down"], r["y"]
-    h_s, y_s = shared_expert(xs_bits, *shared)
+    h_s, y_s = shared_expert(xs_bits, *shared) if len(shared) == 3 else shared_expert_rtn(xs_bits, *shared)
     # Eq.2 + Eq.4: only the k selected terms of the sum are non-zero (sparse gate).
     moe = np.einsum("tj,tjc->tc", w[sel].astype(np.float64), y.astype(np.float64))
     out_f64 = y_s + moe
     out.update(acc_gate=acc_gate, acc_up=acc_up, h=h, q_h=q_h, beta_h=beta_h, acc_down=acc_down,
-               y=y, h_s=h_s, y_s=y_s.astype(np.float32), out_f32=out_f64.astype(np.float32),
+               y=y, h_s=h_s, y_s=y_s.astype(np.float32), out_f64=out_f64, out_f32=out_f64.astype(np.float32),
                out_bf16=f32_to_bf16(out_f64.astype(np.float32)))
+    return out
+
+
+def block_forward(x_a_bf16, norm, w_router_bf16, bias, k, shared, experts, tokens=None):
+    """The MoE half of a block, Eq.2: x_l = x^a + MoE(LN(x^a)) + FFN(LN(x^a)).
+
+    norm = ("rms", gamma, eps) or ("layer", gamma, beta, eps); the other arguments as in
+    layer_forward.  The normalised hidden state is a bf16 tensor; the residual x^a enters the
+    fp64 sum unrounded and the result is rounded once to bf16.
+    Returns layer_forward's dict for the normalised input plus xn (bf16 bits, all tokens) and
+    block_f32 / block_bf16 for the evaluated tokens."""
+    if norm[0] == "rms":
+        xn = rms_norm(x_a_bf16, norm[1], norm[2])
+    elif norm[0] == "layer":
+        xn = layer_norm(x_a_bf16, norm[1], norm[2], norm[3])
+    else:
+        raise ValueError(norm[0])
+    out = layer_forward(xn, w_router_bf16, bias, k, shared, experts, tokens=tokens)
+    blk = bf16_to_f32(x_a_bf16[out["tokens"]]).astype(np.float64) + out["out_f64"]
+    out.update(xn=xn, block_f32=blk.astype(np.float32), block_bf16=f32_to_bf16(blk.astype(np.float32)))
     return out
