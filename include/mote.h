@@ -79,6 +79,33 @@ size_t mote_packed_bytes(int64_t n_out, int64_t n_in);
 mote_status mote_pack_ternary(const void* w, int w_dtype, int64_t n_out, int64_t n_in,
                               uint32_t* packed, float* alpha, void* hip_stream);
 
+/* The 1-bit weight quantiser of the routed-expert ablation (Section 4.4, Table 5: binary weight
+ * network): t = sign(W) with sign(0) = +1, alpha as above.  The codes t + 1 in {0, 2} use the same
+ * 2-bit container, so binary experts run through mote_layer_forward unchanged (a 1-bit container
+ * is not provided).  Arguments and limits as mote_pack_ternary. */
+mote_status mote_pack_binary(const void* w, int w_dtype, int64_t n_out, int64_t n_in,
+                             uint32_t* packed, float* alpha, void* hip_stream);
+
+/* ---------------------------------------------------------------------------------------
+ * Round-to-nearest INT8 / INT4 quantisation of a shared-expert matrix (Section 4.3, Table 3).
+ * The paper names the method only; this library's reading: weight-only, symmetric, one scale
+ * per output channel,
+ *   s_n = max(max_c |W[n,c]|, 1e-5) / qmax            (fp32 divide; qmax = 127 or 7)
+ *   q   = clip(round_half_even(W[n,c] / s_n), -qmax, qmax)   (fp32 divide)
+ * Storage: row-major over output rows, n_in*bits/8 bytes per row, two's-complement bytes (INT8)
+ * or nibbles (INT4; position p of a row in byte p/2, bits 4*(p%2)..+3), channels permuted inside
+ * groups: INT8 groups of 32, position 16g + 8a + i holds channel 16a + 8g + i; INT4 groups of 64,
+ * position 32g + 8s + i holds channel 16s + 8g + i (g, a in {0,1}, s in 0..3, i in 0..7), so that
+ * the 16 bytes a lane reads are its operands of consecutive 32x32x16 MFMAs.
+ *
+ * w      in : device bf16 [n_out, n_in]
+ * packed out: device, mote_rtn_packed_bytes(n_out, n_in, bits) bytes
+ * scales out: device fp32 [n_out]
+ * Limits: bits in {8, 4}; n_out % 32 == 0, n_in % 128 == 0. */
+size_t mote_rtn_packed_bytes(int64_t n_out, int64_t n_in, int bits);
+mote_status mote_pack_rtn(const void* w, int64_t n_out, int64_t n_in, int bits, void* packed,
+                          float* scales, void* hip_stream);
+
 /* ---------------------------------------------------------------------------------------
  * Router: gate softmax of Eq.3 and GShard-style top-k selection (Section 3.1; Section 4.1
  * uses top-1 routing).
@@ -100,6 +127,17 @@ mote_status mote_router_topk(const void* x, const void* w_router, const float* r
                              int T, int d, int E, int k, int32_t* topk_idx, float* topk_p,
                              int32_t* expert_counts, void* hip_stream);
 
+/* Router plus the load-balancing statistic of Section 3.3 (Eq.12, following Switch
+ * Transformers):  loss = E/|X| * sum_i t_i * sum_x P(x)_i, t_i = number of (token, slot) pairs
+ * routed to expert i, exactly as printed (the cited work divides by |X| once more: loss / T).
+ * Outputs beyond mote_router_topk (all required): expert_counts int32 [E] = t_i, gate_p fp32 [T, E]
+ * = the whole gate distribution, gate_p_sum fp32 [E] = sum_x P(x)_i (fp64 sums in a fixed order),
+ * loss fp32 [1].  T >= 1. */
+mote_status mote_router_balance(const void* x, const void* w_router, const float* router_bias,
+                                int T, int d, int E, int k, int32_t* topk_idx, float* topk_p,
+                                int32_t* expert_counts, float* gate_p, float* gate_p_sum, float* loss,
+                                void* hip_stream);
+
 /* ---------------------------------------------------------------------------------------
  * Whole layer.
  */
@@ -114,6 +152,13 @@ typedef struct {
   const uint32_t* wt_up;       /* E matrices [F_r, d]                                     */
   const uint32_t* wt_down;     /* E matrices [d, F_r]                                     */
   const float* alpha;          /* fp32 [E, 3]: (gate, up, down) scale of each expert      */
+  /* Post-training quantised shared expert (Section 4.3, Table 3).  shared_bits == 0: ws_* are bf16
+   * (the paper's layer).  8 or 4: ws_* point at the packed codes written by mote_pack_rtn and
+   * ss_* at their fp32 row scales ([F_s], [F_s], [d]); activations stay bf16. */
+  int shared_bits;
+  const float* ss_gate;
+  const float* ss_up;
+  const float* ss_down;
 } mote_layer;
 
 /* Optional copies of the intermediates, for stage-wise parity checks.  Every member may be
@@ -136,6 +181,7 @@ typedef struct {
   uint16_t* h_s;       /* [T, F_s] bf16 hidden activation of the shared expert            */
   float* y_s;          /* [T, d]  shared expert output                                    */
   float* out_f32;      /* [T, d]  layer output before the final bf16 rounding             */
+  uint16_t* xn;        /* [T, d]  LN(x^a), written by mote_block_forward only             */
 } mote_taps;
 
 /* Bytes of scratch that serve mote_layer_forward for every batch of 1..T_max tokens (0 on a bad
@@ -153,6 +199,25 @@ size_t mote_layer_workspace_bytes(const mote_layer* layer, int T_max);
  * Limits: d, F_s, F_r % 128 == 0; 1 <= E <= 64; 1 <= k <= min(E, 8); 0 <= T; T*k < 2^24;
  *         T*d, T*F_s and T*k*F_r below 2^31 (32-bit byte offsets inside the kernels). */
 mote_status mote_layer_forward(const mote_layer* layer, const void* x, int T, void* out,
+                               void* workspace, size_t workspace_bytes, const mote_taps* taps,
+                               void* hip_stream);
+
+/* The MoE half of a block, Eq.2:  out = x^a + MoE(LN(x^a)) + FFN(LN(x^a)).
+ * LN is the base model's normalisation: RMSNorm for the Qwen2.5 models the paper up-cycles
+ * (y = x / sqrt(mean x^2 + eps) * gamma), or layer normalisation taken literally
+ * (y = (x - mean) / sqrt(var + eps) * gamma + beta, biased variance).  Statistics in fp64; LN(x^a)
+ * is rounded once to bf16 (it is the bf16 hidden state the layer of Section 3.1 acts on); the
+ * residual x^a is added in fp32 before the single bf16 rounding of the output.
+ * gamma, beta: device bf16 [d] (beta only for MOTE_NORM_LAYER).  Everything else as in
+ * mote_layer_forward, including the workspace size. */
+enum { MOTE_NORM_RMS = 1, MOTE_NORM_LAYER = 2 };
+typedef struct {
+  int kind;            /* MOTE_NORM_RMS or MOTE_NORM_LAYER */
+  const void* gamma;   /* bf16 [d] */
+  const void* beta;    /* bf16 [d], MOTE_NORM_LAYER only */
+  double eps;
+} mote_norm;
+mote_status mote_block_forward(const mote_layer* layer, const mote_norm* norm, const void* x_a, int T, void* out,
                                void* workspace, size_t workspace_bytes, const mote_taps* taps,
                                void* hip_stream);
 

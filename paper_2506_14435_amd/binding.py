@@ -21,6 +21,7 @@ STAGE_NAMES = ("router_quant", "dispatch", "routed_gate_up", "quant_h", "routed_
 # every symbol include/mote.h declares
 EXPORTS = ("mote_status_string", "mote_version", "mote_packed_bytes", "mote_pack_ternary",
            "mote_router_topk", "mote_layer_workspace_bytes", "mote_layer_forward", "mote_layer_forward_static",
+           "mote_block_forward", "mote_router_balance", "mote_pack_binary", "mote_rtn_packed_bytes", "mote_pack_rtn",
            "mote_stage_timing", "mote_stage_times", "mote_tuning_set", "mote_calib_copy")
 KNOBS = ("no_fork", "fork_min_log2", "event_fence", "quant_wide", "routed_variant", "routed_down_variant",
          "shared_variant", "group_m", "dynamic_rounds", "decode_variant", "router_token_blocks")
@@ -36,11 +37,19 @@ class MoteLayerStruct(ctypes.Structure):
                 ("w_router", c_void_p), ("router_bias", c_void_p),
                 ("ws_gate", c_void_p), ("ws_up", c_void_p), ("ws_down", c_void_p),
                 ("wt_gate", c_void_p), ("wt_up", c_void_p), ("wt_down", c_void_p),
-                ("alpha", c_void_p)]
+                ("alpha", c_void_p),
+                ("shared_bits", c_int), ("ss_gate", c_void_p), ("ss_up", c_void_p), ("ss_down", c_void_p)]
+
+
+class MoteNormStruct(ctypes.Structure):
+    _fields_ = [("kind", c_int), ("gamma", c_void_p), ("beta", c_void_p), ("eps", ctypes.c_double)]
+
+
+NORM_RMS, NORM_LAYER = 1, 2
 
 
 TAP_FIELDS = ("topk_idx", "topk_p", "counts", "row_of", "tok_of", "q_x", "beta_x", "acc_gate",
-              "acc_up", "h", "q_h", "beta_h", "acc_down", "h_s", "y_s", "out_f32")
+              "acc_up", "h", "q_h", "beta_h", "acc_down", "h_s", "y_s", "out_f32", "xn")
 
 
 class MoteTapsStruct(ctypes.Structure):
@@ -74,6 +83,18 @@ def load_library() -> ctypes.CDLL:
     lib.mote_layer_forward.restype = c_int
     lib.mote_layer_forward.argtypes = [POINTER(MoteLayerStruct), c_void_p, c_int, c_void_p, c_void_p,
                                        c_size_t, POINTER(MoteTapsStruct), c_void_p]
+    lib.mote_block_forward.restype = c_int
+    lib.mote_block_forward.argtypes = [POINTER(MoteLayerStruct), POINTER(MoteNormStruct), c_void_p, c_int, c_void_p,
+                                       c_void_p, c_size_t, POINTER(MoteTapsStruct), c_void_p]
+    lib.mote_router_balance.restype = c_int
+    lib.mote_router_balance.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int,
+                                        c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
+    lib.mote_pack_binary.restype = c_int
+    lib.mote_pack_binary.argtypes = [c_void_p, c_int, c_int64, c_int64, c_void_p, c_void_p, c_void_p]
+    lib.mote_rtn_packed_bytes.restype = c_size_t
+    lib.mote_rtn_packed_bytes.argtypes = [c_int64, c_int64, c_int]
+    lib.mote_pack_rtn.restype = c_int
+    lib.mote_pack_rtn.argtypes = [c_void_p, c_int64, c_int64, c_int, c_void_p, c_void_p, c_void_p]
     lib.mote_layer_forward_static.restype = c_int
     lib.mote_layer_forward_static.argtypes = [POINTER(MoteLayerStruct), c_void_p, c_int, c_void_p,
                                               POINTER(MoteTapsStruct), c_void_p]
@@ -121,8 +142,9 @@ def mote_packed_bytes(n_out: int, n_in: int) -> int:
     return load_library().mote_packed_bytes(n_out, n_in)
 
 
-def mote_pack_ternary(w: torch.Tensor, packed: torch.Tensor = None, alpha: torch.Tensor = None):
-    """w [n_out, n_in] fp32 or bf16 device tensor -> (packed int32 [n_out*n_in/16], alpha fp32 [1])."""
+def mote_pack_ternary(w: torch.Tensor, packed: torch.Tensor = None, alpha: torch.Tensor = None, binary: bool = False):
+    """w [n_out, n_in] fp32 or bf16 device tensor -> (packed int32 [n_out*n_in/16], alpha fp32 [1]).
+    binary=True calls mote_pack_binary (the 1-bit quantiser in the same 2-bit container)."""
     lib = load_library()
     if w.dtype == torch.float32:
         dt = MOTE_DTYPE_F32
@@ -136,9 +158,50 @@ def mote_pack_ternary(w: torch.Tensor, packed: torch.Tensor = None, alpha: torch
         packed = torch.empty(max(n_out * n_in // 16, 1), dtype=torch.int32, device=w.device)
     if alpha is None:
         alpha = torch.empty(1, dtype=torch.float32, device=w.device)
-    _check(lib.mote_pack_ternary(_ptr(w), dt, n_out, n_in, _ptr(packed), _ptr(alpha), _stream()),
-           "mote_pack_ternary")
+    fn = lib.mote_pack_binary if binary else lib.mote_pack_ternary
+    _check(fn(_ptr(w), dt, n_out, n_in, _ptr(packed), _ptr(alpha), _stream()),
+           "mote_pack_binary" if binary else "mote_pack_ternary")
     return packed, alpha
+
+
+def mote_rtn_packed_bytes(n_out: int, n_in: int, bits: int) -> int:
+    return load_library().mote_rtn_packed_bytes(n_out, n_in, bits)
+
+
+def mote_pack_rtn(w: torch.Tensor, bits: int):
+    """w [n_out, n_in] bf16 device tensor -> (packed uint8 [n_out*n_in*bits/8], scales fp32 [n_out])."""
+    lib = load_library()
+    _dev(w, torch.bfloat16, "w")
+    n_out, n_in = w.shape
+    nbytes = lib.mote_rtn_packed_bytes(n_out, n_in, bits)
+    if nbytes == 0:
+        raise MoteError("mote_pack_rtn: bits must be 8 or 4")
+    packed = torch.empty(nbytes, dtype=torch.uint8, device=w.device)
+    scales = torch.empty(n_out, dtype=torch.float32, device=w.device)
+    _check(lib.mote_pack_rtn(_ptr(w), n_out, n_in, bits, _ptr(packed), _ptr(scales), _stream()), "mote_pack_rtn")
+    return packed, scales
+
+
+def mote_router_balance(x: torch.Tensor, w_router: torch.Tensor, k: int, router_bias: torch.Tensor = None):
+    """Router plus Eq.12: returns (topk_idx, topk_p, counts, gate_p [T,E], gate_p_sum [E], loss [1])."""
+    lib = load_library()
+    _dev(x, torch.bfloat16, "x")
+    _dev(w_router, torch.bfloat16, "w_router")
+    if router_bias is not None:
+        _dev(router_bias, torch.float32, "router_bias")
+    n_tok, d = x.shape
+    n_exp = w_router.shape[1]
+    dev = x.device
+    idx = torch.empty(n_tok, k, dtype=torch.int32, device=dev)
+    p = torch.empty(n_tok, k, dtype=torch.float32, device=dev)
+    counts = torch.zeros(n_exp, dtype=torch.int32, device=dev)
+    gate_p = torch.empty(n_tok, n_exp, dtype=torch.float32, device=dev)
+    gate_sum = torch.empty(n_exp, dtype=torch.float32, device=dev)
+    loss = torch.empty(1, dtype=torch.float32, device=dev)
+    _check(lib.mote_router_balance(_ptr(x), _ptr(w_router), _ptr(router_bias), n_tok, d, n_exp, k, _ptr(idx), _ptr(p),
+                                   _ptr(counts), _ptr(gate_p), _ptr(gate_sum), _ptr(loss), _stream()),
+           "mote_router_balance")
+    return idx, p, counts, gate_p, gate_sum, loss
 
 
 def mote_router_topk(x: torch.Tensor, w_router: torch.Tensor, k: int, router_bias: torch.Tensor = None,
@@ -163,11 +226,14 @@ class MoteLayer:
     """Holds the device tensors of one layer and the C struct that points at them."""
 
     def __init__(self, w_router, ws_gate, ws_up, ws_down, wt_gate, wt_up, wt_down, alpha, top_k,
-                 router_bias=None):
+                 router_bias=None, shared_bits=0, shared_scales=None):
+        """shared_bits 0: ws_* are bf16 matrices.  8 / 4: ws_* are the packed uint8 codes of
+        mote_pack_rtn and shared_scales = (s_gate [F_s], s_up [F_s], s_down [d]) fp32."""
+        sdt = torch.bfloat16 if shared_bits == 0 else torch.uint8
         self.tensors = dict(w_router=_dev(w_router, torch.bfloat16, "w_router"),
-                            ws_gate=_dev(ws_gate, torch.bfloat16, "ws_gate"),
-                            ws_up=_dev(ws_up, torch.bfloat16, "ws_up"),
-                            ws_down=_dev(ws_down, torch.bfloat16, "ws_down"),
+                            ws_gate=_dev(ws_gate, sdt, "ws_gate"),
+                            ws_up=_dev(ws_up, sdt, "ws_up"),
+                            ws_down=_dev(ws_down, sdt, "ws_down"),
                             wt_gate=_dev(wt_gate, torch.int32, "wt_gate"),
                             wt_up=_dev(wt_up, torch.int32, "wt_up"),
                             wt_down=_dev(wt_down, torch.int32, "wt_down"),
@@ -175,7 +241,15 @@ class MoteLayer:
         if router_bias is not None:
             self.tensors["router_bias"] = _dev(router_bias, torch.float32, "router_bias")
         d, n_exp = w_router.shape
-        f_s = ws_gate.shape[0]
+        if shared_bits == 0:
+            f_s = ws_gate.shape[0]
+            ss = (None, None, None)
+        else:
+            ss = tuple(_dev(t, torch.float32, "shared_scales") for t in shared_scales)
+            f_s = ss[0].numel()
+            if ws_gate.numel() != f_s * d * shared_bits // 8 or ss[2].numel() != d:
+                raise MoteError("packed shared expert and its scales disagree in size")
+            self.tensors.update(ss_gate=ss[0], ss_up=ss[1], ss_down=ss[2])
         f_r = wt_gate.numel() * 16 // (n_exp * d)
         self.d_model, self.d_ff_shared, self.d_ff_routed, self.n_experts, self.top_k = d, f_s, f_r, n_exp, top_k
         if tuple(alpha.shape) != (n_exp, 3):
@@ -187,7 +261,8 @@ class MoteLayer:
                                       router_bias.data_ptr() if router_bias is not None else None,
                                       ws_gate.data_ptr(), ws_up.data_ptr(), ws_down.data_ptr(),
                                       wt_gate.data_ptr(), wt_up.data_ptr(), wt_down.data_ptr(),
-                                      alpha.data_ptr())
+                                      alpha.data_ptr(), shared_bits,
+                                      *[t.data_ptr() if t is not None else None for t in ss])
         self._workspace = None
 
     def workspace_bytes(self, n_tokens: int) -> int:
@@ -214,7 +289,7 @@ def alloc_taps(layer: MoteLayer, n_tokens: int, names=TAP_FIELDS):
                 acc_gate=((r, fr), torch.int32), acc_up=((r, fr), torch.int32), h=((r, fr), torch.bfloat16),
                 q_h=((r, fr), torch.int8), beta_h=((r,), torch.float32), acc_down=((r, d), torch.int32),
                 h_s=((n_tokens, fs), torch.bfloat16), y_s=((n_tokens, d), torch.float32),
-                out_f32=((n_tokens, d), torch.float32))
+                out_f32=((n_tokens, d), torch.float32), xn=((n_tokens, d), torch.bfloat16))
     return {n: torch.empty(spec[n][0], dtype=spec[n][1], device=dev) for n in names}
 
 
@@ -237,6 +312,33 @@ def mote_layer_forward(layer: MoteLayer, x: torch.Tensor, out: torch.Tensor = No
     _check(lib.mote_layer_forward(ctypes.byref(layer.struct), _ptr(x), n_tok, _ptr(out), _ptr(workspace),
                                   workspace.numel(), ctypes.byref(ts) if ts is not None else None, _stream()),
            "mote_layer_forward")
+    return out
+
+
+def mote_block_forward(layer: MoteLayer, x_a: torch.Tensor, gamma: torch.Tensor, beta: torch.Tensor = None,
+                       eps: float = 1e-6, out: torch.Tensor = None, taps: dict = None,
+                       workspace: torch.Tensor = None) -> torch.Tensor:
+    """out = x_a + MoE(LN(x_a)) + FFN(LN(x_a)) (Eq.2); RMSNorm when beta is None, else layer normalisation."""
+    lib = load_library()
+    _dev(x_a, torch.bfloat16, "x_a")
+    _dev(gamma, torch.bfloat16, "gamma")
+    if beta is not None:
+        _dev(beta, torch.bfloat16, "beta")
+    n_tok = x_a.shape[0]
+    if x_a.shape[1] != layer.d_model or gamma.numel() != layer.d_model:
+        raise MoteError("x_a / gamma have the wrong width")
+    if out is None:
+        out = torch.empty_like(x_a)
+    if workspace is None:
+        workspace = layer.workspace(max(n_tok, 1))
+    norm = MoteNormStruct(NORM_RMS if beta is None else NORM_LAYER, gamma.data_ptr(),
+                          beta.data_ptr() if beta is not None else None, float(eps))
+    ts = None
+    if taps is not None:
+        ts = MoteTapsStruct(*[taps[n].data_ptr() if n in taps else None for n in TAP_FIELDS])
+    _check(lib.mote_block_forward(ctypes.byref(layer.struct), ctypes.byref(norm), _ptr(x_a), n_tok, _ptr(out),
+                                  _ptr(workspace), workspace.numel(), ctypes.byref(ts) if ts is not None else None,
+                                  _stream()), "mote_block_forward")
     return out
 
 

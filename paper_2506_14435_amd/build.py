@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmote.so")
 SOURCES = ["mote_api.hip", "pack_ternary.hip", "router.hip", "ternary_gemm.hip", "shared_ffn.hip", "decode_gemm.hip",
-           "elementwise.hip"]
+           "elementwise.hip", "block_extras.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fhip-fp32-correctly-rounded-divide-sqrt",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
@@ -30,7 +30,7 @@ def build(verbose: bool = False, extra_flags=()) -> str:
     """Compiles every kernel translation unit and links libmote.so.  Always recompiles."""
     obj_dir = os.path.join(HERE, "_build")
     os.makedirs(obj_dir, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(6, os.cpu_count() or 1)) as ex:
+    with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as ex:
         results = list(ex.map(lambda s: _compile(s, obj_dir, list(extra_flags)), SOURCES))
     objs = [o for o, _ in results]
     if verbose:

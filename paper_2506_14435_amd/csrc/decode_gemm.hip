@@ -730,6 +730,197 @@ __global__ __launch_bounds__(64) void shared_wave_kernel(SharedDecodeArgs a, int
   }
 }
 
+// ---------------------------------------------------------- quantised shared expert (decode)
+// The shared expert with RTN INT8 / INT4 weights (Section 4.3): same wave-streaming scheme as
+// shared_wave_kernel, K steps of 64 channels, bf16 token rows, but a weight row of a step is 64
+// (INT8) or 32 (INT4) bytes of two's-complement codes in the packed channel order, so a
+// 32-row fragment is two / one 1-KiB loads per matrix instead of four.  A lane (row r, K half g)
+// reads 16 bytes of its row: INT8 the operands of two MFMAs (K sub-steps 2j, 2j+1), INT4 of all
+// four; the codes are sign-extended, converted to fp32 and cut to bf16 (exact: |q| <= 127).  The
+// row scales multiply the fp32 sums in the epilogue, so the arithmetic is s_n * sum_c q[n,c] x[c].
+struct SharedQDecodeArgs {
+  const uint16_t* act;          // [M, K] bf16
+  const unsigned char* w0;      // packed codes [N, K*BITS/8] (gate / down)
+  const unsigned char* w1;      // (up)
+  const float* s0;              // row scales [N]
+  const float* s1;
+  int M, N, K;
+  uint16_t* h_out;
+  float* y_out;
+  int64_t plane_stride;
+};
+
+template <int MODE, int BITS, int AL>
+struct SharedQWaveCfg {
+  static constexpr int NMAT = MODE == 0 ? 2 : 1;
+  static constexpr int MFR = AL > 4 ? 2 : 1;
+  static constexpr int WL = BITS == 8 ? 2 : 1;               // 1-KiB loads per matrix and K step
+  static constexpr int W_LOADS = NMAT * WL, L = W_LOADS + AL;
+  static constexpr int A_OFF = W_LOADS * 1024;
+  static constexpr int SLOT = L * 1024;
+  static constexpr int TAIL = (MFR * 4 - AL) * 1024;
+  static constexpr int S_LDS = (65536 - TAIL) / SLOT, S_CNT = 2 + 63 / L;
+  static constexpr int S0 = S_LDS < S_CNT ? S_LDS : S_CNT;
+  static constexpr int S = S0 > 12 ? 12 : S0;               // 12 steps in flight are plenty
+  static constexpr int LDS = S * SLOT + TAIL;
+};
+
+// eight consecutive two's-complement codes (bytes of lo/hi, or nibbles of lo) -> bf16x8
+template <int BITS>
+__device__ __forceinline__ bf16x8 codes_to_bf16(uint32_t lo, uint32_t hi) {
+  float f[8];
+  if constexpr (BITS == 8) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      f[i] = static_cast<float>(static_cast<int>(lo << (24 - 8 * i)) >> 24);
+      f[4 + i] = static_cast<float>(static_cast<int>(hi << (24 - 8 * i)) >> 24);
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) f[i] = static_cast<float>(static_cast<int>(lo << (28 - 4 * i)) >> 28);
+  }
+  union { uint32_t u[4]; bf16x8 v; } r;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)   // small integers: the upper halves of the fp32 patterns are the bf16 values
+    r.u[i] = (__float_as_uint(f[2 * i]) >> 16) | (__float_as_uint(f[2 * i + 1]) & 0xFFFF0000u);
+  return r.v;
+}
+
+template <int MODE, int BITS, int AL>
+__global__ __launch_bounds__(64) void shared_qwave_kernel(SharedQDecodeArgs a, int kc_count, int steps_per_plane) {
+  using Cfg = SharedQWaveCfg<MODE, BITS, AL>;
+  constexpr int NMAT = Cfg::NMAT, MFR = Cfg::MFR, L = Cfg::L, SLOT = Cfg::SLOT, S = Cfg::S, A_LOADS = AL, WL = Cfg::WL;
+  constexpr int WROW = BITS == 8 ? 64 : 32;        // bytes of a weight row per K step
+  constexpr int kBufferFlags = 0x00020000;
+  extern __shared__ __attribute__((aligned(16))) unsigned char s_ring[];
+  const int M = a.M, N = a.N, K = a.K, KT = K >> 6;
+  const int lane = threadIdx.x, r32 = lane & 31, g = lane >> 5;
+  const int kc = MODE == 1 ? blockIdx.x % kc_count : 0;
+  const int quads = N >> 2;
+  const int c0 = MODE == 1 ? (blockIdx.x / kc_count) * 32 : static_cast<int>(static_cast<int64_t>(blockIdx.x) * quads / gridDim.x) * 4;
+  const int c1 = MODE == 1 ? c0 + 32 : static_cast<int>(static_cast<int64_t>(blockIdx.x + 1) * quads / gridDim.x) * 4;
+  const int step0 = kc * steps_per_plane;
+  const int nsteps = min(steps_per_plane, KT - step0);
+  const uint32_t lds0 = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) unsigned char*)s_ring);
+  auto make_rsrc = [&](const void* base, int64_t bytes) {
+    const uint64_t p = reinterpret_cast<uint64_t>(base);
+    v4i r;
+    r.x = static_cast<int>(static_cast<uint32_t>(p));
+    r.y = static_cast<int>(static_cast<uint32_t>(p >> 32) & 0xFFFFu);
+    r.z = static_cast<int>(bytes);
+    r.w = kBufferFlags;
+    return r;
+  };
+  const int64_t wrow_bytes = static_cast<int64_t>(K) * BITS / 8;
+  const v4i rsrc_a = make_rsrc(a.act, static_cast<int64_t>(M) * K * 2);
+  const v4i rsrc_w0 = make_rsrc(a.w0, static_cast<int64_t>(N) * wrow_bytes);
+  const v4i rsrc_w1 = make_rsrc(NMAT == 2 ? a.w1 : a.w0, static_cast<int64_t>(N) * wrow_bytes);
+  // weight load i of a fragment covers 1024 / WROW rows: lane l lands at LDS byte 16 l of the load,
+  // i.e. row l / (WROW/16), chunk l % (WROW/16) -- the fragment sits row-major in LDS
+  constexpr int LPR = WROW / 16, RPL = 64 / LPR;   // lanes per row, rows per load
+  uint32_t w_voff[WL];
+#pragma unroll
+  for (int i = 0; i < WL; ++i) {
+    const int wrow = c0 + RPL * i + lane / LPR;
+    w_voff[i] = wrow < c1 ? static_cast<uint32_t>(wrow) * static_cast<uint32_t>(wrow_bytes) + step0 * WROW + (lane % LPR) * 16
+                          : 0x80000000u;   // out of range: nothing is fetched
+  }
+  const int ld_row = lane >> 3;
+  uint32_t a_voff[A_LOADS];
+#pragma unroll
+  for (int i = 0; i < A_LOADS; ++i) {
+    const int chunk = (lane & 7) ^ ((4 * i + (ld_row >> 1)) & 7);
+    a_voff[i] = static_cast<uint32_t>(min(8 * i + ld_row, M - 1)) * static_cast<uint32_t>(K) * 2u + step0 * 128 + chunk * 16;
+  }
+#define MOTE_DMA(lds_, voff_, rsrc_, soff_)                                                        \
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"           \
+               :: "s"(lds_), "v"(voff_), "s"(rsrc_), "s"(soff_) : "memory")
+#define MOTE_ISSUE(step_, slot_)                                                                   \
+  {                                                                                                \
+    const uint32_t base_ = lds0 + (slot_) * SLOT;                                                  \
+    _Pragma("unroll") for (int i = 0; i < WL; ++i) MOTE_DMA(base_ + i * 1024, w_voff[i], rsrc_w0, (step_) * WROW);  \
+    if constexpr (NMAT == 2) {                                                                     \
+      _Pragma("unroll") for (int i = 0; i < WL; ++i) MOTE_DMA(base_ + (WL + i) * 1024, w_voff[i], rsrc_w1, (step_) * WROW);  \
+    }                                                                                              \
+    _Pragma("unroll") for (int i = 0; i < A_LOADS; ++i)                                            \
+      MOTE_DMA(base_ + Cfg::A_OFF + i * 1024, a_voff[i], rsrc_a, (step_) * 128);                  \
+  }
+
+  v16f acc[NMAT][MFR];
+#pragma unroll
+  for (int m = 0; m < NMAT; ++m)
+#pragma unroll
+    for (int f = 0; f < MFR; ++f)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[m][f][v] = 0.0f;
+
+  for (int j = 0; j < S - 1 && j < nsteps; ++j) MOTE_ISSUE(j, j);
+  const int rd = r32 * 128, sw = (r32 >> 1) & 7;
+  int slot = 0, slot_fill = S - 1;
+  for (int j = 0; j < nsteps; ++j) {
+    wait_steps_ahead<L, S - 2>(nsteps - 1 - j);
+    const unsigned char* const st = s_ring + slot * SLOT;
+    // this lane's codes of the step: INT8 two 16-byte reads per matrix (K sub-steps 0,1 and 2,3), INT4 one
+    u4 wq[NMAT][WL];
+#pragma unroll
+    for (int m = 0; m < NMAT; ++m)
+#pragma unroll
+      for (int i = 0; i < WL; ++i)
+        wq[m][i] = *reinterpret_cast<const u4*>(st + m * WL * 1024 + r32 * WROW + (i * 2 + g) * 16);
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4) {
+      const int co = ((2 * s4 + g) ^ sw) << 4;
+      bf16x8 af[MFR];
+#pragma unroll
+      for (int f = 0; f < MFR; ++f) af[f] = *reinterpret_cast<const bf16x8*>(st + Cfg::A_OFF + f * 4096 + rd + co);
+#pragma unroll
+      for (int m = 0; m < NMAT; ++m) {
+        bf16x8 wf;
+        if constexpr (BITS == 8) {
+          const u4 q = wq[m][s4 >> 1];
+          wf = (s4 & 1) ? codes_to_bf16<8>(q.z, q.w) : codes_to_bf16<8>(q.x, q.y);
+        } else {
+          const u4 q = wq[m][0];
+          wf = codes_to_bf16<4>(s4 == 0 ? q.x : s4 == 1 ? q.y : s4 == 2 ? q.z : q.w, 0u);
+        }
+#pragma unroll
+        for (int f = 0; f < MFR; ++f) acc[m][f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, af[f], acc[m][f], 0, 0, 0);
+      }
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    if (j + S - 1 < nsteps) MOTE_ISSUE(j + S - 1, slot_fill);
+    slot_fill = slot;
+    slot = slot + 1 == S ? 0 : slot + 1;
+  }
+#undef MOTE_DMA
+#undef MOTE_ISSUE
+
+#pragma unroll
+  for (int f = 0; f < MFR; ++f) {
+    const int row = f * 32 + r32;
+    if (row >= M) continue;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int ch = c0 + 8 * q + 4 * g;
+      if (ch >= c1) continue;
+      const int64_t o = static_cast<int64_t>(row) * N + ch;
+      const float4 sc0 = *reinterpret_cast<const float4*>(a.s0 + ch);
+      if constexpr (MODE == 0) {
+        const float4 sc1 = *reinterpret_cast<const float4*>(a.s1 + ch);
+        const float gv[4] = {acc[0][f][4 * q] * sc0.x, acc[0][f][4 * q + 1] * sc0.y, acc[0][f][4 * q + 2] * sc0.z, acc[0][f][4 * q + 3] * sc0.w};
+        const float uv[4] = {acc[1][f][4 * q] * sc1.x, acc[1][f][4 * q + 1] * sc1.y, acc[1][f][4 * q + 2] * sc1.z, acc[1][f][4 * q + 3] * sc1.w};
+        uint2 packed;
+        packed.x = cvt_pk_bf16(uv[0] * silu_fast(gv[0]), uv[1] * silu_fast(gv[1]));
+        packed.y = cvt_pk_bf16(uv[2] * silu_fast(gv[2]), uv[3] * silu_fast(gv[3]));
+        *reinterpret_cast<uint2*>(a.h_out + o) = packed;
+      } else {
+        *reinterpret_cast<float4*>(a.y_out + static_cast<int64_t>(kc) * a.plane_stride + o) =
+            make_float4(acc[0][f][4 * q] * sc0.x, acc[0][f][4 * q + 1] * sc0.y, acc[0][f][4 * q + 2] * sc0.z, acc[0][f][4 * q + 3] * sc0.w);
+      }
+    }
+  }
+}
+
 // K planes of the decode down projection: (fragments x planes) workgroups should fill two
 // slots per CU evenly, with planes of at least 8 K steps of 64.  The second value is the plane length.
 static void shared_decode_down_split(int d, int K, int* kc_out, int* steps_out) {
@@ -778,6 +969,49 @@ hipError_t launch_shared_decode_gate_up(const uint16_t* x, const uint16_t* w_gat
   // channel runs instead of fragments: see the kernel
   const int runs = std::max(device_cus() * 2, n_frags);
   return launch_shared_wave<0>(a, std::min(runs, F / 4), 1, KT, stream);
+}
+
+template <int MODE, int BITS, int AL>
+static hipError_t launch_shared_qwave_al(const SharedQDecodeArgs& a, int n_blocks, int kc, int steps_per_plane, hipStream_t stream) {
+  constexpr int lds = SharedQWaveCfg<MODE, BITS, AL>::LDS;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(shared_qwave_kernel<MODE, BITS, AL>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  shared_qwave_kernel<MODE, BITS, AL><<<n_blocks, 64, lds, stream>>>(a, kc, steps_per_plane);
+  return hipGetLastError();
+}
+
+template <int MODE, int BITS>
+static hipError_t launch_shared_qwave(const SharedQDecodeArgs& a, int n_blocks, int kc, int steps_per_plane, hipStream_t stream) {
+  if (a.M <= 8) return launch_shared_qwave_al<MODE, BITS, 1>(a, n_blocks, kc, steps_per_plane, stream);
+  if (a.M <= 16) return launch_shared_qwave_al<MODE, BITS, 2>(a, n_blocks, kc, steps_per_plane, stream);
+  if (a.M <= 32) return launch_shared_qwave_al<MODE, BITS, 4>(a, n_blocks, kc, steps_per_plane, stream);
+  return launch_shared_qwave_al<MODE, BITS, 8>(a, n_blocks, kc, steps_per_plane, stream);
+}
+
+hipError_t launch_shared_q_decode_gate_up(const uint16_t* x, const void* w_gate, const void* w_up, const float* s_gate,
+                                          const float* s_up, int bits, int T, int d, int F, uint16_t* h_s,
+                                          hipStream_t stream) {
+  SharedQDecodeArgs a{x, static_cast<const unsigned char*>(w_gate), static_cast<const unsigned char*>(w_up), s_gate, s_up,
+                      T, F, d, h_s, nullptr, 0};
+  const int n_frags = F / 32, KT = d >> 6;
+  const int runs = std::min(std::max(device_cus() * 2, n_frags), F / 4);
+  return bits == 8 ? launch_shared_qwave<0, 8>(a, runs, 1, KT, stream) : launch_shared_qwave<0, 4>(a, runs, 1, KT, stream);
+}
+
+hipError_t launch_shared_q_decode_down(const uint16_t* h_s, const void* w_down, const float* s_down, int bits, int T,
+                                       int d, int F, float* y_s, hipStream_t stream) {
+  SharedQDecodeArgs a{h_s, static_cast<const unsigned char*>(w_down), nullptr, s_down, nullptr, T, d, F, nullptr, y_s,
+                      static_cast<int64_t>(T) * d};
+  const int n_frags = d / 32;
+  int kc, steps;
+  shared_decode_down_split(d, F, &kc, &steps);
+  return bits == 8 ? launch_shared_qwave<1, 8>(a, n_frags * kc, kc, steps, stream)
+                   : launch_shared_qwave<1, 4>(a, n_frags * kc, kc, steps, stream);
 }
 
 hipError_t launch_shared_decode_down(const uint16_t* h_s, const uint16_t* w_down, int T, int d, int F, float* y_s,

@@ -181,6 +181,11 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
       for (int i = 0; i < 8; ++i) o[i] = fmaf(p, static_cast<float>(dsum[i]) * sc, o[i]);
     }
   }
+  if (a.residual) {   // x^a of Eq.2, added in fp32 before the single rounding
+    const uint4 rb = *reinterpret_cast<const uint4*>(a.residual + yo);
+    o[0] += bf16_lo(rb.x); o[1] += bf16_hi(rb.x); o[2] += bf16_lo(rb.y); o[3] += bf16_hi(rb.y);
+    o[4] += bf16_lo(rb.z); o[5] += bf16_hi(rb.z); o[6] += bf16_lo(rb.w); o[7] += bf16_hi(rb.w);
+  }
   uint4 ob;
   ob.x = cvt_pk_bf16(o[0], o[1]);
   ob.y = cvt_pk_bf16(o[2], o[3]);

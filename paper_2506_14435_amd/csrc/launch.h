@@ -23,14 +23,15 @@ enum Knob {
 };
 int knob(int id);
 
+// binary: the 1-bit quantiser t = sign(w) (sign(0) = +1) instead of the ternary RoundClip
 hipError_t launch_pack_ternary(const void* w, bool is_bf16, int64_t n_out, int64_t n_in, uint32_t* packed,
-                               float* alpha, hipStream_t stream);
+                               float* alpha, bool binary, hipStream_t stream);
 
 // Router (Eq.3 + top-k) fused with Q_a(x) (Eq.8).  q_x / beta_x / rowsum_x may be null
 // (router only).
 hipError_t launch_router_quant(const uint16_t* x, const uint16_t* w_router, const float* bias, int T, int d,
                                int E, int k, int32_t* topk_idx, float* topk_p, int8_t* q_x, float* beta_x,
-                               int32_t* rowsum_x, hipStream_t stream);
+                               int32_t* rowsum_x, float* gate_p, hipStream_t stream);   // gate_p: optional fp32 [T, E], the whole softmax
 
 hipError_t launch_expert_counts(const int32_t* topk_idx, int R, int E, int32_t* counts, hipStream_t stream);
 
@@ -105,6 +106,28 @@ hipError_t launch_shared_gate_up(const uint16_t* x, const uint16_t* w_gate, cons
                                  int F, uint16_t* h_s, hipStream_t stream);
 hipError_t launch_shared_down(const uint16_t* h_s, const uint16_t* w_down, int T, int d, int F, float* y_s,
                               hipStream_t stream);
+// The same GEMMs with a per-output-channel scale applied to the fp32 sums (integer-valued bf16
+// weights of an RTN-quantised shared expert); scales may be null.
+hipError_t launch_shared_gate_up_scaled(const uint16_t* x, const uint16_t* w_gate, const uint16_t* w_up,
+                                        const float* s_gate, const float* s_up, int T, int d, int F, uint16_t* h_s,
+                                        hipStream_t stream);
+hipError_t launch_shared_down_scaled(const uint16_t* h_s, const uint16_t* w_down, const float* s_down, int T, int d,
+                                     int F, float* y_s, hipStream_t stream);
+// RTN-quantised shared expert, decode (T <= kSharedDecodeMaxTokens): packed INT8 / INT4 codes
+hipError_t launch_shared_q_decode_gate_up(const uint16_t* x, const void* w_gate, const void* w_up, const float* s_gate,
+                                          const float* s_up, int bits, int T, int d, int F, uint16_t* h_s,
+                                          hipStream_t stream);
+hipError_t launch_shared_q_decode_down(const uint16_t* h_s, const void* w_down, const float* s_down, int bits, int T,
+                                       int d, int F, float* y_s, hipStream_t stream);
+hipError_t launch_rtn_pack(const uint16_t* w, int64_t n_out, int64_t n_in, int bits, void* packed, float* scales,
+                           hipStream_t stream);
+hipError_t launch_rtn_dequant(const void* packed, int64_t n_out, int64_t n_in, int bits, uint16_t* out, hipStream_t stream);
+// LN(.) of Eq.1-2: kind 1 RMSNorm, kind 2 layer normalisation (beta used by kind 2 only)
+hipError_t launch_norm_rows(const uint16_t* x, const uint16_t* gamma, const uint16_t* beta, int kind, double eps, int T,
+                            int d, uint16_t* y, hipStream_t stream);
+// Eq.12 from the gate probabilities [T, E] and the routed counts [E]
+hipError_t launch_balance(const float* gate_p, const int32_t* counts, int T, int E, float* gate_p_sum, float* loss,
+                          hipStream_t stream);
 
 // out = bf16( y_s + sum_j p[t,j] * (acc_down[row_of[t,j]] * (beta_h/127 * alpha_down)) ).
 // y_s and acc_down may come as several partial planes (decode K splits), added in plane order.
@@ -116,6 +139,7 @@ struct CombineArgs {
   const float* beta_h; const float* alpha;
   const int32_t* topk_idx; const float* topk_p; const int32_t* row_of;
   int T, d, k;
+  const uint16_t* residual;   // optional bf16 [T, d] added before the final rounding (x^a of Eq.2)
   uint16_t* out;
   float* out_f32;         // optional taps
   float* tap_y_s;         // [T, d] summed shared output

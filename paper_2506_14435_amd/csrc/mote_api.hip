@@ -33,6 +33,9 @@ struct Workspace {
   uint16_t* h; int8_t* q_h; float* beta_h; int32_t* rs_h; int32_t* acc_down;
   // shared expert
   uint16_t* h_s; float* y_s;
+  uint16_t* deq_gate; uint16_t* deq_up; uint16_t* deq_down;   // integer-valued bf16 copies of RTN weights (large batches)
+  // block prologue
+  uint16_t* xn;      // LN(x^a), bf16 [T, d]
   size_t bytes;
   int max_tiles;
   int tile_m;        // 32: decode kernels, else large-batch kernels
@@ -54,6 +57,7 @@ bool layer_shape_ok(const mote_layer* l) {
   if (l->d_model % 128 || l->d_ff_shared % 128 || l->d_ff_routed % 128) return false;
   if (l->n_experts < 1 || l->n_experts > 64) return false;
   if (l->top_k < 1 || l->top_k > l->n_experts || l->top_k > 8) return false;
+  if (l->shared_bits != 0 && l->shared_bits != 8 && l->shared_bits != 4) return false;
   return true;
 }
 
@@ -97,6 +101,12 @@ Workspace carve(const mote_layer* l, int T, char* base) {
   w.acc_down = reinterpret_cast<int32_t*>(take(R * d * 4 * static_cast<size_t>(std::max(w.d_planes, w.d_split))));
   w.h_s = reinterpret_cast<uint16_t*>(take(static_cast<size_t>(T) * Fs * 2));
   w.y_s = reinterpret_cast<float*>(take(static_cast<size_t>(T) * d * 4 * static_cast<size_t>(w.y_planes)));
+  w.xn = reinterpret_cast<uint16_t*>(take(static_cast<size_t>(T) * d * 2));
+  if (l->shared_bits != 0 && T > kSharedDecodeMaxTokens) {
+    w.deq_gate = reinterpret_cast<uint16_t*>(take(d * Fs * 2));
+    w.deq_up = reinterpret_cast<uint16_t*>(take(d * Fs * 2));
+    w.deq_down = reinterpret_cast<uint16_t*>(take(d * Fs * 2));
+  }
   w.bytes = off;
   return w;
 }
@@ -187,8 +197,35 @@ mote_status mote_pack_ternary(const void* w, int w_dtype, int64_t n_out, int64_t
   if (w_dtype != MOTE_DTYPE_F32 && w_dtype != MOTE_DTYPE_BF16) return MOTE_ERR_INVALID_ARG;
   if (n_out <= 0 || n_in <= 0) return MOTE_ERR_INVALID_ARG;
   if (n_out % 32 || n_in % 128) return MOTE_ERR_UNSUPPORTED_SHAPE;
-  MOTE_HIP(launch_pack_ternary(w, w_dtype == MOTE_DTYPE_BF16, n_out, n_in, packed, alpha,
+  MOTE_HIP(launch_pack_ternary(w, w_dtype == MOTE_DTYPE_BF16, n_out, n_in, packed, alpha, false,
                                static_cast<hipStream_t>(hip_stream)));
+  return MOTE_OK;
+}
+
+mote_status mote_pack_binary(const void* w, int w_dtype, int64_t n_out, int64_t n_in, uint32_t* packed,
+                             float* alpha, void* hip_stream) {
+  if (!w || !packed || !alpha) return MOTE_ERR_INVALID_ARG;
+  if (w_dtype != MOTE_DTYPE_F32 && w_dtype != MOTE_DTYPE_BF16) return MOTE_ERR_INVALID_ARG;
+  if (n_out <= 0 || n_in <= 0) return MOTE_ERR_INVALID_ARG;
+  if (n_out % 32 || n_in % 128) return MOTE_ERR_UNSUPPORTED_SHAPE;
+  MOTE_HIP(launch_pack_ternary(w, w_dtype == MOTE_DTYPE_BF16, n_out, n_in, packed, alpha, true,
+                               static_cast<hipStream_t>(hip_stream)));
+  return MOTE_OK;
+}
+
+size_t mote_rtn_packed_bytes(int64_t n_out, int64_t n_in, int bits) {
+  if (n_out <= 0 || n_in <= 0 || (bits != 8 && bits != 4)) return 0;
+  return static_cast<size_t>(n_out) * static_cast<size_t>(n_in) * static_cast<size_t>(bits) / 8;
+}
+
+mote_status mote_pack_rtn(const void* w, int64_t n_out, int64_t n_in, int bits, void* packed, float* scales,
+                          void* hip_stream) {
+  if (!w || !packed || !scales) return MOTE_ERR_INVALID_ARG;
+  if (bits != 8 && bits != 4) return MOTE_ERR_INVALID_ARG;
+  if (n_out <= 0 || n_in <= 0) return MOTE_ERR_INVALID_ARG;
+  if (n_out % 32 || n_in % 128 || n_out >= (int64_t{1} << 31) || n_in >= (int64_t{1} << 24)) return MOTE_ERR_UNSUPPORTED_SHAPE;
+  MOTE_HIP(launch_rtn_pack(static_cast<const uint16_t*>(w), n_out, n_in, bits, packed, scales,
+                           static_cast<hipStream_t>(hip_stream)));
   return MOTE_OK;
 }
 
@@ -201,8 +238,23 @@ mote_status mote_router_topk(const void* x, const void* w_router, const float* r
   if (!x || !w_router || !topk_idx || !topk_p) return MOTE_ERR_INVALID_ARG;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   MOTE_HIP(launch_router_quant(static_cast<const uint16_t*>(x), static_cast<const uint16_t*>(w_router), router_bias,
-                               T, d, E, k, topk_idx, topk_p, nullptr, nullptr, nullptr, stream));
+                               T, d, E, k, topk_idx, topk_p, nullptr, nullptr, nullptr, nullptr, stream));
   if (expert_counts) MOTE_HIP(launch_expert_counts(topk_idx, T * k, E, expert_counts, stream));
+  return MOTE_OK;
+}
+
+mote_status mote_router_balance(const void* x, const void* w_router, const float* router_bias, int T, int d, int E,
+                                int k, int32_t* topk_idx, float* topk_p, int32_t* expert_counts, float* gate_p,
+                                float* gate_p_sum, float* loss, void* hip_stream) {
+  if (T < 1) return MOTE_ERR_INVALID_ARG;   // the statistic divides by the number of tokens
+  if (d <= 0 || d % 128 || E < 1 || E > 64 || k < 1 || k > E || k > 8) return MOTE_ERR_UNSUPPORTED_SHAPE;
+  if (static_cast<int64_t>(T) * k >= (1 << 24)) return MOTE_ERR_UNSUPPORTED_SHAPE;
+  if (!x || !w_router || !topk_idx || !topk_p || !expert_counts || !gate_p || !gate_p_sum || !loss) return MOTE_ERR_INVALID_ARG;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  MOTE_HIP(launch_router_quant(static_cast<const uint16_t*>(x), static_cast<const uint16_t*>(w_router), router_bias,
+                               T, d, E, k, topk_idx, topk_p, nullptr, nullptr, nullptr, gate_p, stream));
+  MOTE_HIP(launch_expert_counts(topk_idx, T * k, E, expert_counts, stream));
+  MOTE_HIP(launch_balance(gate_p, expert_counts, T, E, gate_p_sum, loss, stream));
   return MOTE_OK;
 }
 
@@ -240,9 +292,11 @@ namespace {
 
 // The forward pass behind both entry points.  one_stream: everything on the caller's stream and
 // no host-side object is created (no helper stream, no events).
-mote_status forward_impl(const mote_layer* layer, const void* x, int T, void* out, void* workspace,
-                         size_t workspace_bytes, const mote_taps* taps, void* hip_stream, bool one_stream) {
+mote_status forward_impl(const mote_layer* layer, const mote_norm* norm, const void* x, int T, void* out,
+                         void* workspace, size_t workspace_bytes, const mote_taps* taps, void* hip_stream,
+                         bool one_stream) {
   if (!layer || T < 0) return MOTE_ERR_INVALID_ARG;
+  if (norm && (norm->kind != MOTE_NORM_RMS && norm->kind != MOTE_NORM_LAYER)) return MOTE_ERR_INVALID_ARG;
   if (!layer_shape_ok(layer)) return MOTE_ERR_UNSUPPORTED_SHAPE;
   if (!batch_ok(layer, T)) return MOTE_ERR_UNSUPPORTED_SHAPE;
   if (T == 0) return MOTE_OK;
@@ -250,6 +304,8 @@ mote_status forward_impl(const mote_layer* layer, const void* x, int T, void* ou
   if (!layer->w_router || !layer->ws_gate || !layer->ws_up || !layer->ws_down || !layer->wt_gate || !layer->wt_up ||
       !layer->wt_down || !layer->alpha)
     return MOTE_ERR_INVALID_ARG;
+  if (layer->shared_bits != 0 && (!layer->ss_gate || !layer->ss_up || !layer->ss_down)) return MOTE_ERR_INVALID_ARG;
+  if (norm && (!norm->gamma || (norm->kind == MOTE_NORM_LAYER && !norm->beta))) return MOTE_ERR_INVALID_ARG;
   if (reinterpret_cast<uintptr_t>(workspace) % kAlign) return MOTE_ERR_INVALID_ARG;
   const Workspace w = carve(layer, T, static_cast<char*>(workspace));
   if (w.bytes > workspace_bytes) return MOTE_ERR_WORKSPACE_TOO_SMALL;
@@ -259,6 +315,11 @@ mote_status forward_impl(const mote_layer* layer, const void* x, int T, void* ou
   const int E = layer->n_experts, k = layer->top_k;
   const int R = T * k;
   const uint16_t* xb = static_cast<const uint16_t*>(x);
+  if (norm) {   // Eq.2: the layer acts on LN(x^a); the residual x^a itself enters the combine
+    MOTE_HIP(launch_norm_rows(xb, static_cast<const uint16_t*>(norm->gamma), static_cast<const uint16_t*>(norm->beta),
+                              norm->kind, norm->eps, T, d, w.xn, stream));
+    xb = w.xn;
+  }
   const bool timing = g_timing && !one_stream;
   if (timing) MOTE_HIP(ensure_events());
   auto mark = [&](int i) -> hipError_t { return timing ? hipEventRecord(g_ev[i], stream) : hipSuccess; };
@@ -286,19 +347,41 @@ mote_status forward_impl(const mote_layer* layer, const void* x, int T, void* ou
   SideStream* side = nullptr;
   if (!timing && !one_stream && fork_enabled() && fork_pays) MOTE_HIP(side_stream(&side));
   hipStream_t sstream = side ? side->stream : stream;
+  // Shared expert: bf16 weights (Eq.2), or RTN INT8 / INT4 codes with row scales (Section 4.3).  Small
+  // batches stream the codes themselves; large batches first expand them to integer-valued bf16
+  // matrices (exact) for the bf16 MFMA GEMMs, whose epilogue applies the row scales.
+  const int sbits = layer->shared_bits;
+  auto shared_gate_up = [&](hipStream_t s) -> hipError_t {
+    if (sbits == 0)
+      return decode_shared ? launch_shared_decode_gate_up(xb, sg, su, T, d, Fs, w.h_s, s)
+                           : launch_shared_gate_up(xb, sg, su, T, d, Fs, w.h_s, s);
+    if (decode_shared)
+      return launch_shared_q_decode_gate_up(xb, layer->ws_gate, layer->ws_up, layer->ss_gate, layer->ss_up, sbits, T, d,
+                                            Fs, w.h_s, s);
+    hipError_t e = launch_rtn_dequant(layer->ws_gate, Fs, d, sbits, w.deq_gate, s);
+    if (e != hipSuccess) return e;
+    if ((e = launch_rtn_dequant(layer->ws_up, Fs, d, sbits, w.deq_up, s)) != hipSuccess) return e;
+    if ((e = launch_rtn_dequant(layer->ws_down, d, Fs, sbits, w.deq_down, s)) != hipSuccess) return e;
+    return launch_shared_gate_up_scaled(xb, w.deq_gate, w.deq_up, layer->ss_gate, layer->ss_up, T, d, Fs, w.h_s, s);
+  };
+  auto shared_down = [&](hipStream_t s) -> hipError_t {
+    if (sbits == 0)
+      return decode_shared ? launch_shared_decode_down(w.h_s, sd, T, d, Fs, w.y_s, s)
+                           : launch_shared_down(w.h_s, sd, T, d, Fs, w.y_s, s);
+    if (decode_shared) return launch_shared_q_decode_down(w.h_s, layer->ws_down, layer->ss_down, sbits, T, d, Fs, w.y_s, s);
+    return launch_shared_down_scaled(w.h_s, w.deq_down, layer->ss_down, T, d, Fs, w.y_s, s);
+  };
   if (side) {
     MOTE_HIP(hipEventRecord(side->fork, stream));
     MOTE_HIP(hipStreamWaitEvent(side->stream, side->fork, 0));
-    MOTE_HIP(decode_shared ? launch_shared_decode_gate_up(xb, sg, su, T, d, Fs, w.h_s, sstream)
-                           : launch_shared_gate_up(xb, sg, su, T, d, Fs, w.h_s, sstream));
-    MOTE_HIP(decode_shared ? launch_shared_decode_down(w.h_s, sd, T, d, Fs, w.y_s, sstream)
-                           : launch_shared_down(w.h_s, sd, T, d, Fs, w.y_s, sstream));
+    MOTE_HIP(shared_gate_up(sstream));
+    MOTE_HIP(shared_down(sstream));
     MOTE_HIP(hipEventRecord(side->join, side->stream));
   }
 
   MOTE_HIP(mark(0));
   MOTE_HIP(launch_router_quant(xb, static_cast<const uint16_t*>(layer->w_router), layer->router_bias, T, d, E, k,
-                               w.topk_idx, w.topk_p, w.q_x, w.beta_x, w.rs_x, stream));
+                               w.topk_idx, w.topk_p, w.q_x, w.beta_x, w.rs_x, nullptr, stream));
   MOTE_HIP(mark(1));
   DispatchPlan plan{w.counts, w.offsets, w.row_of, w.tok_of, w.tile_expert, w.tile_row0, w.tile_rows, w.n_tiles, w.row_planes, w.sched};
   MOTE_HIP(launch_dispatch_plan(w.topk_idx, T, k, E, tile_m, plan, stream));
@@ -330,11 +413,9 @@ mote_status forward_impl(const mote_layer* layer, const void* x, int T, void* ou
     MOTE_HIP(mark(6));
     MOTE_HIP(mark(7));
   } else {
-    MOTE_HIP(decode_shared ? launch_shared_decode_gate_up(xb, sg, su, T, d, Fs, w.h_s, stream)
-                           : launch_shared_gate_up(xb, sg, su, T, d, Fs, w.h_s, stream));
+    MOTE_HIP(shared_gate_up(stream));
     MOTE_HIP(mark(6));
-    MOTE_HIP(decode_shared ? launch_shared_decode_down(w.h_s, sd, T, d, Fs, w.y_s, stream)
-                           : launch_shared_down(w.h_s, sd, T, d, Fs, w.y_s, stream));
+    MOTE_HIP(shared_down(stream));
     MOTE_HIP(mark(7));
   }
   CombineArgs ca{};
@@ -345,6 +426,7 @@ mote_status forward_impl(const mote_layer* layer, const void* x, int T, void* ou
   ca.beta_h = w.beta_h; ca.alpha = layer->alpha;
   ca.topk_idx = w.topk_idx; ca.topk_p = w.topk_p; ca.row_of = w.row_of;
   ca.T = T; ca.d = d; ca.k = k;
+  ca.residual = norm ? static_cast<const uint16_t*>(x) : nullptr;
   ca.out = static_cast<uint16_t*>(out);
   ca.out_f32 = taps ? taps->out_f32 : nullptr;
   ca.tap_y_s = taps ? taps->y_s : nullptr;
@@ -370,6 +452,7 @@ mote_status forward_impl(const mote_layer* layer, const void* x, int T, void* ou
     MOTE_HIP(tap(taps->q_h, w.q_h, Rz * Fr));
     MOTE_HIP(tap(taps->beta_h, w.beta_h, Rz * 4));
     MOTE_HIP(tap(taps->h_s, w.h_s, Tz * Fs * 2));
+    if (norm) MOTE_HIP(tap(taps->xn, w.xn, Tz * d * 2));
   }
   return MOTE_OK;
 }
@@ -400,7 +483,13 @@ extern "C" {
 
 mote_status mote_layer_forward(const mote_layer* layer, const void* x, int T, void* out, void* workspace,
                                size_t workspace_bytes, const mote_taps* taps, void* hip_stream) {
-  return forward_impl(layer, x, T, out, workspace, workspace_bytes, taps, hip_stream, false);
+  return forward_impl(layer, nullptr, x, T, out, workspace, workspace_bytes, taps, hip_stream, false);
+}
+
+mote_status mote_block_forward(const mote_layer* layer, const mote_norm* norm, const void* x_a, int T, void* out,
+                               void* workspace, size_t workspace_bytes, const mote_taps* taps, void* hip_stream) {
+  if (!norm) return MOTE_ERR_INVALID_ARG;
+  return forward_impl(layer, norm, x_a, T, out, workspace, workspace_bytes, taps, hip_stream, false);
 }
 
 mote_status mote_layer_forward_static(const mote_layer* layer, const void* x, int T, void* out,
@@ -414,7 +503,7 @@ mote_status mote_layer_forward_static(const mote_layer* layer, const void* x, in
   MOTE_HIP(static_scratch(&ws));
   // Nothing in the array has to start at zero: the dispatch plan kernel of every forward zeroes
   // the tile counters and the plane words it uses, everything else is written before it is read.
-  return forward_impl(layer, x, T, out, ws, MOTE_STATIC_WORKSPACE_BYTES, taps, hip_stream, true);
+  return forward_impl(layer, nullptr, x, T, out, ws, MOTE_STATIC_WORKSPACE_BYTES, taps, hip_stream, true);
 }
 
 mote_status mote_stage_timing(int enable) {

@@ -58,7 +58,7 @@ __global__ __launch_bounds__(kPackThreads) void alpha_kernel(const double* __res
 template <typename T>
 __global__ __launch_bounds__(kPackThreads) void pack_kernel(const T* __restrict__ w, int64_t n_words, int tiles_k,
                                                             int64_t n_in, const float* __restrict__ alpha_ptr,
-                                                            uint32_t* __restrict__ packed) {
+                                                            bool binary, uint32_t* __restrict__ packed) {
   const int64_t wi = static_cast<int64_t>(blockIdx.x) * kPackThreads + threadIdx.x;
   if (wi >= n_words) return;
   const float alpha = alpha_ptr[0];
@@ -72,8 +72,10 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(const T* __restrict_
   uint32_t word = 0;
 #pragma unroll
   for (int i = 0; i < 16; ++i) {
-    float q = rintf(load_w<T>(w, base + i) / alpha);   // IEEE divide, round half to even
+    const float wv = load_w<T>(w, base + i);
+    float q = rintf(wv / alpha);   // IEEE divide, round half to even
     q = fminf(fmaxf(q, -1.0f), 1.0f);
+    if (binary) q = wv < 0.0f ? -1.0f : 1.0f;   // 1-bit quantiser of the routed-expert ablation: sign(w), sign(0) = +1
     const uint32_t code = static_cast<uint32_t>(static_cast<int>(q) + 1);
     word |= code << (8 * (i & 3) + 2 * (i >> 2));
   }
@@ -81,7 +83,7 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(const T* __restrict_
 }
 
 template <typename T>
-static hipError_t pack_impl(const T* w, int64_t n_out, int64_t n_in, uint32_t* packed, float* alpha,
+static hipError_t pack_impl(const T* w, int64_t n_out, int64_t n_in, uint32_t* packed, float* alpha, bool binary,
                             hipStream_t stream) {
   const int64_t n = n_out * n_in;
   const int64_t n_words = n / 16;
@@ -95,14 +97,14 @@ static hipError_t pack_impl(const T* w, int64_t n_out, int64_t n_in, uint32_t* p
   alpha_kernel<<<1, kPackThreads, 0, stream>>>(partial, n_partial, static_cast<double>(n), alpha);
   const int64_t blocks = (n_words + kPackThreads - 1) / kPackThreads;
   pack_kernel<T><<<static_cast<unsigned>(blocks), kPackThreads, 0, stream>>>(
-      w, n_words, static_cast<int>(n_in / 128), n_in, alpha, packed);
+      w, n_words, static_cast<int>(n_in / 128), n_in, alpha, binary, packed);
   return hipGetLastError();
 }
 
 hipError_t launch_pack_ternary(const void* w, bool is_bf16, int64_t n_out, int64_t n_in, uint32_t* packed,
-                               float* alpha, hipStream_t stream) {
-  if (is_bf16) return pack_impl<uint16_t>(static_cast<const uint16_t*>(w), n_out, n_in, packed, alpha, stream);
-  return pack_impl<float>(static_cast<const float*>(w), n_out, n_in, packed, alpha, stream);
+                               float* alpha, bool binary, hipStream_t stream) {
+  if (is_bf16) return pack_impl<uint16_t>(static_cast<const uint16_t*>(w), n_out, n_in, packed, alpha, binary, stream);
+  return pack_impl<float>(static_cast<const float*>(w), n_out, n_in, packed, alpha, binary, stream);
 }
 
 }  // namespace mote

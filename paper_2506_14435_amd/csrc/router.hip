@@ -55,7 +55,7 @@ template <int EMAX, int TPW, int NW>
 __global__ __launch_bounds__(64 * NW) void router_quant_kernel(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ w_router, const float* __restrict__ bias, int T,
     int d, int E, int k, int32_t* __restrict__ topk_idx, float* __restrict__ topk_p, int8_t* __restrict__ q_x,
-    float* __restrict__ beta_x, int32_t* __restrict__ rowsum_x) {
+    float* __restrict__ beta_x, int32_t* __restrict__ rowsum_x, float* __restrict__ gate_p) {
   constexpr int NV = EMAX * TPW;           // logits of a token group; lane l ends up with logit l % NV
   static_assert(NV <= 64 && 64 % NV == 0, "at most one finished logit per lane");
   constexpr int kWaves = NW;               // wavefronts that split the channels of one token group
@@ -145,6 +145,8 @@ __global__ __launch_bounds__(64 * NW) void router_quant_kernel(
 #pragma unroll
     for (int off = EMAX / 2; off > 0; off >>= 1) sum += __shfl_xor(sum, off, kWave);
     const float pr = static_cast<float>(ex / sum);
+    if (gate_p != nullptr && valid && lane < NV && t0 + (lane % NV) / EMAX < T)
+      gate_p[static_cast<int64_t>(t0 + (lane % NV) / EMAX) * E + e] = pr;   // the whole gate distribution (Eq.12 needs it)
     // top-k: k rounds of an arg-max butterfly over the EMAX lanes of a token.  Every lane of the
     // group ends a round with the winner (largest logit, ties to the lower expert index); the
     // winner's own lane then leaves the contest.
@@ -233,7 +235,7 @@ static int router_token_blocks() { return knob(kKnobRouterTokenBlocks); }
 
 hipError_t launch_router_quant(const uint16_t* x, const uint16_t* w_router, const float* bias, int T, int d,
                                int E, int k, int32_t* topk_idx, float* topk_p, int8_t* q_x, float* beta_x,
-                               int32_t* rowsum_x, hipStream_t stream) {
+                               int32_t* rowsum_x, float* gate_p, hipStream_t stream) {
   if (T == 0) return hipSuccess;
   // Few tokens: four wavefronts share a token group so that more of the chip takes part;
   // many tokens: one wavefront per group keeps the cross-lane reduction cost per token low.
@@ -243,20 +245,20 @@ hipError_t launch_router_quant(const uint16_t* x, const uint16_t* w_router, cons
     const int blocks = (T + kTpw - 1) / kTpw;
     if (T <= router_token_blocks())   // a few tokens: one token per workgroup, a quarter of the arithmetic and of the reduction per lane
       router_quant_kernel<16, 1, 4><<<T, 256, 0, stream>>>(x, w_router, bias, T, d, E, k, topk_idx, topk_p, q_x, beta_x,
-                                                           rowsum_x);
+                                                           rowsum_x, gate_p);
     else if (coop)
       router_quant_kernel<16, kTpw, 4><<<blocks, 256, 0, stream>>>(x, w_router, bias, T, d, E, k, topk_idx, topk_p, q_x,
-                                                                   beta_x, rowsum_x);
+                                                                   beta_x, rowsum_x, gate_p);
     else
       router_quant_kernel<16, kTpw, 1><<<blocks, 64, 0, stream>>>(x, w_router, bias, T, d, E, k, topk_idx, topk_p, q_x,
-                                                                  beta_x, rowsum_x);
+                                                                   beta_x, rowsum_x, gate_p);
   } else {
     if (coop)
       router_quant_kernel<64, 1, 4><<<T, 256, 0, stream>>>(x, w_router, bias, T, d, E, k, topk_idx, topk_p, q_x, beta_x,
-                                                           rowsum_x);
+                                                           rowsum_x, gate_p);
     else
       router_quant_kernel<64, 1, 1><<<T, 64, 0, stream>>>(x, w_router, bias, T, d, E, k, topk_idx, topk_p, q_x, beta_x,
-                                                          rowsum_x);
+                                                           rowsum_x, gate_p);
   }
   return hipGetLastError();
 }

@@ -69,6 +69,8 @@ struct SharedGemmArgs {
   uint16_t* h_out;       // gate-up: bf16 [M, N]
   float* y_out;          // down: fp32 [planes][M, N]
   int64_t plane_stride;  // elements between partial planes
+  const float* scale0;   // optional fp32 [N]: the sums of w0 (w1) are multiplied by scale0 (scale1)
+  const float* scale1;   // per output channel (RTN-quantised weights held as integer-valued bf16)
 };
 
 template <typename Cfg>
@@ -343,6 +345,25 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void shared_gemm_ker
                           : s_lds + (Cfg::PATCH_IN_STAGE ? st_nx2 : Cfg::STAGES * STAGE_BYTES) + wave * Cfg::PATCH_BYTES;
     const int m0 = mt * BM, n_wave0 = nt * BN + wn * BN_W * 32;
     const int rd_row = lane / LANES_PER_ROW, rd_chunk = lane % LANES_PER_ROW;
+    if (a.scale0 != nullptr) {   // row scales of quantised weights (uniform branch, not taken by the bf16 expert)
+#pragma unroll
+      for (int f = 0; f < BN_W; ++f) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int ch = min(n_wave0 + f * 32 + 8 * q + 4 * g, N - 4);
+          const float4 s0 = *reinterpret_cast<const float4*>(a.scale0 + ch);
+          float4 s1 = s0;
+          if constexpr (NMAT == 2) s1 = *reinterpret_cast<const float4*>(a.scale1 + ch);
+#pragma unroll
+          for (int i = 0; i < BM_W; ++i) {
+            acc[0][i][f][4 * q] *= s0.x; acc[0][i][f][4 * q + 1] *= s0.y; acc[0][i][f][4 * q + 2] *= s0.z; acc[0][i][f][4 * q + 3] *= s0.w;
+            if constexpr (NMAT == 2) {
+              acc[1][i][f][4 * q] *= s1.x; acc[1][i][f][4 * q + 1] *= s1.y; acc[1][i][f][4 * q + 2] *= s1.z; acc[1][i][f][4 * q + 3] *= s1.w;
+            }
+          }
+        }
+      }
+    }
 #pragma unroll
     for (int i = 0; i < BM_W; ++i) {
 #pragma unroll
@@ -443,8 +464,14 @@ static hipError_t launch_shared_cfg(const SharedGemmArgs& a, int kplanes, hipStr
 
 hipError_t launch_shared_gate_up(const uint16_t* x, const uint16_t* w_gate, const uint16_t* w_up, int T, int d,
                                  int F, uint16_t* h_s, hipStream_t stream) {
+  return launch_shared_gate_up_scaled(x, w_gate, w_up, nullptr, nullptr, T, d, F, h_s, stream);
+}
+
+hipError_t launch_shared_gate_up_scaled(const uint16_t* x, const uint16_t* w_gate, const uint16_t* w_up,
+                                        const float* s_gate, const float* s_up, int T, int d, int F, uint16_t* h_s,
+                                        hipStream_t stream) {
   if (T == 0) return hipSuccess;
-  SharedGemmArgs a{x, w_gate, w_up, T, F, d, h_s, nullptr, 0};
+  SharedGemmArgs a{x, w_gate, w_up, T, F, d, h_s, nullptr, 0, s_gate, s_up};
   // Operand traffic per flop halves with a 256 x 256 tile (one 8-wavefront workgroup per CU): the
   // 128-row tile at two workgroups per CU saturates the L2 -> L1 path first.  Small problems keep
   // the 128-row tile, which leaves fewer CUs idle in the last round.  Of its two forms, eight
@@ -489,8 +516,13 @@ int shared_down_planes(int T, int d, int F) {
 
 hipError_t launch_shared_down(const uint16_t* h_s, const uint16_t* w_down, int T, int d, int F, float* y_s,
                               hipStream_t stream) {
+  return launch_shared_down_scaled(h_s, w_down, nullptr, T, d, F, y_s, stream);
+}
+
+hipError_t launch_shared_down_scaled(const uint16_t* h_s, const uint16_t* w_down, const float* s_down, int T, int d,
+                                     int F, float* y_s, hipStream_t stream) {
   if (T == 0) return hipSuccess;
-  SharedGemmArgs a{h_s, w_down, nullptr, T, d, F, nullptr, y_s, static_cast<int64_t>(T) * d};
+  SharedGemmArgs a{h_s, w_down, nullptr, T, d, F, nullptr, y_s, static_cast<int64_t>(T) * d, s_down, nullptr};
   const int planes = shared_down_planes(T, d, F);
   if (planes > 1) return launch_shared_cfg<SharedCfg<1, 2, 2, 2, 2, 2>>(a, planes, stream);   // small problem: 128 x 128 tiles
   int v = shared_variant();

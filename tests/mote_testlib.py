@@ -12,7 +12,7 @@ import workloads as W
 class GpuProblem:
     """Device side of a workload: weights packed by mote_pack_ternary on the GPU."""
 
-    def __init__(self, cfg: W.MoteConfig, device="cuda:0", latent_source=None):
+    def __init__(self, cfg: W.MoteConfig, device="cuda:0", latent_source=None, shared_bits=0, binary_experts=False):
         import paper_2506_14435_amd as M
         self.cfg = cfg
         dev = torch.device(device)
@@ -32,25 +32,37 @@ class GpuProblem:
                     lat = W.make_latent(cfg, ex, m).to(dev)
                 else:
                     lat = latent_source(ex, m)
-                M.mote_pack_ternary(lat, packed=self.wt[m][ex], alpha=tmp_alpha)
+                M.mote_pack_ternary(lat, packed=self.wt[m][ex], alpha=tmp_alpha, binary=binary_experts)
                 self.alpha[ex, m] = tmp_alpha[0]
                 del lat
+        self.shared_bits = shared_bits
+        self.shared_scales = None
+        self.shared_bf16 = self.shared
+        if shared_bits:          # post-training quantised shared expert: packed by mote_pack_rtn on the GPU
+            packed = [M.mote_pack_rtn(t, shared_bits) for t in self.shared]
+            self.shared = tuple(p for p, _ in packed)
+            self.shared_scales = tuple(s for _, s in packed)
         torch.cuda.synchronize()
         self.layer = M.MoteLayer(self.w_router, *self.shared, *self.wt, self.alpha, cfg.top_k,
-                                 router_bias=self.bias)
+                                 router_bias=self.bias, shared_bits=shared_bits, shared_scales=self.shared_scales)
 
 
 class OracleProblem:
     """Oracle side of the same workload: numpy inputs; experts ternarised lazily by the
     oracle's own Q_w."""
 
-    def __init__(self, cfg: W.MoteConfig):
+    def __init__(self, cfg: W.MoteConfig, shared_bits=0, binary_experts=False):
         self.cfg = cfg
+        self.binary_experts = binary_experts
         self.x = W.bf16_bits(W.make_x(cfg))
         self.w_router = W.bf16_bits(W.make_router(cfg))
         bias = W.make_router_bias(cfg)
         self.bias = None if bias is None else bias.numpy()
         self.shared = tuple(W.bf16_bits(t) for t in W.make_shared(cfg))
+        if shared_bits:
+            from oracle import mote_oracle as O
+            q = [O.rtn_quantize(w, shared_bits) for w in self.shared]
+            self.shared = (*q[0], *q[1], *q[2])
         self._experts = {}
 
     def experts(self, e: int):
@@ -58,7 +70,8 @@ class OracleProblem:
         if e not in self._experts:
             r = []
             for m in range(3):
-                t, a = O.ternarize(W.make_latent(self.cfg, e, m).numpy())
+                lat = W.make_latent(self.cfg, e, m).numpy()
+                t, a = O.binarize(lat) if self.binary_experts else O.ternarize(lat)
                 r += [t, a]
             self._experts[e] = tuple(r)
         return self._experts[e]
@@ -66,6 +79,11 @@ class OracleProblem:
     def forward(self, tokens=None):
         from oracle import mote_oracle as O
         return O.layer_forward(self.x, self.w_router, self.bias, self.cfg.top_k, self.shared, self.experts,
+                               tokens=tokens)
+
+    def block_forward(self, norm, tokens=None):
+        from oracle import mote_oracle as O
+        return O.block_forward(self.x, norm, self.w_router, self.bias, self.cfg.top_k, self.shared, self.experts,
                                tokens=tokens)
 
 
