@@ -51,8 +51,9 @@ def pick_config(name: str):
     raise SystemExit(f"unknown workload {name}")
 
 
-def stage_work(cfg, counts):
-    """Algorithmic work per launch of each stage: (bound, amount, unit, peak)."""
+def stage_work(cfg, counts, shared_bits=0):
+    """Algorithmic work per launch of each stage: (bound, amount, unit, peak).  shared_bits: 0 for the
+    bf16 shared expert, 8 / 4 for the RTN-quantised one (bytes per weight = bits / 8, plus 4-byte row scales)."""
     T, d, F, E, k = cfg.n_tokens, cfg.d_model, cfg.d_ff, cfg.n_experts, cfg.top_k
     R = T * k
     n_active = int((counts > 0).sum())
@@ -61,8 +62,10 @@ def stage_work(cfg, counts):
     if decode:  # HBM-bound: packed expert bytes actually touched (+ their activations)
         w["routed_gate_up"] = ("hbm", n_active * 2 * d * F / 4 + R * d + R * F * 2, "GB/s", PEAK_HBM_GBS)
         w["routed_down"] = ("hbm", n_active * d * F / 4 + R * F + R * d * 4, "GB/s", PEAK_HBM_GBS)
-        w["shared_gate_up"] = ("hbm", 2 * d * F * 2 + T * d * 2 + T * F * 2, "GB/s", PEAK_HBM_GBS)
-        w["shared_down"] = ("hbm", d * F * 2 + T * F * 2 + T * d * 4, "GB/s", PEAK_HBM_GBS)
+        wb = (shared_bits or 16) / 8.0
+        sc = 4 if shared_bits else 0
+        w["shared_gate_up"] = ("hbm", 2 * d * F * wb + 2 * F * sc + T * d * 2 + T * F * 2, "GB/s", PEAK_HBM_GBS)
+        w["shared_down"] = ("hbm", d * F * wb + d * sc + T * F * 2 + T * d * 4, "GB/s", PEAK_HBM_GBS)
     else:       # MFMA-bound
         w["routed_gate_up"] = ("mfma", 2.0 * R * 2 * d * F, "TFLOP/s", PEAK_I8_TOPS)
         w["routed_down"] = ("mfma", 2.0 * R * d * F, "TFLOP/s", PEAK_I8_TOPS)
@@ -132,7 +135,8 @@ def cpu_baseline(cfg, budget_s=20.0):
                       f"experts already ternarised; {reps} pass(es) of {t_small:.2f} s"}
 
 
-def measure(workload: str, steps, warmup, graph: bool, calib_copy_mib: int, stage_steps_max: int = 200):
+def measure(workload: str, steps, warmup, graph: bool, calib_copy_mib: int, stage_steps_max: int = 200,
+            shared_bits: int = 0):
     """Times one workload: whole forwards, then per-stage durations.  Returns the result dict
     (without cpu_baseline) and the config."""
     import torch
@@ -147,7 +151,8 @@ def measure(workload: str, steps, warmup, graph: bool, calib_copy_mib: int, stag
         shape = (cfg.d_ff, cfg.d_model) if m < 2 else (cfg.d_model, cfg.d_ff)
         return torch.randn(*shape, device=dev, generator=gen) * cfg.sigma_latent
 
-    gp = GpuProblem(cfg, dev, latent_source=latent if cfg.n_experts * cfg.d_model * cfg.d_ff > 5e7 else None)
+    gp = GpuProblem(cfg, dev, latent_source=latent if cfg.n_experts * cfg.d_model * cfg.d_ff > 5e7 else None,
+                    shared_bits=shared_bits)
     out = torch.empty_like(gp.x)
     ws = gp.layer.workspace(cfg.n_tokens)
     taps = M.alloc_taps(gp.layer, cfg.n_tokens, ("counts",))
@@ -163,7 +168,8 @@ def measure(workload: str, steps, warmup, graph: bool, calib_copy_mib: int, stag
             sh = tuple(t.clone() for t in gp.shared)
             wt = [t.clone() for t in gp.wt]
             keep.append((sh, wt))
-            layers.append(M.MoteLayer(gp.w_router, *sh, *wt, gp.alpha, cfg.top_k, router_bias=gp.bias))
+            layers.append(M.MoteLayer(gp.w_router, *sh, *wt, gp.alpha, cfg.top_k, router_bias=gp.bias,
+                                      shared_bits=shared_bits, shared_scales=gp.shared_scales))
     n_layers = len(layers)
 
     M.mote_layer_forward(gp.layer, gp.x, out=out, workspace=ws, taps=taps)
@@ -228,7 +234,7 @@ def measure(workload: str, steps, warmup, graph: bool, calib_copy_mib: int, stag
     M.mote_stage_timing(False)
     stage_ms = {n: v / stage_steps for n, v in acc.items()}
 
-    work = stage_work(cfg, counts)
+    work = stage_work(cfg, counts, shared_bits)
     candidates = ("routed_gate_up", "routed_down", "shared_gate_up", "shared_down")
     dom = max(candidates, key=lambda n: stage_ms[n])
     stages = {}
@@ -256,11 +262,13 @@ def measure(workload: str, steps, warmup, graph: bool, calib_copy_mib: int, stag
     result = {
         "metric": "MoTE-layer tokens/s", "value": round(tokens_per_s, 1), "unit": "tokens/s",
         "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(ms_per_step, 5),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "i8+bf16",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "i8+bf16" if not shared_bits else f"i8+bf16 (shared expert weights int{shared_bits})",
         "data": "synthetic",
         "config": {"workload": cfg.name, "d_model": cfg.d_model, "d_ff": cfg.d_ff, "n_experts": cfg.n_experts,
                    "top_k": cfg.top_k, "tokens": cfg.n_tokens, "expert_loads": counts.tolist(),
-                   "weight_copies_rotated": n_layers, "launch": launch, "conditioning_forwards": conditioning},
+                   "weight_copies_rotated": n_layers, "launch": launch, "conditioning_forwards": conditioning,
+                   "shared_expert_bits": shared_bits or 16},
         "roofline": roofline,
         "routed_gemms": routed_pair,
         "stages": stages,
@@ -305,6 +313,8 @@ def main():
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run the library's plain copy kernel on this many MiB (three launches): the "
                          "known-size transfer that scales rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings")
+    ap.add_argument("--shared-bits", type=int, default=0, choices=(0, 8, 4),
+                    help="0: bf16 shared expert (the paper's layer); 8 / 4: RTN-quantised shared expert (Section 4.3)")
     ap.add_argument("--tune", action="append", default=[], metavar="KNOB=VALUE",
                     help="experiment knob of the library (mote_tuning_set), e.g. --tune no_fork=1")
     args = ap.parse_args()
@@ -324,7 +334,8 @@ def main():
         M.mote_tuning_set(name, int(val))
     headline = args.workload == "headline"
     main_workload = "c3" if headline else args.workload
-    result, cfg = measure(main_workload, args.steps, args.warmup, args.graph, args.calib_copy_mib)
+    result, cfg = measure(main_workload, args.steps, args.warmup, args.graph, args.calib_copy_mib,
+                          shared_bits=args.shared_bits)
     if headline:
         # The metric names three figures: tokens/s of the layer, the decode shapes' packed-weight
         # stream against the HBM peak and the prefill shape's routed GEMMs against the int8 MFMA
@@ -332,6 +343,11 @@ def main():
         # measured after it with their own default step counts.
         result["decode"] = [brief(measure(f"c4_T{t}_n{n}", None, None, args.graph, 0)[0]) for t, n in DECODE_POINTS]
         result["c5"] = brief(measure("c5", None, None, args.graph, 0)[0])
+        # Section 4.3: the shared expert quantised to INT8 / INT4 (its bf16 weights are most of a small
+        # decode step's bytes)
+        result["decode_rtn_shared"] = [
+            dict(brief(measure(f"c4_T{t}_n{n}", None, None, args.graph, 0, shared_bits=b)[0]), shared_expert_bits=b)
+            for b in (8, 4) for t, n in ((1, 2), (4, 4), (64, 16))]
         d64 = result["decode"][-1]
         result["targets"] = {
             "prefill_routed_i8_frac": result["routed_gemms"]["frac"], "prefill_target": 0.5,

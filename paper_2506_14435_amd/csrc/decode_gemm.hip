@@ -750,19 +750,26 @@ struct SharedQDecodeArgs {
   int64_t plane_stride;
 };
 
+// NW wavefronts of a workgroup share a channel run and split its K steps (each with a private
+// ring), then add their fp32 partial sums through LDS: with one wavefront per workgroup the chain
+// of K steps of a wavefront (wait, LDS reads, conversions, MFMAs), not HBM, set the kernel's time.
 template <int MODE, int BITS, int AL>
 struct SharedQWaveCfg {
   static constexpr int NMAT = MODE == 0 ? 2 : 1;
   static constexpr int MFR = AL > 4 ? 2 : 1;
+  static constexpr int NW = AL > 4 ? 2 : 4;                  // wavefronts per workgroup
   static constexpr int WL = BITS == 8 ? 2 : 1;               // 1-KiB loads per matrix and K step
   static constexpr int W_LOADS = NMAT * WL, L = W_LOADS + AL;
   static constexpr int A_OFF = W_LOADS * 1024;
   static constexpr int SLOT = L * 1024;
   static constexpr int TAIL = (MFR * 4 - AL) * 1024;
-  static constexpr int S_LDS = (65536 - TAIL) / SLOT, S_CNT = 2 + 63 / L;
+  static constexpr int S_LDS = ((80 * 1024 - TAIL) / NW) / SLOT, S_CNT = 2 + 63 / L;
   static constexpr int S0 = S_LDS < S_CNT ? S_LDS : S_CNT;
-  static constexpr int S = S0 > 12 ? 12 : S0;               // 12 steps in flight are plenty
-  static constexpr int LDS = S * SLOT + TAIL;
+  static constexpr int S = S0 > 8 ? 8 : S0;                  // ring slots per wavefront
+  static constexpr int RING = S * SLOT;
+  static constexpr int RED = NW * NMAT * MFR * 16 * 64 * 4;  // partial sums of all wavefronts
+  static constexpr int LDS = (NW * RING + TAIL) > RED ? (NW * RING + TAIL) : RED;
+  static_assert(S >= 2, "at least one K step in flight");
 };
 
 // eight consecutive two's-complement codes (bytes of lo/hi, or nibbles of lo) -> bf16x8
@@ -787,21 +794,29 @@ __device__ __forceinline__ bf16x8 codes_to_bf16(uint32_t lo, uint32_t hi) {
 }
 
 template <int MODE, int BITS, int AL>
-__global__ __launch_bounds__(64) void shared_qwave_kernel(SharedQDecodeArgs a, int kc_count, int steps_per_plane) {
+__global__ __launch_bounds__((64 * SharedQWaveCfg<MODE, BITS, AL>::NW)) void shared_qwave_kernel(SharedQDecodeArgs a, int kc_count,
+                                                                                              int steps_per_plane) {
   using Cfg = SharedQWaveCfg<MODE, BITS, AL>;
   constexpr int NMAT = Cfg::NMAT, MFR = Cfg::MFR, L = Cfg::L, SLOT = Cfg::SLOT, S = Cfg::S, A_LOADS = AL, WL = Cfg::WL;
+  constexpr int NW = Cfg::NW;
   constexpr int WROW = BITS == 8 ? 64 : 32;        // bytes of a weight row per K step
   constexpr int kBufferFlags = 0x00020000;
   extern __shared__ __attribute__((aligned(16))) unsigned char s_ring[];
   const int M = a.M, N = a.N, K = a.K, KT = K >> 6;
-  const int lane = threadIdx.x, r32 = lane & 31, g = lane >> 5;
+  const int lane = threadIdx.x & 63, r32 = lane & 31, g = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int kc = MODE == 1 ? blockIdx.x % kc_count : 0;
   const int quads = N >> 2;
   const int c0 = MODE == 1 ? (blockIdx.x / kc_count) * 32 : static_cast<int>(static_cast<int64_t>(blockIdx.x) * quads / gridDim.x) * 4;
   const int c1 = MODE == 1 ? c0 + 32 : static_cast<int>(static_cast<int64_t>(blockIdx.x + 1) * quads / gridDim.x) * 4;
-  const int step0 = kc * steps_per_plane;
-  const int nsteps = min(steps_per_plane, KT - step0);
-  const uint32_t lds0 = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) unsigned char*)s_ring);
+  // K steps of the workgroup, then this wavefront's share of them
+  const int wg_step0 = kc * steps_per_plane;
+  const int wg_steps = min(steps_per_plane, KT - wg_step0);
+  const int per_wave = (wg_steps + NW - 1) / NW;
+  const int step0 = wg_step0 + wave * per_wave;
+  const int nsteps = max(0, min(per_wave, wg_steps - wave * per_wave));
+  unsigned char* const my_ring = s_ring + wave * Cfg::RING;
+  const uint32_t lds0 = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) unsigned char*)my_ring);
   auto make_rsrc = [&](const void* base, int64_t bytes) {
     const uint64_t p = reinterpret_cast<uint64_t>(base);
     v4i r;
@@ -859,7 +874,7 @@ __global__ __launch_bounds__(64) void shared_qwave_kernel(SharedQDecodeArgs a, i
   int slot = 0, slot_fill = S - 1;
   for (int j = 0; j < nsteps; ++j) {
     wait_steps_ahead<L, S - 2>(nsteps - 1 - j);
-    const unsigned char* const st = s_ring + slot * SLOT;
+    const unsigned char* const st = my_ring + slot * SLOT;
     // this lane's codes of the step: INT8 two 16-byte reads per matrix (K sub-steps 0,1 and 2,3), INT4 one
     u4 wq[NMAT][WL];
 #pragma unroll
@@ -895,27 +910,49 @@ __global__ __launch_bounds__(64) void shared_qwave_kernel(SharedQDecodeArgs a, i
 #undef MOTE_DMA
 #undef MOTE_ISSUE
 
+  // cross-wavefront reduction: every wavefront parks its partial sums in LDS (the rings are done
+  // with), then wavefront w finishes the channel quads q = w, w + NW, ...
+  float* const red = reinterpret_cast<float*>(s_ring);
+  constexpr int NV = NMAT * MFR * 16;
+  __syncthreads();
+#pragma unroll
+  for (int m = 0; m < NMAT; ++m)
+#pragma unroll
+    for (int f = 0; f < MFR; ++f)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) red[((wave * NV) + (m * MFR + f) * 16 + v) * 64 + lane] = acc[m][f][v];
+  __syncthreads();
 #pragma unroll
   for (int f = 0; f < MFR; ++f) {
     const int row = f * 32 + r32;
-    if (row >= M) continue;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
+    for (int qq = 0; qq < 4 / NW; ++qq) {
+      const int q = wave + qq * NW;
       const int ch = c0 + 8 * q + 4 * g;
-      if (ch >= c1) continue;
+      if (row >= M || ch >= c1) continue;
+      float sum[NMAT][4];
+#pragma unroll
+      for (int m = 0; m < NMAT; ++m)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          float t = 0.0f;
+#pragma unroll
+          for (int ww = 0; ww < NW; ++ww) t += red[((ww * NV) + (m * MFR + f) * 16 + 4 * q + j) * 64 + lane];   // fixed order
+          sum[m][j] = t;
+        }
       const int64_t o = static_cast<int64_t>(row) * N + ch;
       const float4 sc0 = *reinterpret_cast<const float4*>(a.s0 + ch);
       if constexpr (MODE == 0) {
         const float4 sc1 = *reinterpret_cast<const float4*>(a.s1 + ch);
-        const float gv[4] = {acc[0][f][4 * q] * sc0.x, acc[0][f][4 * q + 1] * sc0.y, acc[0][f][4 * q + 2] * sc0.z, acc[0][f][4 * q + 3] * sc0.w};
-        const float uv[4] = {acc[1][f][4 * q] * sc1.x, acc[1][f][4 * q + 1] * sc1.y, acc[1][f][4 * q + 2] * sc1.z, acc[1][f][4 * q + 3] * sc1.w};
+        const float gv[4] = {sum[0][0] * sc0.x, sum[0][1] * sc0.y, sum[0][2] * sc0.z, sum[0][3] * sc0.w};
+        const float uv[4] = {sum[NMAT - 1][0] * sc1.x, sum[NMAT - 1][1] * sc1.y, sum[NMAT - 1][2] * sc1.z, sum[NMAT - 1][3] * sc1.w};
         uint2 packed;
         packed.x = cvt_pk_bf16(uv[0] * silu_fast(gv[0]), uv[1] * silu_fast(gv[1]));
         packed.y = cvt_pk_bf16(uv[2] * silu_fast(gv[2]), uv[3] * silu_fast(gv[3]));
         *reinterpret_cast<uint2*>(a.h_out + o) = packed;
       } else {
         *reinterpret_cast<float4*>(a.y_out + static_cast<int64_t>(kc) * a.plane_stride + o) =
-            make_float4(acc[0][f][4 * q] * sc0.x, acc[0][f][4 * q + 1] * sc0.y, acc[0][f][4 * q + 2] * sc0.z, acc[0][f][4 * q + 3] * sc0.w);
+            make_float4(sum[0][0] * sc0.x, sum[0][1] * sc0.y, sum[0][2] * sc0.z, sum[0][3] * sc0.w);
       }
     }
   }
@@ -981,7 +1018,7 @@ static hipError_t launch_shared_qwave_al(const SharedQDecodeArgs& a, int n_block
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  shared_qwave_kernel<MODE, BITS, AL><<<n_blocks, 64, lds, stream>>>(a, kc, steps_per_plane);
+  shared_qwave_kernel<MODE, BITS, AL><<<n_blocks, 64 * SharedQWaveCfg<MODE, BITS, AL>::NW, lds, stream>>>(a, kc, steps_per_plane);
   return hipGetLastError();
 }
 
