@@ -434,6 +434,63 @@ def _check_down_rows(cfg, op, taps, rows):
         assert np.array_equal(acc_down[sel], O.ternary_matmul_int(op.experts(int(e))[4], q_h[sel])), f"expert {e}"
 
 
+def _check_rows_of_every_expert(cfg, op, taps, tile_m=128, keep=()):
+    """Full-size run: for EVERY expert, dispatch rows of its first, a middle and its last row tile
+    (first and last row of each) go through the oracle's ternary expert: gate / up accumulators
+    bit-exact, h up to rare one-step flips, Q_a(h) bit-exact on the GPU's own h, down accumulators
+    bit-exact on the GPU's own q_h.  One expert is ternarised at a time."""
+    E = cfg.n_experts
+    counts = taps["counts"].cpu().numpy()
+    tok_of = taps["tok_of"].cpu().numpy()
+    offs = np.concatenate([[0], np.cumsum(counts)])
+    x = O.bf16_to_f32(op.x)
+    seen = []
+    for e in range(E):
+        n = int(counts[e])
+        if n == 0:
+            continue
+        n_tiles = (n + tile_m - 1) // tile_m
+        local = set()
+        for t in sorted({0, n_tiles // 2, n_tiles - 1}):
+            local.update({t * tile_m, min(t * tile_m + tile_m - 1, n - 1)})
+        rows = offs[e] + np.array(sorted(local))
+        rows_t = torch.from_numpy(rows.astype(np.int64)).cuda()
+        r = O.ternary_expert(x[tok_of[rows]], *op.experts(e))
+        assert np.array_equal(taps["acc_gate"][rows_t].cpu().numpy(), r["acc_gate"]), f"expert {e}"
+        assert np.array_equal(taps["acc_up"][rows_t].cpu().numpy(), r["acc_up"]), f"expert {e}"
+        h_g = bits(taps["h"][rows_t])
+        neq = h_g != r["h"]
+        assert neq.mean() <= 5 * H_FLIP_RATE, (e, neq.mean())        # a few rows: the rate itself is noisy
+        if neq.any():
+            a, b = O.bf16_to_f32(h_g[neq]).astype(np.float64), O.bf16_to_f32(r["h"][neq]).astype(np.float64)
+            assert (np.abs(a - b) <= np.maximum(np.abs(a), np.abs(b)) * 2.0 ** -7 + 1e-30).all()
+        q_h_want, beta_h_want = O.absmax_int8(O.bf16_to_f32(h_g))
+        q_h = taps["q_h"][rows_t].cpu().numpy()
+        assert np.array_equal(q_h, q_h_want), f"expert {e}"
+        assert np.array_equal(taps["beta_h"][rows_t].cpu().numpy(), beta_h_want[:, 0]), f"expert {e}"
+        assert np.array_equal(taps["acc_down"][rows_t].cpu().numpy(),
+                              O.ternary_matmul_int(op.experts(e)[4], q_h)), f"expert {e}"
+        seen.append(e)
+        if e not in keep:
+            op._experts.pop(e, None)                                  # one expert's matrices at a time
+    _log(f"  rows of the first / middle / last row tile checked for experts {seen}")
+    assert seen == [e for e in range(E) if counts[e] > 0]
+
+
+def _check_shared_tiles(cfg, op, taps, tile=256):
+    """Shared expert at full size: first and last token of every row tile of the shared GEMMs."""
+    T = cfg.n_tokens
+    toks = np.unique(np.concatenate([np.arange(0, T, tile), np.minimum(np.arange(tile - 1, T + tile - 1, tile), T - 1)]))
+    tok_t = torch.from_numpy(toks.astype(np.int64)).cuda()
+    h_ref, y_ref = O.shared_expert(op.x[toks], *op.shared)
+    hs_neq = (bits(taps["h_s"][tok_t]) != h_ref).mean()
+    assert hs_neq <= 5e-3, hs_neq
+    y = taps["y_s"][tok_t].cpu().numpy()
+    assert np.allclose(y, y_ref, rtol=0, atol=2e-3 + 2e-3 * np.abs(y_ref).max())
+    _log(f"  shared expert on {len(toks)} tokens (both ends of every {tile}-row tile): h_s flip rate {hs_neq:.2e}, "
+         f"max |dy_s| {np.abs(y - y_ref).max():.2e}")
+
+
 FULL_TAPS = ("topk_idx", "topk_p", "counts", "row_of", "tok_of", "q_x", "beta_x", "acc_gate", "acc_up", "h", "q_h",
              "beta_h", "acc_down")
 
@@ -454,8 +511,10 @@ def test_layer_config3_prefill_sampled():
     cfg = W.C3
     _log(f"layer {cfg.name}")
     gp, op = GpuProblem(cfg), OracleProblem(cfg)
-    out, taps = _run_layer(gp, FULL_TAPS)
+    out, taps = _run_layer(gp, FULL_TAPS + ("h_s", "y_s"))
     _check_sampled(cfg, 48, 3, out, taps, op)
+    _check_rows_of_every_expert(cfg, op, taps, keep=np.argsort(-taps["counts"].cpu().numpy(), kind="stable")[:3])
+    _check_shared_tiles(cfg, op, taps)
     # The last round of the down projection's tile lists is nearly empty at this shape: its row
     # tiles (the last ones in dispatch order) are cut into K planes.  Rows of the first and of
     # the last tiles, all channels.
@@ -518,10 +577,19 @@ def test_layer_config5_skewed_sampled():
     cfg = W.C5
     _log(f"layer {cfg.name}")
     gp, op = GpuProblem(cfg), OracleProblem(cfg)
-    out, taps = _run_layer(gp, FULL_TAPS)
+    out, taps = _run_layer(gp, FULL_TAPS + ("h_s", "y_s"))
     _check_sampled(cfg, 24, 2, out, taps, op)
     counts = taps["counts"].cpu().numpy()
     assert 6.0 <= counts.max() / counts.min() <= 14.0                # loads imbalanced about 10x
+    # every expert at its real load (7037 down to 708 rows): both ends and the middle of its row tiles
+    _check_rows_of_every_expert(cfg, op, taps)
+    _check_shared_tiles(cfg, op, taps)
+    # down accumulators of the first and of the last dispatch rows on every channel (the tiles of the
+    # last round are the ones a drawn or cut schedule treats differently)
+    R = cfg.n_tokens * cfg.top_k
+    rng = np.random.default_rng(11)
+    rows = np.concatenate([rng.choice(1024, 16, replace=False), R - 1 - rng.choice(1400, 32, replace=False)])
+    _check_down_rows(cfg, op, taps, np.sort(rows))
 
 
 # ------------------------------------------------------------------------ error paths
