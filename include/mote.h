@@ -260,6 +260,11 @@ mote_status mote_stage_timing(int enable);
  * milliseconds to host memory `ms`; a stage that did not run reports 0. */
 mote_status mote_stage_times(float* ms_host);
 
+/* Milliseconds that two consecutive event records on `hip_stream` read with nothing between them
+ * (median of 33 pairs; synchronises with the stream).  A stage time of mote_stage_times is the
+ * stage's kernel plus this much, which matters for kernels of a few tens of microseconds. */
+mote_status mote_event_pair_overhead(float* ms_host, void* hip_stream);
+
 /* Tuning knobs for experiments (the defaults are what the measurements chose; the library reads
  * nothing from the environment).  Host-side state, not thread-safe.  Some knobs change the
  * workspace layout: set them before mote_layer_workspace_bytes and keep them until the forwards

@@ -22,7 +22,7 @@ STAGE_NAMES = ("router_quant", "dispatch", "routed_gate_up", "quant_h", "routed_
 EXPORTS = ("mote_status_string", "mote_version", "mote_packed_bytes", "mote_pack_ternary",
            "mote_router_topk", "mote_layer_workspace_bytes", "mote_layer_forward", "mote_layer_forward_static",
            "mote_block_forward", "mote_router_balance", "mote_pack_binary", "mote_rtn_packed_bytes", "mote_pack_rtn",
-           "mote_stage_timing", "mote_stage_times", "mote_tuning_set", "mote_calib_copy")
+           "mote_stage_timing", "mote_stage_times", "mote_event_pair_overhead", "mote_tuning_set", "mote_calib_copy")
 KNOBS = ("no_fork", "fork_min_log2", "event_fence", "quant_wide", "routed_variant", "routed_down_variant",
          "shared_variant", "group_m", "dynamic_rounds", "decode_variant", "router_token_blocks")
 
@@ -102,6 +102,8 @@ def load_library() -> ctypes.CDLL:
     lib.mote_stage_timing.argtypes = [c_int]
     lib.mote_stage_times.restype = c_int
     lib.mote_stage_times.argtypes = [POINTER(c_float)]
+    lib.mote_event_pair_overhead.restype = c_int
+    lib.mote_event_pair_overhead.argtypes = [POINTER(c_float), c_void_p]
     lib.mote_tuning_set.restype = c_int
     lib.mote_tuning_set.argtypes = [c_int, c_int]
     lib.mote_calib_copy.restype = c_int
@@ -390,6 +392,13 @@ def mote_stage_times() -> dict:
     buf = (c_float * len(STAGE_NAMES))()
     _check(load_library().mote_stage_times(buf), "mote_stage_times")
     return {n: float(buf[i]) for i, n in enumerate(STAGE_NAMES)}
+
+
+def mote_event_pair_overhead() -> float:
+    """Milliseconds two back-to-back event records on the current stream read with no kernel between them."""
+    v = c_float()
+    _check(load_library().mote_event_pair_overhead(ctypes.byref(v), _stream()), "mote_event_pair_overhead")
+    return float(v.value)
 
 
 def mote_tuning_set(knob, value: int) -> None:

@@ -521,6 +521,27 @@ mote_status mote_stage_times(float* ms_host) {
   return MOTE_OK;
 }
 
+mote_status mote_event_pair_overhead(float* ms_host, void* hip_stream) {
+  if (!ms_host) return MOTE_ERR_INVALID_ARG;
+  // What two consecutive event records read when nothing runs between them: the share of a stage
+  // time that is not the kernel.  Median of 33 pairs on the caller's stream.
+  constexpr int kPairs = 33;
+  static hipEvent_t ev[kPairs + 1];
+  static bool ready = false;
+  if (!ready) {
+    for (int i = 0; i <= kPairs; ++i) MOTE_HIP(hipEventCreate(&ev[i]));
+    ready = true;
+  }
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  for (int i = 0; i <= kPairs; ++i) MOTE_HIP(hipEventRecord(ev[i], stream));
+  MOTE_HIP(hipEventSynchronize(ev[kPairs]));
+  float d[kPairs];
+  for (int i = 0; i < kPairs; ++i) MOTE_HIP(hipEventElapsedTime(&d[i], ev[i], ev[i + 1]));
+  std::sort(d, d + kPairs);
+  *ms_host = d[kPairs / 2];
+  return MOTE_OK;
+}
+
 mote_status mote_tuning_set(int knob_id, int value) {
   if (knob_id < 0 || knob_id >= mote::kKnobCount) return MOTE_ERR_INVALID_ARG;
   mote::g_knobs[knob_id] = value;
