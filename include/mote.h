@@ -282,7 +282,9 @@ enum {
   MOTE_KNOB_DYNAMIC_ROUNDS = 8,      /* tiles per workgroup from which tiles are drawn (4)             */
   MOTE_KNOB_DECODE_VARIANT = 9,      /* 1 / 0 forces / forbids the wave-streaming decode kernel (-1)   */
   MOTE_KNOB_ROUTER_TOKEN_BLOCKS = 10,/* largest T with one token per router workgroup (256)            */
-  MOTE_N_KNOBS = 11
+  MOTE_KNOB_DOWN_SPLIT_TILES = 11,   /* routed down projection: two K planes while it has fewer
+                                        128 x 128 output tiles than this (600)                         */
+  MOTE_N_KNOBS = 12
 };
 mote_status mote_tuning_set(int knob, int value);
 

@@ -19,6 +19,7 @@ enum Knob {
   kKnobDynamicRounds,        // tiles per workgroup from which tiles are drawn
   kKnobDecodeVariant,        // 1 / 0 forces / forbids the wave-streaming routed decode kernel
   kKnobRouterTokenBlocks,    // largest T with one token per router workgroup
+  kKnobDownSplitTiles,       // routed down projection: two K planes while there are fewer 128 x 128 output tiles than this
   kKnobCount
 };
 int knob(int id);

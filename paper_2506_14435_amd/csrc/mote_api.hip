@@ -12,7 +12,7 @@ namespace mote {
 static int g_knobs[kKnobCount] = {
     /* NoFork */ 0, /* ForkMinLog2 */ 29, /* EventFence */ 0, /* QuantWide */ 0, /* RoutedVariant */ 0,
     /* RoutedDownVariant */ -1, /* SharedVariant */ 0, /* GroupM */ 2, /* DynamicRounds */ 4,
-    /* DecodeVariant */ -1, /* RouterTokenBlocks */ 256};
+    /* DecodeVariant */ -1, /* RouterTokenBlocks */ 256, /* DownSplitTiles */ 600};
 int knob(int id) { return (id >= 0 && id < kKnobCount) ? g_knobs[id] : -1; }
 }  // namespace mote
 

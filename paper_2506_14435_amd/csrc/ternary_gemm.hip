@@ -26,6 +26,7 @@
 #include <stdlib.h>
 
 #include <algorithm>
+#include <type_traits>
 #include "common.h"
 #include "launch.h"
 
@@ -87,7 +88,10 @@ __device__ __forceinline__ int lds_a_offset(int row, int chunk) { return row * 1
 // about 800 cycles per K step) before it reaches its first MFMA.
 constexpr int kFixedShares = 1 << 20;   // n_static from which every tile of a workgroup is fixed
 
-template <typename Cfg>
+// SKIP: 32-row fragments of a partly filled row tile that hold no rows are neither read nor
+// contracted.  The conditions cost full tiles about 8 % (scalar branches inside the K loop), so the
+// variant is launched only when most row tiles are partly filled (few rows per expert).
+template <typename Cfg, bool SKIP>
 __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_kernel(RoutedGemmArgs a, int n_ntiles, int kplanes, int ktp, int group_m, int n_static) {
   constexpr int NMAT = Cfg::NMAT, BM_W = Cfg::BM_W, BN_W = Cfg::BN_W;
   constexpr int BM = Cfg::BM, BN = Cfg::BN, THREADS = Cfg::THREADS;
@@ -419,6 +423,10 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
     }
     // row gather of the next tile: the indices are in registers when the K loop ends
     if (has_next) MOTE_GATHER(row02, rows2);
+    // Rows of this wavefront's block that exist: the last row tile of an expert is half empty on
+    // average, and a 32-row fragment without rows is neither read nor contracted (its MFMA slots go
+    // to the other wavefronts of the SIMD).  Wavefront-uniform, so these are scalar branches.
+    const int rows_w = SKIP ? __builtin_amdgcn_readfirstlane(rows - (wave_u % Cfg::WAVES_M) * BM_W * 32) : BM_W * 32;
 
     // (2) K loop.  K step kt contracts stage st_cur while the loads of kt+2 are issued, one
     // quarter of them per 32-channel sub-step (a burst of loads right after the barrier fills
@@ -436,7 +444,7 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
       v4i af[2][BM_W];
 #pragma unroll
       for (int i = 0; i < BM_W; ++i)
-        af[0][i] = *reinterpret_cast<const v4i*>(st + lds_a_offset(a_row_base + i * 32, g));
+        if (!SKIP || i * 32 < rows_w) af[0][i] = *reinterpret_cast<const v4i*>(st + lds_a_offset(a_row_base + i * 32, g));
 #pragma unroll
       for (int s = 0; s < 4; ++s) {
         if (pf) {   // quarter s of the loads of K step kt+2
@@ -450,17 +458,21 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
         if (s < 3) {
 #pragma unroll
           for (int i = 0; i < BM_W; ++i)
-            af[(s + 1) & 1][i] = *reinterpret_cast<const v4i*>(st + lds_a_offset(a_row_base + i * 32, 2 * (s + 1) + g));
+            if (!SKIP || i * 32 < rows_w)
+              af[(s + 1) & 1][i] = *reinterpret_cast<const v4i*>(st + lds_a_offset(a_row_base + i * 32, 2 * (s + 1) + g));
         }
+        if (!SKIP || rows_w > 0) {
 #pragma unroll
-        for (int m = 0; m < NMAT; ++m)
+          for (int m = 0; m < NMAT; ++m)
 #pragma unroll
-          for (int f = 0; f < BN_W; ++f) {
-            const v4i bf = unpack_codes(wf[m][f][s]);
+            for (int f = 0; f < BN_W; ++f) {
+              const v4i bf = unpack_codes(wf[m][f][s]);
 #pragma unroll
-            for (int i = 0; i < BM_W; ++i)
-              acc[m][i][f] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bf, af[s & 1][i], acc[m][i][f], 0, 0, 0);
-          }
+              for (int i = 0; i < BM_W; ++i)
+                if (!SKIP || i * 32 < rows_w)
+                  acc[m][i][f] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bf, af[s & 1][i], acc[m][i][f], 0, 0, 0);
+            }
+        }
         __builtin_amdgcn_sched_barrier(0);  // keep each quarter's loads with its quarter
       }
       // K step kt+1 landed everywhere (kt+2 stays in flight); after the last step: every
@@ -506,6 +518,7 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
     const int rd_row = lane_e / LANES_PER_ROW, rd_chunk = lane_e % LANES_PER_ROW;
 #pragma unroll
     for (int i = 0; i < BM_W; ++i) {
+      if (SKIP && i * 32 >= rows_w) continue;   // a fragment without rows has nothing to store
       const int rl = wm * BM_W * 32 + i * 32 + r32e;
       float sg = 0.0f, su = 0.0f;
       if constexpr (Cfg::MODE == 0) {
@@ -625,7 +638,7 @@ template <typename Cfg>
 static int resident_blocks() {
   static int n = 0;
   if (n == 0) {
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, routed_gemm_kernel<Cfg>, Cfg::THREADS, 0) != hipSuccess || n <= 0)
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, routed_gemm_kernel<Cfg, false>, Cfg::THREADS, 0) != hipSuccess || n <= 0)
       n = Cfg::MIN_BLOCKS;
   }
   return n;
@@ -660,7 +673,13 @@ static hipError_t launch_cfg(const RoutedGemmArgs& a, int kplanes, hipStream_t s
   // (max_tiles bounds the row tiles for any routing; the expected number is rows / tile_m plus a few)
   const int64_t expected = std::min<int64_t>(a.max_tiles, a.out_rows / a.tile_m + 8) * n_ntiles * kplanes;
   const int n_static = expected >= routed_dynamic_rounds() * blocks ? 1 : kAllStatic;
-  routed_gemm_kernel<Cfg><<<static_cast<unsigned>(blocks), Cfg::THREADS, 0, stream>>>(a, n_ntiles, kplanes, ktp, tile_group_m(), n_static);
+  // few rows per expert: most row tiles are partly filled (T = 512 at the 3B width with 16 experts:
+  // gate-up 88.8 -> 73.2 us, down 47.6 -> 40.1 us; T = 1024: 134 -> 116 us)
+  const int64_t n_experts = std::max<int64_t>(1, a.max_tiles - a.out_rows / a.tile_m);
+  if (a.out_rows <= 160 * n_experts)
+    routed_gemm_kernel<Cfg, true><<<static_cast<unsigned>(blocks), Cfg::THREADS, 0, stream>>>(a, n_ntiles, kplanes, ktp, tile_group_m(), n_static);
+  else
+    routed_gemm_kernel<Cfg, false><<<static_cast<unsigned>(blocks), Cfg::THREADS, 0, stream>>>(a, n_ntiles, kplanes, ktp, tile_group_m(), n_static);
   return hipGetLastError();
 }
 
@@ -691,6 +710,10 @@ int routed_down_planes(int T, int k, int E, int d, int F) {
   const int64_t tiles = mtiles * ((d + 127) / 128);
   const int KT = F >> 7;
   int planes = tiles > 0 ? static_cast<int>((512 + tiles / 2) / tiles) : 1;
+  // between one and two workgroups per CU's worth of 128 x 128 tiles, two planes of 128-wide tiles fill the
+  // chip better than one plane of 256-wide ones (3B width, 16 experts: T = 1024 398 -> 367 us per forward,
+  // T = 1536 520 -> 503 us; from T = 2048 on, 640 tiles, no gain, and a loss at T = 3072)
+  if (planes == 1 && tiles < knob(kKnobDownSplitTiles)) planes = 2;
   if (planes > F / 2048) planes = F / 2048;   // every plane adds an int32 partial output (C2, F = 4864: 2 planes 30 us, 3 planes 41 us)
   int fill = tiles > 0 ? static_cast<int>(256 / tiles) : 1;   // few tiles: up to one workgroup per CU, planes of at least 4 K steps
   if (fill > KT / 4) fill = KT / 4;
