@@ -88,14 +88,18 @@ __device__ __forceinline__ int lds_a_offset(int row, int chunk) { return row * 1
 // about 800 cycles per K step) before it reaches its first MFMA.
 constexpr int kFixedShares = 1 << 20;   // n_static from which every tile of a workgroup is fixed
 
-// SKIP: 32-row fragments of a partly filled row tile that hold no rows are neither read nor
-// contracted.  The conditions cost full tiles about 8 % (scalar branches inside the K loop), so the
-// variant is launched only when most row tiles are partly filled (few rows per expert).
-template <typename Cfg, bool SKIP>
+// SKIP_: what a partly filled row tile (the last one of an expert, half empty on average) saves.
+//   2: every 32-row fragment that holds no rows is neither read nor contracted.  The conditions
+//      cost full tiles about 8 % (scalar branches between the MFMAs), so this variant is launched
+//      only when most row tiles are partly filled (few rows per expert).
+//   1: only a wavefront whose whole block of rows is empty idles through the K steps (it still
+//      issues its share of the loads and meets the barriers): one scalar branch per K step.
+template <typename Cfg, int SKIP_>
 __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_kernel(RoutedGemmArgs a, int n_ntiles, int kplanes, int ktp, int group_m, int n_static) {
   constexpr int NMAT = Cfg::NMAT, BM_W = Cfg::BM_W, BN_W = Cfg::BN_W;
   constexpr int BM = Cfg::BM, BN = Cfg::BN, THREADS = Cfg::THREADS;
   constexpr int A_BYTES = Cfg::A_BYTES, STAGE_BYTES = Cfg::STAGE_BYTES;
+  constexpr bool SKIP = SKIP_ == 2;                 // fragment-level tests inside the K loop
   constexpr int NB = BN / 32;                       // 32-channel blocks of the tile
   constexpr int W_PER_WAVE = Cfg::W_PER_WAVE;       // weight fragments a wavefront requests per K step
   constexpr int NLOAD = Cfg::A_PASSES + W_PER_WAVE; // vector-memory operations a wavefront issues per K step
@@ -426,13 +430,25 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
     // Rows of this wavefront's block that exist: the last row tile of an expert is half empty on
     // average, and a 32-row fragment without rows is neither read nor contracted (its MFMA slots go
     // to the other wavefronts of the SIMD).  Wavefront-uniform, so these are scalar branches.
-    const int rows_w = SKIP ? __builtin_amdgcn_readfirstlane(rows - (wave_u % Cfg::WAVES_M) * BM_W * 32) : BM_W * 32;
+    const int rows_w = SKIP_ != 0 ? __builtin_amdgcn_readfirstlane(rows - (wave_u % Cfg::WAVES_M) * BM_W * 32) : BM_W * 32;
 
     // (2) K loop.  K step kt contracts stage st_cur while the loads of kt+2 are issued, one
     // quarter of them per 32-channel sub-step (a burst of loads right after the barrier fills
     // the CU's vector-memory queue and stalls every wavefront in issue), into the stage that the
     // barrier at the end of step kt-1 released.
-    for (int kt = 0; kt < ktl; ++kt) {
+    const int ktl_mm = (SKIP_ == 1 && rows_w <= 0) ? 0 : ktl;   // a wavefront without rows contracts nothing ...
+    for (int kt = 0; kt < ktl - ktl_mm; ++kt) {                  // ... it only issues its share of the loads and meets the barriers
+      const bool pf = kt + 2 < ktl;
+      if (pf) {
+#pragma unroll
+        for (int p = 0; p < Cfg::A_PASSES; ++p) MOTE_DMA_A(st_nx2, kt + 2, p);
+#pragma unroll
+        for (int i = 0; i < W_PER_WAVE; ++i) MOTE_DMA_W(st_nx2, kt + 2, i);
+      }
+      MOTE_WAIT_BARRIER(pf);
+      const int t = st_cur; st_cur = st_nxt; st_nxt = st_nx2; st_nx2 = t;
+    }
+    for (int kt = 0; kt < ktl_mm; ++kt) {
       const bool pf = kt + 2 < ktl;
       const unsigned char* const st = s_lds + st_cur;
       u4 wf[NMAT][BN_W];
@@ -518,7 +534,7 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void routed_gemm_ker
     const int rd_row = lane_e / LANES_PER_ROW, rd_chunk = lane_e % LANES_PER_ROW;
 #pragma unroll
     for (int i = 0; i < BM_W; ++i) {
-      if (SKIP && i * 32 >= rows_w) continue;   // a fragment without rows has nothing to store
+      if ((SKIP && i * 32 >= rows_w) || (SKIP_ == 1 && rows_w <= 0)) continue;   // nothing to store
       const int rl = wm * BM_W * 32 + i * 32 + r32e;
       float sg = 0.0f, su = 0.0f;
       if constexpr (Cfg::MODE == 0) {
@@ -638,7 +654,7 @@ template <typename Cfg>
 static int resident_blocks() {
   static int n = 0;
   if (n == 0) {
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, routed_gemm_kernel<Cfg, false>, Cfg::THREADS, 0) != hipSuccess || n <= 0)
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, routed_gemm_kernel<Cfg, 1>, Cfg::THREADS, 0) != hipSuccess || n <= 0)
       n = Cfg::MIN_BLOCKS;
   }
   return n;
@@ -677,9 +693,9 @@ static hipError_t launch_cfg(const RoutedGemmArgs& a, int kplanes, hipStream_t s
   // gate-up 88.8 -> 73.2 us, down 47.6 -> 40.1 us; T = 1024: 134 -> 116 us)
   const int64_t n_experts = std::max<int64_t>(1, a.max_tiles - a.out_rows / a.tile_m);
   if (a.out_rows <= 160 * n_experts)
-    routed_gemm_kernel<Cfg, true><<<static_cast<unsigned>(blocks), Cfg::THREADS, 0, stream>>>(a, n_ntiles, kplanes, ktp, tile_group_m(), n_static);
+    routed_gemm_kernel<Cfg, 2><<<static_cast<unsigned>(blocks), Cfg::THREADS, 0, stream>>>(a, n_ntiles, kplanes, ktp, tile_group_m(), n_static);
   else
-    routed_gemm_kernel<Cfg, false><<<static_cast<unsigned>(blocks), Cfg::THREADS, 0, stream>>>(a, n_ntiles, kplanes, ktp, tile_group_m(), n_static);
+    routed_gemm_kernel<Cfg, 1><<<static_cast<unsigned>(blocks), Cfg::THREADS, 0, stream>>>(a, n_ntiles, kplanes, ktp, tile_group_m(), n_static);
   return hipGetLastError();
 }
 
