@@ -68,6 +68,17 @@ __device__ __forceinline__ int quant_i8(float x, float s) {
   return static_cast<int>(r);
 }
 
+// One 32-bit word of the packed ternary format = 16 codes t+1, code i at bit 8*(i%4) + 2*(i/4):
+// (w >> 2j) & 0x03030303 are the four int8 operand registers of one v_mfma_i32_32x32x32_i8.
+__device__ __forceinline__ v4i unpack_codes(uint32_t w) {
+  v4i b;
+  b.x = static_cast<int>(w & 0x03030303u);
+  b.y = static_cast<int>((w >> 2) & 0x03030303u);
+  b.z = static_cast<int>((w >> 4) & 0x03030303u);
+  b.w = static_cast<int>((w >> 6) & 0x03030303u);
+  return b;
+}
+
 // Load of a wavefront-uniform value through the constant address space: a scalar load
 // (s_load, counted by lgkmcnt) instead of a vector-memory operation.  Only for memory that no
 // kernel writes while this one runs.

@@ -33,15 +33,6 @@ namespace mote {
 
 constexpr int kDecThreads = 256;
 
-__device__ __forceinline__ v4i unpack_codes_dec(uint32_t w) {
-  v4i b;
-  b.x = static_cast<int>(w & 0x03030303u);
-  b.y = static_cast<int>((w >> 2) & 0x03030303u);
-  b.z = static_cast<int>((w >> 4) & 0x03030303u);
-  b.w = static_cast<int>((w >> 6) & 0x03030303u);
-  return b;
-}
-
 // ------------------------------------------------------------------------- routed experts
 template <int MODE>
 __global__ __launch_bounds__(kDecThreads) void routed_decode_kernel(RoutedGemmArgs a, int n_frags, int kc_count,
@@ -114,7 +105,7 @@ __global__ __launch_bounds__(kDecThreads) void routed_decode_kernel(RoutedGemmAr
           for (int s = 0; s < 4; ++s) {
 #pragma unroll
             for (int m = 0; m < NMAT; ++m)
-              acc[m] = __builtin_amdgcn_mfma_i32_32x32x32_i8(unpack_codes_dec(wr[j][m][s]), ar[j][s], acc[m], 0, 0, 0);
+              acc[m] = __builtin_amdgcn_mfma_i32_32x32x32_i8(unpack_codes(wr[j][m][s]), ar[j][s], acc[m], 0, 0, 0);
           }
           const int nx = base + j + PD;
           if (nx < nsteps) {
@@ -258,7 +249,7 @@ __global__ __launch_bounds__(kDecThreads, 2) void routed_stream_kernel(RoutedGem
       if (s < nsteps) {                                                                                   \
         _Pragma("unroll") for (int b = 0; b < 4; ++b)                                                     \
           _Pragma("unroll") for (int m = 0; m < NMAT; ++m)                                                \
-            acc[m] = __builtin_amdgcn_mfma_i32_32x32x32_i8(unpack_codes_dec(w_[m][s][b]), ar[s][b],       \
+            acc[m] = __builtin_amdgcn_mfma_i32_32x32x32_i8(unpack_codes(w_[m][s][b]), ar[s][b],       \
                                                            acc[m], 0, 0, 0);                              \
       }                                                                                                   \
     if ((nxt_) < nf_end) { MOTE_LOADW(w_, (nxt_)); }                                                      \
@@ -451,7 +442,7 @@ __global__ __launch_bounds__(kDecThreads, 2) void routed_wave_kernel(RoutedGemmA
           const v4i af = *reinterpret_cast<const v4i*>(s_a + ((kt * 8 + 2 * s + g) * 32 + r32) * 16);
 #pragma unroll
           for (int m = 0; m < NMAT; ++m)
-            acc[m] = __builtin_amdgcn_mfma_i32_32x32x32_i8(unpack_codes_dec(wr[kt % D][m][s]), af, acc[m], 0, 0, 0);
+            acc[m] = __builtin_amdgcn_mfma_i32_32x32x32_i8(unpack_codes(wr[kt % D][m][s]), af, acc[m], 0, 0, 0);
         }
         // refill the slot: step kt + D of this fragment, or step kt + D - 16 of the next one
 #pragma unroll

@@ -58,15 +58,6 @@ struct RoutedCfg {
   static_assert(64 % (PATCH_F * 32 * OUT_BYTES / 16) == 0, "an epilogue read covers whole rows");
 };
 
-__device__ __forceinline__ v4i unpack_codes(uint32_t w) {
-  v4i b;
-  b.x = static_cast<int>(w & 0x03030303u);
-  b.y = static_cast<int>((w >> 2) & 0x03030303u);
-  b.z = static_cast<int>((w >> 4) & 0x03030303u);
-  b.w = static_cast<int>((w >> 6) & 0x03030303u);
-  return b;
-}
-
 #ifdef MOTE_TRACE
 __device__ unsigned long long g_trace[1024 * 32 * 8];
 #define MOTE_TP(k_) if (Cfg::MODE == MOTE_TRACE && tid == 0 && tile_it < 32) g_trace[(blockIdx.x * 32 + tile_it) * 8 + (k_)] = __builtin_readcyclecounter();
@@ -660,7 +651,7 @@ static int resident_blocks() {
   return n;
 }
 
-// Row tiles per band of the tile order (environment variable MOTE_GROUP_M, read once; a value
+// Row tiles per band of the tile order (knob group_m; a value
 // larger than the number of row tiles gives the plain row-tile-fastest sweep).
 int tile_group_m() {
   // default 2; steady state, 2 against 8: T = 2048 at the 3B width 0.464 vs 0.474 ms, C5 11.60 vs 11.65 ms, C2 equal; 1 costs 3 % at the 0.5B width
@@ -699,7 +690,7 @@ static hipError_t launch_cfg(const RoutedGemmArgs& a, int kplanes, hipStream_t s
   return hipGetLastError();
 }
 
-// Tuning switch (environment variable MOTE_ROUTED_VARIANT, read once): selects the tile
+// Knob routed_variant: selects the tile
 // configuration of the large-batch kernels.
 static int routed_variant() { return knob(kKnobRoutedVariant); }
 
