@@ -9,6 +9,17 @@ import torch
 import workloads as W
 
 
+# Routed-expert weights depend on (seed, shape) only, not on the batch: configurations that differ in
+# the number of tokens share them.  Small caches keep the full-size tests from drawing and ternarising
+# the same 48 matrices again (device: packed words and scales; host: the oracle's ternary matrices).
+_GPU_WEIGHTS = {}
+_ORACLE_EXPERTS = {}
+
+
+def _weights_key(cfg, binary):
+    return (cfg.seed, cfg.d_model, cfg.d_ff, cfg.n_experts, cfg.sigma_latent, bool(binary))
+
+
 class GpuProblem:
     """Device side of a workload: weights packed by mote_pack_ternary on the GPU."""
 
@@ -23,18 +34,26 @@ class GpuProblem:
         self.bias = None if bias is None else bias.to(dev)
         self.shared = tuple(t.to(dev) for t in W.make_shared(cfg))
         words = d * f // 16
-        self.wt = [torch.empty(e, words, dtype=torch.int32, device=dev) for _ in range(3)]
-        self.alpha = torch.empty(e, 3, dtype=torch.float32, device=dev)
-        tmp_alpha = torch.empty(1, dtype=torch.float32, device=dev)
-        for ex in range(e):
-            for m in range(3):
-                if latent_source is None:
-                    lat = W.make_latent(cfg, ex, m).to(dev)
-                else:
-                    lat = latent_source(ex, m)
-                M.mote_pack_ternary(lat, packed=self.wt[m][ex], alpha=tmp_alpha, binary=binary_experts)
-                self.alpha[ex, m] = tmp_alpha[0]
-                del lat
+        key = _weights_key(cfg, binary_experts) + (str(dev),)
+        cached = _GPU_WEIGHTS.get(key) if latent_source is None else None
+        if cached is not None:
+            self.wt, self.alpha = cached
+        else:
+            self.wt = [torch.empty(e, words, dtype=torch.int32, device=dev) for _ in range(3)]
+            self.alpha = torch.empty(e, 3, dtype=torch.float32, device=dev)
+            tmp_alpha = torch.empty(1, dtype=torch.float32, device=dev)
+            for ex in range(e):
+                for m in range(3):
+                    if latent_source is None:
+                        lat = W.make_latent(cfg, ex, m).to(dev)
+                    else:
+                        lat = latent_source(ex, m)
+                    M.mote_pack_ternary(lat, packed=self.wt[m][ex], alpha=tmp_alpha, binary=binary_experts)
+                    self.alpha[ex, m] = tmp_alpha[0]
+                    del lat
+            if latent_source is None and e * d * f >= 5e7:       # only the large shapes are worth keeping
+                _GPU_WEIGHTS.clear()                              # one large shape at a time
+                _GPU_WEIGHTS[key] = (self.wt, self.alpha)
         self.shared_bits = shared_bits
         self.shared_scales = None
         self.shared_bf16 = self.shared
@@ -63,7 +82,14 @@ class OracleProblem:
             from oracle import mote_oracle as O
             q = [O.rtn_quantize(w, shared_bits) for w in self.shared]
             self.shared = (*q[0], *q[1], *q[2])
-        self._experts = {}
+        key = _weights_key(cfg, binary_experts)
+        if cfg.n_experts * cfg.d_model * cfg.d_ff >= 5e7:
+            if key not in _ORACLE_EXPERTS:
+                _ORACLE_EXPERTS.clear()                           # one large shape at a time
+                _ORACLE_EXPERTS[key] = {}
+            self._experts = _ORACLE_EXPERTS[key]
+        else:
+            self._experts = {}
 
     def experts(self, e: int):
         from oracle import mote_oracle as O
