@@ -4,7 +4,7 @@ One step = one pass of the whole hot path (router + Q_a(x), dispatch, routed gat
 with SwiGLU, Q_a(h), routed down GEMM, shared FFN, combine) over one batch of synthetic
 tokens whose inputs and weights already sit in HBM.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload headline|c2|c3|c5|c4_T<T>_n<n>]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload headline|c2|c3|c5|c4_T<T>_n<n>|<c2|c3|c5|p05|p15|p3>_T<T>]
 
 Without --workload the timed workload is the prefill shape (c3: d=2048, F=11008, E=16, top-2,
 T=8192); the decode shapes (c4) and the skewed shape (c5) are measured after it and ride along in
@@ -36,8 +36,10 @@ def pick_config(name: str):
         return W.C2
     if name == "c3":
         return W.C3
-    if name.startswith("c3_T"):          # the 3B width at another batch size (mid-size prefill chunks)
-        return W.C3.with_tokens(int(name[4:]), name=f"c3_qwen3b_T{int(name[4:])}")
+    if "_T" in name and name.split("_T")[0] in ("c2", "c3", "c5", "p05", "p15", "p3"):   # a shape at another batch size
+        base, n_tok = name.split("_T")
+        cfg = pick_config(base)
+        return cfg.with_tokens(int(n_tok), name=f"{cfg.name.replace('_prefill', '')}_T{int(n_tok)}")
     if name == "c5":
         return W.C5
     if name in ("p05", "p15", "p3"):   # the paper's own layer: E = 4, top-1, T = 2048

@@ -284,7 +284,10 @@ enum {
   MOTE_KNOB_ROUTER_TOKEN_BLOCKS = 10,/* largest T with one token per router workgroup (256)            */
   MOTE_KNOB_DOWN_SPLIT_TILES = 11,   /* routed down projection: two K planes while it has fewer
                                         128 x 128 output tiles than this (600)                         */
-  MOTE_N_KNOBS = 12
+  MOTE_KNOB_MID_ROWS_LO = 12,        /* 64-row plan tiles (wave-streaming kernel) when an expert sees on
+                                        average more than this many rows (31) ...                      */
+  MOTE_KNOB_MID_ROWS_HI = 13,        /* ... and at most this many (60); lo >= hi switches them off     */
+  MOTE_N_KNOBS = 14
 };
 mote_status mote_tuning_set(int knob, int value);
 

@@ -317,22 +317,30 @@ __global__ __launch_bounds__(kDecThreads, 2) void routed_stream_kernel(RoutedGem
 // order, so "all but the ring's loads" retires the plane while the weights keep streaming.
 #ifdef MOTE_TRACE_DEC
 __device__ unsigned long long g_dtrace[1024 * 4 * 24];
-#define MOTE_DTP(k_) if (MODE == MOTE_TRACE_DEC && lane == 0 && (k_) < 24) g_dtrace[(blockIdx.x * 4 + wave) * 24 + (k_)] = wall_clock64();
+#define MOTE_DTP(k_) if (MODE == MOTE_TRACE_DEC && lane == 0 && (k_) < 24) g_dtrace[(blockIdx.x * NW + wave) * 24 + (k_)] = wall_clock64();
 extern "C" int mote_debug_dtrace(void* dst, size_t bytes) { return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_dtrace), bytes); }
 #else
 #define MOTE_DTP(k_)
 #endif
 
-template <int MODE>
-__global__ __launch_bounds__(kDecThreads, 2) void routed_wave_kernel(RoutedGemmArgs a, int n_frags, int kc_count) {
+// MF: 32-row fragments of a row tile (plan tiles of 32 * MF rows).  MF = 1: two workgroups of four
+// wavefronts per CU, 64 KiB plane each.  MF = 2 (experts with some tens of rows each): one workgroup
+// of eight wavefronts per CU with a 128 KiB plane; every unpacked weight fragment feeds two MFMAs.
+template <int MODE, int MF>
+__global__ __launch_bounds__(kDecThreads * MF, 2) void routed_wave_kernel(RoutedGemmArgs a, int n_frags, int kc_count) {
   constexpr int NMAT = MODE == 0 ? 2 : 1;
+  constexpr int NT = kDecThreads * MF;                    // threads of the workgroup
+  constexpr int NW = NT / 64;                             // its wavefronts
+  constexpr int ROWS = 32 * MF;                           // rows of the plane
+  constexpr int STEP_BYTES = ROWS * 128;                  // one K step of the plane
   constexpr int D = 8;                                    // K steps of packed weights in flight per wavefront (16 measured no faster)
   constexpr int kBufferFlags = 0x00020000;                // raw buffer, 32-bit data format
   constexpr int kWeightAux = 2;                           // weight loads are non-temporal: every byte is used once (measured: 42 -> 39.5 us)
   constexpr uint32_t kOutOfRange = 0x80000000u;           // lane offset past any buffer of <= 2 GiB
-  // activations of the plane: [K step 16][16-byte chunk 8][row 32][16 bytes]; a quarter wavefront
-  // reads 16 consecutive rows of one chunk = 256 contiguous bytes
-  __shared__ __attribute__((aligned(16))) unsigned char s_a[16 * 8 * 32 * 16];
+  // activations of the plane: [K step 16][block of 8 rows][position 8][row of the block 8][16 bytes],
+  // the 16-byte chunk c of a row sits at position c ^ (block & 1): a quarter wavefront reads one chunk
+  // of 16 consecutive rows = two runs of 128 bytes in different halves of the 64 banks
+  extern __shared__ __attribute__((aligned(16))) unsigned char s_a[];
 
   const int K = a.K, N = a.N, KT = K >> 7;
   const int tid = threadIdx.x, lane = tid & 63;
@@ -340,6 +348,8 @@ __global__ __launch_bounds__(kDecThreads, 2) void routed_wave_kernel(RoutedGemmA
   const int r32 = lane & 31, g = lane >> 5;
   const int64_t expert_words = static_cast<int64_t>(N) * K / 16;
   const uint32_t lds0 = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) unsigned char*)s_a);
+  // MFMA operand of lane (r32, g), fragment f, sub-step s of K step kt: chunk 2s + g of row 32f + r32
+  const int a_lane = (r32 >> 3) * 1024 + (((g ^ ((r32 >> 3) & 1)) * 8 + (r32 & 7)) << 4);
   auto make_rsrc = [&](const void* base, int64_t bytes) {
     const uint64_t p = reinterpret_cast<uint64_t>(base);
     v4i r;
@@ -351,17 +361,33 @@ __global__ __launch_bounds__(kDecThreads, 2) void routed_wave_kernel(RoutedGemmA
   };
   const v4i rsrc_q = make_rsrc(a.q, a.q_rows * K);
   const int groups = load_uniform(a.plan.n_tiles) * kc_count;
+  // Each (row tile, K plane) group is shared evenly by floor(grid / groups) workgroups.  Where that
+  // would leave more than a quarter of the grid idle (MF = 2: one workgroup per CU, groups often
+  // between half the grid and the grid), the (group, fragment) units are cut into equal runs instead
+  // and a workgroup may end one group and start the next (slower per unit: two plane loads).
   const int bpg = max(1, static_cast<int>(gridDim.x) / max(groups, 1));   // workgroups per (row tile, K plane) group
   const int gstride = gridDim.x / bpg;                                     // groups in flight
   const int g0 = blockIdx.x / bpg, part = blockIdx.x - g0 * bpg;
-  if (g0 >= gstride) return;                                               // left-over workgroups
-  const int nf0 = part * n_frags / bpg;
-  const int nf_end = (part + 1) * n_frags / bpg;
+  const bool even = MF == 2 && static_cast<int64_t>(bpg) * min(groups, gstride) * 4 < static_cast<int64_t>(gridDim.x) * 3;
+  if (!even && g0 >= gstride) return;                                      // left-over workgroups
+  const int64_t units = static_cast<int64_t>(groups) * n_frags;
+  int64_t u = static_cast<int64_t>(blockIdx.x) * units / gridDim.x;
+  const int64_t u_end = static_cast<int64_t>(blockIdx.x + 1) * units / gridDim.x;
   int tp = 0;
   MOTE_DTP(tp) ++tp;
-  for (int grp = g0; grp < groups; grp += gstride) {
+  bool first = true;
+  for (int grp = even ? static_cast<int>(u / n_frags) : g0; even ? u < u_end : grp < groups;) {
     // every wavefront is done with the previous plane (a plain barrier: the loads in flight stay in flight)
-    if (grp != g0) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    if (!first) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    first = false;
+    int nf0, nf_end;
+    if (!even) {
+      nf0 = part * n_frags / bpg;
+      nf_end = (part + 1) * n_frags / bpg;
+    } else {
+      nf0 = static_cast<int>(u - static_cast<int64_t>(grp) * n_frags);
+      nf_end = static_cast<int>(min(static_cast<int64_t>(n_frags), nf0 + (u_end - u)));
+    }
     const int mt = grp / kc_count, kc = grp - mt * kc_count;
     const int expert = load_uniform(a.plan.tile_expert + mt);
     const int row0 = load_uniform(a.plan.tile_row0 + mt);
@@ -372,22 +398,34 @@ __global__ __launch_bounds__(kDecThreads, 2) void routed_wave_kernel(RoutedGemmA
     const int nsteps = (kc + 1) * KT / kc_count - step0;
 
     // ---- activation plane into LDS, requested first ----
-    const int slot = row0 + min(r32, rows - 1);
-    const int src = a.gather ? a.gather[slot] : slot;
     {
-      // rows past the end of the tile are not fetched (their accumulator rows are never stored)
-      const uint32_t voff = r32 < rows ? static_cast<uint32_t>(src) * static_cast<uint32_t>(K) + step0 * 128 + g * 16
-                                       : kOutOfRange;
-      // load i covers K step i/4, chunks 2*(i%4) and 2*(i%4)+1 (lane l: chunk + l/32, row l%32)
-      for (int i = wave; i < nsteps * 4; i += 4) {
-        const uint32_t dst = lds0 + static_cast<uint32_t>(((i >> 2) * 8 + 2 * (i & 3)) * 512);
-        const int soff = (i >> 2) * 128 + (i & 3) * 32;
+      // A load fills 1 KiB of the plane with the 128 bytes of a K step of eight rows (lane l: row
+      // l % 8 of the block, position l / 8): whole cache lines.  Wavefront w loads row block w of
+      // every K step.  Rows past the end of the tile are not fetched (their accumulator rows are
+      // never stored).
+      const int lrow = wave * 8 + (lane & 7);
+      const int lslot = row0 + min(lrow, rows - 1);
+      const int lsrc = a.gather ? a.gather[lslot] : lslot;
+      const uint32_t voff = lrow < rows ? static_cast<uint32_t>(lsrc) * static_cast<uint32_t>(K) + step0 * 128 +
+                                              (((lane >> 3) ^ (wave & 1)) << 4)
+                                        : kOutOfRange;
+      for (int st = 0; st < nsteps; ++st) {
+        const uint32_t dst = lds0 + static_cast<uint32_t>(st * STEP_BYTES + wave * 1024);
+        const int soff = st * 128;
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                      :: "s"(dst), "v"(voff), "s"(rsrc_q), "s"(soff) : "memory");
       }
     }
-    const float m_beta = a.beta[src];
-    const int m_rs = a.rowsum[src];
+    // rows of this lane in the MFMA layout: fragment f holds row 32 f + r32
+    float m_beta[MF];
+    int m_rs[MF];
+#pragma unroll
+    for (int f = 0; f < MF; ++f) {
+      const int slot = row0 + min(f * 32 + r32, rows - 1);
+      const int src = a.gather ? a.gather[slot] : slot;
+      m_beta[f] = a.beta[src];
+      m_rs[f] = a.rowsum[src];
+    }
 
     // ---- weight ring ----
     __amdgpu_buffer_rsrc_t rw[NMAT];
@@ -398,7 +436,7 @@ __global__ __launch_bounds__(kDecThreads, 2) void routed_wave_kernel(RoutedGemmA
                                                 static_cast<int>(expert_words * 4), kBufferFlags);
     const uint32_t w_lane = lane * 16;
     u4 wr[D][NMAT];
-    int nf = nf0 + wave;   // this wavefront's fragments: nf0 + wave, + 4, ...
+    int nf = nf0 + wave;   // this wavefront's fragments: nf0 + wave, + NW, ...
     {   // the first D steps of the first fragment (out of range if this wavefront has none)
       const uint32_t oob = nf < nf_end ? 0u : kOutOfRange;
 #pragma unroll
@@ -410,15 +448,20 @@ __global__ __launch_bounds__(kDecThreads, 2) void routed_wave_kernel(RoutedGemmA
     }
 
     // steps past the end of the contraction contribute nothing: zero activations
-    for (int i = nsteps * 256 + tid; i < 16 * 256; i += kDecThreads)   // 256 x 16 bytes per K step
+    for (int i = nsteps * 256 * MF + tid; i < 16 * 256 * MF; i += NT)   // 256 * MF x 16 bytes per K step
       *reinterpret_cast<u4*>(s_a + i * 16) = u4{0u, 0u, 0u, 0u};
-    float sg = 0.0f, su = 0.0f;
-    if constexpr (MODE == 0) {
-      const float sx = m_beta / 127.0f;
-      sg = sx * load_uniform(a.alpha + expert * 3 + 0);
-      su = sx * load_uniform(a.alpha + expert * 3 + 1);
+    float sg[MF], su[MF];
+    int corr[MF];
+#pragma unroll
+    for (int f = 0; f < MF; ++f) {
+      sg[f] = 0.0f; su[f] = 0.0f;
+      if constexpr (MODE == 0) {
+        const float sx = m_beta[f] / 127.0f;
+        sg[f] = sx * load_uniform(a.alpha + expert * 3 + 0);
+        su[f] = sx * load_uniform(a.alpha + expert * 3 + 1);
+      }
+      corr[f] = (MODE == 0 || kc == 0) ? m_rs[f] : 0;   // zero-point correction enters one plane only
     }
-    const int corr = (MODE == 0 || kc == 0) ? m_rs : 0;   // zero-point correction enters one plane only
     const __amdgpu_buffer_rsrc_t r_out = __builtin_amdgcn_make_buffer_rsrc(
         MODE == 0 ? static_cast<void*>(a.h) : static_cast<void*>(a.acc_out + static_cast<int64_t>(kc) * a.partial_stride), 0,
         static_cast<int>(a.out_rows * N * (MODE == 0 ? 2 : 4)), kBufferFlags);
@@ -428,21 +471,30 @@ __global__ __launch_bounds__(kDecThreads, 2) void routed_wave_kernel(RoutedGemmA
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" :: "n"(D * NMAT) : "memory");
     MOTE_DTP(tp) ++tp;
 
-    for (; nf < nf_end; nf += 4) {
-      const uint32_t oob_next = nf + 4 < nf_end ? 0u : kOutOfRange;
-      v16i acc[NMAT];
+    for (; nf < nf_end; nf += NW) {
+      const uint32_t oob_next = nf + NW < nf_end ? 0u : kOutOfRange;
+      v16i acc[NMAT][MF];
 #pragma unroll
       for (int m = 0; m < NMAT; ++m)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[m][v] = 0;
+        for (int f = 0; f < MF; ++f)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) acc[m][f][v] = 0;
 #pragma unroll
       for (int kt = 0; kt < 16; ++kt) {
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-          const v4i af = *reinterpret_cast<const v4i*>(s_a + ((kt * 8 + 2 * s + g) * 32 + r32) * 16);
+          v4i af[MF];
 #pragma unroll
-          for (int m = 0; m < NMAT; ++m)
-            acc[m] = __builtin_amdgcn_mfma_i32_32x32x32_i8(unpack_codes(wr[kt % D][m][s]), af, acc[m], 0, 0, 0);
+          for (int f = 0; f < MF; ++f)
+            af[f] = *reinterpret_cast<const v4i*>(s_a + kt * STEP_BYTES + f * 4096 + s * 256 + a_lane);
+#pragma unroll
+          for (int m = 0; m < NMAT; ++m) {
+            const v4i wf = unpack_codes(wr[kt % D][m][s]);
+#pragma unroll
+            for (int f = 0; f < MF; ++f)
+              acc[m][f] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf, af[f], acc[m][f], 0, 0, 0);
+          }
         }
         // refill the slot: step kt + D of this fragment, or step kt + D - 16 of the next one
 #pragma unroll
@@ -453,42 +505,51 @@ __global__ __launch_bounds__(kDecThreads, 2) void routed_wave_kernel(RoutedGemmA
                                                                   (nf * KT + step0 + kt + D) * 1024, kWeightAux);
           else
             wr[kt % D][m] = __builtin_amdgcn_raw_buffer_load_b128(rw[m], w_lane + (kt + D - 16 < nsteps ? oob_next : kOutOfRange),
-                                                                  ((nf + 4) * KT + step0 + kt + D - 16) * 1024, kWeightAux);
+                                                                  ((nf + NW) * KT + step0 + kt + D - 16) * 1024, kWeightAux);
         }
         __builtin_amdgcn_sched_barrier(0);   // one K step at a time: the LDS reads of later steps would pile up in registers
       }
-      // ---- epilogue of the fragment: lane l owns row r32 and channels 8q + 4g .. +3 ----
-      const bool row_ok = r32 < rows;
+      // ---- epilogue of the fragment: lane l owns rows 32 f + r32 and channels 8q + 4g .. +3 ----
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const uint32_t o = static_cast<uint32_t>(row0 + r32) * static_cast<uint32_t>(N) + nf * 32 + 8 * q + 4 * g;
-        int sum[NMAT][4];
+      for (int f = 0; f < MF; ++f) {
+        const bool row_ok = f * 32 + r32 < rows;
 #pragma unroll
-        for (int m = 0; m < NMAT; ++m)
+        for (int q = 0; q < 4; ++q) {
+          const uint32_t o = static_cast<uint32_t>(row0 + f * 32 + r32) * static_cast<uint32_t>(N) + nf * 32 + 8 * q + 4 * g;
+          int sum[NMAT][4];
 #pragma unroll
-          for (int j = 0; j < 4; ++j) sum[m][j] = acc[m][4 * q + j] - corr;
-        if constexpr (MODE == 0) {
-          float hv[4];
+          for (int m = 0; m < NMAT; ++m)
 #pragma unroll
-          for (int j = 0; j < 4; ++j)
-            hv[j] = (static_cast<float>(sum[NMAT - 1][j]) * su) * silu_fast(static_cast<float>(sum[0][j]) * sg);
-          typedef unsigned u2v __attribute__((ext_vector_type(2)));
-          u2v packed;
-          packed.x = cvt_pk_bf16(hv[0], hv[1]);
-          packed.y = cvt_pk_bf16(hv[2], hv[3]);
-          __builtin_amdgcn_raw_buffer_store_b64(packed, r_out, row_ok ? o * 2u : kOutOfRange, 0, 0);
-          if (row_ok && a.tap_gate != nullptr)
-            *reinterpret_cast<int4*>(a.tap_gate + o) = make_int4(sum[0][0], sum[0][1], sum[0][2], sum[0][3]);
-          if (row_ok && a.tap_up != nullptr)
-            *reinterpret_cast<int4*>(a.tap_up + o) =
-                make_int4(sum[NMAT - 1][0], sum[NMAT - 1][1], sum[NMAT - 1][2], sum[NMAT - 1][3]);
-        } else {
-          const u4 d4 = {static_cast<unsigned>(sum[0][0]), static_cast<unsigned>(sum[0][1]),
-                         static_cast<unsigned>(sum[0][2]), static_cast<unsigned>(sum[0][3])};
-          __builtin_amdgcn_raw_buffer_store_b128(d4, r_out, row_ok ? o * 4u : kOutOfRange, 0, 0);
+            for (int j = 0; j < 4; ++j) sum[m][j] = acc[m][f][4 * q + j] - corr[f];
+          if constexpr (MODE == 0) {
+            float hv[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+              hv[j] = (static_cast<float>(sum[NMAT - 1][j]) * su[f]) * silu_fast(static_cast<float>(sum[0][j]) * sg[f]);
+            typedef unsigned u2v __attribute__((ext_vector_type(2)));
+            u2v packed;
+            packed.x = cvt_pk_bf16(hv[0], hv[1]);
+            packed.y = cvt_pk_bf16(hv[2], hv[3]);
+            __builtin_amdgcn_raw_buffer_store_b64(packed, r_out, row_ok ? o * 2u : kOutOfRange, 0, 0);
+            if (row_ok && a.tap_gate != nullptr)
+              *reinterpret_cast<int4*>(a.tap_gate + o) = make_int4(sum[0][0], sum[0][1], sum[0][2], sum[0][3]);
+            if (row_ok && a.tap_up != nullptr)
+              *reinterpret_cast<int4*>(a.tap_up + o) =
+                  make_int4(sum[NMAT - 1][0], sum[NMAT - 1][1], sum[NMAT - 1][2], sum[NMAT - 1][3]);
+          } else {
+            const u4 d4 = {static_cast<unsigned>(sum[0][0]), static_cast<unsigned>(sum[0][1]),
+                           static_cast<unsigned>(sum[0][2]), static_cast<unsigned>(sum[0][3])};
+            __builtin_amdgcn_raw_buffer_store_b128(d4, r_out, row_ok ? o * 4u : kOutOfRange, 0, 0);
+          }
         }
       }
       MOTE_DTP(tp) ++tp;
+    }
+    if (!even) {
+      grp += gstride;
+    } else {
+      u += nf_end - nf0;
+      ++grp;
     }
   }
   MOTE_DTP(tp) ++tp;
@@ -507,6 +568,30 @@ static int device_cus() {
 }
 
 int routed_decode_down_planes(int K) { return ((K >> 7) + 15) / 16; }
+
+template <int MODE, int MF>
+static hipError_t launch_wave(const RoutedGemmArgs& a, int n_frags, int kc, hipStream_t stream) {
+  constexpr int kLds = 16 * 8 * 32 * MF * 16;   // the activation plane
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(routed_wave_kernel<MODE, MF>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  routed_wave_kernel<MODE, MF><<<device_cus() * (MF == 1 ? 2 : 1), kDecThreads * MF, kLds, stream>>>(a, n_frags, kc);
+  return hipGetLastError();
+}
+
+// Plan tiles of 64 rows (experts with some tens of rows each) always run the wave-streaming kernel:
+// the shape must give it whole planes and enough fragments.
+bool routed_mid_kernel_fits(int d, int F) {
+  const int KTg = d >> 7, KTd = F >> 7;
+  if (KTg > 16 || 16 * 3 > KTg * 4) return false;                        // gate-up: one plane, at most a third of it padding
+  const int kc = routed_decode_down_planes(F);
+  if (kc * 16 * 3 > KTd * 4) return false;
+  return F / 32 >= 256 && static_cast<int64_t>(d / 32) * kc >= 192;
+}
 
 // The wave-streaming kernel wants whole 16-step planes (a ragged last plane is padded with
 // zero activations) and enough units to give every wavefront of the grid a fragment.
@@ -527,11 +612,10 @@ hipError_t launch_routed_decode_gate_up(const RoutedGemmArgs& a, hipStream_t str
   const int64_t max_units = static_cast<int64_t>(a.max_tiles) * n_frags;
   int64_t blocks = static_cast<int64_t>(device_cus()) * 4;
   if (blocks > max_units) blocks = max_units;
+  if (a.tile_m == 64) return launch_wave<0, 2>(a, n_frags, 1, stream);
   if (KT <= 16) {
-    if (use_wave_kernel(a, n_frags, 1))
-      routed_wave_kernel<0><<<device_cus() * 2, kDecThreads, 0, stream>>>(a, n_frags, 1);
-    else
-      routed_stream_kernel<0><<<device_cus() * 2, kDecThreads, 0, stream>>>(a, n_frags, 1);
+    if (use_wave_kernel(a, n_frags, 1)) return launch_wave<0, 1>(a, n_frags, 1, stream);
+    routed_stream_kernel<0><<<device_cus() * 2, kDecThreads, 0, stream>>>(a, n_frags, 1);
     return hipGetLastError();
   }
   routed_decode_kernel<0><<<static_cast<unsigned>(blocks), kDecThreads, 0, stream>>>(a, n_frags, 1, (KT + 3) / 4);
@@ -542,10 +626,9 @@ hipError_t launch_routed_decode_down(const RoutedGemmArgs& a, hipStream_t stream
   if (a.max_tiles == 0) return hipSuccess;
   const int n_frags = a.N / 32;
   const int kc = routed_decode_down_planes(a.K);
-  if (use_wave_kernel(a, n_frags, kc))
-    routed_wave_kernel<1><<<device_cus() * 2, kDecThreads, 0, stream>>>(a, n_frags, kc);
-  else
-    routed_stream_kernel<1><<<device_cus() * 3, kDecThreads, 0, stream>>>(a, n_frags, kc);
+  if (a.tile_m == 64) return launch_wave<1, 2>(a, n_frags, kc, stream);
+  if (use_wave_kernel(a, n_frags, kc)) return launch_wave<1, 1>(a, n_frags, kc, stream);
+  routed_stream_kernel<1><<<device_cus() * 3, kDecThreads, 0, stream>>>(a, n_frags, kc);
   return hipGetLastError();
 }
 

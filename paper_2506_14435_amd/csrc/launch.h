@@ -20,6 +20,8 @@ enum Knob {
   kKnobDecodeVariant,        // 1 / 0 forces / forbids the wave-streaming routed decode kernel
   kKnobRouterTokenBlocks,    // largest T with one token per router workgroup
   kKnobDownSplitTiles,       // routed down projection: two K planes while there are fewer 128 x 128 output tiles than this
+  kKnobMidRowsLo,            // 64-row plan tiles for more than this many rows per expert on average ...
+  kKnobMidRowsHi,            // ... and at most this many
   kKnobCount
 };
 int knob(int id);
@@ -84,7 +86,8 @@ int routed_down_tile_n(int planes);
 int routed_down_planes(int T, int k, int E, int d, int F);   // large-batch down: K planes for a shape
 int shared_down_planes(int T, int d, int F);
 int tile_group_m();                      // row tiles per band of the large-batch tile order
-int routed_tile_m(int T, int k, int E);  // plan tile size chosen for a workload (32 = decode kernels)
+int routed_tile_m(int T, int k, int E, int d, int F);  // plan tile size chosen for a workload (32, 64: decode kernels)
+bool routed_mid_kernel_fits(int d, int F);             // the 64-row wave-streaming kernel serves this shape
 
 // Decode (small batch) variants: weights streamed once, K split across wavefronts and, for the
 // down projections, across workgroups into partial planes that the combine kernel adds.

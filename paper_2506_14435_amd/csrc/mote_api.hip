@@ -12,7 +12,8 @@ namespace mote {
 static int g_knobs[kKnobCount] = {
     /* NoFork */ 0, /* ForkMinLog2 */ 29, /* EventFence */ 0, /* QuantWide */ 0, /* RoutedVariant */ 0,
     /* RoutedDownVariant */ -1, /* SharedVariant */ 0, /* GroupM */ 2, /* DynamicRounds */ 4,
-    /* DecodeVariant */ -1, /* RouterTokenBlocks */ 256, /* DownSplitTiles */ 600};
+    /* DecodeVariant */ -1, /* RouterTokenBlocks */ 256, /* DownSplitTiles */ 600, /* MidRowsLo */ 31,
+    /* MidRowsHi */ 60};
 int knob(int id) { return (id >= 0 && id < kKnobCount) ? g_knobs[id] : -1; }
 }  // namespace mote
 
@@ -38,7 +39,7 @@ struct Workspace {
   uint16_t* xn;      // LN(x^a), bf16 [T, d]
   size_t bytes;
   int max_tiles;
-  int tile_m;        // 32: decode kernels, else large-batch kernels
+  int tile_m;        // 32, 64: decode kernels, 128: large-batch kernels
   int d_planes;      // uniform partial planes of the routed down accumulators
   int d_split;       // planes a tile of the last round may be cut into instead (large batch, d_planes == 1)
   int y_planes;      // partial planes of the shared expert output
@@ -73,10 +74,10 @@ Workspace carve(const mote_layer* l, int T, char* base) {
   const size_t R = static_cast<size_t>(T) * l->top_k;
   const size_t d = l->d_model, Fr = l->d_ff_routed, Fs = l->d_ff_shared;
   w.max_tiles = static_cast<int>(R / 32 + l->n_experts);
-  w.tile_m = routed_tile_m(T, l->top_k, l->n_experts);
-  w.d_planes = w.tile_m == 32 ? routed_decode_down_planes(l->d_ff_routed)
+  w.tile_m = routed_tile_m(T, l->top_k, l->n_experts, l->d_model, l->d_ff_routed);
+  w.d_planes = w.tile_m != 128 ? routed_decode_down_planes(l->d_ff_routed)
                               : routed_down_planes(T, l->top_k, l->n_experts, l->d_model, l->d_ff_routed);
-  w.d_split = (w.tile_m != 32 && w.d_planes == 1) ? kSplitMaxPlanes : 1;
+  w.d_split = (w.tile_m == 128 && w.d_planes == 1) ? kSplitMaxPlanes : 1;
   w.y_planes = T <= kSharedDecodeMaxTokens ? shared_decode_down_planes(l->d_model, l->d_ff_shared)
                                            : shared_down_planes(T, l->d_model, l->d_ff_shared);
   w.topk_idx = reinterpret_cast<int32_t*>(take(R * 4));
@@ -277,6 +278,8 @@ size_t mote_layer_workspace_bytes(const mote_layer* layer, int T_max) {
   need = carve(layer, T_max, nullptr).bytes;
   consider(kSharedDecodeMaxTokens);
   consider(int64_t{48} * E / k);
+  consider(static_cast<int64_t>(knob(kKnobMidRowsLo)) * E / k);
+  consider(static_cast<int64_t>(knob(kKnobMidRowsHi)) * E / k);
   for (int64_t m = 1;; ++m) {   // largest T with floor(T*k/128) == m - 1
     const int64_t t = (128 * m - 1) / k;
     if (t > T_max) break;
@@ -325,7 +328,7 @@ mote_status forward_impl(const mote_layer* layer, const mote_norm* norm, const v
   auto mark = [&](int i) -> hipError_t { return timing ? hipEventRecord(g_ev[i], stream) : hipSuccess; };
 
   const int tile_m = w.tile_m;
-  const bool decode_routed = tile_m == 32;
+  const bool decode_routed = tile_m != 128;
   const bool decode_shared = T <= kSharedDecodeMaxTokens;
   const uint16_t* sg = static_cast<const uint16_t*>(layer->ws_gate);
   const uint16_t* su = static_cast<const uint16_t*>(layer->ws_up);

@@ -481,8 +481,12 @@ hipError_t launch_shared_gate_up_scaled(const uint16_t* x, const uint16_t* w_gat
   int v = shared_variant();
   if (v == 0) v = static_cast<int64_t>((T + 255) / 256) * ((F + 127) / 128) >= 384 ? 5 : 3;
   // fewer 128 x (128+128) tiles than fill the workgroup slots: half-width tiles (d=896, T=512:
-  // 0.090 -> 0.083 ms per forward; d=1536, T=512: 0.143 -> 0.131 ms)
-  if (shared_variant() == 0 && static_cast<int64_t>((T + 127) / 128) * ((F + 127) / 128) < 300) v = 1;
+  // 0.090 -> 0.083 ms per forward; d=1536, T=512: 0.143 -> 0.131 ms).  Not below four row tiles:
+  // at most one full-width tile per CU then, and a tile of either width takes about as long
+  // (this kernel alone, T=256: d=896 14.7 vs 18.7 us, d=1536 24 vs 38 us, d=2048 31 vs 49 us).
+  if (shared_variant() == 0 && (T + 127) / 128 >= 4 &&
+      static_cast<int64_t>((T + 127) / 128) * ((F + 127) / 128) < 300)
+    v = 1;
   switch (v) {
     case 1: return launch_shared_cfg<SharedCfg<0, 2, 1, 2, 2, 2>>(a, 1, stream);   // 128 x (64+64)
     case 2: return launch_shared_cfg<SharedCfg<0, 2, 2, 4, 2, 1>>(a, 1, stream);   // 256 x (128+128), 8 wavefronts, 1 workgroup / CU

@@ -694,9 +694,13 @@ static hipError_t launch_cfg(const RoutedGemmArgs& a, int kplanes, hipStream_t s
 // configuration of the large-batch kernels.
 static int routed_variant() { return knob(kKnobRoutedVariant); }
 
-// Plan tile height: 32-row tiles when experts see few rows (decode), else 128.
-int routed_tile_m(int T, int k, int E) {
+// Plan tile height by the average number of rows an expert sees: 32-row tiles for few rows
+// (decode kernels), 64-row tiles for some tens of rows where the wave-streaming kernel fits the
+// shape (the weights are then streamed once per 64 rows; the large-batch kernel would run half-empty
+// 128-row tiles and re-read the activations for every channel tile), else 128.
+int routed_tile_m(int T, int k, int E, int d, int F) {
   const int64_t avg = (static_cast<int64_t>(T) * k + E - 1) / E;
+  if (avg > knob(kKnobMidRowsLo) && avg <= knob(kKnobMidRowsHi) && routed_mid_kernel_fits(d, F)) return 64;
   if (avg <= 48) return 32;
   return 128;
 }

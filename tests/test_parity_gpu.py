@@ -524,10 +524,11 @@ def test_layer_config3_prefill_sampled():
     _check_down_rows(cfg, op, taps, np.sort(rows))
 
 
-@pytest.mark.parametrize("T", [256, 512, 768, 1024, 1536])
+@pytest.mark.parametrize("T", [256, 320, 448, 512, 768, 1024, 1536])
 def test_layer_3b_width_mid_size_batches(T):
     """The 3B width (the weights of configuration 3) between decode and prefill: 32 to 192 rows per
-    expert.  T = 256 still runs the small-batch kernels; 512 and 768 the large-batch kernels whose
+    expert.  T = 256, 320 and 448 run the wave-streaming kernel on 64-row tiles (at 448 some experts
+    have more than 64 rows, i.e. a second, short tile); 512 and 768 the large-batch kernels whose
     partly filled row tiles skip their empty fragments; 1024 and 1536 the down projection in two K
     planes.  Routing for all tokens, rows of every expert's first / middle / last row tile, sampled
     tokens end to end, both ends of every shared row tile."""
@@ -536,11 +537,27 @@ def test_layer_3b_width_mid_size_batches(T):
     gp, op = GpuProblem(cfg), OracleProblem(cfg)
     out, taps = _run_layer(gp, FULL_TAPS + ("h_s", "y_s"))
     _check_sampled(cfg, 24, 4, out, taps, op)
-    _check_rows_of_every_expert(cfg, op, taps, tile_m=32 if T <= 256 else 128)
+    _check_rows_of_every_expert(cfg, op, taps, tile_m=64 if T <= 480 else 128)
     _check_shared_tiles(cfg, op, taps, tile=128)
     R = cfg.n_tokens * cfg.top_k
     rng = np.random.default_rng(T)
     _check_down_rows(cfg, op, taps, np.sort(rng.choice(R, 48, replace=False)))
+
+
+@pytest.mark.parametrize("T", [136, 192, 240])
+def test_layer_1p5b_width_64_row_tiles(T):
+    """The paper's 1.5B layer (four experts, top-1) with 34 to 60 rows per expert: 64-row tiles whose
+    planes are shorter than the kernel's 16 K steps (gate-up 12 steps, down 14), so the padding
+    steps are exercised."""
+    cfg = W.P15.with_tokens(T, name=f"paper_1.5b_top1_T{T}")
+    _log(f"layer {cfg.name}")
+    gp, op = GpuProblem(cfg), OracleProblem(cfg)
+    out, taps = _run_layer(gp, FULL_TAPS + ("h_s", "y_s"))
+    _check_sampled(cfg, 24, 4, out, taps, op)
+    _check_rows_of_every_expert(cfg, op, taps, tile_m=64)
+    R = cfg.n_tokens * cfg.top_k
+    rng = np.random.default_rng(T)
+    _check_down_rows(cfg, op, taps, np.sort(rng.choice(R, 32, replace=False)))
 
 
 @pytest.mark.parametrize("cfg", [W.P05, W.P15, W.P3], ids=lambda c: c.name)
