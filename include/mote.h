@@ -280,7 +280,8 @@ enum {
   MOTE_KNOB_SHARED_VARIANT = 6,      /* ... of the shared GEMMs (0: chosen by shape)                   */
   MOTE_KNOB_GROUP_M = 7,             /* row tiles per band of the tile order (2)                       */
   MOTE_KNOB_DYNAMIC_ROUNDS = 8,      /* tiles per workgroup from which tiles are drawn (4)             */
-  MOTE_KNOB_DECODE_VARIANT = 9,      /* 1 / 0 forces / forbids the wave-streaming decode kernel (-1)   */
+  MOTE_KNOB_DECODE_VARIANT = 9,      /* routed decode kernel: 0 K-split, 1 / 2 wave-streaming with two
+                                        workgroups of four / one of eight wavefronts per CU (-1: by shape) */
   MOTE_KNOB_ROUTER_TOKEN_BLOCKS = 10,/* largest T with one token per router workgroup (256)            */
   MOTE_KNOB_DOWN_SPLIT_TILES = 11,   /* routed down projection: two K planes while it has fewer
                                         128 x 128 output tiles than this (600)                         */

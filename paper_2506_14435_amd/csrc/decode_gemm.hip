@@ -323,17 +323,22 @@ extern "C" int mote_debug_dtrace(void* dst, size_t bytes) { return (int)hipMemcp
 #define MOTE_DTP(k_)
 #endif
 
-// MF: 32-row fragments of a row tile (plan tiles of 32 * MF rows).  MF = 1: two workgroups of four
-// wavefronts per CU, 64 KiB plane each.  MF = 2 (experts with some tens of rows each): one workgroup
-// of eight wavefronts per CU with a 128 KiB plane; every unpacked weight fragment feeds two MFMAs.
-template <int MODE, int MF>
-__global__ __launch_bounds__(kDecThreads * MF, 2) void routed_wave_kernel(RoutedGemmArgs a, int n_frags, int kc_count) {
+// MF: 32-row fragments of a row tile (plan tiles of 32 * MF rows), NW: wavefronts of the workgroup,
+// which share one plane: 64 KiB (MF = 1) or 128 KiB (MF = 2: experts with some tens of rows each;
+// every unpacked weight fragment feeds two MFMAs).  Eight wavefronts in one workgroup per CU beat
+// two workgroups of four: the second workgroup of a CU got its plane 4-5 us after the first (its
+// loads queue behind the first one's weight ring) and ended 6 us later; alone the kernel takes the
+// same time either way, beside the shared expert's kernels the forward is 3-7 % faster (T = 16..64).
+template <int MODE, int MF, int NW>
+__global__ __launch_bounds__(64 * NW, 2) void routed_wave_kernel(RoutedGemmArgs a, int n_frags, int kc_count) {
   constexpr int NMAT = MODE == 0 ? 2 : 1;
-  constexpr int NT = kDecThreads * MF;                    // threads of the workgroup
-  constexpr int NW = NT / 64;                             // its wavefronts
+  constexpr int NT = 64 * NW;                             // threads of the workgroup (NW wavefronts)
+  constexpr int RB = 4 * MF;                              // blocks of eight rows in the plane
+  static_assert(NW % RB == 0, "a wavefront loads one row block of the plane");
   constexpr int ROWS = 32 * MF;                           // rows of the plane
   constexpr int STEP_BYTES = ROWS * 128;                  // one K step of the plane
   constexpr int D = 8;                                    // K steps of packed weights in flight per wavefront (16 measured no faster)
+  constexpr int DF = 4;                                   // ... of which this many are requested before the plane
   constexpr int kBufferFlags = 0x00020000;                // raw buffer, 32-bit data format
   constexpr int kWeightAux = 2;                           // weight loads are non-temporal: every byte is used once (measured: 42 -> 39.5 us)
   constexpr uint32_t kOutOfRange = 0x80000000u;           // lane offset past any buffer of <= 2 GiB
@@ -360,6 +365,15 @@ __global__ __launch_bounds__(kDecThreads * MF, 2) void routed_wave_kernel(Routed
     return r;
   };
   const v4i rsrc_q = make_rsrc(a.q, a.q_rows * K);
+  // The tile list (at most 64 entries here) is fetched whole, lane l entry l, beside the tile
+  // count it depends on: the weights can then be requested after one memory round trip.
+  const bool tile_table = a.max_tiles <= 64;
+  int t_expert = 0, t_row0 = 0, t_rows = 0;
+  if (tile_table && lane < a.max_tiles) {
+    t_expert = a.plan.tile_expert[lane];
+    t_row0 = a.plan.tile_row0[lane];
+    t_rows = a.plan.tile_rows[lane];
+  }
   const int groups = load_uniform(a.plan.n_tiles) * kc_count;
   // Each (row tile, K plane) group is shared evenly by floor(grid / groups) workgroups.  Where that
   // would leave more than a quarter of the grid idle (MF = 2: one workgroup per CU, groups often
@@ -389,45 +403,34 @@ __global__ __launch_bounds__(kDecThreads * MF, 2) void routed_wave_kernel(Routed
       nf_end = static_cast<int>(min(static_cast<int64_t>(n_frags), nf0 + (u_end - u)));
     }
     const int mt = grp / kc_count, kc = grp - mt * kc_count;
-    const int expert = load_uniform(a.plan.tile_expert + mt);
-    const int row0 = load_uniform(a.plan.tile_row0 + mt);
-    const int rows = load_uniform(a.plan.tile_rows + mt);
+    const int expert = tile_table ? __builtin_amdgcn_readlane(t_expert, mt) : load_uniform(a.plan.tile_expert + mt);
+    const int row0 = tile_table ? __builtin_amdgcn_readlane(t_row0, mt) : load_uniform(a.plan.tile_row0 + mt);
+    const int rows = tile_table ? __builtin_amdgcn_readlane(t_rows, mt) : load_uniform(a.plan.tile_rows + mt);
     // the K planes share the contraction evenly (at most 16 steps each): with planes of 16 steps and
     // a short last one, the workgroups of the last plane had a third of the bytes of the others
     const int step0 = kc * KT / kc_count;
     const int nsteps = (kc + 1) * KT / kc_count - step0;
 
-    // ---- activation plane into LDS, requested first ----
-    {
-      // A load fills 1 KiB of the plane with the 128 bytes of a K step of eight rows (lane l: row
-      // l % 8 of the block, position l / 8): whole cache lines.  Wavefront w loads row block w of
-      // every K step.  Rows past the end of the tile are not fetched (their accumulator rows are
-      // never stored).
-      const int lrow = wave * 8 + (lane & 7);
-      const int lslot = row0 + min(lrow, rows - 1);
-      const int lsrc = a.gather ? a.gather[lslot] : lslot;
-      const uint32_t voff = lrow < rows ? static_cast<uint32_t>(lsrc) * static_cast<uint32_t>(K) + step0 * 128 +
-                                              (((lane >> 3) ^ (wave & 1)) << 4)
-                                        : kOutOfRange;
-      for (int st = 0; st < nsteps; ++st) {
-        const uint32_t dst = lds0 + static_cast<uint32_t>(st * STEP_BYTES + wave * 1024);
-        const int soff = st * 128;
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-                     :: "s"(dst), "v"(voff), "s"(rsrc_q), "s"(soff) : "memory");
-      }
-    }
-    // rows of this lane in the MFMA layout: fragment f holds row 32 f + r32
-    float m_beta[MF];
-    int m_rs[MF];
+    // Order of the requests (vector-memory operations complete in issue order): the row indices
+    // the plane depends on, the first half of the weight ring (it needs only the tile's expert:
+    // HBM is busy from here on), the row scales, the plane, the rest of the ring.
+    // Plane: a load fills 1 KiB with the 128 bytes of a K step of eight rows (lane l: row l % 8
+    // of the block, position l / 8): whole cache lines.  Wavefront w loads row block w % RB of
+    // every (NW / RB)-th K step.  Rows past the end of the tile are not fetched (their accumulator
+    // rows are never stored).
+    const int lblock = wave % RB;
+    const int lrow = lblock * 8 + (lane & 7);
+    const int lslot = row0 + min(lrow, rows - 1);
+    const int lsrc = a.gather ? a.gather[lslot] : lslot;
+    int src_f[MF];   // rows of this lane in the MFMA layout: fragment f holds row 32 f + r32
 #pragma unroll
     for (int f = 0; f < MF; ++f) {
       const int slot = row0 + min(f * 32 + r32, rows - 1);
-      const int src = a.gather ? a.gather[slot] : slot;
-      m_beta[f] = a.beta[src];
-      m_rs[f] = a.rowsum[src];
+      src_f[f] = a.gather ? a.gather[slot] : slot;
     }
+    __builtin_amdgcn_sched_barrier(0);
 
-    // ---- weight ring ----
+    // ---- weight ring, first half ----
     __amdgpu_buffer_rsrc_t rw[NMAT];
     rw[0] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(a.w_gate) + expert * expert_words, 0,
                                               static_cast<int>(expert_words * 4), kBufferFlags);
@@ -437,15 +440,47 @@ __global__ __launch_bounds__(kDecThreads * MF, 2) void routed_wave_kernel(Routed
     const uint32_t w_lane = lane * 16;
     u4 wr[D][NMAT];
     int nf = nf0 + wave;   // this wavefront's fragments: nf0 + wave, + NW, ...
-    {   // the first D steps of the first fragment (out of range if this wavefront has none)
-      const uint32_t oob = nf < nf_end ? 0u : kOutOfRange;
+    const uint32_t oob = nf < nf_end ? 0u : kOutOfRange;   // out of range if this wavefront has no fragment
 #pragma unroll
-      for (int j = 0; j < D; ++j)
+    for (int j = 0; j < DF; ++j)
 #pragma unroll
-        for (int m = 0; m < NMAT; ++m)
-          wr[j][m] = __builtin_amdgcn_raw_buffer_load_b128(rw[m], w_lane + (j < nsteps ? oob : kOutOfRange),
-                                                           (nf * KT + step0 + j) * 1024, kWeightAux);
+      for (int m = 0; m < NMAT; ++m)
+        wr[j][m] = __builtin_amdgcn_raw_buffer_load_b128(rw[m], w_lane + (j < nsteps ? oob : kOutOfRange),
+                                                         (nf * KT + step0 + j) * 1024, kWeightAux);
+    __builtin_amdgcn_sched_barrier(0);
+
+    // the row scales before the plane: the compiler does not see the plane's loads, and its wait for
+    // the row indices would otherwise count them as the first half of the ring
+    float m_beta[MF];
+    int m_rs[MF];
+#pragma unroll
+    for (int f = 0; f < MF; ++f) {
+      m_beta[f] = a.beta[src_f[f]];
+      m_rs[f] = a.rowsum[src_f[f]];
     }
+    __builtin_amdgcn_sched_barrier(0);
+    // ---- activation plane into LDS ----
+    {
+      const uint32_t voff = lrow < rows ? static_cast<uint32_t>(lsrc) * static_cast<uint32_t>(K) + step0 * 128 +
+                                              (((lane >> 3) ^ (lblock & 1)) << 4)
+                                        : kOutOfRange;
+      for (int st = wave / RB; st < nsteps; st += NW / RB) {
+        const uint32_t dst = lds0 + static_cast<uint32_t>(st * STEP_BYTES + lblock * 1024);
+        const int soff = st * 128;
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                     :: "s"(dst), "v"(voff), "s"(rsrc_q), "s"(soff) : "memory");
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- weight ring, second half ----
+#pragma unroll
+    for (int j = DF; j < D; ++j)
+#pragma unroll
+      for (int m = 0; m < NMAT; ++m)
+        wr[j][m] = __builtin_amdgcn_raw_buffer_load_b128(rw[m], w_lane + (j < nsteps ? oob : kOutOfRange),
+                                                         (nf * KT + step0 + j) * 1024, kWeightAux);
+    __builtin_amdgcn_sched_barrier(0);
 
     // steps past the end of the contraction contribute nothing: zero activations
     for (int i = nsteps * 256 * MF + tid; i < 16 * 256 * MF; i += NT)   // 256 * MF x 16 bytes per K step
@@ -466,9 +501,9 @@ __global__ __launch_bounds__(kDecThreads * MF, 2) void routed_wave_kernel(Routed
         MODE == 0 ? static_cast<void*>(a.h) : static_cast<void*>(a.acc_out + static_cast<int64_t>(kc) * a.partial_stride), 0,
         static_cast<int>(a.out_rows * N * (MODE == 0 ? 2 : 4)), kBufferFlags);
     MOTE_DTP(tp) ++tp;
-    // the plane and the row metadata (everything requested before the ring) have landed; the ring stays in flight
-    // (a plain barrier: __syncthreads() would also drain the ring)
-    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" :: "n"(D * NMAT) : "memory");
+    // the plane and the row metadata (everything requested before the second half of the ring) have landed;
+    // that half stays in flight (a plain barrier: __syncthreads() would also drain it)
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" :: "n"((D - DF) * NMAT) : "memory");
     MOTE_DTP(tp) ++tp;
 
     for (; nf < nf_end; nf += NW) {
@@ -569,17 +604,17 @@ static int device_cus() {
 
 int routed_decode_down_planes(int K) { return ((K >> 7) + 15) / 16; }
 
-template <int MODE, int MF>
+template <int MODE, int MF, int NW>
 static hipError_t launch_wave(const RoutedGemmArgs& a, int n_frags, int kc, hipStream_t stream) {
   constexpr int kLds = 16 * 8 * 32 * MF * 16;   // the activation plane
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(routed_wave_kernel<MODE, MF>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(routed_wave_kernel<MODE, MF, NW>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  routed_wave_kernel<MODE, MF><<<device_cus() * (MF == 1 ? 2 : 1), kDecThreads * MF, kLds, stream>>>(a, n_frags, kc);
+  routed_wave_kernel<MODE, MF, NW><<<device_cus() * (8 / NW), 64 * NW, kLds, stream>>>(a, n_frags, kc);
   return hipGetLastError();
 }
 
@@ -597,13 +632,13 @@ bool routed_mid_kernel_fits(int d, int F) {
 // zero activations) and enough units to give every wavefront of the grid a fragment.
 static bool use_wave_kernel(const RoutedGemmArgs& a, int n_frags, int kc) {
   const int forced = knob(kKnobDecodeVariant);
-  if (forced >= 0) return forced == 1;
+  if (forced >= 0) return forced >= 1;
   const int KT = a.K >> 7;
   const int padded = kc * 16;
   if (padded * 3 > KT * 4) return false;                                 // more than a third of the MFMA work would be padding
   if (static_cast<int64_t>(a.q_rows) * a.K >= (int64_t{1} << 31)) return false;
   // few dispatch rows = few row tiles: the K-split kernel keeps all four wavefronts of a workgroup busy then
-  return a.out_rows >= 64 && static_cast<int64_t>(n_frags) * kc >= 256;
+  return a.out_rows >= 32 && static_cast<int64_t>(n_frags) * kc >= 256;
 }
 
 hipError_t launch_routed_decode_gate_up(const RoutedGemmArgs& a, hipStream_t stream) {
@@ -612,9 +647,10 @@ hipError_t launch_routed_decode_gate_up(const RoutedGemmArgs& a, hipStream_t str
   const int64_t max_units = static_cast<int64_t>(a.max_tiles) * n_frags;
   int64_t blocks = static_cast<int64_t>(device_cus()) * 4;
   if (blocks > max_units) blocks = max_units;
-  if (a.tile_m == 64) return launch_wave<0, 2>(a, n_frags, 1, stream);
+  if (a.tile_m == 64) return launch_wave<0, 2, 8>(a, n_frags, 1, stream);
   if (KT <= 16) {
-    if (use_wave_kernel(a, n_frags, 1)) return launch_wave<0, 1>(a, n_frags, 1, stream);
+    if (use_wave_kernel(a, n_frags, 1))
+      return knob(kKnobDecodeVariant) == 1 ? launch_wave<0, 1, 4>(a, n_frags, 1, stream) : launch_wave<0, 1, 8>(a, n_frags, 1, stream);
     routed_stream_kernel<0><<<device_cus() * 2, kDecThreads, 0, stream>>>(a, n_frags, 1);
     return hipGetLastError();
   }
@@ -626,8 +662,9 @@ hipError_t launch_routed_decode_down(const RoutedGemmArgs& a, hipStream_t stream
   if (a.max_tiles == 0) return hipSuccess;
   const int n_frags = a.N / 32;
   const int kc = routed_decode_down_planes(a.K);
-  if (a.tile_m == 64) return launch_wave<1, 2>(a, n_frags, kc, stream);
-  if (use_wave_kernel(a, n_frags, kc)) return launch_wave<1, 1>(a, n_frags, kc, stream);
+  if (a.tile_m == 64) return launch_wave<1, 2, 8>(a, n_frags, kc, stream);
+  if (use_wave_kernel(a, n_frags, kc))
+    return knob(kKnobDecodeVariant) == 1 ? launch_wave<1, 1, 4>(a, n_frags, kc, stream) : launch_wave<1, 1, 8>(a, n_frags, kc, stream);
   routed_stream_kernel<1><<<device_cus() * 3, kDecThreads, 0, stream>>>(a, n_frags, kc);
   return hipGetLastError();
 }

@@ -17,7 +17,7 @@ enum Knob {
   kKnobSharedVariant,        // ... of the shared GEMMs (0: by shape)
   kKnobGroupM,               // row tiles per band of the tile order
   kKnobDynamicRounds,        // tiles per workgroup from which tiles are drawn
-  kKnobDecodeVariant,        // 1 / 0 forces / forbids the wave-streaming routed decode kernel
+  kKnobDecodeVariant,        // routed decode kernel: 0 K-split, 1 / 2 wave-streaming with 4 / 8 wavefronts per workgroup
   kKnobRouterTokenBlocks,    // largest T with one token per router workgroup
   kKnobDownSplitTiles,       // routed down projection: two K planes while there are fewer 128 x 128 output tiles than this
   kKnobMidRowsLo,            // 64-row plan tiles for more than this many rows per expert on average ...
