@@ -34,7 +34,8 @@ The paper prints no worked numerical example of the layer, so the readings R1-R3
 written statement here: "parity unpinned" with respect to the authors' own code.
 The same holds for the readings taken beyond Section 3.1: the granularity and rounding
 of the RTN shared expert (Section 4.3 names the method only), RMSNorm as the LN of
-Eq.1-2, the count t_i in Eq.12, and sign(0) = +1 of the 1-bit quantiser.
+Eq.1-2, the count t_i in Eq.12, sign(0) = +1 of the 1-bit quantiser, and the operand
+precision of the straight-through gradients of Section 3.2.
 """
 from __future__ import annotations
 
@@ -385,6 +386,42 @@ def binarize(w: np.ndarray):
 
 
 # ----------------------------------------------------------------- whole layer
+
+def ste_linear_backward(dy_bf16, offsets, experts, q, beta):
+    """Straight-through estimator of Section 3.2 for the grouped ternary linear layer of
+    Section 3.1, Y_e = Q_a(X_e) Q_w(W_e)^T (rows grouped by expert e, offsets[e] .. offsets[e+1]):
+    the quantisers are skipped on the way back, dL/dW = dL/dQ_w(W) and dL/dX = dL/dQ_a(X), so
+
+        dX[r, c]   = sum_n dY[r, n] * (alpha_e * t_e[n, c])                    (gradient w.r.t. Q_a(X))
+        dW_e[n, c] = sum_{r in e} dY[r, n] * ((beta_r / 127) * q[r, c])        (gradient w.r.t. Q_w(W))
+
+    dy_bf16: bit patterns [R, N]; experts: list of (t [N, K] in {-1,0,1}, alpha fp32);
+    q int8 [R, K], beta fp32 [R] or [R, 1] (the clamped absmax of Q_a).  Returns dX fp64 [R, K],
+    dW fp64 [E, N, K] and the scaled gradient rows as bf16 bit patterns.
+    Reading (the paper states only the two identities and that gradients stay in full
+    precision): the sums run over bf16 operands with a wide accumulator, as a mixed-precision
+    trainer computes them; the activation scale beta_r / 127 (one fp32 divide, as in the forward
+    pass) is folded into the gradient row, dYs[r, n] = bf16(fp32(dY[r, n]) * (beta_r / 127)), one
+    fp32 multiply and one rounding, because the contraction index of dW is r and a scale per r
+    cannot be applied after the sum; int8 codes and ternary values are exact in bf16.  alpha_e
+    multiplies the finished sum."""
+    dy = bf16_to_f32(dy_bf16)
+    R, N = dy.shape
+    K = q.shape[1]
+    scale = (np.asarray(beta, np.float32).reshape(-1) / np.float32(127.0)).astype(np.float32)
+    dys_bits = f32_to_bf16((dy * scale[:, None]).astype(np.float32))
+    dys = bf16_to_f32(dys_bits).astype(np.float64)
+    dx = np.zeros((R, K), np.float64)
+    dw = np.zeros((len(experts), N, K), np.float64)
+    for e, (t, alpha) in enumerate(experts):
+        lo, hi = int(offsets[e]), int(offsets[e + 1])
+        if hi == lo:
+            continue
+        dx[lo:hi] = float(np.float32(alpha)) * (dy[lo:hi].astype(np.float64) @ t.astype(np.float64))
+        dw[e] = dys[lo:hi].T @ q[lo:hi].astype(np.float64)
+    return dx, dw, dys_bits
+
+
 def layer_forward(x_bf16, w_router_bf16, bias, k, shared, experts, tokens=None):
     """MoE(x) + FFN(x) of Eq.2 (no residual, no LayerNorm: those are the outer terms).
 

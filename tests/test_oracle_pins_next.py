@@ -292,3 +292,100 @@ def test_binarize_hand_case_and_invariants():
     assert np.array_equal(O.unpack_int2(words, 64, 128)[:40, :64], t)
     t0, a0 = O.binarize(np.zeros((4, 4), np.float32))
     assert (t0 == 1).all() and a0 == np.float32(1e-5)
+
+
+# ------------------------------------------------- straight-through gradients (Section 3.2)
+def _ste_case(seed, R=11, N=12, K=10, E=3, exact_scale=False):
+    rng = np.random.default_rng(seed)
+    cuts = np.sort(rng.integers(0, R + 1, E - 1))
+    offsets = np.concatenate([[0], cuts, [R]])
+    dy = _bf(rng.standard_normal((R, N)))
+    experts = [(rng.integers(-1, 2, (N, K)).astype(np.int8), np.float32(rng.uniform(0.01, 0.05))) for _ in range(E)]
+    x = rng.standard_normal((R, K)).astype(np.float32)
+    if exact_scale:                       # absmax 127 * 2^-5: beta / 127 = 2^-5, a power of two
+        x = np.clip(x, -3.0, 3.0)
+        x[:, 0] = 127.0 * 2.0 ** -5
+    q, beta = O.absmax_int8(x)
+    return dy, offsets, experts, q, beta.reshape(-1)
+
+
+def test_ste_backward_is_the_gradient_of_the_dequantised_bilinear_form():
+    """With the quantisers skipped (Section 3.2) the layer is Y = Xq Wq^T, whose gradients autograd
+    (a library routine) gives: dXq = dY Wq and dWq = dY^T Xq.  The scale of each row is a power
+    of two here, so folding it into the bf16 gradient row is exact and the match is to rounding."""
+    dy, offsets, experts, q, beta = _ste_case(1, exact_scale=True)
+    assert np.all(beta == np.float32(127.0 * 2.0 ** -5))
+    dx, dw, _ = O.ste_linear_backward(dy, offsets, experts, q, beta)
+    dy_t = torch.from_numpy(O.bf16_to_f32(dy).astype(np.float64))
+    for e, (t, alpha) in enumerate(experts):
+        lo, hi = offsets[e], offsets[e + 1]
+        xq = torch.tensor(q[lo:hi].astype(np.float64) * (float(beta[0]) / 127.0), requires_grad=True)
+        wq = torch.tensor(t.astype(np.float64) * float(alpha), requires_grad=True)
+        y = xq @ wq.T
+        y.backward(dy_t[lo:hi])
+        assert np.allclose(dx[lo:hi], xq.grad.numpy(), rtol=1e-13, atol=1e-15)
+        # dW is the gradient w.r.t. Q_w(W) = alpha * t itself (not w.r.t. t): no factor alpha
+        assert np.allclose(dw[e], wq.grad.numpy(), rtol=1e-13, atol=1e-15)
+
+
+def test_ste_backward_finite_differences_and_scalar_loops():
+    """Central differences of L = sum(G * Y) in single entries of Q_a(X) and Q_w(W) (L is bilinear,
+    so the difference quotient is exact up to rounding), and the two sums written as scalar loops."""
+    dy, offsets, experts, q, beta = _ste_case(2, R=7, N=5, K=6, E=2, exact_scale=True)
+    dx, dw, dys = O.ste_linear_backward(dy, offsets, experts, q, beta)
+    g = O.bf16_to_f32(dy).astype(np.float64)
+    s = beta.astype(np.float64) / 127.0
+
+    def loss(xq, wqs):
+        return sum(float((g[offsets[e]:offsets[e + 1]] * (xq[offsets[e]:offsets[e + 1]] @ wqs[e].T)).sum())
+                   for e in range(len(experts)))
+
+    xq = q.astype(np.float64) * s[:, None]
+    wqs = [t.astype(np.float64) * float(a) for t, a in experts]
+    h = 0.5
+    for (r, c) in [(0, 0), (3, 4), (6, 5)]:
+        xp, xm = xq.copy(), xq.copy()
+        xp[r, c] += h
+        xm[r, c] -= h
+        assert math.isclose((loss(xp, wqs) - loss(xm, wqs)) / (2 * h), dx[r, c], rel_tol=1e-12, abs_tol=1e-14)
+    for (e, n, c) in [(0, 0, 0), (1, 4, 5), (1, 2, 3)]:
+        wp = [w.copy() for w in wqs]
+        wm = [w.copy() for w in wqs]
+        wp[e][n, c] += h
+        wm[e][n, c] -= h
+        assert math.isclose((loss(xq, wp) - loss(xq, wm)) / (2 * h), dw[e][n, c], rel_tol=1e-12, abs_tol=1e-14)
+    for e, (t, alpha) in enumerate(experts):
+        for r in range(offsets[e], offsets[e + 1]):
+            for c in range(q.shape[1]):
+                want = sum(g[r, n] * float(alpha) * int(t[n, c]) for n in range(t.shape[0]))
+                assert math.isclose(dx[r, c], want, rel_tol=1e-12, abs_tol=1e-14)
+        for n in range(t.shape[0]):
+            for c in range(q.shape[1]):
+                want = sum(g[r, n] * s[r] * int(q[r, c]) for r in range(offsets[e], offsets[e + 1]))
+                assert math.isclose(dw[e][n, c], want, rel_tol=1e-12, abs_tol=1e-14)
+
+
+def test_ste_backward_scale_folding_rounds_once_and_empty_experts():
+    """A scale that is not a power of two: the gradient row carries it, rounded once to bf16 (half
+    an ulp, at most 2^-8 relative), so dW stays within that of the unrounded sum; an expert without rows
+    gets a zero dW and touches no row of dX."""
+    dy, offsets, experts, q, beta = _ste_case(3, R=16, N=8, K=9, E=4)
+    offsets = np.array([0, 5, 5, 12, 16])              # expert 1 has no rows
+    dx, dw, dys = O.ste_linear_backward(dy, offsets, experts, q, beta)
+    g = O.bf16_to_f32(dy).astype(np.float64)
+    s32 = (beta / np.float32(127.0)).astype(np.float32)
+    want_bits = _bits(torch.from_numpy((O.bf16_to_f32(dy) * s32[:, None]).astype(np.float32)).to(torch.bfloat16))
+    assert np.array_equal(dys, want_bits)              # torch's fp32 -> bf16 conversion rounds to nearest even
+    assert not dw[1].any()
+    for e in (0, 2, 3):
+        lo, hi = offsets[e], offsets[e + 1]
+        terms = g[lo:hi, :, None] * s32.astype(np.float64)[lo:hi, None, None] * q[lo:hi, None, :].astype(np.float64)
+        exact = terms.sum(axis=0)
+        assert np.all(np.abs(dw[e] - exact) <= 2.0 ** -8 * np.abs(terms).sum(axis=0) + 1e-18)
+        assert np.abs(dw[e] - exact).max() > 0          # the rounding is really there
+    # a sign flip of one ternary weight moves exactly one column of one expert's dX rows
+    t2 = experts[0][0].copy()
+    t2[3, 4] = -1 if t2[3, 4] >= 0 else 1
+    dx2, _, _ = O.ste_linear_backward(dy, offsets, [(t2, experts[0][1])] + experts[1:], q, beta)
+    diff = np.argwhere(dx2 != dx)
+    assert set(diff[:, 1]) == {4} and set(diff[:, 0]) <= set(range(0, 5))
