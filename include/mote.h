@@ -107,6 +107,37 @@ mote_status mote_pack_rtn(const void* w, int64_t n_out, int64_t n_in, int bits, 
                           float* scales, void* hip_stream);
 
 /* ---------------------------------------------------------------------------------------
+ * Straight-through estimator of Section 3.2 (quantisation-aware training) for one grouped ternary
+ * linear layer of Section 3.1, Y_e = Q_a(X_e) Q_w(W_e)^T, rows grouped by expert: the gradients
+ * by-pass both quantisers, dL/dW = dL/dQ_w(W) and dL/dX = dL/dQ_a(X), i.e.
+ *
+ *   dx[r, c]    = alpha_e * sum_n dy[r, n] * t_e[n, c]                         (r a row of expert e)
+ *   dw[e][n, c] = sum_{r in e} bf16(dy[r, n] * (beta[r] / 127)) * q[r, c]
+ *
+ * bf16 operands (ternary values and int8 codes are exact in bf16), fp32 accumulation on the bf16
+ * MFMA; the activation scale beta[r] / 127 (one fp32 divide) is folded into the gradient row
+ * with one fp32 multiply and one rounding to bf16, because dw contracts over r.
+ *
+ * dy           in : bf16 [R, N], row r belongs to expert e for offsets[e] <= r < offsets[e+1]
+ * offsets_host in : HOST int32 [E + 1], ascending, offsets[0] = 0, offsets[E] = R (the expert
+ *                   counts of the forward pass, read back by the caller)
+ * packed       in : E packed ternary matrices [N, K] back to back (mote_pack_ternary)
+ * alpha        in : fp32, alpha of expert e at alpha[e * alpha_stride]
+ * q, beta      in : Q_a(X): int8 [R, K] and the clamped absmax fp32 [R] of each row
+ * dx           out: fp32 [R, K]
+ * dw           out: fp32 [E, N, K] (zero for an expert without rows)
+ * workspace       : device, >= mote_ste_backward_workspace_bytes(R, N, K, E) bytes, 256-byte aligned
+ * Limits: N % 128 == 0, K % 128 == 0, 1 <= E <= 64, R >= 0; every operand of one expert below
+ * 2 GiB.  Enqueued on hip_stream; the host array is read before the call returns.
+ * Returns MOTE_ERR_INVALID_ARG for NULL pointers or offsets that are not ascending from 0 to R,
+ * MOTE_ERR_UNSUPPORTED_SHAPE, MOTE_ERR_WORKSPACE_TOO_SMALL, MOTE_ERR_HIP. */
+size_t mote_ste_backward_workspace_bytes(int R, int N, int K, int E);
+mote_status mote_ste_linear_backward(const void* dy, const int32_t* offsets_host, const uint32_t* packed,
+                                     const float* alpha, int alpha_stride, const int8_t* q, const float* beta,
+                                     int R, int N, int K, int E, float* dx, float* dw, void* workspace,
+                                     size_t workspace_bytes, void* hip_stream);
+
+/* ---------------------------------------------------------------------------------------
  * Router: gate softmax of Eq.3 and GShard-style top-k selection (Section 3.1; Section 4.1
  * uses top-1 routing).
  *

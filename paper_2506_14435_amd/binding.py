@@ -22,6 +22,7 @@ STAGE_NAMES = ("router_quant", "dispatch", "routed_gate_up", "quant_h", "routed_
 EXPORTS = ("mote_status_string", "mote_version", "mote_packed_bytes", "mote_pack_ternary",
            "mote_router_topk", "mote_layer_workspace_bytes", "mote_layer_forward", "mote_layer_forward_static",
            "mote_block_forward", "mote_router_balance", "mote_pack_binary", "mote_rtn_packed_bytes", "mote_pack_rtn",
+           "mote_ste_backward_workspace_bytes", "mote_ste_linear_backward",
            "mote_stage_timing", "mote_stage_times", "mote_event_pair_overhead", "mote_tuning_set", "mote_calib_copy")
 KNOBS = ("no_fork", "fork_min_log2", "event_fence", "quant_wide", "routed_variant", "routed_down_variant",
          "shared_variant", "group_m", "dynamic_rounds", "decode_variant", "router_token_blocks", "down_split_tiles",
@@ -99,6 +100,12 @@ def load_library() -> ctypes.CDLL:
     lib.mote_layer_forward_static.restype = c_int
     lib.mote_layer_forward_static.argtypes = [POINTER(MoteLayerStruct), c_void_p, c_int, c_void_p,
                                               POINTER(MoteTapsStruct), c_void_p]
+    lib.mote_ste_backward_workspace_bytes.restype = c_size_t
+    lib.mote_ste_backward_workspace_bytes.argtypes = [c_int, c_int, c_int, c_int]
+    lib.mote_ste_linear_backward.restype = c_int
+    lib.mote_ste_linear_backward.argtypes = [c_void_p, POINTER(ctypes.c_int32), c_void_p, c_void_p, c_int, c_void_p,
+                                             c_void_p, c_int, c_int, c_int, c_int, c_void_p, c_void_p, c_void_p,
+                                             c_size_t, c_void_p]
     lib.mote_stage_timing.restype = c_int
     lib.mote_stage_timing.argtypes = [c_int]
     lib.mote_stage_times.restype = c_int
@@ -205,6 +212,30 @@ def mote_router_balance(x: torch.Tensor, w_router: torch.Tensor, k: int, router_
                                    _ptr(counts), _ptr(gate_p), _ptr(gate_sum), _ptr(loss), _stream()),
            "mote_router_balance")
     return idx, p, counts, gate_p, gate_sum, loss
+
+
+def mote_ste_linear_backward(dy: torch.Tensor, offsets, packed: torch.Tensor, alpha: torch.Tensor, alpha_stride: int,
+                             q: torch.Tensor, beta: torch.Tensor, n_out: int, n_in: int, workspace: torch.Tensor = None):
+    """Straight-through gradients of a grouped ternary linear layer (Section 3.2).  dy bf16 [R, N] grouped
+    by expert, offsets: host sequence of E + 1 row offsets, packed: E packed matrices [N, K], alpha fp32
+    (expert e at alpha[e * alpha_stride]), q int8 [R, K], beta fp32 [R] -> (dx fp32 [R, K], dw fp32 [E, N, K])."""
+    lib = load_library()
+    _dev(dy, torch.bfloat16, "dy")
+    _dev(q, torch.int8, "q")
+    _dev(beta, torch.float32, "beta")
+    _dev(alpha, torch.float32, "alpha")
+    offs = (ctypes.c_int32 * len(offsets))(*[int(v) for v in offsets])
+    n_exp = len(offsets) - 1
+    n_rows = dy.shape[0]
+    need = lib.mote_ste_backward_workspace_bytes(n_rows, n_out, n_in, n_exp)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dy.device)
+    dx = torch.empty(n_rows, n_in, dtype=torch.float32, device=dy.device)
+    dw = torch.empty(n_exp, n_out, n_in, dtype=torch.float32, device=dy.device)
+    _check(lib.mote_ste_linear_backward(_ptr(dy), offs, _ptr(packed), _ptr(alpha), alpha_stride, _ptr(q), _ptr(beta),
+                                        n_rows, n_out, n_in, n_exp, _ptr(dx), _ptr(dw), _ptr(workspace),
+                                        ctypes.c_size_t(workspace.numel()), _stream()), "mote_ste_linear_backward")
+    return dx, dw
 
 
 def mote_router_topk(x: torch.Tensor, w_router: torch.Tensor, k: int, router_bias: torch.Tensor = None,

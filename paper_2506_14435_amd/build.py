@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmote.so")
 SOURCES = ["mote_api.hip", "pack_ternary.hip", "router.hip", "ternary_gemm.hip", "shared_ffn.hip", "decode_gemm.hip",
-           "elementwise.hip", "block_extras.hip"]
+           "elementwise.hip", "block_extras.hip", "ste_backward.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fhip-fp32-correctly-rounded-divide-sqrt",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]

@@ -545,6 +545,33 @@ mote_status mote_event_pair_overhead(float* ms_host, void* hip_stream) {
   return MOTE_OK;
 }
 
+size_t mote_ste_backward_workspace_bytes(int R, int N, int K, int E) {
+  if (R < 0 || N <= 0 || K <= 0 || E < 1 || E > 64 || N % 128 || K % 128) return 0;
+  return ste_backward_workspace_bytes(R, N, K, E);
+}
+
+mote_status mote_ste_linear_backward(const void* dy, const int32_t* offsets_host, const uint32_t* packed,
+                                     const float* alpha, int alpha_stride, const int8_t* q, const float* beta,
+                                     int R, int N, int K, int E, float* dx, float* dw, void* workspace,
+                                     size_t workspace_bytes, void* hip_stream) {
+  if (R < 0 || N <= 0 || K <= 0 || E < 1 || E > 64 || N % 128 || K % 128) return MOTE_ERR_UNSUPPORTED_SHAPE;
+  if (!offsets_host || !packed || !alpha || !dw || !workspace || alpha_stride < 1) return MOTE_ERR_INVALID_ARG;
+  if (R > 0 && (!dy || !q || !beta || !dx)) return MOTE_ERR_INVALID_ARG;
+  if (offsets_host[0] != 0 || offsets_host[E] != R) return MOTE_ERR_INVALID_ARG;
+  const int64_t lim = int64_t{1} << 31;
+  for (int e = 0; e < E; ++e) {
+    const int64_t rows = static_cast<int64_t>(offsets_host[e + 1]) - offsets_host[e];
+    if (rows < 0) return MOTE_ERR_INVALID_ARG;
+    if ((rows + 64) * N * 2 >= lim || (rows + 64) * K * 4 >= lim) return MOTE_ERR_UNSUPPORTED_SHAPE;
+  }
+  if (static_cast<int64_t>(N) * K * 4 >= lim) return MOTE_ERR_UNSUPPORTED_SHAPE;
+  if (reinterpret_cast<uintptr_t>(workspace) % kAlign) return MOTE_ERR_INVALID_ARG;
+  if (ste_backward_workspace_bytes(R, N, K, E) > workspace_bytes) return MOTE_ERR_WORKSPACE_TOO_SMALL;
+  MOTE_HIP(launch_ste_backward(static_cast<const uint16_t*>(dy), offsets_host, packed, alpha, alpha_stride, q, beta, R, N,
+                               K, E, dx, dw, workspace, static_cast<hipStream_t>(hip_stream)));
+  return MOTE_OK;
+}
+
 mote_status mote_tuning_set(int knob_id, int value) {
   if (knob_id < 0 || knob_id >= mote::kKnobCount) return MOTE_ERR_INVALID_ARG;
   mote::g_knobs[knob_id] = value;

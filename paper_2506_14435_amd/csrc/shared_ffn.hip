@@ -539,4 +539,17 @@ hipError_t launch_shared_down_scaled(const uint16_t* h_s, const uint16_t* w_down
   }
 }
 
+// Plain bf16 GEMM with fp32 output for other callers: out[m, n] = scale[n] * sum_k act[m, k] * w[n, k]
+// (scale optional), one K plane.  K must be a multiple of 64.
+hipError_t launch_gemm_tn_f32(const uint16_t* act, const uint16_t* w, int M, int N, int K, float* out, const float* scale,
+                              hipStream_t stream) {
+  if (M == 0 || N == 0) return hipSuccess;
+  SharedGemmArgs a{act, w, nullptr, M, N, K, nullptr, out, static_cast<int64_t>(M) * N, scale, nullptr};
+  if (static_cast<int64_t>((M + 255) / 256) * ((N + 255) / 256) >= 256)
+    return launch_shared_cfg<SharedCfg<1, 2, 4, 4, 2, 1, 4>>(a, 1, stream);   // 256 x 256
+  if (static_cast<int64_t>((M + 127) / 128) * ((N + 255) / 256) >= 256)
+    return launch_shared_cfg<SharedCfg<1, 2, 4, 2, 2, 2>>(a, 1, stream);      // 128 x 256
+  return launch_shared_cfg<SharedCfg<1, 2, 2, 2, 2, 2>>(a, 1, stream);        // 128 x 128
+}
+
 }  // namespace mote

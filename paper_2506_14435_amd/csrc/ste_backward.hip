@@ -1,0 +1,187 @@
+// Straight-through estimator of Section 3.2 for the grouped ternary linear layer of Section 3.1,
+// Y_e = Q_a(X_e) Q_w(W_e)^T: the quantisers are skipped on the way back, so with the rows of dY
+// grouped by expert
+//
+//   dX[r, c]   = alpha_e * sum_n dY[r, n] * t_e[n, c]
+//   dW_e[n, c] = sum_{r in e} bf16(dY[r, n] * beta_r / 127) * q[r, c]
+//
+// Both are dense bf16 contractions with fp32 accumulation (ternary values and int8 codes are
+// exact in bf16) and run on the bf16 MFMA GEMM of the shared expert, which contracts two
+// row-major operands along their rows.  The kernels here bring the operands into that form:
+//
+//   expand_ternary_t_kernel : packed 2-bit codes of W_e [N, K] -> bf16 matrix [K, N] of t_e^T
+//   transpose_rows_kernel   : dY_e [rows, N] bf16, scaled by beta_r / 127 and rounded once
+//                             -> [N, rows_pad]; q_e [rows, K] int8 -> bf16 [K, rows_pad]
+//                             (rows_pad = rows rounded up to 64, the padding is zero)
+//   fill_alpha_kernel       : alpha_e broadcast over the K output channels of dX (the GEMM
+//                             epilogue multiplies per output channel)
+#include "common.h"
+#include "launch.h"
+
+namespace mote {
+
+constexpr int kSteThreads = 256;
+
+// One workgroup expands four packed tiles (32 output rows x 128 input channels each, consecutive
+// row tiles nt = 4 b .. 4 b + 3 of one K tile) into a 128 x 128 block of the transposed matrix:
+// out[(128 kt + c) * N + 128 b + n] = t[128 b + n][128 kt + c].
+__global__ __launch_bounds__(kSteThreads) void expand_ternary_t_kernel(const uint32_t* __restrict__ packed, int N, int K,
+                                                                       uint16_t* __restrict__ out) {
+  __shared__ uint16_t s_t[128][128 + 2];   // [c][n], two bf16 of padding per row
+  const int tiles_k = K >> 7;
+  const int kt = blockIdx.x % tiles_k, nb = blockIdx.x / tiles_k;
+  const int tid = threadIdx.x;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int nt = nb * 4 + j;
+    const uint32_t word = packed[(static_cast<int64_t>(nt) * tiles_k + kt) * 256 + tid];
+    const int lane = tid >> 2, s = tid & 3;
+    const int r = lane & 31, g = lane >> 5;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int code = (word >> (8 * (i & 3) + 2 * (i >> 2))) & 3;
+      // t = code - 1 as bf16: -1 = 0xBF80, 0 = 0, +1 = 0x3F80
+      s_t[32 * s + 16 * g + i][32 * j + r] = code == 1 ? 0 : (code == 0 ? 0xBF80 : 0x3F80);
+    }
+  }
+  __syncthreads();
+  // row c of the block: 128 bf16 = 256 bytes, written by 16 threads of 16 bytes
+  for (int i = tid; i < 128 * 16; i += kSteThreads) {
+    const int c = i >> 4, part = i & 15;
+    u4 v;
+    const uint16_t* src = &s_t[c][part * 8];
+    v.x = src[0] | (static_cast<uint32_t>(src[1]) << 16);
+    v.y = src[2] | (static_cast<uint32_t>(src[3]) << 16);
+    v.z = src[4] | (static_cast<uint32_t>(src[5]) << 16);
+    v.w = src[6] | (static_cast<uint32_t>(src[7]) << 16);
+    *reinterpret_cast<u4*>(out + (static_cast<int64_t>(kt) * 128 + c) * N + nb * 128 + part * 8) = v;
+  }
+}
+
+// in [rows, C] (bf16 bit patterns scaled by beta[r] / 127, or int8 codes) -> out [C, rows_pad]
+// bf16, 64 x 64 tiles through LDS.  Rows from `rows` up to rows_pad are written as zeros.
+template <bool INT8>
+__global__ __launch_bounds__(kSteThreads) void transpose_rows_kernel(const void* __restrict__ in, const float* __restrict__ beta,
+                                                                     int rows, int rows_pad, int C, uint16_t* __restrict__ out) {
+  __shared__ uint16_t s_t[64][64 + 2];   // [c][r]
+  const int c_tiles = C >> 6;
+  const int ct = blockIdx.x % c_tiles, rt = blockIdx.x / c_tiles;
+  const int tid = threadIdx.x;
+  // load: thread t reads 16 consecutive channels of row rt * 64 + t / 4
+  {
+    const int r = rt * 64 + (tid >> 2), c0 = ct * 64 + (tid & 3) * 16;
+    uint16_t v[16];
+    if (r < rows) {
+      if constexpr (INT8) {
+        const u4 raw = *reinterpret_cast<const u4*>(static_cast<const int8_t*>(in) + static_cast<int64_t>(r) * C + c0);
+        const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int q = static_cast<int8_t>((w[i >> 2] >> (8 * (i & 3))) & 0xFF);
+          v[i] = f32_to_bf16(static_cast<float>(q));   // |q| <= 128: exact
+        }
+      } else {
+        const float s = beta[r] / 127.0f;   // the scale of Q_a, as the forward pass forms it
+        const uint16_t* src = static_cast<const uint16_t*>(in) + static_cast<int64_t>(r) * C + c0;
+        const u4 a = *reinterpret_cast<const u4*>(src), b = *reinterpret_cast<const u4*>(src + 8);
+        const uint32_t w[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          v[2 * i] = f32_to_bf16(bf16_lo(w[i]) * s);
+          v[2 * i + 1] = f32_to_bf16(bf16_hi(w[i]) * s);
+        }
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) v[i] = 0;
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s_t[(tid & 3) * 16 + i][tid >> 2] = v[i];
+  }
+  __syncthreads();
+  // store: thread t writes 16 consecutive rows of channel ct * 64 + t / 4
+  {
+    const int c = tid >> 2, r0 = (tid & 3) * 16;
+    const uint16_t* src = &s_t[c][r0];
+    u4 a, b;
+    a.x = src[0] | (static_cast<uint32_t>(src[1]) << 16);
+    a.y = src[2] | (static_cast<uint32_t>(src[3]) << 16);
+    a.z = src[4] | (static_cast<uint32_t>(src[5]) << 16);
+    a.w = src[6] | (static_cast<uint32_t>(src[7]) << 16);
+    b.x = src[8] | (static_cast<uint32_t>(src[9]) << 16);
+    b.y = src[10] | (static_cast<uint32_t>(src[11]) << 16);
+    b.z = src[12] | (static_cast<uint32_t>(src[13]) << 16);
+    b.w = src[14] | (static_cast<uint32_t>(src[15]) << 16);
+    uint16_t* dst = out + static_cast<int64_t>(ct * 64 + c) * rows_pad + rt * 64 + r0;
+    *reinterpret_cast<u4*>(dst) = a;
+    *reinterpret_cast<u4*>(dst + 8) = b;
+  }
+}
+
+__global__ __launch_bounds__(kSteThreads) void fill_alpha_kernel(const float* __restrict__ alpha, int alpha_stride, int E,
+                                                                 int K, float* __restrict__ out) {
+  const int i = blockIdx.x * kSteThreads + threadIdx.x;
+  if (i < E * K) out[i] = alpha[(i / K) * alpha_stride];
+}
+
+__global__ __launch_bounds__(kSteThreads) void fill_zero_kernel(float* __restrict__ out, int64_t n4) {
+  const int64_t stride = static_cast<int64_t>(gridDim.x) * kSteThreads;
+  for (int64_t i = static_cast<int64_t>(blockIdx.x) * kSteThreads + threadIdx.x; i < n4; i += stride)
+    reinterpret_cast<float4*>(out)[i] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+}
+
+static inline size_t ste_align(size_t v) { return (v + 255) / 256 * 256; }
+
+// Workspace: the expanded transposed weights of one expert at a time [K, N], the transposed
+// scaled gradient rows [N, rows_pad_e] and codes [K, rows_pad_e] of every expert back to back
+// (sum of rows_pad_e <= R + 63 E), and alpha broadcast [E, K].
+size_t ste_backward_workspace_bytes(int R, int N, int K, int E) {
+  const size_t rp = static_cast<size_t>(R) + 64 * static_cast<size_t>(E);
+  return ste_align(static_cast<size_t>(K) * N * 2) + ste_align(rp * N * 2) + ste_align(rp * K * 2) +
+         ste_align(static_cast<size_t>(E) * K * 4);
+}
+
+hipError_t launch_ste_backward(const uint16_t* dy, const int32_t* offsets_host, const uint32_t* packed, const float* alpha,
+                               int alpha_stride, const int8_t* q, const float* beta, int R, int N, int K, int E,
+                               float* dx, float* dw, void* workspace, hipStream_t stream) {
+  char* ws = static_cast<char*>(workspace);
+  const size_t rp_total = static_cast<size_t>(R) + 64 * static_cast<size_t>(E);
+  uint16_t* wt = reinterpret_cast<uint16_t*>(ws);
+  ws += ste_align(static_cast<size_t>(K) * N * 2);
+  uint16_t* dyt = reinterpret_cast<uint16_t*>(ws);
+  ws += ste_align(rp_total * N * 2);
+  uint16_t* qt = reinterpret_cast<uint16_t*>(ws);
+  ws += ste_align(rp_total * K * 2);
+  float* alpha_vec = reinterpret_cast<float*>(ws);
+
+  fill_alpha_kernel<<<(E * K + kSteThreads - 1) / kSteThreads, kSteThreads, 0, stream>>>(alpha, alpha_stride, E, K, alpha_vec);
+  const int64_t words = static_cast<int64_t>(N) * K / 16;
+  size_t pad_off = 0;   // padded rows before this expert
+  for (int e = 0; e < E; ++e) {
+    const int row0 = offsets_host[e], rows = offsets_host[e + 1] - offsets_host[e];
+    float* dw_e = dw + static_cast<int64_t>(e) * N * K;
+    if (rows == 0) {   // no token reached this expert: its gradient is zero
+      fill_zero_kernel<<<1024, kSteThreads, 0, stream>>>(dw_e, static_cast<int64_t>(N) * K / 4);
+      continue;
+    }
+    const int rows_pad = (rows + 63) / 64 * 64;
+    // dX rows of this expert
+    expand_ternary_t_kernel<<<(N / 128) * (K / 128), kSteThreads, 0, stream>>>(packed + e * words, N, K, wt);
+    hipError_t err = launch_gemm_tn_f32(dy + static_cast<int64_t>(row0) * N, wt, rows, K, N, dx + static_cast<int64_t>(row0) * K,
+                                        alpha_vec + static_cast<int64_t>(e) * K, stream);
+    if (err != hipSuccess) return err;
+    // dW of this expert
+    uint16_t* dyt_e = dyt + pad_off * N;
+    uint16_t* qt_e = qt + pad_off * K;
+    transpose_rows_kernel<false><<<(rows_pad / 64) * (N / 64), kSteThreads, 0, stream>>>(
+        dy + static_cast<int64_t>(row0) * N, beta + row0, rows, rows_pad, N, dyt_e);
+    transpose_rows_kernel<true><<<(rows_pad / 64) * (K / 64), kSteThreads, 0, stream>>>(
+        q + static_cast<int64_t>(row0) * K, nullptr, rows, rows_pad, K, qt_e);
+    err = launch_gemm_tn_f32(dyt_e, qt_e, N, K, rows_pad, dw_e, nullptr, stream);
+    if (err != hipSuccess) return err;
+    pad_off += rows_pad;
+  }
+  return hipGetLastError();
+}
+
+}  // namespace mote

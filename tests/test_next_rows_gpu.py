@@ -1,7 +1,7 @@
 """GPU parity of the pieces around the layer of Section 3.1, each through the C ABI against the
 CPU oracle: the post-training quantised shared expert (Section 4.3), the block of Eq.1-2
-(normalisation prologue, residual epilogue), the load-balancing statistic (Eq.12) and the 1-bit
-routed-expert quantiser (Table 5)."""
+(normalisation prologue, residual epilogue), the load-balancing statistic (Eq.12), the 1-bit
+routed-expert quantiser (Table 5) and the straight-through gradients of Section 3.2."""
 import dataclasses
 
 import numpy as np
@@ -266,3 +266,127 @@ def test_rtn_layer_arguments_are_validated():
     assert lib.mote_pack_rtn(ctypes.c_void_p(256), 32, 128, 5, ctypes.c_void_p(256), ctypes.c_void_p(256), None) == 1
     assert lib.mote_pack_rtn(ctypes.c_void_p(256), 33, 128, 8, ctypes.c_void_p(256), ctypes.c_void_p(256), None) == 2
     assert lib.mote_rtn_packed_bytes(32, 128, 5) == 0
+
+
+# -------------------------------------------------- straight-through gradients (Section 3.2)
+def _ste_problem(R, N, K, E, seed, cuts=None):
+    """Seeded inputs of one grouped ternary linear layer on its way back: latent weights ~ N(0, 0.02)
+    packed on the GPU (the pack is bit-exact against the oracle elsewhere), activations ~ N(0, 1)
+    quantised by the oracle's Q_a, gradient rows ~ N(0, 1) in bf16, ragged expert groups."""
+    M = _m()
+    g = torch.Generator().manual_seed(9000 + seed)
+    rng = np.random.default_rng(9000 + seed)
+    if cuts is None:
+        cuts = np.sort(rng.integers(0, R + 1, E - 1))
+    offsets = np.concatenate([[0], np.asarray(cuts, np.int64), [R]]).astype(np.int64)
+    latents = [torch.randn(N, K, generator=g) * 0.02 for _ in range(E)]
+    packed, alpha = [], []
+    for w in latents:
+        p, a = M.mote_pack_ternary(w.cuda())
+        packed.append(p.view(torch.uint8).reshape(-1))
+        alpha.append(a)
+    x = torch.randn(R, K, generator=g).numpy()
+    q, beta = O.absmax_int8(x)
+    dy = torch.randn(R, N, generator=g).to(torch.bfloat16)
+    experts = [O.ternarize(w.numpy()) for w in latents]
+    return dict(offsets=offsets, packed=torch.cat(packed), alpha=torch.cat(alpha), q=q, beta=beta.reshape(-1), dy=dy,
+                experts=experts)
+
+
+def _ste_tight_bound(terms):
+    """terms [n, S]: the products of S sampled outputs in contraction order.  The kernel adds them in
+    that order, 16 at a time, in fp32: every rounding is at most 2^-24 of the running sum, which
+    stays below the largest prefix sum plus one group of 16 products."""
+    n = terms.shape[0]
+    running = np.abs(np.cumsum(terms, axis=0)).max(axis=0) + 16.0 * np.abs(terms).max(axis=0)
+    return (n / 16 + 4) * 2.0 ** -24 * running + 1e-30
+
+
+def _ste_check(p, dx, dw, N, K, experts_checked=None, rows_per_expert=None):
+    """dx and dw against the oracle.  Every element within the worst-case bound of an fp32 sum of
+    exact products (a bf16 value times a ternary value or an int8 code; 2^-24 of sum |terms| per
+    rounding), and a sample of outputs within the much tighter bound of the running sum, which is
+    far below a single product: a dropped or mis-signed term would show."""
+    offsets, dy_bits = p["offsets"], W.bf16_bits(p["dy"])
+    E = len(p["experts"])
+    for e in (range(E) if experts_checked is None else experts_checked):
+        lo, hi = int(offsets[e]), int(offsets[e + 1])
+        rng = np.random.default_rng(100 + e)
+        rows = np.arange(lo, hi)
+        if rows_per_expert is not None and len(rows) > rows_per_expert:
+            rows = np.unique(np.concatenate([[lo, hi - 1], rng.choice(rows, rows_per_expert - 2, replace=False)]))
+        t, alpha = p["experts"][e]
+        # dX on the chosen rows, dW from all rows of the expert
+        sub_dx, _, _ = O.ste_linear_backward(dy_bits[rows], [0, len(rows)], [(t, alpha)], p["q"][rows], p["beta"][rows])
+        _, sub_dw, dys = O.ste_linear_backward(dy_bits[lo:hi], [0, hi - lo], [(t, alpha)], p["q"][lo:hi], p["beta"][lo:hi])
+        got_dw = dw[e].cpu().numpy().astype(np.float64)
+        if hi == lo:
+            assert not got_dw.any(), f"expert {e} without rows"
+            continue
+        got_dx = dx[torch.from_numpy(rows).cuda()].cpu().numpy().astype(np.float64)
+        g = O.bf16_to_f32(dy_bits[rows]).astype(np.float64)
+        a64, t64 = float(alpha), t.astype(np.float64)
+        bound_dx = a64 * (np.abs(g) @ np.abs(t64)) * ((N / 16 + 4) * 2.0 ** -24) + 1e-30
+        assert (np.abs(got_dx - sub_dx) <= bound_dx).all(), (e, np.abs(got_dx - sub_dx).max())
+        gs = O.bf16_to_f32(dys).astype(np.float64)
+        q64 = p["q"][lo:hi].astype(np.float64)
+        bound_dw = (np.abs(gs).T @ np.abs(q64)) * (((hi - lo) / 16 + 4) * 2.0 ** -24) + 1e-30
+        assert (np.abs(got_dw - sub_dw[0]) <= bound_dw).all(), (e, np.abs(got_dw - sub_dw[0]).max())
+        # sampled outputs against the bound of the running sum
+        n_s = 96
+        ri, ci = rng.integers(0, len(rows), n_s), rng.integers(0, K, n_s)
+        terms = g[ri].T * t64[:, ci]                                  # [N, n_s]
+        tight = a64 * _ste_tight_bound(terms) + np.abs(sub_dx[ri, ci]) * 2.0 ** -23
+        assert (np.abs(got_dx[ri, ci] - sub_dx[ri, ci]) <= tight).all(), (e, "dx")
+        assert np.median(tight) < 0.05 * a64 * np.median(np.abs(g)), (np.median(tight), a64)
+        ni, ci = rng.integers(0, N, n_s), rng.integers(0, K, n_s)
+        terms = gs[:, ni] * q64[:, ci]                                # [rows of e, n_s]
+        tight = _ste_tight_bound(terms)
+        assert (np.abs(got_dw[ni, ci] - sub_dw[0][ni, ci]) <= tight).all(), (e, "dw")
+        if hi - lo >= 8:
+            assert np.median(tight) < 0.05 * np.median(np.abs(gs)) * np.median(np.abs(q64)), np.median(tight)
+
+
+@pytest.mark.parametrize("R,N,K,E,cuts", [(300, 256, 128, 3, None), (1000, 512, 384, 4, None),
+                                          (77, 128, 256, 5, [0, 10, 10, 64]), (64, 128, 128, 1, None),
+                                          (513, 384, 256, 2, [512])])
+def test_ste_linear_backward_matches_oracle(R, N, K, E, cuts):
+    M = _m()
+    _log(f"ste backward R={R} N={N} K={K} E={E}")
+    p = _ste_problem(R, N, K, E, seed=R + N + K, cuts=cuts)
+    dx, dw = M.mote_ste_linear_backward(p["dy"].cuda(), p["offsets"], p["packed"].cuda(), p["alpha"].cuda(), 1,
+                                        torch.from_numpy(p["q"]).cuda(), torch.from_numpy(p["beta"]).cuda(), N, K)
+    torch.cuda.synchronize()
+    _ste_check(p, dx, dw, N, K)
+
+
+def test_ste_linear_backward_3b_gate_matrix_sampled():
+    """The gate matrices of configuration 3's width (N = 11008, K = 2048) with eight experts and
+    4096 dispatch rows: two experts through the oracle, every row tile boundary of theirs in dX."""
+    M = _m()
+    R, N, K, E = 4096, 11008, 2048, 8
+    _log(f"ste backward R={R} N={N} K={K} E={E}")
+    p = _ste_problem(R, N, K, E, seed=77)
+    dx, dw = M.mote_ste_linear_backward(p["dy"].cuda(), p["offsets"], p["packed"].cuda(), p["alpha"].cuda(), 1,
+                                        torch.from_numpy(p["q"]).cuda(), torch.from_numpy(p["beta"]).cuda(), N, K)
+    torch.cuda.synchronize()
+    sizes = np.diff(p["offsets"])
+    chosen = [int(np.argmax(sizes)), int(np.argsort(sizes)[len(sizes) // 2])]
+    _ste_check(p, dx, dw, N, K, experts_checked=chosen, rows_per_expert=24)
+
+
+def test_ste_linear_backward_arguments_are_validated():
+    M = _m()
+    lib = M.load_library()
+    import ctypes
+    offs = (ctypes.c_int32 * 3)(0, 5, 9)
+    buf = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda")
+    ptr = ctypes.c_void_p(buf.data_ptr())
+    call = lambda o, R, N, K, E, ws_bytes: lib.mote_ste_linear_backward(ptr, o, ptr, ptr, 1, ptr, ptr, R, N, K, E, ptr, ptr, ptr,
+                                                                       ctypes.c_size_t(ws_bytes), None)
+    assert call(offs, 9, 100, 128, 2, 1 << 20) == 2          # N not a multiple of 128
+    assert call(offs, 10, 128, 128, 2, 1 << 20) == 1         # offsets do not end at R
+    assert call((ctypes.c_int32 * 3)(0, 9, 5), 5, 128, 128, 2, 1 << 20) == 1   # not ascending
+    assert call(offs, 9, 128, 128, 2, 16) == 3               # workspace too small
+    assert lib.mote_ste_backward_workspace_bytes(9, 128, 128, 2) > 0
+    assert lib.mote_ste_backward_workspace_bytes(9, 100, 128, 2) == 0
