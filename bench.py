@@ -4,7 +4,7 @@ One step = one pass of the whole hot path (router + Q_a(x), dispatch, routed gat
 with SwiGLU, Q_a(h), routed down GEMM, shared FFN, combine) over one batch of synthetic
 tokens whose inputs and weights already sit in HBM.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload headline|c2|c3|c5|c4_T<T>_n<n>|<c2|c3|c5|p05|p15|p3>_T<T>]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload headline|c2|c3|c5|c4_T<T>_n<n>|<c2|c3|c5|p05|p15|p3>_T<T>|ste_<shape>]
 
 Without --workload the timed workload is the prefill shape (c3: d=2048, F=11008, E=16, top-2,
 T=8192); the decode shapes (c4) and the skewed shape (c5) are measured after it and ride along in
@@ -92,6 +92,55 @@ def read_traffic(stage: str, workload: str):
             if line.startswith("traffic_bytes_per_launch:"):
                 return float(line.split(":")[1])
     return None
+
+
+def measure_ste(workload: str, steps, warmup):
+    """Straight-through gradients (Section 3.2) of the routed gate matrices of a configuration:
+    R = T*k gradient rows of length d_ff, grouped by expert with seeded multinomial counts."""
+    import numpy as np
+    import torch
+    import paper_2506_14435_amd as M
+    cfg = pick_config(workload[4:])
+    R, N, K, E = cfg.n_tokens * cfg.top_k, cfg.d_ff, cfg.d_model, cfg.n_experts
+    steps = steps or 10
+    warmup = 3 if warmup is None else warmup
+    g = torch.Generator(device="cuda").manual_seed(cfg.seed)
+    counts = np.random.default_rng(cfg.seed).multinomial(R, np.full(E, 1.0 / E))
+    offsets = np.concatenate([[0], np.cumsum(counts)])
+    packed, alpha = [], []
+    for _ in range(E):
+        w = torch.randn(N, K, generator=g, device="cuda") * 0.02
+        pk, a = M.mote_pack_ternary(w)
+        packed.append(pk.view(torch.uint8).reshape(-1))
+        alpha.append(a)
+    packed, alpha = torch.cat(packed), torch.cat(alpha)
+    dy = torch.randn(R, N, generator=g, device="cuda").to(torch.bfloat16)
+    q = torch.randint(-127, 128, (R, K), generator=g, device="cuda", dtype=torch.int8)
+    beta = torch.rand(R, generator=g, device="cuda") * 4 + 1
+    lib = M.load_library()
+    ws = torch.empty(lib.mote_ste_backward_workspace_bytes(R, N, K, E), dtype=torch.uint8, device="cuda")
+    run = lambda: M.mote_ste_linear_backward(dy, offsets, packed, alpha, 1, q, beta, N, K, workspace=ws)
+    t0 = time.time()
+    while time.time() - t0 < 0.1:
+        run()
+    for _ in range(warmup):
+        run()
+    torch.cuda.synchronize()
+    start, end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    start.record()
+    for _ in range(steps):
+        run()
+    end.record()
+    torch.cuda.synchronize()
+    ms = start.elapsed_time(end) / steps
+    flops = 4.0 * R * N * K
+    ach = flops / (ms * 1e-3) / 1e12
+    return {"metric": "ste_backward_rows_per_s", "value": round(R / (ms * 1e-3), 1), "unit": "rows/s", "n_gpus": 1,
+            "steps": steps, "warmup": warmup, "ms_per_step": round(ms, 5), "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": f"ste_backward_{cfg.name}", "rows": R, "n_out": N, "n_in": K, "n_experts": E},
+            "roofline": {"kernel": "shared_gemm_kernel (dX and dW contractions)", "bound": "mfma", "achieved": round(ach, 2),
+                         "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": None}}
 
 
 def cpu_baseline(cfg, budget_s=20.0):
@@ -344,6 +393,9 @@ def main():
     for kv in args.tune:
         name, _, val = kv.partition("=")
         M.mote_tuning_set(name, int(val))
+    if args.workload.startswith("ste_"):   # e.g. ste_c3: the training-side gradient GEMMs, a line of its own
+        print(json.dumps(measure_ste(args.workload, args.steps, args.warmup)))
+        return
     headline = args.workload == "headline"
     main_workload = "c3" if headline else args.workload
     result, cfg = measure(main_workload, args.steps, args.warmup, args.graph, args.calib_copy_mib,

@@ -153,7 +153,9 @@ hipError_t launch_combine(const CombineArgs& a, hipStream_t stream);
 
 // bf16 GEMM of two row-major operands contracted along their rows, fp32 output (shared_ffn.hip)
 hipError_t launch_gemm_tn_f32(const uint16_t* act, const uint16_t* w, int M, int N, int K, float* out, const float* scale,
-                              hipStream_t stream);
+                              int planes, hipStream_t stream);
+hipError_t launch_gemm_tn_f32_kplanes(const uint16_t* act, const uint16_t* w, int M, int N, int K, int kplanes, float* out,
+                                      hipStream_t stream);
 // straight-through gradients of a grouped ternary linear layer (ste_backward.hip); offsets_host: host int32 [E + 1]
 size_t ste_backward_workspace_bytes(int R, int N, int K, int E);
 hipError_t launch_ste_backward(const uint16_t* dy, const int32_t* offsets_host, const uint32_t* packed, const float* alpha,

@@ -540,16 +540,31 @@ hipError_t launch_shared_down_scaled(const uint16_t* h_s, const uint16_t* w_down
 }
 
 // Plain bf16 GEMM with fp32 output for other callers: out[m, n] = scale[n] * sum_k act[m, k] * w[n, k]
-// (scale optional), one K plane.  K must be a multiple of 64.
+// (scale optional).  K must be a multiple of 64.  planes > 1: the contraction is cut into that many
+// K planes and plane p writes its partial sums to out + p * M * N (128 x 128 tiles; for problems
+// with too few output tiles to fill the chip); the caller adds the planes.
 hipError_t launch_gemm_tn_f32(const uint16_t* act, const uint16_t* w, int M, int N, int K, float* out, const float* scale,
-                              hipStream_t stream) {
+                              int planes, hipStream_t stream) {
   if (M == 0 || N == 0) return hipSuccess;
   SharedGemmArgs a{act, w, nullptr, M, N, K, nullptr, out, static_cast<int64_t>(M) * N, scale, nullptr};
+  if (planes > 1) return launch_shared_cfg<SharedCfg<1, 2, 2, 2, 2, 2>>(a, planes, stream);
   if (static_cast<int64_t>((M + 255) / 256) * ((N + 255) / 256) >= 256)
     return launch_shared_cfg<SharedCfg<1, 2, 4, 4, 2, 1, 4>>(a, 1, stream);   // 256 x 256
   if (static_cast<int64_t>((M + 127) / 128) * ((N + 255) / 256) >= 256)
     return launch_shared_cfg<SharedCfg<1, 2, 4, 2, 2, 2>>(a, 1, stream);      // 128 x 256
   return launch_shared_cfg<SharedCfg<1, 2, 2, 2, 2, 2>>(a, 1, stream);        // 128 x 128
+}
+
+// The same contraction cut into kplanes equal K planes, plane p written to out + p * M * N (the
+// caller's use: operands of several problems side by side along K, one plane per problem).
+// K / kplanes must be a multiple of 64.
+hipError_t launch_gemm_tn_f32_kplanes(const uint16_t* act, const uint16_t* w, int M, int N, int K, int kplanes, float* out,
+                                      hipStream_t stream) {
+  if (M == 0 || N == 0 || kplanes < 1) return hipSuccess;
+  SharedGemmArgs a{act, w, nullptr, M, N, K, nullptr, out, static_cast<int64_t>(M) * N, nullptr, nullptr};
+  if (static_cast<int64_t>((M + 255) / 256) * ((N + 255) / 256) * kplanes >= 256)
+    return launch_shared_cfg<SharedCfg<1, 2, 4, 4, 2, 1, 4>>(a, kplanes, stream);   // 256 x 256
+  return launch_shared_cfg<SharedCfg<1, 2, 2, 2, 2, 2>>(a, kplanes, stream);        // 128 x 128
 }
 
 }  // namespace mote

@@ -15,6 +15,8 @@
 //                             (rows_pad = rows rounded up to 64, the padding is zero)
 //   fill_alpha_kernel       : alpha_e broadcast over the K output channels of dX (the GEMM
 //                             epilogue multiplies per output channel)
+#include <algorithm>
+
 #include "common.h"
 #include "launch.h"
 
@@ -58,11 +60,12 @@ __global__ __launch_bounds__(kSteThreads) void expand_ternary_t_kernel(const uin
   }
 }
 
-// in [rows, C] (bf16 bit patterns scaled by beta[r] / 127, or int8 codes) -> out [C, rows_pad]
-// bf16, 64 x 64 tiles through LDS.  Rows from `rows` up to rows_pad are written as zeros.
+// in [rows, C] (bf16 bit patterns scaled by beta[r] / 127, or int8 codes) -> out [C, ld] bf16, columns
+// 0 .. rows_pad - 1 of it (the caller offsets `out` to the expert's first column), 64 x 64 tiles
+// through LDS.  Rows from `rows` up to rows_pad are written as zeros.
 template <bool INT8>
 __global__ __launch_bounds__(kSteThreads) void transpose_rows_kernel(const void* __restrict__ in, const float* __restrict__ beta,
-                                                                     int rows, int rows_pad, int C, uint16_t* __restrict__ out) {
+                                                                     int rows, int rows_pad, int C, int64_t ld, uint16_t* __restrict__ out) {
   __shared__ uint16_t s_t[64][64 + 2];   // [c][r]
   const int c_tiles = C >> 6;
   const int ct = blockIdx.x % c_tiles, rt = blockIdx.x / c_tiles;
@@ -112,7 +115,7 @@ __global__ __launch_bounds__(kSteThreads) void transpose_rows_kernel(const void*
     b.y = src[10] | (static_cast<uint32_t>(src[11]) << 16);
     b.z = src[12] | (static_cast<uint32_t>(src[13]) << 16);
     b.w = src[14] | (static_cast<uint32_t>(src[15]) << 16);
-    uint16_t* dst = out + static_cast<int64_t>(ct * 64 + c) * rows_pad + rt * 64 + r0;
+    uint16_t* dst = out + static_cast<int64_t>(ct * 64 + c) * ld + rt * 64 + r0;
     *reinterpret_cast<u4*>(dst) = a;
     *reinterpret_cast<u4*>(dst + 8) = b;
   }
@@ -130,22 +133,59 @@ __global__ __launch_bounds__(kSteThreads) void fill_zero_kernel(float* __restric
     reinterpret_cast<float4*>(out)[i] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
 }
 
+// out[i] = scale * (plane 0 + plane 1 + ...)[i], planes added in order
+__global__ __launch_bounds__(kSteThreads) void sum_planes_kernel(const float* __restrict__ planes, int n_planes, int64_t n4,
+                                                                 const float* __restrict__ alpha, float* __restrict__ out) {
+  const float scale = alpha[0];
+  const int64_t stride = static_cast<int64_t>(gridDim.x) * kSteThreads;
+  for (int64_t i = static_cast<int64_t>(blockIdx.x) * kSteThreads + threadIdx.x; i < n4; i += stride) {
+    float4 acc = reinterpret_cast<const float4*>(planes)[i];
+    for (int p = 1; p < n_planes; ++p) {
+      const float4 v = reinterpret_cast<const float4*>(planes)[p * n4 + i];
+      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+    reinterpret_cast<float4*>(out)[i] = make_float4(acc.x * scale, acc.y * scale, acc.z * scale, acc.w * scale);
+  }
+}
+
 static inline size_t ste_align(size_t v) { return (v + 255) / 256 * 256; }
 
+// K planes of the dX contraction of one expert: enough 128 x 128 output tiles times planes for two
+// workgroups per CU, planes of at least 16 K steps of 64, at most 8.
+constexpr int kSteMaxPlanes = 8;
+static int ste_dx_planes(int rows, int K, int N) {
+  const int64_t tiles = static_cast<int64_t>((rows + 127) / 128) * ((K + 127) / 128);
+  int planes = static_cast<int>(512 / tiles);
+  if (planes > (N >> 6) / 16) planes = (N >> 6) / 16;
+  if (planes > kSteMaxPlanes) planes = kSteMaxPlanes;
+  return planes < 1 ? 1 : planes;
+}
+
+// dW of all experts in one launch: every expert's transposed block is padded to the longest one
+// (lp rows) and the blocks sit side by side along the contraction axis, [N, E * lp] and
+// [K, E * lp]; the GEMM cuts the contraction into E planes of lp and plane e is dW_e.  Taken when
+// the padding adds at most a quarter to the work and the operands stay below 2 GiB.
+static bool ste_batched_dw(int64_t lp, int64_t sum_pad, int N, int K, int E) {
+  const int64_t lim = int64_t{1} << 31;
+  return E > 1 && E * lp * 4 <= sum_pad * 5 && E * lp * N * 2 < lim && E * lp * K * 2 < lim;
+}
+
 // Workspace: the expanded transposed weights of one expert at a time [K, N], the transposed
-// scaled gradient rows [N, rows_pad_e] and codes [K, rows_pad_e] of every expert back to back
-// (sum of rows_pad_e <= R + 63 E), and alpha broadcast [E, K].
+// scaled gradient rows and codes of every expert (sum of rows_pad_e <= R + 63 E columns, a quarter
+// more for the batched layout), alpha broadcast [E, K], partial planes of dX.
 size_t ste_backward_workspace_bytes(int R, int N, int K, int E) {
-  const size_t rp = static_cast<size_t>(R) + 64 * static_cast<size_t>(E);
+  const size_t rp = (static_cast<size_t>(R) + 64 * static_cast<size_t>(E)) * 5 / 4 + 64;
+  // partial planes of dX: an expert with so few rows that it takes p planes has at most 512 / p tiles of 128 x 128
+  const size_t plane_bytes = static_cast<size_t>(512 + kSteMaxPlanes * ((K + 127) / 128)) * 128 * 128 * 4;
   return ste_align(static_cast<size_t>(K) * N * 2) + ste_align(rp * N * 2) + ste_align(rp * K * 2) +
-         ste_align(static_cast<size_t>(E) * K * 4);
+         ste_align(static_cast<size_t>(E) * K * 4) + ste_align(plane_bytes);
 }
 
 hipError_t launch_ste_backward(const uint16_t* dy, const int32_t* offsets_host, const uint32_t* packed, const float* alpha,
                                int alpha_stride, const int8_t* q, const float* beta, int R, int N, int K, int E,
                                float* dx, float* dw, void* workspace, hipStream_t stream) {
   char* ws = static_cast<char*>(workspace);
-  const size_t rp_total = static_cast<size_t>(R) + 64 * static_cast<size_t>(E);
+  const size_t rp_total = (static_cast<size_t>(R) + 64 * static_cast<size_t>(E)) * 5 / 4 + 64;
   uint16_t* wt = reinterpret_cast<uint16_t*>(ws);
   ws += ste_align(static_cast<size_t>(K) * N * 2);
   uint16_t* dyt = reinterpret_cast<uint16_t*>(ws);
@@ -153,33 +193,66 @@ hipError_t launch_ste_backward(const uint16_t* dy, const int32_t* offsets_host, 
   uint16_t* qt = reinterpret_cast<uint16_t*>(ws);
   ws += ste_align(rp_total * K * 2);
   float* alpha_vec = reinterpret_cast<float*>(ws);
+  ws += ste_align(static_cast<size_t>(E) * K * 4);
+  float* dx_planes = reinterpret_cast<float*>(ws);
+
+  int64_t lp = 64, sum_pad = 0;
+  for (int e = 0; e < E; ++e) {
+    const int64_t rows_pad = (static_cast<int64_t>(offsets_host[e + 1]) - offsets_host[e] + 63) / 64 * 64;
+    lp = std::max(lp, rows_pad);
+    sum_pad += rows_pad;
+  }
+  const bool batched = ste_batched_dw(lp, sum_pad, N, K, E);
 
   fill_alpha_kernel<<<(E * K + kSteThreads - 1) / kSteThreads, kSteThreads, 0, stream>>>(alpha, alpha_stride, E, K, alpha_vec);
   const int64_t words = static_cast<int64_t>(N) * K / 16;
-  size_t pad_off = 0;   // padded rows before this expert
+  size_t pad_off = 0;   // padded rows before this expert (layout of one block per expert)
   for (int e = 0; e < E; ++e) {
     const int row0 = offsets_host[e], rows = offsets_host[e + 1] - offsets_host[e];
     float* dw_e = dw + static_cast<int64_t>(e) * N * K;
+    hipError_t err;
+    if (rows > 0) {   // dX rows of this expert
+      expand_ternary_t_kernel<<<(N / 128) * (K / 128), kSteThreads, 0, stream>>>(packed + e * words, N, K, wt);
+      const int planes = ste_dx_planes(rows, K, N);
+      if (planes == 1) {
+        err = launch_gemm_tn_f32(dy + static_cast<int64_t>(row0) * N, wt, rows, K, N, dx + static_cast<int64_t>(row0) * K,
+                                 alpha_vec + static_cast<int64_t>(e) * K, 1, stream);
+      } else {   // few output tiles: the contraction over N is cut into planes, added in order afterwards
+        err = launch_gemm_tn_f32(dy + static_cast<int64_t>(row0) * N, wt, rows, K, N, dx_planes, nullptr, planes, stream);
+        const int64_t n4 = static_cast<int64_t>(rows) * K / 4;
+        sum_planes_kernel<<<static_cast<unsigned>(std::min<int64_t>((n4 + kSteThreads - 1) / kSteThreads, 2048)), kSteThreads,
+                            0, stream>>>(dx_planes, planes, n4, alpha + static_cast<int64_t>(e) * alpha_stride,
+                                         dx + static_cast<int64_t>(row0) * K);
+      }
+      if (err != hipSuccess) return err;
+    }
+    // operands of dW
+    if (batched) {   // block e of the side-by-side layout, zero beyond its rows
+      const int tiles_r = static_cast<int>(lp / 64);
+      transpose_rows_kernel<false><<<tiles_r * (N / 64), kSteThreads, 0, stream>>>(
+          dy + static_cast<int64_t>(row0) * N, beta + row0, rows, static_cast<int>(lp), N, E * lp, dyt + e * lp);
+      transpose_rows_kernel<true><<<tiles_r * (K / 64), kSteThreads, 0, stream>>>(
+          q + static_cast<int64_t>(row0) * K, nullptr, rows, static_cast<int>(lp), K, E * lp, qt + e * lp);
+      continue;
+    }
     if (rows == 0) {   // no token reached this expert: its gradient is zero
       fill_zero_kernel<<<1024, kSteThreads, 0, stream>>>(dw_e, static_cast<int64_t>(N) * K / 4);
       continue;
     }
     const int rows_pad = (rows + 63) / 64 * 64;
-    // dX rows of this expert
-    expand_ternary_t_kernel<<<(N / 128) * (K / 128), kSteThreads, 0, stream>>>(packed + e * words, N, K, wt);
-    hipError_t err = launch_gemm_tn_f32(dy + static_cast<int64_t>(row0) * N, wt, rows, K, N, dx + static_cast<int64_t>(row0) * K,
-                                        alpha_vec + static_cast<int64_t>(e) * K, stream);
-    if (err != hipSuccess) return err;
-    // dW of this expert
     uint16_t* dyt_e = dyt + pad_off * N;
     uint16_t* qt_e = qt + pad_off * K;
     transpose_rows_kernel<false><<<(rows_pad / 64) * (N / 64), kSteThreads, 0, stream>>>(
-        dy + static_cast<int64_t>(row0) * N, beta + row0, rows, rows_pad, N, dyt_e);
+        dy + static_cast<int64_t>(row0) * N, beta + row0, rows, rows_pad, N, rows_pad, dyt_e);
     transpose_rows_kernel<true><<<(rows_pad / 64) * (K / 64), kSteThreads, 0, stream>>>(
-        q + static_cast<int64_t>(row0) * K, nullptr, rows, rows_pad, K, qt_e);
-    err = launch_gemm_tn_f32(dyt_e, qt_e, N, K, rows_pad, dw_e, nullptr, stream);
+        q + static_cast<int64_t>(row0) * K, nullptr, rows, rows_pad, K, rows_pad, qt_e);
+    err = launch_gemm_tn_f32(dyt_e, qt_e, N, K, rows_pad, dw_e, nullptr, 1, stream);
     if (err != hipSuccess) return err;
     pad_off += rows_pad;
+  }
+  if (batched) {
+    hipError_t err = launch_gemm_tn_f32_kplanes(dyt, qt, N, K, static_cast<int>(E * lp), E, dw, stream);
+    if (err != hipSuccess) return err;
   }
   return hipGetLastError();
 }
