@@ -176,7 +176,8 @@ static bool ste_batched_dw(int64_t lp, int64_t sum_pad, int N, int K, int E) {
 size_t ste_backward_workspace_bytes(int R, int N, int K, int E) {
   const size_t rp = (static_cast<size_t>(R) + 64 * static_cast<size_t>(E)) * 5 / 4 + 64;
   // partial planes of dX: an expert with so few rows that it takes p planes has at most 512 / p tiles of 128 x 128
-  const size_t plane_bytes = static_cast<size_t>(512 + kSteMaxPlanes * ((K + 127) / 128)) * 128 * 128 * 4;
+  const size_t plane_bytes = std::max(static_cast<size_t>(512 + kSteMaxPlanes * ((K + 127) / 128)) * 128 * 128 * 4,
+                                      static_cast<size_t>(kSteMaxPlanes) * R * K * 4);
   return ste_align(static_cast<size_t>(K) * N * 2) + ste_align(rp * N * 2) + ste_align(rp * K * 2) +
          ste_align(static_cast<size_t>(E) * K * 4) + ste_align(plane_bytes);
 }
@@ -213,12 +214,17 @@ hipError_t launch_ste_backward(const uint16_t* dy, const int32_t* offsets_host, 
     hipError_t err;
     if (rows > 0) {   // dX rows of this expert
       expand_ternary_t_kernel<<<(N / 128) * (K / 128), kSteThreads, 0, stream>>>(packed + e * words, N, K, wt);
-      const int planes = ste_dx_planes(rows, K, N);
+      int planes = ste_dx_planes(rows, K, N);
+      // 256 x 256 tiles (less operand traffic per flop) when eight planes of them fill the chip
+      const int64_t tiles256 = static_cast<int64_t>((rows + 255) / 256) * ((K + 255) / 256);
+      const bool big_tiles = tiles256 * kSteMaxPlanes >= 192 && (N >> 6) / 16 >= kSteMaxPlanes;
+      if (big_tiles) planes = kSteMaxPlanes;
       if (planes == 1) {
         err = launch_gemm_tn_f32(dy + static_cast<int64_t>(row0) * N, wt, rows, K, N, dx + static_cast<int64_t>(row0) * K,
                                  alpha_vec + static_cast<int64_t>(e) * K, 1, stream);
       } else {   // few output tiles: the contraction over N is cut into planes, added in order afterwards
-        err = launch_gemm_tn_f32(dy + static_cast<int64_t>(row0) * N, wt, rows, K, N, dx_planes, nullptr, planes, stream);
+        err = big_tiles ? launch_gemm_tn_f32_kplanes(dy + static_cast<int64_t>(row0) * N, wt, rows, K, N, planes, dx_planes, stream)
+                        : launch_gemm_tn_f32(dy + static_cast<int64_t>(row0) * N, wt, rows, K, N, dx_planes, nullptr, planes, stream);
         const int64_t n4 = static_cast<int64_t>(rows) * K / 4;
         sum_planes_kernel<<<static_cast<unsigned>(std::min<int64_t>((n4 + kSteThreads - 1) / kSteThreads, 2048)), kSteThreads,
                             0, stream>>>(dx_planes, planes, n4, alpha + static_cast<int64_t>(e) * alpha_stride,
