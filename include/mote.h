@@ -109,7 +109,7 @@ mote_status mote_pack_rtn(const void* w, int64_t n_out, int64_t n_in, int bits, 
 /* ---------------------------------------------------------------------------------------
  * Straight-through estimator of Section 3.2 (quantisation-aware training) for one grouped ternary
  * linear layer of Section 3.1, Y_e = Q_a(X_e) Q_w(W_e)^T, rows grouped by expert: the gradients
- * by-pass both quantisers, dL/dW = dL/dQ_w(W) and dL/dX = dL/dQ_a(X), i.e.
+ * treat both quantisers as the identity, dL/dW = dL/dQ_w(W) and dL/dX = dL/dQ_a(X), i.e.
  *
  *   dx[r, c]    = alpha_e * sum_n dy[r, n] * t_e[n, c]                         (r a row of expert e)
  *   dw[e][n, c] = sum_{r in e} bf16(dy[r, n] * (beta[r] / 127)) * q[r, c]
