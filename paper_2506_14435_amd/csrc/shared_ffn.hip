@@ -230,48 +230,77 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void shared_gemm_ker
             bf_[m][f] = *reinterpret_cast<const bf16x8*>(st_ + A_BYTES + m * B_BYTES +                    \
                                                          lds_tile_offset(b_row_base + f * 32, 2 * (s_) + g)); \
       }
-#define MOTE_MFMA_HALF(af_, bf_)                                                                          \
-      _Pragma("unroll") for (int m = 0; m < NMAT; ++m)                                                    \
-        _Pragma("unroll") for (int f = 0; f < BN_W; ++f)                                                  \
-          _Pragma("unroll") for (int i = 0; i < BM_W; ++i)                                                \
-            acc[m][i][f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf_[m][f], af_[i], acc[m][i][f], 0, 0, 0);
+      // One half of a K step: the MFMAs of fragments (ua_, ub_), and between them - so that the matrix
+      // pipe never waits for this wavefront to get through a block of other instructions - the reads of
+      // the next half's fragments (fa_, fb_) from (fstage_, sub-step fs_), two per MFMA, then the
+      // direct loads of parity par_ of K step ks_ into dstage_, one per MFMA.  Every wavefront of the
+      // workgroup is in the same half at the same time, so nothing else would cover such a block.
+      constexpr int NM = NMAT * BN_W * BM_W;          // MFMAs of a half
+      constexpr int NR = BM_W + NMAT * BN_W;          // fragment reads of a half
+      constexpr int RPS = 2;                          // fragment reads per MFMA (1: C3 shared down 5 % slower, 3: the same)
+      constexpr int RSLOTS = (NR + RPS - 1) / RPS;
+#define MOTE_SIDE_READ(r_, fa_, fb_, fstage_, fs_)                                                        \
+      if ((r_) < BM_W) {                                                                                  \
+        fa_[(r_) < BM_W ? (r_) : 0] = *reinterpret_cast<const bf16x8*>(                                   \
+            s_lds + (fstage_) + lds_tile_offset(a_row_base + ((r_) < BM_W ? (r_) : 0) * 32, 2 * (fs_) + g)); \
+      } else if ((r_) < NR) {                                                                             \
+        const int b_ = (r_) < NR && (r_) >= BM_W ? (r_) - BM_W : 0;                                       \
+        fb_[b_ / BN_W][b_ % BN_W] = *reinterpret_cast<const bf16x8*>(                                     \
+            s_lds + (fstage_) + A_BYTES + (b_ / BN_W) * B_BYTES + lds_tile_offset(b_row_base + (b_ % BN_W) * 32, 2 * (fs_) + g)); \
+      }
+      // the d_-th direct load of parity par_: the A passes par_, par_ + 2, ..., then the B passes
+#define MOTE_SIDE_DMA(d_, par_, dstage_, ks_)                                                             \
+      {                                                                                                   \
+        constexpr int NA_ = (Cfg::A_PASSES - (par_) + 1) / 2, NB_ = (Cfg::B_PASSES - (par_) + 1) / 2;     \
+        if ((d_) >= 0 && (d_) < NA_) { MOTE_DMA_A(dstage_, ks_, ((d_) >= 0 && (d_) < NA_ ? 2 * (d_) + (par_) : 0)); } \
+        else if ((d_) >= NA_ && (d_) < NA_ + NB_) { MOTE_DMA_B(dstage_, ks_, ((d_) >= NA_ && (d_) < NA_ + NB_ ? 2 * ((d_) - NA_) + (par_) : 0)); } \
+      }
+#define MOTE_HALF(ua_, ub_, fill_, fa_, fb_, fstage_, fs_, dma_, par_, dstage_, ks_)                      \
+      {                                                                                                   \
+        _Pragma("unroll") for (int m_ = 0; m_ < NMAT; ++m_)                                               \
+          _Pragma("unroll") for (int f_ = 0; f_ < BN_W; ++f_)                                             \
+            _Pragma("unroll") for (int i_ = 0; i_ < BM_W; ++i_) {                                         \
+              const int j_ = (m_ * BN_W + f_) * BM_W + i_;                                                \
+              acc[m_][i_][f_] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ub_[m_][f_], ua_[i_], acc[m_][i_][f_], 0, 0, 0); \
+              if (fill_) {                                                                                \
+                _Pragma("unroll") for (int r_ = 0; r_ < RPS; ++r_)                                        \
+                  MOTE_SIDE_READ(RPS * j_ + r_, fa_, fb_, fstage_, fs_)                                   \
+              }                                                                                           \
+              if (dma_) MOTE_SIDE_DMA(j_ - RSLOTS, par_, dstage_, ks_)                                    \
+              __builtin_amdgcn_sched_barrier(0);                                                          \
+            }                                                                                             \
+        /* more side work than MFMAs (small tiles): the rest at the end */                                \
+        _Pragma("unroll") for (int j_ = NM; j_ < RSLOTS + (Cfg::A_PASSES + Cfg::B_PASSES + 1) / 2; ++j_) { \
+          if (fill_) {                                                                                    \
+            _Pragma("unroll") for (int r_ = 0; r_ < RPS; ++r_)                                            \
+              MOTE_SIDE_READ(RPS * j_ + r_, fa_, fb_, fstage_, fs_)                                       \
+          }                                                                                               \
+          if (dma_) MOTE_SIDE_DMA(j_ - RSLOTS, par_, dstage_, ks_)                                        \
+        }                                                                                                 \
+        __builtin_amdgcn_sched_barrier(0);                                                                \
+      }
       MOTE_READ_HALF(af0, bf0, st_cur, 0);
       for (int kt = 0; kt < ktl; ++kt) {
         const bool pf = kt + 3 < ktl;
-        MOTE_READ_HALF(af1, bf1, st_cur, 1);
-        if (pf) {   // first half of the loads of K step kt+3, into the stage that step kt-1 used
-#pragma unroll
-          for (int p = 0; p < Cfg::A_PASSES; ++p)
-            if ((p & 1) == 0) MOTE_DMA_A(st_nx3, kt + 3, p);
-#pragma unroll
-          for (int p = 0; p < Cfg::B_PASSES; ++p)
-            if ((p & 1) == 0) MOTE_DMA_B(st_nx3, kt + 3, p);
-        }
         __builtin_amdgcn_sched_barrier(0);
-        MOTE_MFMA_HALF(af0, bf0);
-        __builtin_amdgcn_sched_barrier(0);
+        // first half: fragments of sub-step 1 of this step; first half of the loads of K step kt+3,
+        // into the stage that step kt-1 used
+        MOTE_HALF(af0, bf0, true, af1, bf1, st_cur, 1, pf, 0, st_nx3, kt + 3)
         // K step kt+1 has landed everywhere (kt+2 and the half of kt+3 stay in flight); every
         // wavefront has finished its reads of this step's stage
         if (pf) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" :: "n"(NLOAD + NH0) : "memory");
         else if (kt + 2 < ktl) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" :: "n"(NLOAD) : "memory");
         else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
         asm volatile("s_barrier" ::: "memory");
-        if (kt + 1 < ktl) MOTE_READ_HALF(af0, bf0, st_nxt, 0);
-        if (pf) {
-#pragma unroll
-          for (int p = 0; p < Cfg::A_PASSES; ++p)
-            if ((p & 1) == 1) MOTE_DMA_A(st_nx3, kt + 3, p);
-#pragma unroll
-          for (int p = 0; p < Cfg::B_PASSES; ++p)
-            if ((p & 1) == 1) MOTE_DMA_B(st_nx3, kt + 3, p);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        MOTE_MFMA_HALF(af1, bf1);
-        __builtin_amdgcn_sched_barrier(0);
+        // second half: fragments of sub-step 0 of the next step (after the last step: of a stage nobody
+        // uses, read and dropped); the other half of the loads
+        MOTE_HALF(af1, bf1, true, af0, bf0, st_nxt, 0, pf, 1, st_nx3, kt + 3)
         const int t = st_cur; st_cur = st_nxt; st_nxt = st_nx2; st_nx2 = st_nx3; st_nx3 = t;
       }
+#undef MOTE_HALF
+#undef MOTE_SIDE_DMA
+#undef MOTE_SIDE_READ
 #undef MOTE_READ_HALF
-#undef MOTE_MFMA_HALF
     } else {
       // K loop.  K step kt contracts stage st_cur while the loads of kt+2 are issued, half of them
       // per 16-element sub-step, into the stage that the barrier at the end of step kt-1 released.
