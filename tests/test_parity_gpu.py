@@ -544,6 +544,24 @@ def test_layer_3b_width_mid_size_batches(T):
     _check_down_rows(cfg, op, taps, np.sort(rng.choice(R, 48, replace=False)))
 
 
+def test_layer_64_row_tiles_with_units_cut_into_equal_runs():
+    """A wider expert (d_ff = 14336: seven K planes in the down projection) at T = 480: 20 row tiles of
+    64 rows give 140 (row tile, K plane) groups for 256 workgroups, so the wave-streaming down kernel
+    cuts the (group, fragment) units into equal runs and a workgroup ends one group and starts the
+    next (asserted from the expert counts)."""
+    cfg = W.MoteConfig("mid_equal_runs_T480", 2048, 14336, 16, 2, 480, seed=31, sigma_shared=0.012)
+    _log(f"layer {cfg.name}")
+    gp, op = GpuProblem(cfg), OracleProblem(cfg)
+    out, taps = _run_layer(gp, FULL_TAPS + ("h_s", "y_s"))
+    counts = taps["counts"].cpu().numpy()
+    groups = int(np.sum((counts + 63) // 64)) * 7
+    assert 128 < groups < 192, groups          # one workgroup per group would leave more than a quarter of 256 idle
+    _check_sampled(cfg, 24, 4, out, taps, op)
+    _check_rows_of_every_expert(cfg, op, taps, tile_m=64)
+    R = cfg.n_tokens * cfg.top_k
+    _check_down_rows(cfg, op, taps, np.sort(np.random.default_rng(480).choice(R, 48, replace=False)))
+
+
 @pytest.mark.parametrize("T", [136, 192, 240])
 def test_layer_1p5b_width_64_row_tiles(T):
     """The paper's 1.5B layer (four experts, top-1) with 34 to 60 rows per expert: 64-row tiles whose
