@@ -627,6 +627,21 @@ def test_layer_config4_decode(T, n):
     _check_sampled(cfg, 12, n, out, taps, op)
 
 
+def test_layer_decode_with_64_experts_tile_list_beyond_one_wavefront():
+    """64 experts at the 3B width (d_ff = 8192), 64 tokens of which the biased router sends to six
+    experts: the bound on the row tiles (R / 32 + E = 68) exceeds the 64 entries the wave-streaming
+    kernel can fetch as one table, so it reads the tile list entry by entry."""
+    cfg = W.MoteConfig("decode_64_experts", 2048, 8192, 64, 2, 64, seed=41, sigma_shared=0.015,
+                       bias_kind="subset", bias_subset=6)
+    _log(f"layer {cfg.name}")
+    gp, op = GpuProblem(cfg), OracleProblem(cfg)
+    out, taps = _run_layer(gp, FULL_TAPS)
+    _, _, idx_o, _ = O.router(op.x, op.w_router, op.bias, cfg.top_k)
+    n = len(np.unique(idx_o))
+    assert 2 <= n <= 6
+    _check_sampled(cfg, 16, n, out, taps, op)
+
+
 def test_layer_config5_skewed_sampled():
     cfg = W.C5
     _log(f"layer {cfg.name}")
