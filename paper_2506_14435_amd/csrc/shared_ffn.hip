@@ -531,7 +531,26 @@ hipError_t launch_shared_gate_up_scaled(const uint16_t* x, const uint16_t* w_gat
 // 42 us, two planes 35 us and a faster combine; the 3B width with T = 2048, F = 11008: one plane
 // on 128 of 512 workgroup slots 220 us).  Pure function of the shape: the workspace layout
 // depends on it.
+// Mid-size batches at the 3B width: 48 to 64 output tiles of 256 x 256, so that four or five K planes
+// of them fill the chip once (one workgroup per CU); the big tile moves less operand data per flop
+// than two planes of 128 x 128 tiles.  Measured alone this kernel takes 111 -> 84 us at the 3B width with
+// T = 2048 (122 -> 87 us on the slower kind of box); the forward, where it shares the chip with the routed
+// chain, gains 1 to 3.5 % at T = 2048 and 0 to 2 % at T = 1536.
+// Not elsewhere: eight planes at T = 1024 make the combine and the kernels after it slower (371 -> 373 us),
+// the 1.5B width (six channel tiles) 293 -> 294 us, the 0.5B width 152 -> 160 us.
+static int shared_down_big_planes(int T, int d, int F) {
+  const int64_t tiles256 = static_cast<int64_t>((T + 255) / 256) * ((d + 255) / 256);
+  if (T < 1536 || d < 2048 || tiles256 > 64) return 0;
+  int planes = static_cast<int>(256 / tiles256);
+  if (planes > F / 1024) planes = F / 1024;
+  return planes >= 2 ? planes : 0;
+}
+
 int shared_down_planes(int T, int d, int F) {
+  if (const int big = shared_down_big_planes(T, d, F)) {
+    const int KT = F >> 6, ktp = (KT + big - 1) / big;
+    return (KT + ktp - 1) / ktp;
+  }
   const int64_t tiles = static_cast<int64_t>((T + 127) / 128) * ((d + 127) / 128);
   const int KT = F >> 6;
   int planes = tiles > 0 ? static_cast<int>(512 / tiles) : 1;   // rounded down: a third plane at the 1.5B width (192 tiles) cost 5 %
@@ -557,6 +576,7 @@ hipError_t launch_shared_down_scaled(const uint16_t* h_s, const uint16_t* w_down
   if (T == 0) return hipSuccess;
   SharedGemmArgs a{h_s, w_down, nullptr, T, d, F, nullptr, y_s, static_cast<int64_t>(T) * d, s_down, nullptr};
   const int planes = shared_down_planes(T, d, F);
+  if (shared_down_big_planes(T, d, F) != 0) return launch_shared_cfg<SharedCfg<1, 2, 4, 4, 2, 1, 4>>(a, planes, stream);
   if (planes > 1) return launch_shared_cfg<SharedCfg<1, 2, 2, 2, 2, 2>>(a, planes, stream);   // small problem: 128 x 128 tiles
   int v = shared_variant();
   if (v == 0) v = static_cast<int64_t>((T + 255) / 256) * ((d + 255) / 256) >= 256 ? 5 : 3;
