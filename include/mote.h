@@ -319,7 +319,10 @@ enum {
   MOTE_KNOB_MID_ROWS_LO = 12,        /* 64-row plan tiles (wave-streaming kernel) when an expert sees on
                                         average more than this many rows (31) ...                      */
   MOTE_KNOB_MID_ROWS_HI = 13,        /* ... and at most this many (60); lo >= hi switches them off     */
-  MOTE_N_KNOBS = 14
+  MOTE_KNOB_STE_BATCH_MIB = 14,      /* mote_ste_linear_backward: the experts of one grouped dX GEMM have at
+                                        most this many MiB of expanded weights together, 1 .. 4095 (4095);
+                                        mote_ste_backward_workspace_bytes depends on it                 */
+  MOTE_N_KNOBS = 15
 };
 mote_status mote_tuning_set(int knob, int value);
 

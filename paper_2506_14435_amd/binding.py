@@ -26,7 +26,7 @@ EXPORTS = ("mote_status_string", "mote_version", "mote_packed_bytes", "mote_pack
            "mote_stage_timing", "mote_stage_times", "mote_event_pair_overhead", "mote_tuning_set", "mote_calib_copy")
 KNOBS = ("no_fork", "fork_min_log2", "event_fence", "quant_wide", "routed_variant", "routed_down_variant",
          "shared_variant", "group_m", "dynamic_rounds", "decode_variant", "router_token_blocks", "down_split_tiles",
-         "mid_rows_lo", "mid_rows_hi")
+         "mid_rows_lo", "mid_rows_hi", "ste_batch_mib")
 
 
 class MoteError(RuntimeError):

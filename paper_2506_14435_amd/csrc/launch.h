@@ -22,6 +22,7 @@ enum Knob {
   kKnobDownSplitTiles,       // routed down projection: two K planes while there are fewer 128 x 128 output tiles than this
   kKnobMidRowsLo,            // 64-row plan tiles for more than this many rows per expert on average ...
   kKnobMidRowsHi,            // ... and at most this many
+  kKnobSteBatchMiB,          // expanded weights (MiB) of the experts that share one grouped dX GEMM
   kKnobCount
 };
 int knob(int id);
@@ -156,6 +157,10 @@ hipError_t launch_gemm_tn_f32(const uint16_t* act, const uint16_t* w, int M, int
                               int planes, hipStream_t stream);
 hipError_t launch_gemm_tn_f32_kplanes(const uint16_t* act, const uint16_t* w, int M, int N, int K, int kplanes, float* out,
                                       hipStream_t stream);
+// the same for groups of rows with a weight matrix (and scale vector) each; row0_host: host int32 [n_groups + 1]
+int grouped_gemm_planes(const int32_t* row0_host, int n_groups, int N, int K, int max_planes);
+hipError_t launch_gemm_grouped_f32(const uint16_t* act, const uint16_t* w, const int32_t* row0_host, int n_groups, int N,
+                                   int K, float* out, const float* scale, int planes, hipStream_t stream);
 // straight-through gradients of a grouped ternary linear layer (ste_backward.hip); offsets_host: host int32 [E + 1]
 size_t ste_backward_workspace_bytes(int R, int N, int K, int E);
 hipError_t launch_ste_backward(const uint16_t* dy, const int32_t* offsets_host, const uint32_t* packed, const float* alpha,

@@ -13,7 +13,7 @@ static int g_knobs[kKnobCount] = {
     /* NoFork */ 0, /* ForkMinLog2 */ 29, /* EventFence */ 0, /* QuantWide */ 0, /* RoutedVariant */ 0,
     /* RoutedDownVariant */ -1, /* SharedVariant */ 0, /* GroupM */ 2, /* DynamicRounds */ 4,
     /* DecodeVariant */ -1, /* RouterTokenBlocks */ 256, /* DownSplitTiles */ 600, /* MidRowsLo */ 31,
-    /* MidRowsHi */ 60};
+    /* MidRowsHi */ 60, /* SteBatchMiB */ 4095};
 int knob(int id) { return (id >= 0 && id < kKnobCount) ? g_knobs[id] : -1; }
 }  // namespace mote
 

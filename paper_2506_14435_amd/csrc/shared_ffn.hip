@@ -73,9 +73,20 @@ struct SharedGemmArgs {
   const float* scale1;   // per output channel (RTN-quantised weights held as integer-valued bf16)
 };
 
-template <typename Cfg>
-__global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void shared_gemm_kernel(SharedGemmArgs a, int n_ntiles,
-                                                                                   int kplanes, int ktp, int group_m) {
+// Grouped rows: group e owns the rows row0[e] .. row0[e+1]-1 of act / the output and the row tiles
+// tile0[e] .. tile0[e+1]-1 (ceil(rows / BM) of them, none for an empty group); its weights are matrix e
+// of w0 ([n][N, K]) and its channel scales row e of scale0 ([n][N]).  A row tile that reaches beyond its
+// group's last row loads the rows that follow (clamped to the last row of act) and stores only its own.
+constexpr int kMaxRowGroups = 64;
+struct RowGroups {
+  int n;
+  int row0[kMaxRowGroups + 1];
+  int tile0[kMaxRowGroups + 1];
+};
+
+template <typename Cfg, bool GROUPED>
+__device__ __forceinline__ void shared_gemm_body(const SharedGemmArgs& a, const RowGroups* rg, int n_ntiles, int kplanes,
+                                                 int ktp, int group_m) {
   constexpr int NMAT = Cfg::NMAT, BM_W = Cfg::BM_W, BN_W = Cfg::BN_W;
   constexpr int BM = Cfg::BM, BN = Cfg::BN;
   constexpr int A_BYTES = Cfg::A_BYTES, B_BYTES = Cfg::B_BYTES, STAGE_BYTES = Cfg::STAGE_BYTES;
@@ -100,7 +111,8 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void shared_gemm_ker
   // With kplanes > 1 (down projection of small problems) the contraction is cut into planes of
   // ktp K steps; each plane writes its own partial output, added later in plane order.
   n_ntiles *= kplanes;
-  const int n_mtiles = (M + BM - 1) / BM;
+  int n_mtiles = (M + BM - 1) / BM;
+  if constexpr (GROUPED) n_mtiles = rg->tile0[rg->n];
   const int xcd = blockIdx.x & 7;
   const bool split_n = n_ntiles >= 16;
   const int xcd_ntiles = split_n ? (n_ntiles - xcd + 7) >> 3 : n_ntiles;
@@ -127,7 +139,7 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void shared_gemm_ker
     return r;
   };
   const v4i rsrc_a = make_rsrc(a.act, static_cast<int64_t>(M) * K * 2);
-  const v4i rsrc_b0 = make_rsrc(a.w0, static_cast<int64_t>(N) * K * 2);
+  const v4i rsrc_b0 = make_rsrc(a.w0, static_cast<int64_t>(GROUPED ? rg->n : 1) * N * K * 2);
   const v4i rsrc_b1 = make_rsrc(NMAT == 2 ? a.w1 : a.w0, static_cast<int64_t>(N) * K * 2);
   // lane l of a wavefront load lands at byte 16*l of a 1-KiB block = tile row l/4, physical
   // chunk l%4, and therefore fetches logical chunk (l%4) ^ swizzle(row)
@@ -135,6 +147,8 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void shared_gemm_ker
   const uint32_t ld_chunk = static_cast<uint32_t>(((lane & 3) ^ ((lane >> 4) & 3)) << 4);
   uint32_t a_off[Cfg::A_PASSES], b_off[Cfg::B_PASSES];   // byte offsets of this lane's 16 bytes, K step 0 of the plane
   int mt, nt, kc, ktl;
+  // first row of the tile, one past the last row it may store, its group (0 without groups)
+  int mrow, mend = M, grp = 0;
   int st_cur = 0, st_nxt = STAGE_BYTES, st_nx2 = 2 * STAGE_BYTES;   // stage of K step kt, kt+1, kt+2 (byte offsets)
   int st_nx3 = 3 * STAGE_BYTES;                                      // ... and kt+3 (ring of four stages only)
 
@@ -149,15 +163,28 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void shared_gemm_ker
     nt_ = ntk_ / kplanes;                                                       \
     kc_ = ntk_ - nt_ * kplanes;                                                 \
   }
-#define MOTE_POINTERS(mt_, nt_, kc_)                                                               \
+  // where row tile mt_ starts and ends (uniform; the group is found by walking the table)
+#define MOTE_ROWS(mt_, mrow_, mend_, grp_)                                      \
+  {                                                                             \
+    if constexpr (GROUPED) {                                                    \
+      int e_ = 0;                                                               \
+      while (e_ + 1 < rg->n && rg->tile0[e_ + 1] <= (mt_)) ++e_;                \
+      grp_ = e_;                                                                \
+      mrow_ = rg->row0[e_] + ((mt_) - rg->tile0[e_]) * BM;                      \
+      mend_ = rg->row0[e_ + 1];                                                 \
+    } else {                                                                    \
+      mrow_ = (mt_) * BM;                                                       \
+    }                                                                           \
+  }
+#define MOTE_POINTERS(mrow_, grp_, nt_, kc_)                                                       \
   {                                                                                                \
     const uint32_t k0_ = static_cast<uint32_t>((kc_) * ktp) * 64u + ld_chunk;                      \
     _Pragma("unroll") for (int p = 0; p < Cfg::A_PASSES; ++p) {                                    \
-      const int row_ = min((mt_) * BM + p * Cfg::ROWS_PER_PASS + ld_row, M - 1);                   \
+      const int row_ = min((mrow_) + p * Cfg::ROWS_PER_PASS + ld_row, M - 1);                      \
       a_off[p] = static_cast<uint32_t>(row_) * static_cast<uint32_t>(K) * 2u + k0_;                \
     }                                                                                              \
     _Pragma("unroll") for (int p = 0; p < Cfg::B_PASSES; ++p) {                                    \
-      const int row_ = min((nt_) * BN + (p * Cfg::ROWS_PER_PASS) % BN + ld_row, N - 1);            \
+      const int row_ = min((nt_) * BN + (p * Cfg::ROWS_PER_PASS) % BN + ld_row, N - 1) + (grp_) * N; \
       b_off[p] = static_cast<uint32_t>(row_) * static_cast<uint32_t>(K) * 2u + k0_;                \
     }                                                                                              \
   }
@@ -186,8 +213,9 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void shared_gemm_ker
 
   // ---- first tile ----
   MOTE_DECODE(slot, mt, nt, kc);
+  MOTE_ROWS(mt, mrow, mend, grp);
   ktl = min(ktp, KT - kc * ktp);
-  MOTE_POINTERS(mt, nt, kc);
+  MOTE_POINTERS(mrow, grp, nt, kc);
   MOTE_ISSUE_STEP(st_cur, 0);
   if (ktl > 1) MOTE_ISSUE_STEP(st_nxt, 1);
 
@@ -195,7 +223,11 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void shared_gemm_ker
     const int nslot = slot + stride;
     const bool has_next = nslot < xcd_work;
     int mt2 = mt, nt2 = nt, kc2 = kc;
-    if (has_next) MOTE_DECODE(nslot, mt2, nt2, kc2);
+    int mrow2 = mrow, mend2 = mend, grp2 = grp;
+    if (has_next) {
+      MOTE_DECODE(nslot, mt2, nt2, kc2);
+      MOTE_ROWS(mt2, mrow2, mend2, grp2);
+    }
     MOTE_WAIT_BARRIER(ktl > 1);   // K step 0 visible to every wavefront; the patches of the previous tile are done
     if constexpr (Cfg::STAGES == 4) {   // the third K step goes where patches of the previous tile were
       if (ktl > 2) MOTE_ISSUE_STEP(st_nx2, 2);
@@ -354,7 +386,7 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void shared_gemm_ker
     int ktl2 = ktl;
     if (has_next) {
       ktl2 = min(ktp, KT - kc2 * ktp);
-      MOTE_POINTERS(mt2, nt2, kc2);
+      MOTE_POINTERS(mrow2, grp2, nt2, kc2);
       MOTE_ISSUE_STEP(st_cur, 0);
       if (ktl2 > 1) MOTE_ISSUE_STEP(st_nxt, 1);
     }
@@ -372,7 +404,7 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void shared_gemm_ker
     unsigned char* const patch =
         Cfg::PATCH_IN_TWO ? s_lds + (wave < Cfg::WAVES / 2 ? st_nx2 : st_nx3) + (wave % (Cfg::WAVES / 2)) * Cfg::PATCH_BYTES
                           : s_lds + (Cfg::PATCH_IN_STAGE ? st_nx2 : Cfg::STAGES * STAGE_BYTES) + wave * Cfg::PATCH_BYTES;
-    const int m0 = mt * BM, n_wave0 = nt * BN + wn * BN_W * 32;
+    const int m0 = mrow, n_wave0 = nt * BN + wn * BN_W * 32;
     const int rd_row = lane / LANES_PER_ROW, rd_chunk = lane % LANES_PER_ROW;
     if (a.scale0 != nullptr) {   // row scales of quantised weights (uniform branch, not taken by the bf16 expert)
 #pragma unroll
@@ -380,7 +412,7 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void shared_gemm_ker
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           const int ch = min(n_wave0 + f * 32 + 8 * q + 4 * g, N - 4);
-          const float4 s0 = *reinterpret_cast<const float4*>(a.scale0 + ch);
+          const float4 s0 = *reinterpret_cast<const float4*>(a.scale0 + static_cast<int64_t>(grp) * N + ch);
           float4 s1 = s0;
           if constexpr (NMAT == 2) s1 = *reinterpret_cast<const float4*>(a.scale1 + ch);
 #pragma unroll
@@ -426,7 +458,7 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void shared_gemm_ker
           const int pr = p * ROWS_PER_READ + rd_row;
           const u4 v = *reinterpret_cast<const u4*>(patch + pr * PATCH_ROW + rd_chunk * 16);
           const int orow = m0 + wm * BM_W * 32 + i * 32 + pr;
-          if (orow < M && rd_n < N) {
+          if (orow < mend && rd_n < N) {
             const int64_t o = static_cast<int64_t>(orow) * N + rd_n;
             if constexpr (Cfg::MODE == 0) *reinterpret_cast<u4*>(a.h_out + o) = v;
             else *reinterpret_cast<u4*>(a.y_out + static_cast<int64_t>(kc) * a.plane_stride + o) = v;
@@ -441,14 +473,29 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void shared_gemm_ker
     // No barrier here: the patches are private and their stage is not refilled before the next
     // tile's first barrier.
     slot = nslot; mt = mt2; nt = nt2; kc = kc2; ktl = ktl2;
+    mrow = mrow2; mend = mend2; grp = grp2;
   }
 #undef MOTE_DECODE
+#undef MOTE_ROWS
 #undef MOTE_POINTERS
 #undef MOTE_DMA
 #undef MOTE_DMA_A
 #undef MOTE_DMA_B
 #undef MOTE_ISSUE_STEP
 #undef MOTE_WAIT_BARRIER
+}
+
+template <typename Cfg>
+__global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void shared_gemm_kernel(SharedGemmArgs a, int n_ntiles,
+                                                                                   int kplanes, int ktp, int group_m) {
+  shared_gemm_body<Cfg, false>(a, nullptr, n_ntiles, kplanes, ktp, group_m);
+}
+
+template <typename Cfg>
+__global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void grouped_gemm_kernel(SharedGemmArgs a, RowGroups rg,
+                                                                                    int n_ntiles, int kplanes, int ktp,
+                                                                                    int group_m) {
+  shared_gemm_body<Cfg, true>(a, &rg, n_ntiles, kplanes, ktp, group_m);
 }
 
 static int shared_cu_count() {
@@ -614,6 +661,92 @@ hipError_t launch_gemm_tn_f32_kplanes(const uint16_t* act, const uint16_t* w, in
   if (static_cast<int64_t>((M + 255) / 256) * ((N + 255) / 256) * kplanes >= 256)
     return launch_shared_cfg<SharedCfg<1, 2, 4, 4, 2, 1, 4>>(a, kplanes, stream);   // 256 x 256
   return launch_shared_cfg<SharedCfg<1, 2, 2, 2, 2, 2>>(a, kplanes, stream);        // 128 x 128
+}
+
+template <typename Cfg>
+static hipError_t launch_grouped_cfg(const SharedGemmArgs& a, const int32_t* row0, int n_groups, int kplanes,
+                                     hipStream_t stream) {
+  RowGroups rg;
+  rg.n = n_groups;
+  int tiles_m = 0;
+  for (int e = 0; e < n_groups; ++e) {
+    rg.row0[e] = row0[e] - row0[0];
+    rg.tile0[e] = tiles_m;
+    tiles_m += (row0[e + 1] - row0[e] + Cfg::BM - 1) / Cfg::BM;
+  }
+  rg.row0[n_groups] = row0[n_groups] - row0[0];
+  rg.tile0[n_groups] = tiles_m;
+  for (int e = n_groups + 1; e <= kMaxRowGroups; ++e) rg.row0[e] = rg.tile0[e] = 0;
+  if (tiles_m == 0) return hipSuccess;
+  const int n_ntiles = (a.N + Cfg::BN - 1) / Cfg::BN;
+  const int KT64 = a.K >> 6;
+  const int ktp = 2 * ((KT64 + kplanes - 1) / kplanes);
+  const size_t lds = Cfg::LDS_BYTES;
+  static bool attr_set = false;
+  static int resident = Cfg::MIN_BLOCKS;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(grouped_gemm_kernel<Cfg>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+    if (e != hipSuccess) return e;
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, grouped_gemm_kernel<Cfg>, Cfg::THREADS, lds) == hipSuccess && n > 0)
+      resident = n;
+    attr_set = true;
+  }
+  const int64_t tiles = static_cast<int64_t>(tiles_m) * n_ntiles * kplanes;
+  int64_t blocks = static_cast<int64_t>(shared_cu_count()) * resident;
+  if (blocks > tiles) blocks = (tiles + 7) / 8 * 8;
+  grouped_gemm_kernel<Cfg><<<static_cast<unsigned>(blocks), Cfg::THREADS, lds, stream>>>(a, rg, n_ntiles, kplanes, ktp,
+                                                                                        tile_group_m());
+  return hipGetLastError();
+}
+
+// Row tiles a grouped launch has with tiles of bm rows.
+static int64_t grouped_row_tiles(const int32_t* row0, int n_groups, int bm) {
+  int64_t t = 0;
+  for (int e = 0; e < n_groups; ++e) t += (row0[e + 1] - row0[e] + bm - 1) / bm;
+  return t;
+}
+
+// K planes of a grouped GEMM (pure function of the group sizes and the shape, at most max_planes).  256 x 256
+// tiles: two planes when one plane leaves more than 15 % of the last round of workgroups empty and two
+// leave less (16 groups of about 1024 rows, N = 2048, K = 11008: 576 tiles on 256 CUs; one / two / three /
+// four planes 2.39 / 2.32 / 2.37 / 2.35 ms for the whole backward call), else one.  Small problems
+// (128 x 128 tiles): as many as give two workgroups per CU, planes of at least 16 K steps of 64.
+int grouped_gemm_planes(const int32_t* row0_host, int n_groups, int N, int K, int max_planes) {
+  const int cus = shared_cu_count();
+  const int64_t t256 = grouped_row_tiles(row0_host, n_groups, 256) * ((N + 255) / 256);
+  if (t256 >= (3 * cus) / 4) {
+    auto eff = [&](int p) {
+      const int64_t rounds = (t256 * p + cus - 1) / cus;
+      return static_cast<double>(t256 * p) / static_cast<double>(rounds * cus);
+    };
+    if (eff(1) >= 0.85 || max_planes < 2 || (K >> 6) < 32) return 1;
+    return eff(2) > eff(1) + 0.05 ? 2 : 1;
+  }
+  const int64_t t128 = grouped_row_tiles(row0_host, n_groups, 128) * ((N + 127) / 128);
+  if (t128 == 0) return 1;
+  int planes = static_cast<int>((2 * cus) / t128);
+  if (planes > (K >> 6) / 16) planes = (K >> 6) / 16;
+  if (planes > max_planes) planes = max_planes;
+  return planes < 1 ? 1 : planes;
+}
+
+// Grouped GEMM for other callers: rows row0_host[e] .. row0_host[e+1]-1 of act (row0_host: n_groups + 1
+// ascending HOST integers; act, out and the rows are counted from row0_host[0], which act and out point at)
+// are contracted with matrix e of w ([n_groups][N, K] bf16) and scaled per channel by row e of scale
+// ([n_groups][N], optional): out[r, n] = scale[e][n] * sum_k act[r, k] * w[e][n, k].  planes as given by
+// grouped_gemm_planes: plane p writes its partial sums to out + p * rows * N and the caller adds them.
+// n_groups <= 64, n_groups * N * K * 2 bytes and rows * K * 2 bytes below 4 GiB, K a multiple of 64.
+hipError_t launch_gemm_grouped_f32(const uint16_t* act, const uint16_t* w, const int32_t* row0_host, int n_groups, int N,
+                                   int K, float* out, const float* scale, int planes, hipStream_t stream) {
+  if (n_groups < 1 || n_groups > kMaxRowGroups) return hipErrorInvalidValue;
+  const int M = row0_host[n_groups] - row0_host[0];
+  if (M == 0 || N == 0) return hipSuccess;
+  SharedGemmArgs a{act, w, nullptr, M, N, K, nullptr, out, static_cast<int64_t>(M) * N, scale, nullptr};
+  if (grouped_row_tiles(row0_host, n_groups, 256) * ((N + 255) / 256) >= (3 * shared_cu_count()) / 4)
+    return launch_grouped_cfg<SharedCfg<1, 2, 4, 4, 2, 1, 4>>(a, row0_host, n_groups, planes, stream);   // 256 x 256
+  return launch_grouped_cfg<SharedCfg<1, 2, 2, 2, 2, 2>>(a, row0_host, n_groups, planes, stream);        // 128 x 128
 }
 
 }  // namespace mote

@@ -133,10 +133,10 @@ __global__ __launch_bounds__(kSteThreads) void fill_zero_kernel(float* __restric
     reinterpret_cast<float4*>(out)[i] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
 }
 
-// out[i] = scale * (plane 0 + plane 1 + ...)[i], planes added in order
+// out[i] = scale * (plane 0 + plane 1 + ...)[i], planes added in order; alpha == nullptr: scale 1
 __global__ __launch_bounds__(kSteThreads) void sum_planes_kernel(const float* __restrict__ planes, int n_planes, int64_t n4,
                                                                  const float* __restrict__ alpha, float* __restrict__ out) {
-  const float scale = alpha[0];
+  const float scale = alpha != nullptr ? alpha[0] : 1.0f;
   const int64_t stride = static_cast<int64_t>(gridDim.x) * kSteThreads;
   for (int64_t i = static_cast<int64_t>(blockIdx.x) * kSteThreads + threadIdx.x; i < n4; i += stride) {
     float4 acc = reinterpret_cast<const float4*>(planes)[i];
@@ -150,15 +150,15 @@ __global__ __launch_bounds__(kSteThreads) void sum_planes_kernel(const float* __
 
 static inline size_t ste_align(size_t v) { return (v + 255) / 256 * 256; }
 
-// K planes of the dX contraction of one expert: enough 128 x 128 output tiles times planes for two
-// workgroups per CU, planes of at least 16 K steps of 64, at most 8.
+// K planes of the dX contraction at most; dX runs as one grouped GEMM over as many experts as have
+// their expanded weights below 4 GiB together (the kernel addresses them with 32-bit byte offsets;
+// the limit is a tuning knob so that tests reach the loop over batches with small matrices).
 constexpr int kSteMaxPlanes = 8;
-static int ste_dx_planes(int rows, int K, int N) {
-  const int64_t tiles = static_cast<int64_t>((rows + 127) / 128) * ((K + 127) / 128);
-  int planes = static_cast<int>(512 / tiles);
-  if (planes > (N >> 6) / 16) planes = (N >> 6) / 16;
-  if (planes > kSteMaxPlanes) planes = kSteMaxPlanes;
-  return planes < 1 ? 1 : planes;
+static int ste_dx_batch(int N, int K, int E) {
+  const int64_t per = static_cast<int64_t>(N) * K * 2;
+  const int64_t lim_mib = std::min(std::max(knob(kKnobSteBatchMiB), 1), 4095);
+  const int64_t g = ((lim_mib << 20) + ((int64_t{1} << 20) - 1)) / per;
+  return static_cast<int>(std::max<int64_t>(1, std::min<int64_t>(g, E)));
 }
 
 // dW of all experts in one launch: every expert's transposed block is padded to the longest one
@@ -170,15 +170,13 @@ static bool ste_batched_dw(int64_t lp, int64_t sum_pad, int N, int K, int E) {
   return E > 1 && E * lp * 4 <= sum_pad * 5 && E * lp * N * 2 < lim && E * lp * K * 2 < lim;
 }
 
-// Workspace: the expanded transposed weights of one expert at a time [K, N], the transposed
+// Workspace: the expanded transposed weights of one batch of experts [experts][K, N], the transposed
 // scaled gradient rows and codes of every expert (sum of rows_pad_e <= R + 63 E columns, a quarter
 // more for the batched layout), alpha broadcast [E, K], partial planes of dX.
 size_t ste_backward_workspace_bytes(int R, int N, int K, int E) {
   const size_t rp = (static_cast<size_t>(R) + 64 * static_cast<size_t>(E)) * 5 / 4 + 64;
-  // partial planes of dX: an expert with so few rows that it takes p planes has at most 512 / p tiles of 128 x 128
-  const size_t plane_bytes = std::max(static_cast<size_t>(512 + kSteMaxPlanes * ((K + 127) / 128)) * 128 * 128 * 4,
-                                      static_cast<size_t>(kSteMaxPlanes) * R * K * 4);
-  return ste_align(static_cast<size_t>(K) * N * 2) + ste_align(rp * N * 2) + ste_align(rp * K * 2) +
+  const size_t plane_bytes = static_cast<size_t>(kSteMaxPlanes) * R * K * 4;
+  return ste_align(static_cast<size_t>(ste_dx_batch(N, K, E)) * K * N * 2) + ste_align(rp * N * 2) + ste_align(rp * K * 2) +
          ste_align(static_cast<size_t>(E) * K * 4) + ste_align(plane_bytes);
 }
 
@@ -187,8 +185,9 @@ hipError_t launch_ste_backward(const uint16_t* dy, const int32_t* offsets_host, 
                                float* dx, float* dw, void* workspace, hipStream_t stream) {
   char* ws = static_cast<char*>(workspace);
   const size_t rp_total = (static_cast<size_t>(R) + 64 * static_cast<size_t>(E)) * 5 / 4 + 64;
+  const int batch = ste_dx_batch(N, K, E);
   uint16_t* wt = reinterpret_cast<uint16_t*>(ws);
-  ws += ste_align(static_cast<size_t>(K) * N * 2);
+  ws += ste_align(static_cast<size_t>(batch) * K * N * 2);
   uint16_t* dyt = reinterpret_cast<uint16_t*>(ws);
   ws += ste_align(rp_total * N * 2);
   uint16_t* qt = reinterpret_cast<uint16_t*>(ws);
@@ -207,31 +206,33 @@ hipError_t launch_ste_backward(const uint16_t* dy, const int32_t* offsets_host, 
 
   fill_alpha_kernel<<<(E * K + kSteThreads - 1) / kSteThreads, kSteThreads, 0, stream>>>(alpha, alpha_stride, E, K, alpha_vec);
   const int64_t words = static_cast<int64_t>(N) * K / 16;
+  // dX: t^T of a batch of experts expanded to bf16, then one grouped GEMM over their rows, scaled by alpha
+  for (int e0 = 0; e0 < E; e0 += batch) {
+    const int nb = std::min(batch, E - e0);
+    const int row0 = offsets_host[e0], rows = offsets_host[e0 + nb] - row0;
+    if (rows == 0) continue;
+    for (int e = e0; e < e0 + nb; ++e)
+      if (offsets_host[e + 1] > offsets_host[e])
+        expand_ternary_t_kernel<<<(N / 128) * (K / 128), kSteThreads, 0, stream>>>(
+            packed + e * words, N, K, wt + static_cast<int64_t>(e - e0) * K * N);
+    const int planes = grouped_gemm_planes(offsets_host + e0, nb, K, N, kSteMaxPlanes);
+    const uint16_t* dy_b = dy + static_cast<int64_t>(row0) * N;
+    float* dx_b = dx + static_cast<int64_t>(row0) * K;
+    const float* alpha_b = alpha_vec + static_cast<int64_t>(e0) * K;
+    hipError_t err = launch_gemm_grouped_f32(dy_b, wt, offsets_host + e0, nb, K, N, planes == 1 ? dx_b : dx_planes, alpha_b,
+                                             planes, stream);
+    if (err != hipSuccess) return err;
+    if (planes > 1) {   // the contraction over N was cut into planes, added in order here
+      const int64_t n4 = static_cast<int64_t>(rows) * K / 4;
+      sum_planes_kernel<<<static_cast<unsigned>(std::min<int64_t>((n4 + kSteThreads - 1) / kSteThreads, 2048)), kSteThreads,
+                          0, stream>>>(dx_planes, planes, n4, nullptr, dx_b);
+    }
+  }
   size_t pad_off = 0;   // padded rows before this expert (layout of one block per expert)
   for (int e = 0; e < E; ++e) {
     const int row0 = offsets_host[e], rows = offsets_host[e + 1] - offsets_host[e];
     float* dw_e = dw + static_cast<int64_t>(e) * N * K;
     hipError_t err;
-    if (rows > 0) {   // dX rows of this expert
-      expand_ternary_t_kernel<<<(N / 128) * (K / 128), kSteThreads, 0, stream>>>(packed + e * words, N, K, wt);
-      int planes = ste_dx_planes(rows, K, N);
-      // 256 x 256 tiles (less operand traffic per flop) when eight planes of them fill the chip
-      const int64_t tiles256 = static_cast<int64_t>((rows + 255) / 256) * ((K + 255) / 256);
-      const bool big_tiles = tiles256 * kSteMaxPlanes >= 192 && (N >> 6) / 16 >= kSteMaxPlanes;
-      if (big_tiles) planes = kSteMaxPlanes;
-      if (planes == 1) {
-        err = launch_gemm_tn_f32(dy + static_cast<int64_t>(row0) * N, wt, rows, K, N, dx + static_cast<int64_t>(row0) * K,
-                                 alpha_vec + static_cast<int64_t>(e) * K, 1, stream);
-      } else {   // few output tiles: the contraction over N is cut into planes, added in order afterwards
-        err = big_tiles ? launch_gemm_tn_f32_kplanes(dy + static_cast<int64_t>(row0) * N, wt, rows, K, N, planes, dx_planes, stream)
-                        : launch_gemm_tn_f32(dy + static_cast<int64_t>(row0) * N, wt, rows, K, N, dx_planes, nullptr, planes, stream);
-        const int64_t n4 = static_cast<int64_t>(rows) * K / 4;
-        sum_planes_kernel<<<static_cast<unsigned>(std::min<int64_t>((n4 + kSteThreads - 1) / kSteThreads, 2048)), kSteThreads,
-                            0, stream>>>(dx_planes, planes, n4, alpha + static_cast<int64_t>(e) * alpha_stride,
-                                         dx + static_cast<int64_t>(row0) * K);
-      }
-      if (err != hipSuccess) return err;
-    }
     // operands of dW
     if (batched) {   // block e of the side-by-side layout, zero beyond its rows
       const int tiles_r = static_cast<int>(lp / 64);

@@ -378,6 +378,41 @@ def test_ste_linear_backward_3b_gate_matrix_sampled():
     _ste_check(p, dx, dw, N, K, experts_checked=chosen, rows_per_expert=24)
 
 
+@pytest.mark.parametrize("R,N,K,E,cuts,what", [
+    # 32 row tiles of 256 x 8 channel tiles = one round of workgroups: one K plane
+    (7816, 1024, 2048, 4, [1000, 2030, 5030], "one plane"),
+    # 34 row tiles x 8 channel tiles = a full round and a nearly empty one: two K planes, added afterwards
+    (8192, 2048, 2048, 8, [1000, 2100, 3100, 4200, 5200, 6150, 7170], "two planes")])
+def test_ste_linear_backward_grouped_dx_on_256_row_tiles(R, N, K, E, cuts, what):
+    """dX of all experts in one grouped GEMM on 256 x 256 tiles: groups that end inside a tile, tiles
+    that read the next group's rows, the last tile clamped at R."""
+    M = _m()
+    _log(f"ste backward, grouped dX on 256-row tiles ({what}) R={R} N={N} K={K} E={E}")
+    p = _ste_problem(R, N, K, E, seed=R + N + E, cuts=cuts)
+    dx, dw = M.mote_ste_linear_backward(p["dy"].cuda(), p["offsets"], p["packed"].cuda(), p["alpha"].cuda(), 1,
+                                        torch.from_numpy(p["q"]).cuda(), torch.from_numpy(p["beta"]).cuda(), N, K)
+    torch.cuda.synchronize()
+    assert torch.isfinite(dx).all()
+    _ste_check(p, dx, dw, N, K, experts_checked=[0, 1, E - 1], rows_per_expert=40)
+
+
+def test_ste_linear_backward_dx_in_batches_of_experts():
+    """With the limit on expanded weights per grouped dX launch lowered to 1 MiB the six experts go
+    through in batches of two: one batch with an expert without rows, one without any row."""
+    M = _m()
+    R, N, K, E = 900, 512, 768, 6
+    _log(f"ste backward in batches of experts R={R} N={N} K={K} E={E}")
+    p = _ste_problem(R, N, K, E, seed=4242, cuts=[0, 400, 400, 400, 700])
+    M.mote_tuning_set("ste_batch_mib", 1)
+    try:
+        dx, dw = M.mote_ste_linear_backward(p["dy"].cuda(), p["offsets"], p["packed"].cuda(), p["alpha"].cuda(), 1,
+                                            torch.from_numpy(p["q"]).cuda(), torch.from_numpy(p["beta"]).cuda(), N, K)
+        torch.cuda.synchronize()
+    finally:
+        M.mote_tuning_set("ste_batch_mib", 4095)
+    _ste_check(p, dx, dw, N, K)
+
+
 def test_ste_linear_backward_arguments_are_validated():
     M = _m()
     lib = M.load_library()
