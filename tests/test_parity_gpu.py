@@ -77,7 +77,11 @@ def test_pack_ternary_degenerate_matrices():
 @pytest.mark.parametrize("T,d,E,k,bias", [(64, 256, 4, 2, False), (1, 256, 4, 1, False), (37, 384, 8, 2, True),
                                           (515, 896, 8, 2, False), (130, 2048, 16, 2, True),
                                           (33, 256, 6, 3, False), (70, 512, 32, 4, True), (9, 128, 64, 8, False),
-                                          (16, 128, 16, 16, False)])
+                                          (16, 128, 16, 16, False),
+                                          # from 4096 tokens on, E <= 16: 16 tokens per workgroup on the fp64 matrix
+                                          # instruction (ragged last workgroup; E not a multiple of 8; a last
+                                          # block of 128 channels; the widest register variant)
+                                          (4099, 384, 6, 3, True), (4112, 896, 8, 2, True), (4100, 3584, 16, 2, False)])
 def test_router_topk_matches_oracle(T, d, E, k, bias):
     M = _m()
     _log(f"router T={T} d={d} E={E} k={k} bias={bias}")
@@ -135,6 +139,29 @@ def test_router_non_finite_hidden_states_select_valid_experts():
         ref = O.router(W.bf16_bits(x[:1]), W.bf16_bits(wr), None, k)
         idx, p, _ = M.mote_router_topk(x.cuda(), wr.cuda(), k, want_counts=False)
         assert np.array_equal(idx.cpu().numpy()[:1], ref[2])
+
+
+def test_router_non_finite_hidden_states_many_tokens():
+    """The same on the kernel that takes over from 4096 tokens: a non-finite token touches neither
+    its 15 neighbours in the accumulator tile nor the range of the indices."""
+    M = _m()
+    T, d, E, k = 4100, 256, 5, 3
+    g = torch.Generator().manual_seed(77)
+    x = torch.randn(T, d, generator=g).to(torch.bfloat16)
+    wr = (torch.randn(d, E, generator=g) * d ** -0.5).to(torch.bfloat16)
+    bad = [1, 17, 18, 4097]
+    x[1, 3] = float("nan")
+    x[17, 7] = float("inf")
+    x[18, 9] = float("-inf")
+    x[4097, :] = float("nan")
+    idx, p, _ = M.mote_router_topk(x.cuda(), wr.cuda(), k, want_counts=False)
+    idx, p = idx.cpu().numpy(), p.cpu().numpy()
+    assert idx.min() >= 0 and idx.max() < E
+    assert all(len(set(row)) == k for row in idx[bad].tolist())
+    good = np.setdiff1d(np.arange(T), bad)
+    _, _, idx_o, w_o = O.router(W.bf16_bits(x[good]), W.bf16_bits(wr), None, k)
+    assert np.array_equal(idx[good], idx_o)
+    assert np.allclose(p[good], w_o, rtol=2e-6, atol=1e-9)
 
 
 # ------------------------------------------------------------------------ whole layer
