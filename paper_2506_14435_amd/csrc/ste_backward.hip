@@ -27,8 +27,8 @@ constexpr int kSteThreads = 256;
 // One workgroup expands four packed tiles (32 output rows x 128 input channels each, consecutive
 // row tiles nt = 4 b .. 4 b + 3 of one K tile) into a 128 x 128 block of the transposed matrix:
 // out[(128 kt + c) * N + 128 b + n] = t[128 b + n][128 kt + c].
-__global__ __launch_bounds__(kSteThreads) void expand_ternary_t_kernel(const uint32_t* __restrict__ packed, int N, int K,
-                                                                       uint16_t* __restrict__ out) {
+__device__ __forceinline__ void expand_ternary_t_body(const uint32_t* __restrict__ packed, int N, int K,
+                                                      uint16_t* __restrict__ out) {
   __shared__ uint16_t s_t[128][128 + 2];   // [c][n], two bf16 of padding per row
   const int tiles_k = K >> 7;
   const int kt = blockIdx.x % tiles_k, nb = blockIdx.x / tiles_k;
@@ -60,12 +60,26 @@ __global__ __launch_bounds__(kSteThreads) void expand_ternary_t_kernel(const uin
   }
 }
 
+// Expert e0 + blockIdx.y of `packed` ([experts][N, K] packed) into matrix blockIdx.y of `out`; experts
+// without rows (row0[e] == row0[e + 1]) are skipped, their matrices are never read.
+struct SteGroups {
+  int n;
+  int row0[65];
+};
+__global__ __launch_bounds__(kSteThreads) void expand_ternary_t_kernel(const uint32_t* __restrict__ packed, int N, int K,
+                                                                       SteGroups grp, int e0, uint16_t* __restrict__ out) {
+  const int e = e0 + blockIdx.y;
+  if (grp.row0[e] == grp.row0[e + 1]) return;
+  expand_ternary_t_body(packed + static_cast<int64_t>(e) * (static_cast<int64_t>(N) * K / 16), N, K,
+                        out + static_cast<int64_t>(blockIdx.y) * K * N);
+}
+
 // in [rows, C] (bf16 bit patterns scaled by beta[r] / 127, or int8 codes) -> out [C, ld] bf16, columns
 // 0 .. rows_pad - 1 of it (the caller offsets `out` to the expert's first column), 64 x 64 tiles
 // through LDS.  Rows from `rows` up to rows_pad are written as zeros.
 template <bool INT8>
-__global__ __launch_bounds__(kSteThreads) void transpose_rows_kernel(const void* __restrict__ in, const float* __restrict__ beta,
-                                                                     int rows, int rows_pad, int C, int64_t ld, uint16_t* __restrict__ out) {
+__device__ __forceinline__ void transpose_rows_body(const void* __restrict__ in, const float* __restrict__ beta, int rows,
+                                                    int C, int64_t ld, uint16_t* __restrict__ out) {
   __shared__ uint16_t s_t[64][64 + 2];   // [c][r]
   const int c_tiles = C >> 6;
   const int ct = blockIdx.x % c_tiles, rt = blockIdx.x / c_tiles;
@@ -119,6 +133,25 @@ __global__ __launch_bounds__(kSteThreads) void transpose_rows_kernel(const void*
     *reinterpret_cast<u4*>(dst) = a;
     *reinterpret_cast<u4*>(dst + 8) = b;
   }
+}
+
+template <bool INT8>
+__global__ __launch_bounds__(kSteThreads) void transpose_rows_kernel(const void* __restrict__ in, const float* __restrict__ beta,
+                                                                     int rows, int rows_pad, int C, int64_t ld, uint16_t* __restrict__ out) {
+  (void)rows_pad;   // the grid covers rows_pad / 64 row tiles
+  transpose_rows_body<INT8>(in, beta, rows, C, ld, out);
+}
+
+// The same for every expert in one launch (blockIdx.y = expert): expert e owns the rows row0[e] .. row0[e+1]-1
+// of `in` and the columns e * lp .. of `out` ([C, n * lp], every block padded with zeros to lp columns).
+template <bool INT8>
+__global__ __launch_bounds__(kSteThreads) void transpose_groups_kernel(const void* __restrict__ in, const float* __restrict__ beta,
+                                                                       SteGroups grp, int lp, int C, uint16_t* __restrict__ out) {
+  const int e = blockIdx.y, r0 = grp.row0[e];
+  const void* const in_e = INT8 ? static_cast<const void*>(static_cast<const int8_t*>(in) + static_cast<int64_t>(r0) * C)
+                                : static_cast<const void*>(static_cast<const uint16_t*>(in) + static_cast<int64_t>(r0) * C);
+  transpose_rows_body<INT8>(in_e, INT8 ? nullptr : beta + r0, grp.row0[e + 1] - r0, C, static_cast<int64_t>(grp.n) * lp,
+                            out + static_cast<int64_t>(e) * lp);
 }
 
 __global__ __launch_bounds__(kSteThreads) void fill_alpha_kernel(const float* __restrict__ alpha, int alpha_stride, int E,
@@ -205,16 +238,15 @@ hipError_t launch_ste_backward(const uint16_t* dy, const int32_t* offsets_host, 
   const bool batched = ste_batched_dw(lp, sum_pad, N, K, E);
 
   fill_alpha_kernel<<<(E * K + kSteThreads - 1) / kSteThreads, kSteThreads, 0, stream>>>(alpha, alpha_stride, E, K, alpha_vec);
-  const int64_t words = static_cast<int64_t>(N) * K / 16;
+  SteGroups grp;
+  grp.n = E;
+  for (int e = 0; e <= 64; ++e) grp.row0[e] = offsets_host[std::min(e, E)];
   // dX: t^T of a batch of experts expanded to bf16, then one grouped GEMM over their rows, scaled by alpha
   for (int e0 = 0; e0 < E; e0 += batch) {
     const int nb = std::min(batch, E - e0);
     const int row0 = offsets_host[e0], rows = offsets_host[e0 + nb] - row0;
     if (rows == 0) continue;
-    for (int e = e0; e < e0 + nb; ++e)
-      if (offsets_host[e + 1] > offsets_host[e])
-        expand_ternary_t_kernel<<<(N / 128) * (K / 128), kSteThreads, 0, stream>>>(
-            packed + e * words, N, K, wt + static_cast<int64_t>(e - e0) * K * N);
+    expand_ternary_t_kernel<<<dim3((N / 128) * (K / 128), nb), kSteThreads, 0, stream>>>(packed, N, K, grp, e0, wt);
     const int planes = grouped_gemm_planes(offsets_host + e0, nb, K, N, kSteMaxPlanes);
     const uint16_t* dy_b = dy + static_cast<int64_t>(row0) * N;
     float* dx_b = dx + static_cast<int64_t>(row0) * K;
@@ -228,20 +260,19 @@ hipError_t launch_ste_backward(const uint16_t* dy, const int32_t* offsets_host, 
                           0, stream>>>(dx_planes, planes, n4, nullptr, dx_b);
     }
   }
+  // operands of dW
+  if (batched) {   // block e of the side-by-side layout, zero beyond its rows: all experts in one launch each
+    const unsigned tiles_r = static_cast<unsigned>(lp / 64);
+    transpose_groups_kernel<false><<<dim3(tiles_r * (N / 64), E), kSteThreads, 0, stream>>>(dy, beta, grp, static_cast<int>(lp),
+                                                                                          N, dyt);
+    transpose_groups_kernel<true><<<dim3(tiles_r * (K / 64), E), kSteThreads, 0, stream>>>(q, nullptr, grp, static_cast<int>(lp),
+                                                                                         K, qt);
+  }
   size_t pad_off = 0;   // padded rows before this expert (layout of one block per expert)
-  for (int e = 0; e < E; ++e) {
+  for (int e = 0; e < E && !batched; ++e) {
     const int row0 = offsets_host[e], rows = offsets_host[e + 1] - offsets_host[e];
     float* dw_e = dw + static_cast<int64_t>(e) * N * K;
     hipError_t err;
-    // operands of dW
-    if (batched) {   // block e of the side-by-side layout, zero beyond its rows
-      const int tiles_r = static_cast<int>(lp / 64);
-      transpose_rows_kernel<false><<<tiles_r * (N / 64), kSteThreads, 0, stream>>>(
-          dy + static_cast<int64_t>(row0) * N, beta + row0, rows, static_cast<int>(lp), N, E * lp, dyt + e * lp);
-      transpose_rows_kernel<true><<<tiles_r * (K / 64), kSteThreads, 0, stream>>>(
-          q + static_cast<int64_t>(row0) * K, nullptr, rows, static_cast<int>(lp), K, E * lp, qt + e * lp);
-      continue;
-    }
     if (rows == 0) {   // no token reached this expert: its gradient is zero
       fill_zero_kernel<<<1024, kSteThreads, 0, stream>>>(dw_e, static_cast<int64_t>(N) * K / 4);
       continue;
