@@ -129,7 +129,7 @@ mote_status mote_pack_rtn(const void* w, int64_t n_out, int64_t n_in, int bits, 
  * workspace       : device, >= mote_ste_backward_workspace_bytes(R, N, K, E) bytes, 256-byte aligned
  *                   (the transposed ternary weights of all experts as bf16, at most 4 GiB of them at a
  *                   time, the transposed gradient rows and codes, partial sums of dx: about
- *                   2 E N K + 3 R (N + K) + 32 R K bytes)
+ *                   2 E N K + 2 R (N + K) + 32 R K bytes)
  * Limits: N % 128 == 0, K % 128 == 0, 1 <= E <= 64, R >= 0; every operand of one expert below
  * 2 GiB.  Enqueued on hip_stream; the host array is read before the call returns.
  * Returns MOTE_ERR_INVALID_ARG for NULL pointers or offsets that are not ascending from 0 to R,

@@ -152,12 +152,11 @@ struct CombineArgs {
 };
 hipError_t launch_combine(const CombineArgs& a, hipStream_t stream);
 
-// bf16 GEMM of two row-major operands contracted along their rows, fp32 output (shared_ffn.hip)
-hipError_t launch_gemm_tn_f32(const uint16_t* act, const uint16_t* w, int M, int N, int K, float* out, const float* scale,
-                              int planes, hipStream_t stream);
-hipError_t launch_gemm_tn_f32_kplanes(const uint16_t* act, const uint16_t* w, int M, int N, int K, int kplanes, float* out,
-                                      hipStream_t stream);
-// the same for groups of rows with a weight matrix (and scale vector) each; row0_host: host int32 [n_groups + 1]
+// bf16 GEMMs of two row-major operands contracted along their rows, fp32 output (shared_ffn.hip):
+// the contraction cut into K ranges given by a host table, one output plane per range
+hipError_t launch_gemm_tn_f32_kgroups(const uint16_t* act, const uint16_t* w, int M, int N, const int32_t* k0_host,
+                                      int n_groups, float* out, hipStream_t stream);
+// groups of rows with a weight matrix (and scale vector) each; row0_host: host int32 [n_groups + 1]
 int grouped_gemm_planes(const int32_t* row0_host, int n_groups, int N, int K, int max_planes);
 hipError_t launch_gemm_grouped_f32(const uint16_t* act, const uint16_t* w, const int32_t* row0_host, int n_groups, int N,
                                    int K, float* out, const float* scale, int planes, hipStream_t stream);

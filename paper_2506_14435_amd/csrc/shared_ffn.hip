@@ -84,7 +84,9 @@ struct RowGroups {
   int tile0[kMaxRowGroups + 1];
 };
 
-template <typename Cfg, bool GROUPED>
+// GROUPED: 0 plain, 1 row groups (above), 2 K ranges: plane p of the kplanes = rg->n planes contracts the
+// K range row0[p] .. row0[p+1]-1 (multiples of 64 elements; an empty range gives a plane of zeros).
+template <typename Cfg, int GROUPED>
 __device__ __forceinline__ void shared_gemm_body(const SharedGemmArgs& a, const RowGroups* rg, int n_ntiles, int kplanes,
                                                  int ktp, int group_m) {
   constexpr int NMAT = Cfg::NMAT, BM_W = Cfg::BM_W, BN_W = Cfg::BN_W;
@@ -112,7 +114,7 @@ __device__ __forceinline__ void shared_gemm_body(const SharedGemmArgs& a, const 
   // ktp K steps; each plane writes its own partial output, added later in plane order.
   n_ntiles *= kplanes;
   int n_mtiles = (M + BM - 1) / BM;
-  if constexpr (GROUPED) n_mtiles = rg->tile0[rg->n];
+  if constexpr (GROUPED == 1) n_mtiles = rg->tile0[rg->n];
   const int xcd = blockIdx.x & 7;
   const bool split_n = n_ntiles >= 16;
   const int xcd_ntiles = split_n ? (n_ntiles - xcd + 7) >> 3 : n_ntiles;
@@ -139,7 +141,7 @@ __device__ __forceinline__ void shared_gemm_body(const SharedGemmArgs& a, const 
     return r;
   };
   const v4i rsrc_a = make_rsrc(a.act, static_cast<int64_t>(M) * K * 2);
-  const v4i rsrc_b0 = make_rsrc(a.w0, static_cast<int64_t>(GROUPED ? rg->n : 1) * N * K * 2);
+  const v4i rsrc_b0 = make_rsrc(a.w0, static_cast<int64_t>(GROUPED == 1 ? rg->n : 1) * N * K * 2);
   const v4i rsrc_b1 = make_rsrc(NMAT == 2 ? a.w1 : a.w0, static_cast<int64_t>(N) * K * 2);
   // lane l of a wavefront load lands at byte 16*l of a 1-KiB block = tile row l/4, physical
   // chunk l%4, and therefore fetches logical chunk (l%4) ^ swizzle(row)
@@ -166,7 +168,7 @@ __device__ __forceinline__ void shared_gemm_body(const SharedGemmArgs& a, const 
   // where row tile mt_ starts and ends (uniform; the group is found by walking the table)
 #define MOTE_ROWS(mt_, mrow_, mend_, grp_)                                      \
   {                                                                             \
-    if constexpr (GROUPED) {                                                    \
+    if constexpr (GROUPED == 1) {                                               \
       int e_ = 0;                                                               \
       while (e_ + 1 < rg->n && rg->tile0[e_ + 1] <= (mt_)) ++e_;                \
       grp_ = e_;                                                                \
@@ -176,9 +178,21 @@ __device__ __forceinline__ void shared_gemm_body(const SharedGemmArgs& a, const 
       mrow_ = (mt_) * BM;                                                       \
     }                                                                           \
   }
-#define MOTE_POINTERS(mrow_, grp_, nt_, kc_)                                                       \
+  // byte offset of plane kc_ in an operand row and its K steps (uniform; GROUPED == 2 reads them from the
+  // table, early enough that the scalar loads are back when the tile starts)
+#define MOTE_KRANGE(kc_, kb_, ktl_)                                                                \
   {                                                                                                \
-    const uint32_t k0_ = static_cast<uint32_t>((kc_) * ktp) * 64u + ld_chunk;                      \
+    if constexpr (GROUPED == 2) {                                                                  \
+      kb_ = static_cast<uint32_t>(rg->row0[kc_]) * 2u;                                             \
+      ktl_ = (rg->row0[(kc_) + 1] - rg->row0[kc_]) >> 5;                                           \
+    } else {                                                                                       \
+      kb_ = static_cast<uint32_t>((kc_) * ktp) * 64u;                                              \
+      ktl_ = min(ktp, KT - (kc_) * ktp);                                                           \
+    }                                                                                              \
+  }
+#define MOTE_POINTERS(mrow_, grp_, nt_, kb_)                                                       \
+  {                                                                                                \
+    const uint32_t k0_ = (kb_) + ld_chunk;                                                         \
     _Pragma("unroll") for (int p = 0; p < Cfg::A_PASSES; ++p) {                                    \
       const int row_ = min((mrow_) + p * Cfg::ROWS_PER_PASS + ld_row, M - 1);                      \
       a_off[p] = static_cast<uint32_t>(row_) * static_cast<uint32_t>(K) * 2u + k0_;                \
@@ -214,8 +228,9 @@ __device__ __forceinline__ void shared_gemm_body(const SharedGemmArgs& a, const 
   // ---- first tile ----
   MOTE_DECODE(slot, mt, nt, kc);
   MOTE_ROWS(mt, mrow, mend, grp);
-  ktl = min(ktp, KT - kc * ktp);
-  MOTE_POINTERS(mrow, grp, nt, kc);
+  uint32_t kb;
+  MOTE_KRANGE(kc, kb, ktl);
+  MOTE_POINTERS(mrow, grp, nt, kb);
   MOTE_ISSUE_STEP(st_cur, 0);
   if (ktl > 1) MOTE_ISSUE_STEP(st_nxt, 1);
 
@@ -223,10 +238,12 @@ __device__ __forceinline__ void shared_gemm_body(const SharedGemmArgs& a, const 
     const int nslot = slot + stride;
     const bool has_next = nslot < xcd_work;
     int mt2 = mt, nt2 = nt, kc2 = kc;
-    int mrow2 = mrow, mend2 = mend, grp2 = grp;
+    int mrow2 = mrow, mend2 = mend, grp2 = grp, ktl2 = ktl;
+    uint32_t kb2 = kb;
     if (has_next) {
       MOTE_DECODE(nslot, mt2, nt2, kc2);
       MOTE_ROWS(mt2, mrow2, mend2, grp2);
+      MOTE_KRANGE(kc2, kb2, ktl2);
     }
     MOTE_WAIT_BARRIER(ktl > 1);   // K step 0 visible to every wavefront; the patches of the previous tile are done
     if constexpr (Cfg::STAGES == 4) {   // the third K step goes where patches of the previous tile were
@@ -383,10 +400,8 @@ __device__ __forceinline__ void shared_gemm_body(const SharedGemmArgs& a, const 
 
     // Start the next tile now: its first two K steps travel while this tile runs its epilogue.
     // The stage of the last K step (now st_nx2) is free until the next tile's first barrier.
-    int ktl2 = ktl;
     if (has_next) {
-      ktl2 = min(ktp, KT - kc2 * ktp);
-      MOTE_POINTERS(mrow2, grp2, nt2, kc2);
+      MOTE_POINTERS(mrow2, grp2, nt2, kb2);
       MOTE_ISSUE_STEP(st_cur, 0);
       if (ktl2 > 1) MOTE_ISSUE_STEP(st_nxt, 1);
     }
@@ -473,10 +488,11 @@ __device__ __forceinline__ void shared_gemm_body(const SharedGemmArgs& a, const 
     // No barrier here: the patches are private and their stage is not refilled before the next
     // tile's first barrier.
     slot = nslot; mt = mt2; nt = nt2; kc = kc2; ktl = ktl2;
-    mrow = mrow2; mend = mend2; grp = grp2;
+    mrow = mrow2; mend = mend2; grp = grp2; kb = kb2;
   }
 #undef MOTE_DECODE
 #undef MOTE_ROWS
+#undef MOTE_KRANGE
 #undef MOTE_POINTERS
 #undef MOTE_DMA
 #undef MOTE_DMA_A
@@ -488,14 +504,20 @@ __device__ __forceinline__ void shared_gemm_body(const SharedGemmArgs& a, const 
 template <typename Cfg>
 __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void shared_gemm_kernel(SharedGemmArgs a, int n_ntiles,
                                                                                    int kplanes, int ktp, int group_m) {
-  shared_gemm_body<Cfg, false>(a, nullptr, n_ntiles, kplanes, ktp, group_m);
+  shared_gemm_body<Cfg, 0>(a, nullptr, n_ntiles, kplanes, ktp, group_m);
 }
 
 template <typename Cfg>
 __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void grouped_gemm_kernel(SharedGemmArgs a, RowGroups rg,
                                                                                     int n_ntiles, int kplanes, int ktp,
                                                                                     int group_m) {
-  shared_gemm_body<Cfg, true>(a, &rg, n_ntiles, kplanes, ktp, group_m);
+  shared_gemm_body<Cfg, 1>(a, &rg, n_ntiles, kplanes, ktp, group_m);
+}
+
+template <typename Cfg>
+__global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_BLOCKS) void kgrouped_gemm_kernel(SharedGemmArgs a, RowGroups rg,
+                                                                                     int n_ntiles, int group_m) {
+  shared_gemm_body<Cfg, 2>(a, &rg, n_ntiles, rg.n, 0, group_m);
 }
 
 static int shared_cu_count() {
@@ -635,34 +657,6 @@ hipError_t launch_shared_down_scaled(const uint16_t* h_s, const uint16_t* w_down
   }
 }
 
-// Plain bf16 GEMM with fp32 output for other callers: out[m, n] = scale[n] * sum_k act[m, k] * w[n, k]
-// (scale optional).  K must be a multiple of 64.  planes > 1: the contraction is cut into that many
-// K planes and plane p writes its partial sums to out + p * M * N (128 x 128 tiles; for problems
-// with too few output tiles to fill the chip); the caller adds the planes.
-hipError_t launch_gemm_tn_f32(const uint16_t* act, const uint16_t* w, int M, int N, int K, float* out, const float* scale,
-                              int planes, hipStream_t stream) {
-  if (M == 0 || N == 0) return hipSuccess;
-  SharedGemmArgs a{act, w, nullptr, M, N, K, nullptr, out, static_cast<int64_t>(M) * N, scale, nullptr};
-  if (planes > 1) return launch_shared_cfg<SharedCfg<1, 2, 2, 2, 2, 2>>(a, planes, stream);
-  if (static_cast<int64_t>((M + 255) / 256) * ((N + 255) / 256) >= 256)
-    return launch_shared_cfg<SharedCfg<1, 2, 4, 4, 2, 1, 4>>(a, 1, stream);   // 256 x 256
-  if (static_cast<int64_t>((M + 127) / 128) * ((N + 255) / 256) >= 256)
-    return launch_shared_cfg<SharedCfg<1, 2, 4, 2, 2, 2>>(a, 1, stream);      // 128 x 256
-  return launch_shared_cfg<SharedCfg<1, 2, 2, 2, 2, 2>>(a, 1, stream);        // 128 x 128
-}
-
-// The same contraction cut into kplanes equal K planes, plane p written to out + p * M * N (the
-// caller's use: operands of several problems side by side along K, one plane per problem).
-// K / kplanes must be a multiple of 64.
-hipError_t launch_gemm_tn_f32_kplanes(const uint16_t* act, const uint16_t* w, int M, int N, int K, int kplanes, float* out,
-                                      hipStream_t stream) {
-  if (M == 0 || N == 0 || kplanes < 1) return hipSuccess;
-  SharedGemmArgs a{act, w, nullptr, M, N, K, nullptr, out, static_cast<int64_t>(M) * N, nullptr, nullptr};
-  if (static_cast<int64_t>((M + 255) / 256) * ((N + 255) / 256) * kplanes >= 256)
-    return launch_shared_cfg<SharedCfg<1, 2, 4, 4, 2, 1, 4>>(a, kplanes, stream);   // 256 x 256
-  return launch_shared_cfg<SharedCfg<1, 2, 2, 2, 2, 2>>(a, kplanes, stream);        // 128 x 128
-}
-
 template <typename Cfg>
 static hipError_t launch_grouped_cfg(const SharedGemmArgs& a, const int32_t* row0, int n_groups, int kplanes,
                                      hipStream_t stream) {
@@ -747,6 +741,50 @@ hipError_t launch_gemm_grouped_f32(const uint16_t* act, const uint16_t* w, const
   if (grouped_row_tiles(row0_host, n_groups, 256) * ((N + 255) / 256) >= (3 * shared_cu_count()) / 4)
     return launch_grouped_cfg<SharedCfg<1, 2, 4, 4, 2, 1, 4>>(a, row0_host, n_groups, planes, stream);   // 256 x 256
   return launch_grouped_cfg<SharedCfg<1, 2, 2, 2, 2, 2>>(a, row0_host, n_groups, planes, stream);        // 128 x 128
+}
+
+template <typename Cfg>
+static hipError_t launch_kgrouped_cfg(const SharedGemmArgs& a, const int32_t* k0, int n_groups, hipStream_t stream) {
+  RowGroups rg;
+  rg.n = n_groups;
+  for (int e = 0; e <= kMaxRowGroups; ++e) {
+    rg.row0[e] = k0[std::min(e, n_groups)];
+    rg.tile0[e] = 0;
+  }
+  const int n_ntiles = (a.N + Cfg::BN - 1) / Cfg::BN;
+  const int n_mtiles = (a.M + Cfg::BM - 1) / Cfg::BM;
+  const size_t lds = Cfg::LDS_BYTES;
+  static bool attr_set = false;
+  static int resident = Cfg::MIN_BLOCKS;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kgrouped_gemm_kernel<Cfg>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+    if (e != hipSuccess) return e;
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kgrouped_gemm_kernel<Cfg>, Cfg::THREADS, lds) == hipSuccess && n > 0)
+      resident = n;
+    attr_set = true;
+  }
+  const int64_t tiles = static_cast<int64_t>(n_mtiles) * n_ntiles * n_groups;
+  int64_t blocks = static_cast<int64_t>(shared_cu_count()) * resident;
+  if (blocks > tiles) blocks = (tiles + 7) / 8 * 8;
+  kgrouped_gemm_kernel<Cfg><<<static_cast<unsigned>(blocks), Cfg::THREADS, lds, stream>>>(a, rg, n_ntiles, tile_group_m());
+  return hipGetLastError();
+}
+
+// Several contractions over consecutive K ranges of the same two operands in one launch: plane p,
+// written to out + p * M * N, is sum over k0_host[p] <= k < k0_host[p+1] of act[m, k] * w[n, k] (operands
+// [M, K] and [N, K] with K = k0_host[n_groups]; the offsets are HOST integers, multiples of 64, ascending from
+// 0; an empty range gives zeros).  The caller's use: one problem per range, its operands side by side along K.
+hipError_t launch_gemm_tn_f32_kgroups(const uint16_t* act, const uint16_t* w, int M, int N, const int32_t* k0_host,
+                                      int n_groups, float* out, hipStream_t stream) {
+  if (n_groups < 1 || n_groups > kMaxRowGroups) return hipErrorInvalidValue;
+  if (M == 0 || N == 0) return hipSuccess;
+  const int K = k0_host[n_groups];
+  SharedGemmArgs a{act, w, nullptr, M, N, K, nullptr, out, static_cast<int64_t>(M) * N, nullptr, nullptr};
+  if (static_cast<int64_t>((M + 255) / 256) * ((N + 255) / 256) * n_groups >= 256)
+    return launch_kgrouped_cfg<SharedCfg<1, 2, 4, 4, 2, 1, 4>>(a, k0_host, n_groups, stream);   // 256 x 256
+  return launch_kgrouped_cfg<SharedCfg<1, 2, 2, 2, 2, 2>>(a, k0_host, n_groups, stream);        // 128 x 128
 }
 
 }  // namespace mote

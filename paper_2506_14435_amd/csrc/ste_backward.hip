@@ -7,12 +7,14 @@
 //
 // Both are dense bf16 contractions with fp32 accumulation (ternary values and int8 codes are
 // exact in bf16) and run on the bf16 MFMA GEMM of the shared expert, which contracts two
-// row-major operands along their rows.  The kernels here bring the operands into that form:
+// row-major operands along their rows: dX of all experts as one launch over groups of rows, each
+// with its own weight matrix; dW of all experts as one launch whose K ranges are the experts.  The
+// kernels here bring the operands into that form, each in one launch over all experts:
 //
 //   expand_ternary_t_kernel : packed 2-bit codes of W_e [N, K] -> bf16 matrix [K, N] of t_e^T
-//   transpose_rows_kernel   : dY_e [rows, N] bf16, scaled by beta_r / 127 and rounded once
-//                             -> [N, rows_pad]; q_e [rows, K] int8 -> bf16 [K, rows_pad]
-//                             (rows_pad = rows rounded up to 64, the padding is zero)
+//   transpose_groups_kernel : dY [R, N] bf16, scaled by beta_r / 127 and rounded once -> [N, sum_pad],
+//                             q [R, K] int8 -> bf16 [K, sum_pad]; expert e in the columns pad0[e] ..,
+//                             its rows rounded up to 64 with zeros
 //   fill_alpha_kernel       : alpha_e broadcast over the K output channels of dX (the GEMM
 //                             epilogue multiplies per output channel)
 #include <algorithm>
@@ -65,6 +67,7 @@ __device__ __forceinline__ void expand_ternary_t_body(const uint32_t* __restrict
 struct SteGroups {
   int n;
   int row0[65];
+  int col0[65];   // first column of the expert's block in the transposed operands (rows padded to 64 per expert)
 };
 __global__ __launch_bounds__(kSteThreads) void expand_ternary_t_kernel(const uint32_t* __restrict__ packed, int N, int K,
                                                                        SteGroups grp, int e0, uint16_t* __restrict__ out) {
@@ -135,23 +138,17 @@ __device__ __forceinline__ void transpose_rows_body(const void* __restrict__ in,
   }
 }
 
-template <bool INT8>
-__global__ __launch_bounds__(kSteThreads) void transpose_rows_kernel(const void* __restrict__ in, const float* __restrict__ beta,
-                                                                     int rows, int rows_pad, int C, int64_t ld, uint16_t* __restrict__ out) {
-  (void)rows_pad;   // the grid covers rows_pad / 64 row tiles
-  transpose_rows_body<INT8>(in, beta, rows, C, ld, out);
-}
-
-// The same for every expert in one launch (blockIdx.y = expert): expert e owns the rows row0[e] .. row0[e+1]-1
-// of `in` and the columns e * lp .. of `out` ([C, n * lp], every block padded with zeros to lp columns).
+// Every expert in one launch (blockIdx.y = expert): expert e owns the rows row0[e] .. row0[e+1]-1
+// of `in` and the columns col0[e] .. col0[e+1]-1 of `out` ([C, ld]; the block is padded with zeros to a
+// multiple of 64 columns).  The grid covers the longest block; workgroups past an expert's block leave.
 template <bool INT8>
 __global__ __launch_bounds__(kSteThreads) void transpose_groups_kernel(const void* __restrict__ in, const float* __restrict__ beta,
-                                                                       SteGroups grp, int lp, int C, uint16_t* __restrict__ out) {
-  const int e = blockIdx.y, r0 = grp.row0[e];
+                                                                       SteGroups grp, int C, int64_t ld, uint16_t* __restrict__ out) {
+  const int e = blockIdx.y, r0 = grp.row0[e], c0 = grp.col0[e];
+  if (static_cast<int>(blockIdx.x / (C >> 6)) * 64 >= grp.col0[e + 1] - c0) return;
   const void* const in_e = INT8 ? static_cast<const void*>(static_cast<const int8_t*>(in) + static_cast<int64_t>(r0) * C)
                                 : static_cast<const void*>(static_cast<const uint16_t*>(in) + static_cast<int64_t>(r0) * C);
-  transpose_rows_body<INT8>(in_e, INT8 ? nullptr : beta + r0, grp.row0[e + 1] - r0, C, static_cast<int64_t>(grp.n) * lp,
-                            out + static_cast<int64_t>(e) * lp);
+  transpose_rows_body<INT8>(in_e, INT8 ? nullptr : beta + r0, grp.row0[e + 1] - r0, C, ld, out + c0);
 }
 
 __global__ __launch_bounds__(kSteThreads) void fill_alpha_kernel(const float* __restrict__ alpha, int alpha_stride, int E,
@@ -194,20 +191,13 @@ static int ste_dx_batch(int N, int K, int E) {
   return static_cast<int>(std::max<int64_t>(1, std::min<int64_t>(g, E)));
 }
 
-// dW of all experts in one launch: every expert's transposed block is padded to the longest one
-// (lp rows) and the blocks sit side by side along the contraction axis, [N, E * lp] and
-// [K, E * lp]; the GEMM cuts the contraction into E planes of lp and plane e is dW_e.  Taken when
-// the padding adds at most a quarter to the work and the operands stay below 2 GiB.
-static bool ste_batched_dw(int64_t lp, int64_t sum_pad, int N, int K, int E) {
-  const int64_t lim = int64_t{1} << 31;
-  return E > 1 && E * lp * 4 <= sum_pad * 5 && E * lp * N * 2 < lim && E * lp * K * 2 < lim;
-}
-
 // Workspace: the expanded transposed weights of one batch of experts [experts][K, N], the transposed
-// scaled gradient rows and codes of every expert (sum of rows_pad_e <= R + 63 E columns, a quarter
-// more for the batched layout), alpha broadcast [E, K], partial planes of dX.
+// scaled gradient rows and codes of every expert (sum of rows_pad_e <= R + 63 E columns, a sixteenth
+// more when near-equal blocks are padded to the longest), alpha
+// broadcast [E, K], partial planes of dX.
+static size_t ste_pad_rows(int R, int E) { return (static_cast<size_t>(R) + 64 * static_cast<size_t>(E)) * 17 / 16 + 64; }
 size_t ste_backward_workspace_bytes(int R, int N, int K, int E) {
-  const size_t rp = (static_cast<size_t>(R) + 64 * static_cast<size_t>(E)) * 5 / 4 + 64;
+  const size_t rp = ste_pad_rows(R, E);
   const size_t plane_bytes = static_cast<size_t>(kSteMaxPlanes) * R * K * 4;
   return ste_align(static_cast<size_t>(ste_dx_batch(N, K, E)) * K * N * 2) + ste_align(rp * N * 2) + ste_align(rp * K * 2) +
          ste_align(static_cast<size_t>(E) * K * 4) + ste_align(plane_bytes);
@@ -217,7 +207,7 @@ hipError_t launch_ste_backward(const uint16_t* dy, const int32_t* offsets_host, 
                                int alpha_stride, const int8_t* q, const float* beta, int R, int N, int K, int E,
                                float* dx, float* dw, void* workspace, hipStream_t stream) {
   char* ws = static_cast<char*>(workspace);
-  const size_t rp_total = (static_cast<size_t>(R) + 64 * static_cast<size_t>(E)) * 5 / 4 + 64;
+  const size_t rp_total = ste_pad_rows(R, E);
   const int batch = ste_dx_batch(N, K, E);
   uint16_t* wt = reinterpret_cast<uint16_t*>(ws);
   ws += ste_align(static_cast<size_t>(batch) * K * N * 2);
@@ -229,18 +219,27 @@ hipError_t launch_ste_backward(const uint16_t* dy, const int32_t* offsets_host, 
   ws += ste_align(static_cast<size_t>(E) * K * 4);
   float* dx_planes = reinterpret_cast<float*>(ws);
 
-  int64_t lp = 64, sum_pad = 0;
-  for (int e = 0; e < E; ++e) {
-    const int64_t rows_pad = (static_cast<int64_t>(offsets_host[e + 1]) - offsets_host[e] + 63) / 64 * 64;
-    lp = std::max(lp, rows_pad);
-    sum_pad += rows_pad;
-  }
-  const bool batched = ste_batched_dw(lp, sum_pad, N, K, E);
-
-  fill_alpha_kernel<<<(E * K + kSteThreads - 1) / kSteThreads, kSteThreads, 0, stream>>>(alpha, alpha_stride, E, K, alpha_vec);
   SteGroups grp;
   grp.n = E;
-  for (int e = 0; e <= 64; ++e) grp.row0[e] = offsets_host[std::min(e, E)];
+  int32_t pad0[65];   // first padded row of every expert = K ranges of the dW contraction
+  int64_t sum_pad = 0, tight = 0;
+  int longest = 0;
+  for (int e = 0; e < E; ++e) {
+    const int rows_pad = (offsets_host[e + 1] - offsets_host[e] + 63) / 64 * 64;
+    tight += rows_pad;
+    longest = std::max(longest, rows_pad);
+  }
+  // near-equal groups: every block as long as the longest (at most 1/16 more contraction steps); tiles of
+  // equal length keep the workgroups of the dW GEMM in step (3B width, 16 groups of about 1024 rows:
+  // 966 -> 921 us for the GEMM)
+  const bool uniform = static_cast<int64_t>(E) * longest * 16 <= tight * 17;
+  for (int e = 0; e <= 64; ++e) {
+    grp.row0[e] = offsets_host[std::min(e, E)];
+    grp.col0[e] = pad0[e] = static_cast<int32_t>(sum_pad);
+    if (e < E) sum_pad += uniform ? longest : (offsets_host[e + 1] - offsets_host[e] + 63) / 64 * 64;
+  }
+
+  fill_alpha_kernel<<<(E * K + kSteThreads - 1) / kSteThreads, kSteThreads, 0, stream>>>(alpha, alpha_stride, E, K, alpha_vec);
   // dX: t^T of a batch of experts expanded to bf16, then one grouped GEMM over their rows, scaled by alpha
   for (int e0 = 0; e0 < E; e0 += batch) {
     const int nb = std::min(batch, E - e0);
@@ -260,38 +259,18 @@ hipError_t launch_ste_backward(const uint16_t* dy, const int32_t* offsets_host, 
                           0, stream>>>(dx_planes, planes, n4, nullptr, dx_b);
     }
   }
-  // operands of dW
-  if (batched) {   // block e of the side-by-side layout, zero beyond its rows: all experts in one launch each
-    const unsigned tiles_r = static_cast<unsigned>(lp / 64);
-    transpose_groups_kernel<false><<<dim3(tiles_r * (N / 64), E), kSteThreads, 0, stream>>>(dy, beta, grp, static_cast<int>(lp),
-                                                                                          N, dyt);
-    transpose_groups_kernel<true><<<dim3(tiles_r * (K / 64), E), kSteThreads, 0, stream>>>(q, nullptr, grp, static_cast<int>(lp),
-                                                                                         K, qt);
+  // dW: the scaled gradient rows and the codes of every expert transposed into [N, sum_pad] and [K, sum_pad]
+  // (expert e in the columns pad0[e] .., padded with zeros to a multiple of 64), then ONE GEMM whose K
+  // ranges are the experts: plane e = dW_e, zeros for an expert without rows.
+  if (sum_pad == 0) {
+    fill_zero_kernel<<<1024, kSteThreads, 0, stream>>>(dw, static_cast<int64_t>(E) * N * K / 4);
+    return hipGetLastError();
   }
-  size_t pad_off = 0;   // padded rows before this expert (layout of one block per expert)
-  for (int e = 0; e < E && !batched; ++e) {
-    const int row0 = offsets_host[e], rows = offsets_host[e + 1] - offsets_host[e];
-    float* dw_e = dw + static_cast<int64_t>(e) * N * K;
-    hipError_t err;
-    if (rows == 0) {   // no token reached this expert: its gradient is zero
-      fill_zero_kernel<<<1024, kSteThreads, 0, stream>>>(dw_e, static_cast<int64_t>(N) * K / 4);
-      continue;
-    }
-    const int rows_pad = (rows + 63) / 64 * 64;
-    uint16_t* dyt_e = dyt + pad_off * N;
-    uint16_t* qt_e = qt + pad_off * K;
-    transpose_rows_kernel<false><<<(rows_pad / 64) * (N / 64), kSteThreads, 0, stream>>>(
-        dy + static_cast<int64_t>(row0) * N, beta + row0, rows, rows_pad, N, rows_pad, dyt_e);
-    transpose_rows_kernel<true><<<(rows_pad / 64) * (K / 64), kSteThreads, 0, stream>>>(
-        q + static_cast<int64_t>(row0) * K, nullptr, rows, rows_pad, K, rows_pad, qt_e);
-    err = launch_gemm_tn_f32(dyt_e, qt_e, N, K, rows_pad, dw_e, nullptr, 1, stream);
-    if (err != hipSuccess) return err;
-    pad_off += rows_pad;
-  }
-  if (batched) {
-    hipError_t err = launch_gemm_tn_f32_kplanes(dyt, qt, N, K, static_cast<int>(E * lp), E, dw, stream);
-    if (err != hipSuccess) return err;
-  }
+  const unsigned tiles_r = static_cast<unsigned>(longest / 64);
+  transpose_groups_kernel<false><<<dim3(tiles_r * (N / 64), E), kSteThreads, 0, stream>>>(dy, beta, grp, N, sum_pad, dyt);
+  transpose_groups_kernel<true><<<dim3(tiles_r * (K / 64), E), kSteThreads, 0, stream>>>(q, nullptr, grp, K, sum_pad, qt);
+  hipError_t err = launch_gemm_tn_f32_kgroups(dyt, qt, N, K, pad0, E, dw, stream);
+  if (err != hipSuccess) return err;
   return hipGetLastError();
 }
 

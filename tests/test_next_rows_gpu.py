@@ -350,7 +350,9 @@ def _ste_check(p, dx, dw, N, K, experts_checked=None, rows_per_expert=None):
 @pytest.mark.parametrize("R,N,K,E,cuts", [(300, 256, 128, 3, None), (1000, 512, 384, 4, None),
                                           (77, 128, 256, 5, [0, 10, 10, 64]), (64, 128, 128, 1, None),
                                           (513, 384, 256, 2, [512]),
-                                          # near-equal groups: dW of all experts in one launch (blocks side by side)
+                                          (200, 128, 128, 3, [120, 200]),          # the last expert without rows
+                                          (1018, 256, 256, 4, [256, 506, 762]),    # near-equal: every block padded to the longest
+                                          # near-equal and unequal groups (dW: one launch, the experts are its K ranges)
                                           (1024, 256, 256, 4, [250, 510, 770]),
                                           (2100, 128, 384, 8, [300, 600, 900, 900, 1200, 1500, 1800])])
 def test_ste_linear_backward_matches_oracle(R, N, K, E, cuts):
