@@ -81,7 +81,8 @@ def test_pack_ternary_degenerate_matrices():
                                           # from 4096 tokens on, E <= 16: 16 tokens per workgroup on the fp64 matrix
                                           # instruction (ragged last workgroup; E not a multiple of 8; a last
                                           # block of 128 channels; the widest register variant)
-                                          (4099, 384, 6, 3, True), (4112, 896, 8, 2, True), (4100, 3584, 16, 2, False)])
+                                          (4099, 384, 6, 3, True), (4112, 896, 8, 2, True), (4100, 3584, 16, 2, False),
+                                          (4096, 128, 16, 1, False), (4097, 4096, 2, 2, True), (4200, 256, 16, 8, False)])
 def test_router_topk_matches_oracle(T, d, E, k, bias):
     M = _m()
     _log(f"router T={T} d={d} E={E} k={k} bias={bias}")
